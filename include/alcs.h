@@ -1,0 +1,171 @@
+/*
+ * alcs.h - C ABI of the MI355X (gfx950) SIMD-structured sparse convolution library.
+ *
+ * The operation is the inference kernel of "Architecture Aware Latency Constrained
+ * Sparse Neural Networks on Mobile Devices" (arXiv 2109.00170), Section 3.2:
+ * every group of V adjacent output channels keeps or drops the weights at one
+ * filter position (c, r, s) as a unit (Section 3.2.1), the kept V-vectors are
+ * stored per group in a grouped CSR format (Section 3.2.2, "Storage format"), and
+ * the convolution is the product of that block-sparse matrix with the (virtual)
+ * patch matrix of the input (Section 3.2.2, "Overview" / "Efficient multiplication
+ * computation").
+ *
+ * Conventions shared by all entry points
+ *   - fp32 data, int32 indices, NCHW tensors, row-major, densely packed.
+ *   - kernel is 1 or 3 (square); pad = (kernel-1)/2 zeros on every side;
+ *     Ho = (H + 2*pad - kernel)/stride + 1, likewise Wo; cross-correlation (the
+ *     filter is not flipped), as in the paper's convolution equation.
+ *   - G = ceil(Cout / V) groups; group g owns output channels [g*V, g*V+V).
+ *     The flattened column index of filter position (c, r, s) is
+ *     col = (c*kernel + r)*kernel + s, K = Cin*kernel*kernel columns per group.
+ *   - Pointers named *_host point to host memory, *_dev to memory of the current
+ *     HIP device.  The caller owns every buffer it passes in.  Device buffers must
+ *     be 16-byte aligned (anything hipMalloc or PyTorch returns is).
+ *   - Every function returns ALCS_OK (0) or a negative alcs_status; nothing throws
+ *     across the boundary.  Launches are asynchronous on `stream` (a hipStream_t
+ *     passed as void*, NULL = the default stream); the library never synchronises
+ *     and never allocates inside alcs_sparse_conv / alcs_dense_conv.
+ *   - Y is overwritten completely and must not alias X, bias or the weights.
+ *   - Inputs are expected to be finite; with Inf/NaN in X the result is
+ *     unspecified (as it is for the defining sum once 0*Inf terms appear).
+ */
+#ifndef ALCS_H
+#define ALCS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum alcs_status {
+    ALCS_OK = 0,
+    ALCS_E_INVALID_ARG = -1, /* null pointer, non-positive size, shape mismatch with the handle */
+    ALCS_E_UNSUPPORTED = -2, /* kernel not in {1,3}, V not in {1,2,4,8,16}, stride not in {1,2}, size limits */
+    ALCS_E_ALLOC = -3,       /* host or device allocation failed */
+    ALCS_E_HIP = -4,         /* a HIP runtime call failed (see alcs_last_hip_error) */
+    ALCS_E_NO_DEVICE = -5    /* the handle has no device copy (packed without a GPU) */
+} alcs_status;
+
+/* Opaque packed weight tensor; created by alcs_pack_weights, owned by the library
+ * until alcs_packed_free.  Immutable after creation; may be used from several
+ * streams at once. */
+typedef struct alcs_packed alcs_packed_t;
+
+/* Human-readable name of a status code (static string, never NULL). */
+const char *alcs_strerror(int status);
+
+/* hipError_t value of the last failing HIP call made by this thread's library
+ * calls (0 if none), for diagnostics after ALCS_E_HIP. */
+int alcs_last_hip_error(void);
+
+/* Library version, encoded major*10000 + minor*100 + patch. */
+int alcs_version(void);
+
+/*
+ * Offline re-organisation of the pruned weights (Section 3.2.2, "Storage format":
+ * "number of non-zero columns", "column offsets", "non-zero values" per filter
+ * group; done once before inference).
+ *
+ *   W_host    [Cout, Cin, kernel, kernel] fp32.
+ *   mask_host [G, Cin, kernel, kernel] uint8, non-zero = block kept; NULL keeps all
+ *             blocks.  The mask rules: a kept block is stored even if its values
+ *             are zero, a dropped block contributes nothing whatever W holds there.
+ *   V         group size, one of 1, 2, 4, 8, 16.  If Cout is not a multiple of V
+ *             the last group is ragged: its missing rows are stored as +0.0f and
+ *             never written to Y.
+ *   out       receives the handle.
+ *
+ * Builds (a) the canonical grouped CSR on the host (see alcs_packed_export) and
+ * (b) a device-side layout tuned for the kernels, uploaded to the current HIP
+ * device with blocking copies.  Without a usable HIP device (b) is skipped, the
+ * call still succeeds, and alcs_sparse_conv on that handle returns
+ * ALCS_E_NO_DEVICE.  Errors: ALCS_E_INVALID_ARG (null W/out, sizes <= 0),
+ * ALCS_E_UNSUPPORTED (kernel, V, or Cin*kernel^2 / Cout beyond 2^24),
+ * ALCS_E_ALLOC, ALCS_E_HIP.
+ */
+int alcs_pack_weights(const float *W_host, const uint8_t *mask_host, int Cout, int Cin, int kernel,
+                      int V, alcs_packed_t **out);
+
+/* Shape of a packed tensor: number of groups G, columns per group K, and the total
+ * number of kept blocks nnzb.  Any output pointer may be NULL. */
+int alcs_packed_info(const alcs_packed_t *p, int *G, int *K, int64_t *nnzb);
+
+/* 1 if the handle has a device copy, else 0 (negative status on a NULL handle). */
+int alcs_packed_on_device(const alcs_packed_t *p);
+
+/*
+ * Canonical grouped CSR of Section 3.2.2, for bit-exact comparison:
+ *   row_ptr_host [G+1]     running total of the per-group kept-column counts
+ *                          (count_g = row_ptr[g+1]-row_ptr[g], row_ptr[0] = 0);
+ *   col_idx_host [nnzb]    column offset of each kept column = its absolute
+ *                          0-based position col in the flattened filter,
+ *                          ascending inside a group;
+ *   vals_host    [nnzb*V]  the V weights of each kept column, top row first.
+ * Caller-allocated host arrays of exactly these sizes.
+ */
+int alcs_packed_export(const alcs_packed_t *p, int32_t *row_ptr_host, int32_t *col_idx_host,
+                       float *vals_host);
+
+/* Host-side consistency check of the tuned layout: re-derives the canonical arrays
+ * from the padded/segmented arrays the kernels read and compares bit for bit, and
+ * checks every padded slot (zero weight, offset of the all-zero row) and every
+ * stored offset against the LDS tile bounds the kernels assume.  Needs no GPU.
+ * Returns ALCS_OK or ALCS_E_INVALID_ARG on the first inconsistency. */
+int alcs_packed_selfcheck(const alcs_packed_t *p);
+
+/* Releases host and device memory of a handle (NULL is ignored).  The caller must
+ * make sure no launch that reads it is still in flight. */
+void alcs_packed_free(alcs_packed_t *p);
+
+/*
+ * The sparse convolution (Section 3.2.2, "Efficient multiplication computation"):
+ *   Y[n, g*V+v, ho, wo] = bias[g*V+v]
+ *       + sum over the group's kept columns j of
+ *         vals[g][j][v] * Xpad[n, c_j, ho*stride + r_j - pad, wo*stride + s_j - pad]
+ *
+ *   Wp        handle from alcs_pack_weights with a device copy on the current device.
+ *   X_dev     [N, Cin, H, W] fp32.
+ *   bias_dev  [Cout] fp32 or NULL (= zeros).
+ *   Y_dev     [N, Cout, Ho, Wo] fp32, fully overwritten.
+ *   Cin, Cout, kernel must equal the values the handle was packed with
+ *   (ALCS_E_INVALID_ARG otherwise - checked on the host before anything is
+ *   launched); stride is 1 or 2.  N*Cout*Ho*Wo and N*Cin*H*W must be < 2^31
+ *   elements per image-channel plane product as checked by the library
+ *   (ALCS_E_UNSUPPORTED).  N == 0 is a no-op that returns ALCS_OK.
+ *   The accumulation order inside a sum is unspecified (fp32 results agree with the
+ *   definition to rounding, not bit for bit).
+ */
+int alcs_sparse_conv(const alcs_packed_t *Wp, const float *X_dev, const float *bias_dev,
+                     float *Y_dev, int N, int Cin, int Cout, int H, int W, int kernel, int stride,
+                     void *stream);
+
+/*
+ * Dense convolution with the same conventions: the sparsity-0 case of the
+ * operation above and the same-GPU baseline (the role the dense models play in the
+ * paper's Section 4.1 timing protocol).
+ *   W_dev [Cout, Cin, kernel, kernel] fp32 on the device; other arguments as above.
+ */
+int alcs_dense_conv(const float *W_dev, const float *X_dev, const float *bias_dev, float *Y_dev,
+                    int N, int Cin, int Cout, int H, int W, int kernel, int stride, void *stream);
+
+/*
+ * Tuning knobs for measurements (process-wide, not thread-safe against concurrent
+ * conv calls).  name is one of "pv" (pixels per lane 1/2/4, 0 = automatic),
+ * "waves" (wavefronts per workgroup, 0 = automatic), "group_tiles" (0 = automatic),
+ * "path" (0 = automatic, 1 = force plain-FMA inner loop, 2 = force MFMA inner loop).
+ * Unknown names return ALCS_E_INVALID_ARG.  Results never depend on the knobs beyond
+ * floating-point summation order.
+ */
+int alcs_set_tuning(const char *name, int value);
+
+/* What the last alcs_sparse_conv call of this thread launched: fills up to `cap`
+ * ints {mode, pv, waves, workgroups, lds_bytes, group_tiles, chunk_channels, path}
+ * and returns how many were written.  For tests and benchmarks. */
+int alcs_last_launch(int *out, int cap);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ALCS_H */

@@ -1,0 +1,20 @@
+"""MI355X-native SIMD-structured sparse convolution (hot path of arXiv 2109.00170, Section 3.2).
+
+Thin ctypes binding over ``libalcs.so`` (see ``include/alcs.h``); every step of the
+path runs in the HIP library.  There is no CPU fallback: if the library has not been
+built, loading fails with an ImportError.
+"""
+from ._binding import (  # noqa: F401
+    AlcsError,
+    Packed,
+    alcs_dense_conv,
+    alcs_last_launch,
+    alcs_pack_weights,
+    alcs_set_tuning,
+    alcs_sparse_conv,
+    alcs_strerror,
+    alcs_version,
+    library_path,
+    load_library,
+    out_size,
+)

@@ -1,0 +1,203 @@
+"""Argument marshalling for the C ABI declared in include/alcs.h.  No arithmetic here."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libalcs.so")
+_lib = None
+
+EXPORTS = [
+    "alcs_strerror", "alcs_last_hip_error", "alcs_version", "alcs_pack_weights", "alcs_packed_info",
+    "alcs_packed_on_device", "alcs_packed_export", "alcs_packed_selfcheck", "alcs_packed_free",
+    "alcs_sparse_conv", "alcs_dense_conv", "alcs_set_tuning", "alcs_last_launch",
+]
+
+
+class AlcsError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = int(status)
+        super().__init__("%s failed: %s (hip error %d)" % (where, alcs_strerror(status), _hip_err()))
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libalcs.so; raise ImportError if it has not been built (no fallback)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError("%s is missing: build it with `python -m paper_2109_00170_amd.build` "
+                          "(or __graft_entry__.build())" % _LIB_PATH)
+    # PyTorch ships its own HIP runtime (libamdhip64.so.7 under torch/lib).  It has to be
+    # in the process before libalcs.so is loaded, so that both resolve to that one
+    # runtime; otherwise two runtimes coexist and streams and the device cannot be shared.
+    import torch  # noqa: F401
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, ci, cip = ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(ctypes.c_int)
+    lib.alcs_strerror.restype = ctypes.c_char_p
+    lib.alcs_strerror.argtypes = [ci]
+    lib.alcs_pack_weights.argtypes = [vp, vp, ci, ci, ci, ci, ctypes.POINTER(vp)]
+    lib.alcs_packed_info.argtypes = [vp, cip, cip, ctypes.POINTER(ctypes.c_int64)]
+    lib.alcs_packed_on_device.argtypes = [vp]
+    lib.alcs_packed_export.argtypes = [vp, vp, vp, vp]
+    lib.alcs_packed_selfcheck.argtypes = [vp]
+    lib.alcs_packed_free.argtypes = [vp]
+    lib.alcs_packed_free.restype = None
+    lib.alcs_sparse_conv.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp]
+    lib.alcs_dense_conv.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp]
+    lib.alcs_set_tuning.argtypes = [ctypes.c_char_p, ci]
+    lib.alcs_last_launch.argtypes = [cip, ci]
+    _lib = lib
+    return lib
+
+
+def _hip_err() -> int:
+    return int(load_library().alcs_last_hip_error())
+
+
+def alcs_strerror(status: int) -> str:
+    return load_library().alcs_strerror(int(status)).decode()
+
+
+def alcs_version() -> int:
+    return int(load_library().alcs_version())
+
+
+def out_size(size: int, kernel: int, stride: int) -> int:
+    """Output extent for pad = (kernel-1)//2 (shape bookkeeping only)."""
+    return (size + 2 * ((kernel - 1) // 2) - kernel) // stride + 1
+
+
+class Packed:
+    """Owner of an alcs_packed_t handle."""
+
+    def __init__(self, handle, Cout, Cin, kernel, V):
+        self._h = handle
+        self.Cout, self.Cin, self.kernel, self.V = Cout, Cin, kernel, V
+        G, K, nnzb = ctypes.c_int(), ctypes.c_int(), ctypes.c_int64()
+        rc = load_library().alcs_packed_info(self._h, ctypes.byref(G), ctypes.byref(K), ctypes.byref(nnzb))
+        if rc != 0:
+            raise AlcsError(rc, "alcs_packed_info")
+        self.G, self.K, self.nnzb = G.value, K.value, nnzb.value
+
+    @property
+    def handle(self):
+        if self._h is None:
+            raise ValueError("packed weights were freed")
+        return self._h
+
+    @property
+    def on_device(self) -> bool:
+        return load_library().alcs_packed_on_device(self.handle) == 1
+
+    def export(self):
+        """Canonical grouped CSR: (row_ptr [G+1] int32, col_idx [nnzb] int32, vals [nnzb,V] fp32)."""
+        row_ptr = np.zeros(self.G + 1, dtype=np.int32)
+        col_idx = np.zeros(max(self.nnzb, 1), dtype=np.int32)
+        vals = np.zeros((max(self.nnzb, 1), self.V), dtype=np.float32)
+        rc = load_library().alcs_packed_export(self.handle, row_ptr.ctypes.data, col_idx.ctypes.data,
+                                               vals.ctypes.data)
+        if rc != 0:
+            raise AlcsError(rc, "alcs_packed_export")
+        return row_ptr, col_idx[: self.nnzb], vals[: self.nnzb]
+
+    def selfcheck(self) -> int:
+        return int(load_library().alcs_packed_selfcheck(self.handle))
+
+    def free(self):
+        if self._h is not None:
+            load_library().alcs_packed_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def alcs_pack_weights(W: np.ndarray, mask: Optional[np.ndarray], V: int) -> Packed:
+    """W [Cout,Cin,k,k] fp32 host array, mask [G,Cin,k,k] uint8 host array or None."""
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    if W.ndim != 4 or W.shape[2] != W.shape[3]:
+        raise ValueError("W must be [Cout, Cin, k, k]")
+    Cout, Cin, k, _ = W.shape
+    mptr = None
+    if mask is not None:
+        mask = np.ascontiguousarray(mask, dtype=np.uint8)
+        if mask.shape != ((Cout + V - 1) // V, Cin, k, k):
+            raise ValueError("mask must be [ceil(Cout/V), Cin, k, k], got %r" % (mask.shape,))
+        mptr = mask.ctypes.data
+    out = ctypes.c_void_p()
+    rc = load_library().alcs_pack_weights(W.ctypes.data, mptr, Cout, Cin, k, int(V), ctypes.byref(out))
+    if rc != 0:
+        raise AlcsError(rc, "alcs_pack_weights")
+    return Packed(out, Cout, Cin, k, int(V))
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        import torch
+        return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if hasattr(stream, "cuda_stream"):
+        return ctypes.c_void_p(stream.cuda_stream)
+    return ctypes.c_void_p(int(stream))
+
+
+def _dev_ptr(t, name, dtype_name="torch.float32"):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous() or str(t.dtype) != dtype_name:
+        raise ValueError("%s must be a contiguous fp32 tensor on the GPU" % name)
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def alcs_sparse_conv(packed: Packed, X, bias, Y, stride: int = 1, stream=None) -> None:
+    """Y[N,Cout,Ho,Wo] = sparse_conv(packed, X[N,Cin,H,W]) + bias; device tensors, async on stream."""
+    N, Cin, H, W = X.shape
+    k = packed.kernel
+    exp = (N, packed.Cout, out_size(H, k, stride), out_size(W, k, stride))
+    if tuple(Y.shape) != exp:
+        raise ValueError("Y must have shape %r, got %r" % (exp, tuple(Y.shape)))
+    rc = load_library().alcs_sparse_conv(packed.handle, _dev_ptr(X, "X"), _dev_ptr(bias, "bias"),
+                                         _dev_ptr(Y, "Y"), N, Cin, packed.Cout, H, W, k, int(stride),
+                                         _stream_ptr(stream))
+    if rc != 0:
+        raise AlcsError(rc, "alcs_sparse_conv")
+
+
+def alcs_dense_conv(W_dev, X, bias, Y, stride: int = 1, stream=None) -> None:
+    """Dense reference: W_dev [Cout,Cin,k,k] on the device."""
+    Cout, Cin, k, _ = W_dev.shape
+    N, Cin2, H, W = X.shape
+    if Cin != Cin2:
+        raise ValueError("channel mismatch")
+    exp = (N, Cout, out_size(H, k, stride), out_size(W, k, stride))
+    if tuple(Y.shape) != exp:
+        raise ValueError("Y must have shape %r, got %r" % (exp, tuple(Y.shape)))
+    rc = load_library().alcs_dense_conv(_dev_ptr(W_dev, "W"), _dev_ptr(X, "X"), _dev_ptr(bias, "bias"),
+                                        _dev_ptr(Y, "Y"), N, Cin, Cout, H, W, k, int(stride),
+                                        _stream_ptr(stream))
+    if rc != 0:
+        raise AlcsError(rc, "alcs_dense_conv")
+
+
+def alcs_set_tuning(name: str, value: int) -> None:
+    rc = load_library().alcs_set_tuning(name.encode(), int(value))
+    if rc != 0:
+        raise AlcsError(rc, "alcs_set_tuning")
+
+
+def alcs_last_launch() -> dict:
+    buf = (ctypes.c_int * 8)()
+    n = load_library().alcs_last_launch(buf, 8)
+    keys = ["mode", "pv", "waves", "workgroups", "lds_bytes", "group_tiles", "chunk_channels", "path"]
+    return {k: int(buf[i]) for i, k in enumerate(keys[:n])}

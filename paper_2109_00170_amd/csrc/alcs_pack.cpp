@@ -1,0 +1,396 @@
+// Host side of the library: argument checks, the canonical grouped CSR of
+// Section 3.2.2 ("Storage format") of arXiv 2109.00170, the padded and segmented
+// layout the kernels read, its self-check, and the upload to the device.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <numeric>
+
+#include "alcs_internal.h"
+
+namespace alcs {
+
+static thread_local int g_last_hip = 0;
+static thread_local int g_last_launch[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+void set_hip_error(int e) { g_last_hip = e; }
+
+Tuning &tuning() {
+    static Tuning t;
+    return t;
+}
+
+void record_launch(int mode, int pv, int waves, int wgs, int lds, int gtiles, int kc, int path) {
+    int v[8] = {mode, pv, waves, wgs, lds, gtiles, kc, path};
+    std::memcpy(g_last_launch, v, sizeof(v));
+}
+
+static inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+// Channel of a canonical column index.
+static inline int col_channel(int col, int kk) { return col / kk; }
+
+// LDS row selector of a real block (see Layout::off).
+static inline int32_t off_of(int col, int k, int table) {
+    if (k == 1) return col;
+    int c = col / 9, tap = col % 9, r = tap / 3, s = tap % 3;
+    int halo = halo3(table + 1);
+    return c * halo * halo + r * halo + s;
+}
+
+static inline int32_t pad_off(int c0, int KC, int k, int table) {
+    if (k == 1) return c0 + KC;
+    int halo = halo3(table + 1);
+    return (c0 + KC) * halo * halo;
+}
+
+int build_layout(alcs_packed *p, int KC) {
+    Layout &L = p->lay;
+    const int k = p->k, kk = k * k, V = p->V, G = p->G;
+    L = Layout();
+    L.KC = KC;
+    L.nchunks = (p->Cin + KC - 1) / KC;
+    L.planes = V >= 4 ? V / 4 : 1;
+    L.VV = V >= 4 ? 4 : V;
+    L.noff = k == 1 ? 1 : 2;
+    try {
+        L.seg.assign((size_t)G * L.nchunks, Seg{0, 0});
+        // pass 1: segment boundaries
+        int64_t cur = 0;
+        std::vector<int32_t> lo((size_t)G * L.nchunks), hi((size_t)G * L.nchunks);
+        for (int g = 0; g < G; ++g) {
+            int32_t t = p->row_ptr[g], end = p->row_ptr[g + 1];
+            for (int ch = 0; ch < L.nchunks; ++ch) {
+                int c_end = std::min(p->Cin, (ch + 1) * KC);
+                int32_t a = t;
+                while (t < end && col_channel(p->col_idx[t], kk) < c_end) ++t;
+                size_t si = (size_t)g * L.nchunks + ch;
+                lo[si] = a;
+                hi[si] = t;
+                int32_t cntp = (int32_t)round_up(t - a, kCntAlign);
+                if (cur > INT32_MAX - 64) return ALCS_E_UNSUPPORTED;
+                L.seg[si] = Seg{(int32_t)cur, cntp};
+                cur += round_up(cntp, kSegAlign);
+            }
+        }
+        L.nblk = cur + kSegAlign;  // one spare run so that a read-ahead stays inside the arrays
+        L.w.assign((size_t)L.planes * L.nblk * L.VV, 0.0f);
+        for (int tb = 0; tb < L.noff; ++tb) L.off[tb].assign((size_t)L.nblk, 0);
+        // pass 2: fill
+        for (int g = 0; g < G; ++g)
+            for (int ch = 0; ch < L.nchunks; ++ch) {
+                size_t si = (size_t)g * L.nchunks + ch;
+                const Seg s = L.seg[si];
+                const int c0 = ch * KC;
+                const int64_t span = round_up(s.cnt, kSegAlign);
+                for (int64_t j = 0; j < span; ++j) {
+                    const int64_t b = s.start + j;
+                    const bool real = j < hi[si] - lo[si];
+                    for (int tb = 0; tb < L.noff; ++tb)
+                        L.off[tb][b] = real ? off_of(p->col_idx[lo[si] + j], k, tb)
+                                            : pad_off(c0, KC, k, tb);
+                    if (!real) continue;
+                    const float *src = &p->vals[(size_t)(lo[si] + j) * V];
+                    for (int v = 0; v < V; ++v) {
+                        int q = v / 4, i = v % 4;
+                        if (V < 4) { q = 0; i = v; }
+                        L.w[((size_t)q * L.nblk + b) * L.VV + i] = src[v];
+                    }
+                }
+            }
+        // the spare run: zero weights, selector of a zero row that exists in every tile
+        for (int64_t b = cur; b < L.nblk; ++b)
+            for (int tb = 0; tb < L.noff; ++tb) L.off[tb][b] = pad_off(0, KC, k, tb);
+        L.order.resize(G);
+        std::iota(L.order.begin(), L.order.end(), 0);
+        std::stable_sort(L.order.begin(), L.order.end(), [&](int a, int b) {
+            return p->row_ptr[a + 1] - p->row_ptr[a] > p->row_ptr[b + 1] - p->row_ptr[b];
+        });
+    } catch (const std::bad_alloc &) {
+        return ALCS_E_ALLOC;
+    }
+    return ALCS_OK;
+}
+
+static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+void release_device(alcs_packed *p) {
+    if (p->dev.blob) {
+        int cur = -1;
+        if (hipGetDevice(&cur) == hipSuccess && cur != p->dev.device) {
+            (void)hipSetDevice(p->dev.device);
+            (void)hipFree(p->dev.blob);
+            (void)hipSetDevice(cur);
+        } else {
+            (void)hipFree(p->dev.blob);
+        }
+    }
+    p->dev = DeviceCopy();
+}
+
+int upload(alcs_packed *p) {
+    const Layout &L = p->lay;
+    int ndev = 0;
+    hipError_t e = hipGetDeviceCount(&ndev);
+    if (e != hipSuccess || ndev <= 0) {
+        (void)hipGetLastError();
+        return ALCS_E_NO_DEVICE;
+    }
+    int dev = 0;
+    if ((e = hipGetDevice(&dev)) != hipSuccess) { set_hip_error((int)e); return ALCS_E_HIP; }
+    const size_t b_seg = L.seg.size() * sizeof(Seg);
+    const size_t b_w = L.w.size() * sizeof(float);
+    const size_t b_off = (size_t)L.nblk * sizeof(int32_t);
+    const size_t b_ord = L.order.size() * sizeof(int32_t);
+    size_t o_seg = 0, o_w = align256(o_seg + b_seg), o_off0 = align256(o_w + b_w);
+    size_t o_off1 = align256(o_off0 + b_off);
+    size_t o_ord = L.noff == 2 ? align256(o_off1 + b_off) : o_off1;
+    size_t total = align256(o_ord + b_ord) + 256;
+    void *blob = nullptr;
+    if ((e = hipMalloc(&blob, total)) != hipSuccess) {
+        set_hip_error((int)e);
+        (void)hipGetLastError();
+        return e == hipErrorOutOfMemory ? ALCS_E_ALLOC : ALCS_E_HIP;
+    }
+    char *base = (char *)blob;
+    auto put = [&](size_t o, const void *src, size_t n) -> hipError_t {
+        return n ? hipMemcpy(base + o, src, n, hipMemcpyHostToDevice) : hipSuccess;
+    };
+    e = put(o_seg, L.seg.data(), b_seg);
+    if (e == hipSuccess) e = put(o_w, L.w.data(), b_w);
+    if (e == hipSuccess) e = put(o_off0, L.off[0].data(), b_off);
+    if (e == hipSuccess && L.noff == 2) e = put(o_off1, L.off[1].data(), b_off);
+    if (e == hipSuccess) e = put(o_ord, L.order.data(), b_ord);
+    if (e != hipSuccess) {
+        set_hip_error((int)e);
+        (void)hipFree(blob);
+        return ALCS_E_HIP;
+    }
+    p->dev.device = dev;
+    p->dev.blob = blob;
+    p->dev.bytes = total;
+    p->dev.seg = (const Seg *)(base + o_seg);
+    p->dev.w = (const float *)(base + o_w);
+    p->dev.off[0] = (const int32_t *)(base + o_off0);
+    p->dev.off[1] = L.noff == 2 ? (const int32_t *)(base + o_off1) : nullptr;
+    p->dev.order = (const int32_t *)(base + o_ord);
+    return ALCS_OK;
+}
+
+// Chunk size policy.  Kernel 1: all input channels in one LDS tile while a 64-pixel
+// tile of Cin+1 rows fits comfortably; above that, chunks of 256 channels.
+// Kernel 3: 32 channels per chunk (the haloed tile is 100 or 289 floats per channel).
+static int default_kc(int Cin, int k) {
+    if (k == 1) return Cin <= 512 ? Cin : 256;
+    return std::min(Cin, 32);
+}
+
+}  // namespace alcs
+
+using namespace alcs;
+
+extern "C" {
+
+const char *alcs_strerror(int status) {
+    switch (status) {
+        case ALCS_OK: return "ALCS_OK";
+        case ALCS_E_INVALID_ARG: return "ALCS_E_INVALID_ARG: bad pointer, size or shape";
+        case ALCS_E_UNSUPPORTED: return "ALCS_E_UNSUPPORTED: kernel/V/stride/size outside the supported set";
+        case ALCS_E_ALLOC: return "ALCS_E_ALLOC: allocation failed";
+        case ALCS_E_HIP: return "ALCS_E_HIP: HIP runtime call failed";
+        case ALCS_E_NO_DEVICE: return "ALCS_E_NO_DEVICE: handle has no device copy";
+        default: return "ALCS: unknown status";
+    }
+}
+
+int alcs_last_hip_error(void) { return g_last_hip; }
+
+int alcs_version(void) { return 100; }
+
+int alcs_pack_weights(const float *W_host, const uint8_t *mask_host, int Cout, int Cin, int kernel,
+                      int V, alcs_packed_t **out) {
+    if (out) *out = nullptr;
+    if (!W_host || !out || Cout <= 0 || Cin <= 0) return ALCS_E_INVALID_ARG;
+    if (kernel != 1 && kernel != 3) return ALCS_E_UNSUPPORTED;
+    if (V != 1 && V != 2 && V != 4 && V != 8 && V != 16) return ALCS_E_UNSUPPORTED;
+    const int64_t K64 = (int64_t)Cin * kernel * kernel;
+    if (K64 > (1 << 24) || Cout > (1 << 24)) return ALCS_E_UNSUPPORTED;
+    const int K = (int)K64, G = (Cout + V - 1) / V;
+    if ((int64_t)G * K > (int64_t)INT32_MAX - 1024) return ALCS_E_UNSUPPORTED;
+    alcs_packed *p = new (std::nothrow) alcs_packed();
+    if (!p) return ALCS_E_ALLOC;
+    p->Cout = Cout; p->Cin = Cin; p->k = kernel; p->V = V; p->G = G; p->K = K;
+    int rc = ALCS_OK;
+    try {
+        // canonical grouped CSR: per group, ascending column, one V-vector per kept column
+        p->row_ptr.assign((size_t)G + 1, 0);
+        int64_t nnzb = 0;
+        if (mask_host) {
+            for (int g = 0; g < G; ++g) {
+                const uint8_t *m = mask_host + (size_t)g * K;
+                int64_t c = 0;
+                for (int col = 0; col < K; ++col) c += m[col] != 0;
+                nnzb += c;
+                p->row_ptr[g + 1] = (int32_t)nnzb;
+            }
+        } else {
+            for (int g = 0; g < G; ++g) p->row_ptr[g + 1] = (int32_t)((int64_t)(g + 1) * K);
+            nnzb = (int64_t)G * K;
+        }
+        p->nnzb = nnzb;
+        p->col_idx.resize((size_t)nnzb);
+        p->vals.resize((size_t)nnzb * V);
+        for (int g = 0; g < G; ++g) {
+            const uint8_t *m = mask_host ? mask_host + (size_t)g * K : nullptr;
+            int64_t t = p->row_ptr[g];
+            for (int col = 0; col < K; ++col) {
+                if (m && !m[col]) continue;
+                p->col_idx[(size_t)t] = col;
+                for (int v = 0; v < V; ++v) {
+                    const int o = g * V + v;
+                    float x = 0.0f;
+                    if (o < Cout) std::memcpy(&x, &W_host[(size_t)o * K + col], sizeof(float));
+                    std::memcpy(&p->vals[(size_t)t * V + v], &x, sizeof(float));
+                }
+                ++t;
+            }
+            p->max_count = std::max(p->max_count, p->row_ptr[g + 1] - p->row_ptr[g]);
+        }
+    } catch (const std::bad_alloc &) {
+        rc = ALCS_E_ALLOC;
+    }
+    if (rc == ALCS_OK) {
+        int KC = tuning().kc > 0 ? std::min(tuning().kc, Cin) : default_kc(Cin, kernel);
+        rc = build_layout(p, KC);
+    }
+    if (rc == ALCS_OK) {
+        rc = upload(p);
+        if (rc == ALCS_E_NO_DEVICE) rc = ALCS_OK;  // host-only handle
+    }
+    if (rc != ALCS_OK) {
+        alcs_packed_free(p);
+        return rc;
+    }
+    *out = p;
+    return ALCS_OK;
+}
+
+int alcs_packed_info(const alcs_packed_t *p, int *G, int *K, int64_t *nnzb) {
+    if (!p) return ALCS_E_INVALID_ARG;
+    if (G) *G = p->G;
+    if (K) *K = p->K;
+    if (nnzb) *nnzb = p->nnzb;
+    return ALCS_OK;
+}
+
+int alcs_packed_on_device(const alcs_packed_t *p) {
+    if (!p) return ALCS_E_INVALID_ARG;
+    return p->dev.blob ? 1 : 0;
+}
+
+int alcs_packed_export(const alcs_packed_t *p, int32_t *row_ptr_host, int32_t *col_idx_host,
+                       float *vals_host) {
+    if (!p || !row_ptr_host) return ALCS_E_INVALID_ARG;
+    if (p->nnzb > 0 && (!col_idx_host || !vals_host)) return ALCS_E_INVALID_ARG;
+    std::memcpy(row_ptr_host, p->row_ptr.data(), p->row_ptr.size() * sizeof(int32_t));
+    if (p->nnzb > 0) {
+        std::memcpy(col_idx_host, p->col_idx.data(), p->col_idx.size() * sizeof(int32_t));
+        std::memcpy(vals_host, p->vals.data(), p->vals.size() * sizeof(float));
+    }
+    return ALCS_OK;
+}
+
+int alcs_packed_selfcheck(const alcs_packed_t *p) {
+    if (!p) return ALCS_E_INVALID_ARG;
+    const Layout &L = p->lay;
+    const int k = p->k, V = p->V;
+    if (L.KC <= 0 || L.nchunks != (p->Cin + L.KC - 1) / L.KC) return ALCS_E_INVALID_ARG;
+    if ((int)L.seg.size() != p->G * L.nchunks || (int)L.order.size() != p->G) return ALCS_E_INVALID_ARG;
+    std::vector<char> seen((size_t)p->G, 0);
+    for (int i = 0; i < p->G; ++i) {
+        int g = L.order[i];
+        if (g < 0 || g >= p->G || seen[g]) return ALCS_E_INVALID_ARG;
+        seen[g] = 1;
+        if (i > 0) {
+            int a = L.order[i - 1];
+            if (p->row_ptr[a + 1] - p->row_ptr[a] < p->row_ptr[g + 1] - p->row_ptr[g]) return ALCS_E_INVALID_ARG;
+        }
+    }
+    const uint32_t zero_bits = 0;
+    for (int g = 0; g < p->G; ++g) {
+        int64_t t = p->row_ptr[g];
+        for (int ch = 0; ch < L.nchunks; ++ch) {
+            const Seg s = L.seg[(size_t)g * L.nchunks + ch];
+            if (s.start % kSegAlign || s.cnt % kCntAlign || s.cnt < 0) return ALCS_E_INVALID_ARG;
+            const int c0 = ch * L.KC, c1 = std::min(p->Cin, c0 + L.KC);
+            const int64_t span = round_up(s.cnt, kSegAlign);
+            if (s.start + span > L.nblk) return ALCS_E_INVALID_ARG;
+            bool in_pad = false;
+            int64_t nreal = 0;
+            for (int64_t j = 0; j < span; ++j) {
+                const int64_t b = s.start + j;
+                const bool is_pad = L.off[0][b] == pad_off(c0, L.KC, k, 0);
+                if (in_pad && !is_pad) return ALCS_E_INVALID_ARG;  // real blocks come first
+                in_pad = is_pad;
+                if (is_pad) {
+                    for (int tb = 1; tb < L.noff; ++tb)
+                        if (L.off[tb][b] != pad_off(c0, L.KC, k, tb)) return ALCS_E_INVALID_ARG;
+                    for (int q = 0; q < L.planes; ++q)
+                        for (int i = 0; i < L.VV; ++i)
+                            if (std::memcmp(&L.w[((size_t)q * L.nblk + b) * L.VV + i], &zero_bits, 4))
+                                return ALCS_E_INVALID_ARG;
+                    continue;
+                }
+                // a real block: must be the next canonical column of this group, inside the
+                // chunk's channel range (so that its LDS row exists), and within the padded count
+                if (j >= s.cnt || t >= p->row_ptr[g + 1]) return ALCS_E_INVALID_ARG;
+                const int col = p->col_idx[(size_t)t];
+                const int c = col_channel(col, k * k);
+                if (c < c0 || c >= c1) return ALCS_E_INVALID_ARG;
+                for (int tb = 0; tb < L.noff; ++tb)
+                    if (L.off[tb][b] != off_of(col, k, tb)) return ALCS_E_INVALID_ARG;
+                for (int v = 0; v < V; ++v) {
+                    int q = V < 4 ? 0 : v / 4, i = V < 4 ? v : v % 4;
+                    if (std::memcmp(&L.w[((size_t)q * L.nblk + b) * L.VV + i],
+                                    &p->vals[(size_t)t * V + v], 4))
+                        return ALCS_E_INVALID_ARG;
+                }
+                ++t;
+                ++nreal;
+            }
+            if (round_up(nreal, kCntAlign) != s.cnt) return ALCS_E_INVALID_ARG;
+        }
+        if (t != p->row_ptr[g + 1]) return ALCS_E_INVALID_ARG;  // every canonical block was found
+    }
+    return ALCS_OK;
+}
+
+void alcs_packed_free(alcs_packed_t *p) {
+    if (!p) return;
+    release_device(p);
+    delete p;
+}
+
+int alcs_set_tuning(const char *name, int value) {
+    if (!name) return ALCS_E_INVALID_ARG;
+    Tuning &t = tuning();
+    if (!std::strcmp(name, "pv")) t.pv = value;
+    else if (!std::strcmp(name, "waves")) t.waves = value;
+    else if (!std::strcmp(name, "group_tiles")) t.group_tiles = value;
+    else if (!std::strcmp(name, "path")) t.path = value;
+    else if (!std::strcmp(name, "chunk_channels")) t.kc = value;
+    else if (!std::strcmp(name, "groups_per_wave")) t.ug = value;
+    else return ALCS_E_INVALID_ARG;
+    return ALCS_OK;
+}
+
+int alcs_last_launch(int *out, int cap) {
+    if (!out || cap <= 0) return 0;
+    int n = cap < 8 ? cap : 8;
+    std::memcpy(out, g_last_launch, n * sizeof(int));
+    return n;
+}
+
+}  // extern "C"

@@ -1,0 +1,657 @@
+// HIP kernels (gfx950) and launcher of alcs_sparse_conv: the sparse x dense
+// multiplication of Section 3.2.2 ("Efficient multiplication computation") of
+// arXiv 2109.00170, re-designed for 64-lane wavefronts.
+//
+// Mapping.  The paper puts the V output channels of a group into one SIMD register
+// and broadcasts an input scalar.  Here the 64 lanes of a wavefront are 64 output
+// pixels (contiguous in NCHW, so global and LDS accesses are coalesced), the V
+// channels of the group are V accumulator registers per lane, and the weight block
+// of a kept column is wave-uniform.  A workgroup stages the input rows of a pixel
+// tile in LDS once; its wavefronts then walk the kept columns of their groups: one
+// LDS row read per kept column, selected by the column's offset, feeds V
+// multiply-accumulates per pixel - the same reuse the paper gets from its V-wide
+// register.
+//
+// For V in {4, 8, 16} the multiply-accumulate is v_mfma_f32_4x4x1_16B_f32: each of
+// its 16 blocks is a 4(channel) x 4(pixel) outer product, and with the block
+// broadcast modifier (cbsz = 4, abid = j) all 16 blocks take their 4 weights from
+// block j of the A register.  One coalesced 256-byte load therefore brings the
+// weights of 16 consecutive kept columns, and every flop the instruction performs is
+// a useful one (nothing is densified).  For V in {1, 2} (and optionally 4) plain
+// v_fma_f32 with scalar-register weights is used.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdint>
+#include <mutex>
+#include <set>
+
+#include "alcs_internal.h"
+
+namespace alcs {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef float f2 __attribute__((ext_vector_type(2)));
+typedef int i4 __attribute__((ext_vector_type(4)));
+
+struct ConvArgs {
+    const float *X;
+    const float *bias;
+    float *Y;
+    const Seg *seg;
+    const float *w;
+    const int32_t *off;
+    const int32_t *order;
+    long long wplane;   // floats between weight planes (nblk * VV)
+    int N, Cin, Cout, H, W, Ho, Wo, stride;
+    int P, Pin;         // Ho*Wo, H*W
+    int NP;             // N * P, flattened output pixels (< 2^31)
+    int G, nchunks, KC;
+    int npt, ngt, gpt;  // pixel tiles, group tiles, groups per group tile
+    int tiles_x, tiles_y;  // 3x3: 8x8 tiles per image
+    int wg_per_xcd, total_wgs;
+};
+
+constexpr int kXcds = 8;
+
+// Index arrays, segment table, bias and (for the FMA form) the weights are read
+// through the constant address space: the addresses are wave-uniform, and this lets
+// the compiler fetch them with scalar loads into SGPRs even though the kernel also
+// stores to global memory (Y never aliases them).
+template <class T>
+using cptr = const T __attribute__((address_space(4))) *;
+template <class T>
+__device__ __forceinline__ cptr<T> as_const(const T *p) {
+    return (cptr<T>)(uintptr_t)p;
+}
+
+typedef int i2 __attribute__((ext_vector_type(2)));
+static_assert(sizeof(Seg) == 8, "Seg is read as two ints");
+__device__ __forceinline__ Seg load_seg(const Seg *table, size_t idx) {
+    const i2 v = *reinterpret_cast<cptr<i2>>((uintptr_t)(table + idx));
+    return Seg{__builtin_amdgcn_readfirstlane(v[0]), __builtin_amdgcn_readfirstlane(v[1])};
+}
+
+// Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Renumber
+// so that consecutive logical ids - which share a pixel tile and differ only in the
+// group tile - land on the same XCD and find the tile's input rows in that L2.
+__device__ __forceinline__ int logical_wg(const ConvArgs &a) {
+    const int id = blockIdx.x;
+    return (id % kXcds) * a.wg_per_xcd + id / kXcds;
+}
+
+// ------------------------------------------------------------------ accumulators
+
+template <int V, int PV, bool MF>
+struct Acc;
+
+template <int V, int PV>
+struct Acc<V, PV, true> {  // MFMA: a[q][pv][i] = channel 4q+i, pixel pv of the lane
+    f4 a[V / 4][PV];
+    __device__ __forceinline__ void zero() {
+#pragma unroll
+        for (int q = 0; q < V / 4; ++q)
+#pragma unroll
+            for (int pv = 0; pv < PV; ++pv) a[q][pv] = f4{0.f, 0.f, 0.f, 0.f};
+    }
+    __device__ __forceinline__ float get(int v, int pv) const { return a[v >> 2][pv][v & 3]; }
+};
+
+template <int V, int PV>
+struct Acc<V, PV, false> {
+    float a[V][PV];
+    __device__ __forceinline__ void zero() {
+#pragma unroll
+        for (int v = 0; v < V; ++v)
+#pragma unroll
+            for (int pv = 0; pv < PV; ++pv) a[v][pv] = 0.f;
+    }
+    __device__ __forceinline__ float get(int v, int pv) const { return a[v][pv]; }
+};
+
+template <int PV>
+__device__ __forceinline__ void lds_read(const float *p, float (&x)[PV]) {
+    if constexpr (PV == 4) {
+        f4 t = *reinterpret_cast<const f4 *>(p);
+        x[0] = t[0]; x[1] = t[1]; x[2] = t[2]; x[3] = t[3];
+    } else if constexpr (PV == 2) {
+        f2 t = *reinterpret_cast<const f2 *>(p);
+        x[0] = t[0]; x[1] = t[1];
+    } else {
+        x[0] = *p;
+    }
+}
+
+// One kept column, MFMA form: all 16 blocks take their 4 weights from block ABID of
+// the weight register (cbsz = 4), the other operand is the lane's pixel value(s).
+template <int ABID, int V, int PV>
+__device__ __forceinline__ void mfma_column(const float (&aw)[V / 4], const float *xp,
+                                            Acc<V, PV, true> &acc) {
+    float x[PV];
+    lds_read<PV>(xp, x);
+#pragma unroll
+    for (int q = 0; q < V / 4; ++q)
+#pragma unroll
+        for (int pv = 0; pv < PV; ++pv)
+            acc.a[q][pv] = __builtin_amdgcn_mfma_f32_4x4x1f32(aw[q], x[pv], acc.a[q][pv], 4, ABID, 0);
+}
+
+// Columns JJ .. JJ+3 of the current run of 16.  The run's 16 row selectors sit in
+// lanes 0..15 of `ov`; v_readlane moves the one that is needed into an SGPR, so the
+// LDS address costs one v_lshl_add per column and no scalar-memory wait.
+template <int JJ, int V, int PV, int SH>
+__device__ __forceinline__ void mfma_quad(const float (&aw)[V / 4], int ov, const float *lds,
+                                          int base, Acc<V, PV, true> &acc) {
+    mfma_column<JJ + 0, V, PV>(aw, lds + base + (__builtin_amdgcn_readlane(ov, JJ + 0) << SH), acc);
+    mfma_column<JJ + 1, V, PV>(aw, lds + base + (__builtin_amdgcn_readlane(ov, JJ + 1) << SH), acc);
+    mfma_column<JJ + 2, V, PV>(aw, lds + base + (__builtin_amdgcn_readlane(ov, JJ + 2) << SH), acc);
+    mfma_column<JJ + 3, V, PV>(aw, lds + base + (__builtin_amdgcn_readlane(ov, JJ + 3) << SH), acc);
+}
+
+// One segment (the kept columns of one group inside one channel chunk), MFMA form.
+// start/cnt are wave-uniform; base is the lane's float index inside an LDS row
+// (minus the chunk's first row); SH = log2(row length) for 1x1, 0 for 3x3 where the
+// stored selector is already a float index.  Weights and selectors of the next run
+// of 16 columns are fetched (two coalesced vector loads) while the current run is
+// being multiplied.
+template <int V, int PV, int SH>
+__device__ __forceinline__ void mac_segment(const ConvArgs &a, int start, int cnt,
+                                            const float *lds, int base, int lane,
+                                            Acc<V, PV, true> &acc) {
+    constexpr int Q = V / 4;
+    if (cnt <= 0) return;
+    const float *wp = a.w + (size_t)start * 4 + lane;
+    const int32_t *op = a.off + start + (lane & 15);
+    float a_nxt[Q];
+#pragma unroll
+    for (int q = 0; q < Q; ++q) a_nxt[q] = wp[(size_t)q * a.wplane];
+    int o_nxt = op[0];
+    for (int j0 = 0; j0 < cnt; j0 += 16) {
+        float aw[Q];
+#pragma unroll
+        for (int q = 0; q < Q; ++q) aw[q] = a_nxt[q];
+        const int ov = o_nxt;
+        if (j0 + 16 < cnt) {
+#pragma unroll
+            for (int q = 0; q < Q; ++q) a_nxt[q] = wp[(size_t)q * a.wplane + (size_t)(j0 + 16) * 4];
+            o_nxt = op[j0 + 16];
+        }
+        mfma_quad<0, V, PV, SH>(aw, ov, lds, base, acc);
+        if (j0 + 4 < cnt) mfma_quad<4, V, PV, SH>(aw, ov, lds, base, acc);
+        if (j0 + 8 < cnt) mfma_quad<8, V, PV, SH>(aw, ov, lds, base, acc);
+        if (j0 + 12 < cnt) mfma_quad<12, V, PV, SH>(aw, ov, lds, base, acc);
+    }
+}
+
+// Same segment with plain FMAs; the V weights of a column come from scalar loads.
+template <int V, int PV, int SH>
+__device__ __forceinline__ void mac_segment(const ConvArgs &a, int start, int cnt,
+                                            const float *lds, int base, int lane,
+                                            Acc<V, PV, false> &acc) {
+    static_assert(V <= 4, "FMA path is built for V <= 4");
+    (void)lane;
+    cptr<float> wp = as_const(a.w) + (size_t)start * V;
+    cptr<int32_t> op = as_const(a.off) + start;
+    for (int j = 0; j < cnt; j += 4) {
+        const i4 o = *reinterpret_cast<cptr<i4>>(op + j);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            float x[PV];
+            lds_read<PV>(lds + base + (o[u] << SH), x);
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                const float wv = wp[(j + u) * V + v];
+#pragma unroll
+                for (int pv = 0; pv < PV; ++pv) acc.a[v][pv] = __builtin_fmaf(wv, x[pv], acc.a[v][pv]);
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------ 1x1: staging
+
+// Rows [c0, c1) of the pixel tile [q0, q0 + TP) of the flattened (n, pixel) axis into
+// LDS rows 0.. (row length TP).  VEC: stride 1 and P % 4 == 0, so four consecutive
+// pixels never straddle an image and are 16-byte aligned.
+template <int TP, bool VEC>
+__device__ __forceinline__ void stage_pw(const ConvArgs &a, float *lds, int q0, int c0, int c1) {
+    const int tid = threadIdx.x, nt = blockDim.x;
+    if constexpr (VEC) {
+        constexpr int NQ = TP / 4;
+        const int quad = tid % NQ, r0 = tid / NQ, rpp = nt / NQ;
+        const int q = q0 + quad * 4;
+        const bool valid = q < a.NP;
+        const int n = valid ? q / a.P : 0;
+        const int p = valid ? q - n * a.P : 0;
+        const float *src = a.X + ((size_t)n * a.Cin + c0) * a.P + p;
+        float *dst = lds + quad * 4;
+        const int rows = c1 - c0;
+        int r = r0;
+        for (; r + 3 * rpp < rows; r += 4 * rpp) {
+            f4 v0 = f4{0, 0, 0, 0}, v1 = v0, v2 = v0, v3 = v0;
+            if (valid) {
+                v0 = *reinterpret_cast<const f4 *>(src + (size_t)r * a.P);
+                v1 = *reinterpret_cast<const f4 *>(src + (size_t)(r + rpp) * a.P);
+                v2 = *reinterpret_cast<const f4 *>(src + (size_t)(r + 2 * rpp) * a.P);
+                v3 = *reinterpret_cast<const f4 *>(src + (size_t)(r + 3 * rpp) * a.P);
+            }
+            *reinterpret_cast<f4 *>(dst + r * TP) = v0;
+            *reinterpret_cast<f4 *>(dst + (r + rpp) * TP) = v1;
+            *reinterpret_cast<f4 *>(dst + (r + 2 * rpp) * TP) = v2;
+            *reinterpret_cast<f4 *>(dst + (r + 3 * rpp) * TP) = v3;
+        }
+        for (; r < rows; r += rpp) {
+            f4 v0 = f4{0, 0, 0, 0};
+            if (valid) v0 = *reinterpret_cast<const f4 *>(src + (size_t)r * a.P);
+            *reinterpret_cast<f4 *>(dst + r * TP) = v0;
+        }
+    } else {
+        const int e = tid % TP, r0 = tid / TP, rpp = nt / TP;
+        const int q = q0 + e;
+        const bool valid = q < a.NP;
+        const int n = valid ? q / a.P : 0;
+        const int po = valid ? q - n * a.P : 0;
+        const int ho = po / a.Wo, wo = po - ho * a.Wo;
+        const float *src = a.X + ((size_t)n * a.Cin + c0) * a.Pin + (size_t)(ho * a.stride) * a.W + wo * a.stride;
+        const int rows = c1 - c0;
+        int r = r0;
+        for (; r + 3 * rpp < rows; r += 4 * rpp) {
+            float v0 = 0, v1 = 0, v2 = 0, v3 = 0;
+            if (valid) {
+                v0 = src[(size_t)r * a.Pin];
+                v1 = src[(size_t)(r + rpp) * a.Pin];
+                v2 = src[(size_t)(r + 2 * rpp) * a.Pin];
+                v3 = src[(size_t)(r + 3 * rpp) * a.Pin];
+            }
+            lds[r * TP + e] = v0;
+            lds[(r + rpp) * TP + e] = v1;
+            lds[(r + 2 * rpp) * TP + e] = v2;
+            lds[(r + 3 * rpp) * TP + e] = v3;
+        }
+        for (; r < rows; r += rpp) lds[r * TP + e] = valid ? src[(size_t)r * a.Pin] : 0.f;
+    }
+}
+
+// Where a lane's PV pixels go in Y (offset of channel 0; add ch * P).
+template <int PV>
+struct PixOut {
+    long long yoff[PV];
+    bool valid[PV];
+};
+
+template <int PV, bool VEC>
+__device__ __forceinline__ void pix_out(const ConvArgs &a, int q0, int lane, PixOut<PV> &px) {
+#pragma unroll
+    for (int pv = 0; pv < PV; ++pv) {
+        const int q = q0 + lane * PV + pv;
+        px.valid[pv] = q < a.NP;
+        if (VEC && pv > 0) {
+            px.yoff[pv] = px.yoff[0] + pv;
+        } else {
+            const int n = px.valid[pv] ? q / a.P : 0;
+            const int p = px.valid[pv] ? q - n * a.P : 0;
+            px.yoff[pv] = (long long)n * a.Cout * a.P + p;
+        }
+    }
+}
+
+// Epilogue: Y = acc + bias for the V channels of group g (rows beyond Cout of a
+// ragged last group are not stored).
+template <int V, int PV, bool MF, bool VEC>
+__device__ __forceinline__ void store_group(const ConvArgs &a, const Acc<V, PV, MF> &acc, int g,
+                                            const PixOut<PV> &px) {
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        const int ch = g * V + v;
+        if (ch >= a.Cout) break;
+        const float b = a.bias ? as_const(a.bias)[ch] : 0.f;
+        float *dst = a.Y + (size_t)ch * a.P;
+        if constexpr (VEC && PV == 4) {
+            if (px.valid[0])
+                *reinterpret_cast<f4 *>(dst + px.yoff[0]) =
+                    f4{acc.get(v, 0) + b, acc.get(v, 1) + b, acc.get(v, 2) + b, acc.get(v, 3) + b};
+        } else if constexpr (VEC && PV == 2) {
+            if (px.valid[0]) *reinterpret_cast<f2 *>(dst + px.yoff[0]) = f2{acc.get(v, 0) + b, acc.get(v, 1) + b};
+        } else {
+#pragma unroll
+            for (int pv = 0; pv < PV; ++pv)
+                if (px.valid[pv]) dst[px.yoff[pv]] = acc.get(v, pv) + b;
+        }
+    }
+}
+
+// ------------------------------------------------------------------ 1x1 kernels
+
+// Mode 1: all input channels of the pixel tile are resident in LDS (one chunk); each
+// wavefront walks through the groups of the workgroup's group tile, longest first.
+template <int V, int PV, bool MF, bool VEC>
+__global__ void __launch_bounds__(1024) k_pw_resident(const ConvArgs a) {
+    extern __shared__ float lds[];
+    constexpr int TP = 64 * PV;
+    constexpr int SH = 6 + (PV == 4 ? 2 : PV == 2 ? 1 : 0);
+    const int logical = logical_wg(a);
+    if (logical >= a.total_wgs) return;
+    const int pt = logical / a.ngt, gt = logical - pt * a.ngt;
+    const int q0 = pt * TP;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), nw = blockDim.x >> 6;
+
+    stage_pw<TP, VEC>(a, lds, q0, 0, a.Cin);
+    for (int t = tid; t < TP; t += blockDim.x) lds[a.KC * TP + t] = 0.f;  // the all-zero row
+    __syncthreads();
+
+    PixOut<PV> px;
+    pix_out<PV, VEC>(a, q0, lane, px);
+    const int g_begin = gt * a.gpt;
+    const int ng = min(a.G, g_begin + a.gpt) - g_begin;
+    for (int r = 0; r * nw < ng; ++r) {
+        const int idx = r * nw + ((r & 1) ? nw - 1 - wave : wave);  // snake order evens the load
+        if (idx >= ng) continue;
+        const int g = __builtin_amdgcn_readfirstlane(as_const(a.order)[g_begin + idx]);
+        const Seg s = load_seg(a.seg, g);
+        Acc<V, PV, MF> acc;
+        acc.zero();
+        mac_segment<V, PV, SH>(a, s.start, s.cnt, lds, lane * PV, lane, acc);
+        store_group<V, PV, MF, VEC>(a, acc, g, px);
+    }
+}
+
+// Mode 2: input channels streamed through LDS in chunks of KC; every wavefront owns
+// UG groups for the whole kernel and keeps their accumulators in registers.
+template <int V, int PV, int UG, bool MF, bool VEC>
+__global__ void __launch_bounds__(512) k_pw_chunked(const ConvArgs a) {
+    extern __shared__ float lds[];
+    constexpr int TP = 64 * PV;
+    constexpr int SH = 6 + (PV == 4 ? 2 : PV == 2 ? 1 : 0);
+    const int logical = logical_wg(a);
+    if (logical >= a.total_wgs) return;
+    const int pt = logical / a.ngt, gt = logical - pt * a.ngt;
+    const int q0 = pt * TP;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g_begin = gt * a.gpt;
+    const int ng = min(a.G, g_begin + a.gpt) - g_begin;
+
+    int gid[UG];
+    Acc<V, PV, MF> acc[UG];
+#pragma unroll
+    for (int u = 0; u < UG; ++u) {
+        const int idx = wave * UG + u;
+        gid[u] = idx < ng ? __builtin_amdgcn_readfirstlane(as_const(a.order)[g_begin + idx]) : -1;
+        acc[u].zero();
+    }
+    for (int t = tid; t < TP; t += blockDim.x) lds[a.KC * TP + t] = 0.f;
+    for (int ch = 0; ch < a.nchunks; ++ch) {
+        const int c0 = ch * a.KC, c1 = min(a.Cin, c0 + a.KC);
+        if (ch) __syncthreads();
+        stage_pw<TP, VEC>(a, lds, q0, c0, c1);
+        __syncthreads();
+        const int base = lane * PV - (c0 << SH);
+#pragma unroll
+        for (int u = 0; u < UG; ++u) {
+            if (gid[u] < 0) continue;
+            const Seg s = load_seg(a.seg, (size_t)gid[u] * a.nchunks + ch);
+            mac_segment<V, PV, SH>(a, s.start, s.cnt, lds, base, lane, acc[u]);
+        }
+    }
+    PixOut<PV> px;
+    pix_out<PV, VEC>(a, q0, lane, px);
+#pragma unroll
+    for (int u = 0; u < UG; ++u)
+        if (gid[u] >= 0) store_group<V, PV, MF, VEC>(a, acc[u], gid[u], px);
+}
+
+// ------------------------------------------------------------------ 3x3 kernel
+
+// One workgroup = one 8x8 tile of output pixels of one image (lane = pixel) and a
+// tile of groups; input channels are streamed in chunks of KC with their halo
+// ((8-1)*stride+3 squared floats per channel).  The selector stored with every kept
+// column is c*HA + r*halo + s, so the tap shift costs nothing at run time.
+template <int V, int STRIDE, int UG, bool MF>
+__global__ void __launch_bounds__(512) k_conv3(const ConvArgs a) {
+    extern __shared__ float lds[];
+    constexpr int HALO = (kTile3 - 1) * STRIDE + 3;
+    constexpr int HA = HALO * HALO;
+    const int logical = logical_wg(a);
+    if (logical >= a.total_wgs) return;
+    const int pt = logical / a.ngt, gt = logical - pt * a.ngt;
+    const int tiles_per_img = a.tiles_x * a.tiles_y;
+    const int n = pt / tiles_per_img, trem = pt - n * tiles_per_img;
+    const int tyi = trem / a.tiles_x, txi = trem - tyi * a.tiles_x;
+    const int oy0 = tyi * kTile3, ox0 = txi * kTile3;
+    const int iy0 = oy0 * STRIDE - 1, ix0 = ox0 * STRIDE - 1;
+    const int tid = threadIdx.x, lane = tid & 63, nt = blockDim.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g_begin = gt * a.gpt;
+    const int ng = min(a.G, g_begin + a.gpt) - g_begin;
+
+    int gid[UG];
+    Acc<V, 1, MF> acc[UG];
+#pragma unroll
+    for (int u = 0; u < UG; ++u) {
+        const int idx = wave * UG + u;
+        gid[u] = idx < ng ? __builtin_amdgcn_readfirstlane(as_const(a.order)[g_begin + idx]) : -1;
+        acc[u].zero();
+    }
+    for (int t = tid; t < HA; t += nt) lds[a.KC * HA + t] = 0.f;
+
+    // staging: a thread keeps one halo position and walks over channels
+    const int rpp = nt / HA > 0 ? nt / HA : 1;  // channel rows per pass (nt >= HA is guaranteed by the launcher for stride 1)
+    const int pos = tid % HA, r0 = tid / HA;
+    const int hy = pos / HALO, hx = pos - hy * HALO;
+    const int iy = iy0 + hy, ix = ix0 + hx;
+    const bool inb = iy >= 0 && iy < a.H && ix >= 0 && ix < a.W;
+    const float *src = a.X + (size_t)n * a.Cin * a.Pin + (inb ? (size_t)iy * a.W + ix : 0);
+
+    const int ly = lane >> 3, lx = lane & 7;
+    const int lane_base = (ly * STRIDE) * HALO + lx * STRIDE;
+    for (int ch = 0; ch < a.nchunks; ++ch) {
+        const int c0 = ch * a.KC, c1 = min(a.Cin, c0 + a.KC);
+        if (ch) __syncthreads();
+        if (nt >= HA) {
+            if (r0 < rpp)
+                for (int r = r0; r < c1 - c0; r += rpp)
+                    lds[r * HA + pos] = inb ? src[(size_t)(c0 + r) * a.Pin] : 0.f;
+        } else {
+            // fewer threads than halo positions: loop over positions as well
+            for (int e = tid; e < (c1 - c0) * HA; e += nt) {
+                const int r = e / HA, ps = e - r * HA;
+                const int y = ps / HALO, x = ps - y * HALO;
+                const int yy = iy0 + y, xx = ix0 + x;
+                float v = 0.f;
+                if (yy >= 0 && yy < a.H && xx >= 0 && xx < a.W)
+                    v = a.X[((size_t)n * a.Cin + c0 + r) * a.Pin + (size_t)yy * a.W + xx];
+                lds[e] = v;
+            }
+        }
+        __syncthreads();
+        const int base = lane_base - c0 * HA;
+#pragma unroll
+        for (int u = 0; u < UG; ++u) {
+            if (gid[u] < 0) continue;
+            const Seg s = load_seg(a.seg, (size_t)gid[u] * a.nchunks + ch);
+            mac_segment<V, 1, 0>(a, s.start, s.cnt, lds, base, lane, acc[u]);
+        }
+    }
+    const int oy = oy0 + ly, ox = ox0 + lx;
+    PixOut<1> px;
+    px.valid[0] = oy < a.Ho && ox < a.Wo;
+    px.yoff[0] = (long long)n * a.Cout * a.P + (long long)oy * a.Wo + ox;
+#pragma unroll
+    for (int u = 0; u < UG; ++u)
+        if (gid[u] >= 0) store_group<V, 1, MF, false>(a, acc[u], gid[u], px);
+}
+
+// ------------------------------------------------------------------ launcher
+
+constexpr int kMaxLds = 160 * 1024;
+constexpr int kCUs = 256;
+
+static inline int ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
+
+typedef void (*kern_t)(const ConvArgs);
+
+template <int V, bool MF>
+static kern_t pick_resident(int pv, bool vec) {
+    if (vec) {
+        if (pv == 4) return k_pw_resident<V, 4, MF, true>;
+        if (pv == 2) return k_pw_resident<V, 2, MF, true>;
+        return k_pw_resident<V, 1, MF, true>;
+    }
+    return k_pw_resident<V, 1, MF, false>;
+}
+
+template <int V, bool MF>
+static kern_t pick_chunked(bool vec) {
+    return vec ? k_pw_chunked<V, 1, 4, MF, true> : k_pw_chunked<V, 1, 4, MF, false>;
+}
+
+template <int V, bool MF>
+static kern_t pick_conv3(int stride) {
+    return stride == 1 ? k_conv3<V, 1, 4, MF> : k_conv3<V, 2, 4, MF>;
+}
+
+constexpr int kUG = 4;  // groups per wavefront in the chunked kernels
+
+// Dynamic LDS above 64 KB has to be allowed per kernel once; remember which kernels
+// already have the full 160 KB enabled.
+static int set_lds_limit(kern_t k, int lds) {
+    if (lds <= 64 * 1024) return ALCS_OK;
+    static std::mutex mu;
+    static std::set<const void *> done;
+    std::lock_guard<std::mutex> lock(mu);
+    if (done.count((const void *)k)) return ALCS_OK;
+    hipError_t e = hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds);
+    if (e != hipSuccess) { set_hip_error((int)e); return ALCS_E_HIP; }
+    done.insert((const void *)k);
+    return ALCS_OK;
+}
+
+}  // namespace alcs
+
+using namespace alcs;
+
+extern "C" int alcs_sparse_conv(const alcs_packed_t *Wp, const float *X_dev, const float *bias_dev,
+                                float *Y_dev, int N, int Cin, int Cout, int H, int W, int kernel,
+                                int stride, void *stream) {
+    if (!Wp || N < 0 || H <= 0 || W <= 0) return ALCS_E_INVALID_ARG;
+    if (Cin != Wp->Cin || Cout != Wp->Cout || kernel != Wp->k) return ALCS_E_INVALID_ARG;
+    if (stride != 1 && stride != 2) return ALCS_E_UNSUPPORTED;
+    if (N == 0) return ALCS_OK;
+    if (!X_dev || !Y_dev) return ALCS_E_INVALID_ARG;
+    if (((uintptr_t)X_dev | (uintptr_t)Y_dev) & 15) return ALCS_E_INVALID_ARG;
+    const int pad = (kernel - 1) / 2;
+    const int Ho = (H + 2 * pad - kernel) / stride + 1, Wo = (W + 2 * pad - kernel) / stride + 1;
+    if (Ho <= 0 || Wo <= 0) return ALCS_E_INVALID_ARG;
+    const long long P = (long long)Ho * Wo, Pin = (long long)H * W;
+    if (P > INT32_MAX || Pin > INT32_MAX) return ALCS_E_UNSUPPORTED;
+    if ((long double)N * Cin * Pin >= 9e18L || (long double)N * Cout * P >= 9e18L) return ALCS_E_UNSUPPORTED;
+    if (!Wp->dev.blob) return ALCS_E_NO_DEVICE;
+    int cur = -1;
+    hipError_t e = hipGetDevice(&cur);
+    if (e != hipSuccess) { set_hip_error((int)e); return ALCS_E_HIP; }
+    if (cur != Wp->dev.device) return ALCS_E_INVALID_ARG;
+
+    const Layout &L = Wp->lay;
+    const Tuning &T = tuning();
+    const int V = Wp->V, G = Wp->G;
+    ConvArgs a{};
+    a.X = X_dev; a.bias = bias_dev; a.Y = Y_dev;
+    a.seg = Wp->dev.seg; a.w = Wp->dev.w; a.order = Wp->dev.order;
+    a.off = Wp->dev.off[kernel == 3 && stride == 2 ? 1 : 0];
+    a.wplane = (long long)L.nblk * L.VV;
+    a.N = N; a.Cin = Cin; a.Cout = Cout; a.H = H; a.W = W; a.Ho = Ho; a.Wo = Wo; a.stride = stride;
+    a.P = (int)P; a.Pin = (int)Pin;
+    if ((long long)N * P > INT32_MAX - 1024) return ALCS_E_UNSUPPORTED;
+    a.NP = (int)((long long)N * P);
+    a.G = G; a.nchunks = L.nchunks; a.KC = L.KC;
+
+    bool mfma = V >= 4;
+    if (V == 4 && T.path == 1) mfma = false;
+    kern_t kern = nullptr;
+    int lds = 0, nw = 0, pv = 1, mode = 0;
+
+    if (kernel == 1) {
+        const bool vec = stride == 1 && (P % 4 == 0);
+        if (L.nchunks == 1) {
+            mode = 1;
+            // pixels per lane: the widest tile whose Cin+1 rows fit in about 64 KB and that
+            // still leaves a few workgroups per compute unit
+            pv = 1;
+            if (vec) {
+                for (int cand = 4; cand >= 2; cand >>= 1) {
+                    const long long need = (long long)(Cin + 1) * 64 * cand * 4;
+                    const long long tiles = ((long long)a.NP + 64 * cand - 1) / (64 * cand);
+                    if (need <= 64 * 1024 && tiles >= 4 * kCUs) { pv = cand; break; }
+                }
+                if (T.pv == 1 || T.pv == 2 || T.pv == 4) pv = T.pv;
+            }
+            const int TP = 64 * pv;
+            lds = (Cin + 1) * TP * 4;
+            if (lds > kMaxLds) return ALCS_E_UNSUPPORTED;
+            a.npt = ceil_div(a.NP, TP);
+            // split the groups over several workgroups only when there are too few pixel tiles
+            int ngt = 1;
+            if (a.npt < 2 * kCUs) ngt = std::min(std::max(1, G / 8), ceil_div(2 * kCUs, a.npt));
+            if (T.group_tiles > 0) ngt = std::min(T.group_tiles, G);
+            a.gpt = ceil_div(G, ngt);
+            a.ngt = ceil_div(G, a.gpt);
+            nw = lds > 80 * 1024 ? 16 : (lds > 40 * 1024 ? 8 : 4);
+            nw = std::min(nw, std::max(1, a.gpt));
+            if (T.waves > 0) nw = std::min(T.waves, 16);
+            switch (V) {
+                case 1: kern = pick_resident<1, false>(pv, vec); break;
+                case 2: kern = pick_resident<2, false>(pv, vec); break;
+                case 4: kern = mfma ? pick_resident<4, true>(pv, vec) : pick_resident<4, false>(pv, vec); break;
+                case 8: kern = pick_resident<8, true>(pv, vec); break;
+                case 16: kern = pick_resident<16, true>(pv, vec); break;
+            }
+        } else {
+            mode = 2;
+            pv = 1;
+            lds = (L.KC + 1) * 64 * 4;
+            a.npt = ceil_div(a.NP, 64);
+            nw = 8;
+            if (T.waves > 0) nw = std::min(T.waves, 8);
+            a.gpt = nw * kUG;
+            a.ngt = ceil_div(G, a.gpt);
+            switch (V) {
+                case 1: kern = pick_chunked<1, false>(vec); break;
+                case 2: kern = pick_chunked<2, false>(vec); break;
+                case 4: kern = mfma ? pick_chunked<4, true>(vec) : pick_chunked<4, false>(vec); break;
+                case 8: kern = pick_chunked<8, true>(vec); break;
+                case 16: kern = pick_chunked<16, true>(vec); break;
+            }
+        }
+    } else {
+        mode = 3;
+        const int halo = halo3(stride);
+        lds = (L.KC + 1) * halo * halo * 4;
+        a.tiles_x = ceil_div(Wo, kTile3);
+        a.tiles_y = ceil_div(Ho, kTile3);
+        a.npt = a.tiles_x * a.tiles_y * N;
+        nw = 8;
+        if (T.waves > 0) nw = std::min(T.waves, 8);
+        a.gpt = nw * kUG;
+        a.ngt = ceil_div(G, a.gpt);
+        switch (V) {
+            case 1: kern = pick_conv3<1, false>(stride); break;
+            case 2: kern = pick_conv3<2, false>(stride); break;
+            case 4: kern = mfma ? pick_conv3<4, true>(stride) : pick_conv3<4, false>(stride); break;
+            case 8: kern = pick_conv3<8, true>(stride); break;
+            case 16: kern = pick_conv3<16, true>(stride); break;
+        }
+    }
+    if (!kern || lds > kMaxLds) return ALCS_E_UNSUPPORTED;
+    const long long total = (long long)a.npt * a.ngt;
+    if (total > (1LL << 30)) return ALCS_E_UNSUPPORTED;
+    a.total_wgs = (int)total;
+    a.wg_per_xcd = ceil_div(total, kXcds);
+    int rc = set_lds_limit(kern, lds);
+    if (rc != ALCS_OK) return rc;
+    record_launch(mode, pv, nw, a.total_wgs, lds, a.ngt, L.KC, mfma ? 2 : 1);
+    hipLaunchKernelGGL(kern, dim3(a.wg_per_xcd * kXcds), dim3(nw * 64), lds, (hipStream_t)stream, a);
+    e = hipGetLastError();
+    if (e != hipSuccess) { set_hip_error((int)e); return ALCS_E_HIP; }
+    return ALCS_OK;
+}

@@ -1,0 +1,176 @@
+"""GPU parity, element by element, at sizes the oracle finishes in seconds: every
+kernel variant (group size, pixels per lane, resident / chunked / 3x3, vector and
+scalar staging, MFMA and FMA inner loops), ragged tails and degenerate masks."""
+import numpy as np
+import pytest
+
+import paper_2109_00170_amd as alcs
+import workloads
+from gpu_util import TOL, oracle_ref, rel_err, run_dense, run_sparse
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True)
+def _reset_tuning():
+    yield
+    for k in ("pv", "waves", "group_tiles", "path", "chunk_channels", "groups_per_wave"):
+        alcs.alcs_set_tuning(k, 0)
+
+
+def check(L, seed, with_bias=True, **tuning):
+    for k, v in tuning.items():
+        alcs.alcs_set_tuning(k, v)
+    d = workloads.make_layer(L, seed, with_bias=with_bias)
+    got, info = run_sparse(d)
+    ref = oracle_ref(d)
+    assert got.shape == ref.shape
+    assert not np.isnan(got).any(), "some outputs were never written"
+    err = rel_err(got, ref)
+    assert err <= TOL, "%s %s: rel err %.3g" % (L.name, info, err)
+    return info
+
+
+def test_config1_single_pointwise_layer():
+    """Config 1: 1x1, batch 1, 64->64 at 56x56, V=4, 512 of 1024 blocks kept."""
+    L = workloads.config1()
+    d = workloads.make_layer(L, workloads.seed_for(1, 0))
+    assert d.nnzb == 512
+    got, info = run_sparse(d)
+    assert rel_err(got, oracle_ref(d)) <= TOL
+
+
+@pytest.mark.parametrize("V", [1, 2, 4, 8, 16])
+@pytest.mark.parametrize("pv", [1, 2, 4])
+def test_pointwise_resident_all_group_sizes(V, pv):
+    # 3 images of 20x20 = 1200 pixels: several tiles and a ragged last tile; Cout=44 is ragged for V=8,16
+    L = workloads.Layer("pw_v%d" % V, 48, 44, 20, 20, N=3, V=V, sparsity=0.6, x_dist="relu")
+    info = check(L, 100 + V, pv=pv)
+    assert info["mode"] == 1 and info["pv"] == pv
+
+
+@pytest.mark.parametrize("V", [1, 4, 8])
+def test_pointwise_odd_pixel_count_uses_scalar_staging(V):
+    L = workloads.Layer("pw7x7_v%d" % V, 40, 24, 7, 7, N=5, V=V, sparsity=0.5)
+    info = check(L, 200 + V)
+    assert info["mode"] == 1 and info["pv"] == 1
+
+
+@pytest.mark.parametrize("V", [2, 4, 16])
+def test_pointwise_stride2(V):
+    L = workloads.Layer("pw_s2_v%d" % V, 24, 32, 15, 13, k=1, stride=2, N=2, V=V, sparsity=0.5)
+    check(L, 300 + V)
+
+
+@pytest.mark.parametrize("V,kc", [(1, 16), (4, 16), (4, 40), (8, 24), (16, 64)])
+def test_pointwise_chunked(V, kc):
+    L = workloads.Layer("pw_chunk_v%d" % V, 100, 72, 12, 12, N=3, V=V, sparsity=0.7)
+    info = check(L, 400 + V + kc, chunk_channels=kc)
+    assert info["mode"] == 2 and info["chunk_channels"] == kc
+
+
+def test_pointwise_chunked_default_for_wide_inputs():
+    L = workloads.Layer("pw_wide", 1100, 40, 7, 7, N=3, V=4, sparsity=0.9)
+    info = check(L, 450)
+    assert info["mode"] == 2
+
+
+def test_pointwise_fma_path_for_v4_matches_too():
+    L = workloads.Layer("pw_fma", 64, 64, 16, 16, N=2, V=4, sparsity=0.5)
+    info = check(L, 460, path=1)
+    assert info["path"] == 1
+    info = check(L, 460, path=2)
+    assert info["path"] == 2
+
+
+@pytest.mark.parametrize("groups", [1, 3])
+def test_pointwise_group_tiles(groups):
+    L = workloads.Layer("pw_gt", 64, 96, 10, 10, N=2, V=4, sparsity=0.5)
+    info = check(L, 470, group_tiles=groups, waves=2)
+    assert info["group_tiles"] == groups
+
+
+@pytest.mark.parametrize("V", [1, 4, 8])
+@pytest.mark.parametrize("stride", [1, 2])
+def test_conv3x3(V, stride):
+    # 19x17: tiles of 8x8 with ragged right/bottom edges; 40 channels = 2 chunks of 32
+    L = workloads.Layer("c3_v%d_s%d" % (V, stride), 40, 36, 19, 17, k=3, stride=stride, N=2, V=V,
+                        sparsity=0.7, w_std=0.05)
+    info = check(L, 500 + V + stride)
+    assert info["mode"] == 3
+
+
+def test_conv3x3_tap_shared_pattern_and_many_groups():
+    L = workloads.Layer("c3_shared", 64, 200, 14, 14, k=3, stride=1, N=2, V=4, sparsity=0.8,
+                        w_std=0.05, tap_shared=True)
+    check(L, 520)
+
+
+def test_conv3x3_few_waves_uses_position_loop():
+    L = workloads.Layer("c3_small_wg", 16, 16, 9, 9, k=3, stride=2, N=1, V=4, sparsity=0.5)
+    check(L, 530, waves=2)
+
+
+def test_degenerate_masks():
+    import torch
+    L = workloads.Layer("deg", 32, 16, 8, 8, N=2, V=4, sparsity=0.5)
+    d = workloads.make_layer(L, 600, with_bias=True)
+    # everything dropped: output is the bias, exactly
+    d.mask[:] = 0
+    got, _ = run_sparse(d)
+    assert np.array_equal(got, np.broadcast_to(d.bias[None, :, None, None], got.shape))
+    # everything kept equals the dense conv of the oracle
+    d.mask[:] = 1
+    got, _ = run_sparse(d)
+    assert rel_err(got, oracle_ref(d)) <= TOL
+    # one group empty, one full
+    d.mask[:] = 0
+    d.mask[1] = 1
+    got, _ = run_sparse(d)
+    assert rel_err(got, oracle_ref(d)) <= TOL
+    assert np.array_equal(got[:, :4], np.broadcast_to(d.bias[None, :4, None, None], got[:, :4].shape))
+    del torch
+
+
+def test_identity_input_reads_back_weights_exactly():
+    """1x1 with X one-hot per channel: every sum has one term, so Y is the pruned
+    weight matrix bit for bit - pins the column indexing through the compute path."""
+    V, Cin, Cout = 4, 64, 40
+    L = workloads.Layer("ident", Cin, Cout, 8, 8, N=1, V=V, sparsity=0.5)
+    d = workloads.make_layer(L, 700)
+    d.X[:] = np.eye(Cin, dtype=np.float32).reshape(1, Cin, 8, 8)
+    got, _ = run_sparse(d)
+    keep = np.repeat(d.mask.reshape(L.G, Cin), V, axis=0)[:Cout].astype(bool)
+    expect = np.where(keep, d.W.reshape(Cout, Cin), np.float32(0))
+    assert got.reshape(Cout, Cin).tobytes() == expect.tobytes()
+
+
+def test_impulse_3x3_exact():
+    L = workloads.Layer("imp", 1, 4, 9, 9, k=3, stride=1, N=1, V=4, sparsity=0.0)
+    d = workloads.make_layer(L, 710)
+    d.X[:] = 0
+    d.X[0, 0, 4, 5] = 1.0
+    got, _ = run_sparse(d)
+    ref = oracle_ref(d)
+    assert got.tobytes() == ref.tobytes()
+
+
+@pytest.mark.parametrize("k,stride,Cout,Cin,HW,N", [(1, 1, 64, 64, 56, 1), (1, 1, 200, 70, 14, 3),
+                                                    (1, 1, 40, 33, 7, 5), (1, 2, 24, 20, 9, 2),
+                                                    (3, 1, 36, 20, 12, 2), (3, 2, 130, 17, 11, 2)])
+def test_dense_conv(k, stride, Cout, Cin, HW, N):
+    L = workloads.Layer("dense", Cin, Cout, HW, HW + (0 if k == 1 and stride == 1 and HW % 2 == 0 else 1),
+                        k=k, stride=stride, N=N, V=4, sparsity=0.0, w_std=0.05, mask_kind="none")
+    d = workloads.make_layer(L, 800 + Cout, with_bias=True)
+    got = run_dense(d)
+    ref = oracle_ref(d)
+    assert not np.isnan(got).any()
+    assert rel_err(got, ref) <= TOL
+
+
+def test_sparse_at_sparsity_zero_equals_dense():
+    L = workloads.Layer("s0", 96, 64, 14, 14, N=2, V=4, sparsity=0.0)
+    d = workloads.make_layer(L, 900, with_bias=True)
+    a, _ = run_sparse(d)
+    b = run_dense(d)
+    assert rel_err(a, b) <= TOL
