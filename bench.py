@@ -1,0 +1,235 @@
+#!/usr/bin/env python3
+"""Benchmark of the sparse pointwise convolution path on one MI355X.
+
+Workload (config.workload): the 13 pointwise 1x1 convolutions of a MobileNetV1-shaped
+network at 224x224 input, batch 32, V=4, 90 % of the 4x1 weight blocks dropped
+(exact count per layer, seeded), weights N(0, 0.1), inputs ReLU(N(0, 1)), fp32.
+One "step" = one alcs_sparse_conv launch per layer, all 13 layers, inputs and packed
+weights already resident in HBM.  value = dense-equivalent GFLOP/s of the whole step
+(2*N*Ho*Wo*Cout*Cin per layer, as if nothing were pruned, divided by the step time).
+
+Prints one JSON line on stdout; a per-layer table goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix peak, published
+
+
+def layer_bytes(L, nnzb):
+    """Algorithmic bytes of one call: X once, Y once, the grouped CSR once."""
+    packed = 4 * (L.G + 1) + 4 * nnzb + 4 * L.V * nnzb
+    return L.x_bytes() + L.y_bytes() + packed
+
+
+def layer_flops(L, nnzb):
+    """Algorithmic flops: two per multiply-accumulate of a kept weight."""
+    return 2.0 * L.N * L.Ho * L.Wo * L.V * nnzb
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--batch", type=int, default=32)
+    ap.add_argument("--sparsity", type=float, default=0.9,
+                    help="block sparsity of every layer; a negative value draws U(0.7,0.9) per layer")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-batch", type=int, default=32)
+    ap.add_argument("--layers-json", default=None, help="also write the per-layer table to this file")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the path needs no exchange between GPUs); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2109_00170_amd as alcs
+    import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    alcs.load_library()
+
+    sp = None if args.sparsity < 0 else args.sparsity
+    layers = workloads.mobilenet_v1_pointwise(args.batch, sp)
+    data, packed, Xs, Ys, nnzb = [], [], [], [], []
+    for i, L in enumerate(layers):
+        d = workloads.make_layer(L, workloads.seed_for(2, i))
+        data.append(d)
+        p = alcs.alcs_pack_weights(d.W, d.mask, L.V)
+        assert p.on_device
+        packed.append(p)
+        nnzb.append(p.nnzb)
+        Xs.append(torch.from_numpy(d.X).to(dev))
+        Ys.append(torch.empty((L.N, L.Cout, L.Ho, L.Wo), dtype=torch.float32, device=dev))
+    stream = torch.cuda.current_stream()
+    stream_ptr = stream.cuda_stream
+
+    def run_layer(i):
+        alcs.alcs_sparse_conv(packed[i], Xs[i], None, Ys[i], stride=layers[i].stride, stream=stream_ptr)
+
+    def run_step():
+        for i in range(len(layers)):
+            run_layer(i)
+
+    for _ in range(args.warmup):
+        run_step()
+    torch.cuda.synchronize()
+
+    # untimed pass with an event pair around every launch: per-layer durations in the
+    # same launch order and with the same buffers as the timed steps
+    nprof = max(5, min(args.steps, 20))
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in layers] for _ in range(nprof)]
+    torch.cuda._sleep(100_000_000)  # keep the GPU busy (~40 ms) so that the host runs ahead of it:
+    # otherwise an event pair around a short kernel measures the host's submission time
+    for s in range(nprof):
+        for i in range(len(layers)):
+            ev[s][i][0].record(stream)
+            run_layer(i)
+            ev[s][i][1].record(stream)
+    torch.cuda.synchronize()
+    layer_us = [float(np.median([ev[s][i][0].elapsed_time(ev[s][i][1]) * 1e3 for s in range(nprof)]))
+                for i in range(len(layers))]
+    launch = []
+    for i in range(len(layers)):
+        run_layer(i)
+        launch.append(alcs.alcs_last_launch())
+    torch.cuda.synchronize()
+    dom = int(np.argmax(layer_us))
+
+    # ---- timed region: exactly `steps` steps; events bracket the dominant layer's launch ----
+    dom_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        for i in range(len(layers)):
+            if i == dom:
+                dom_ev[s][0].record(stream)
+                run_layer(i)
+                dom_ev[s][1].record(stream)
+            else:
+                run_layer(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    dom_us = float(np.mean([a.elapsed_time(b) * 1e3 for a, b in dom_ev]))
+
+    dense_flops = sum(L.dense_flops() for L in layers)
+    alg_flops = sum(layer_flops(L, n) for L, n in zip(layers, nnzb))
+    alg_bytes = sum(layer_bytes(L, n) for L, n in zip(layers, nnzb))
+    value = dense_flops / (ms_per_step * 1e-3) / 1e9
+
+    # ---- parity on the buffers that were timed: sampled outputs against the CPU oracle ----
+    import oracle
+    max_err = 0.0
+    rng = np.random.default_rng(12345)
+    for i, L in enumerate(layers):
+        y = Ys[i].cpu().numpy().reshape(-1)
+        idx = rng.choice(y.size, size=2000, replace=False)
+        Wd = oracle.densify(data[i].W, data[i].mask, L.V)
+        ref = oracle.conv_at(Wd, data[i].X, idx, stride=L.stride)
+        scale = float(np.max(np.abs(y)))
+        max_err = max(max_err, float(np.max(np.abs(y[idx] - ref)) / scale))
+
+    # ---- per-layer table ----
+    rows = []
+    roof_sum = 0.0
+    for i, L in enumerate(layers):
+        b = layer_bytes(L, nnzb[i])
+        f = layer_flops(L, nnzb[i])
+        t_hbm = b / (HBM_PEAK_GBS * 1e9)
+        t_mfma = f / (MFMA_FP32_PEAK_TFLOPS * 1e12)
+        t_roof = max(t_hbm, t_mfma)
+        roof_sum += t_roof
+        us = layer_us[i]
+        rows.append({"layer": L.name, "Cin": L.Cin, "Cout": L.Cout, "HW": L.H, "N": L.N,
+                     "sparsity": round(L.sparsity, 4), "nnzb": nnzb[i], "us": round(us, 2),
+                     "dense_equiv_gflops": round(L.dense_flops() / us / 1e3, 1),
+                     "actual_gflops": round(f / us / 1e3, 1),
+                     "effective_gbs": round(b / us / 1e3, 1),
+                     "bound": "hbm" if t_hbm >= t_mfma else "mfma",
+                     "roofline_us": round(t_roof * 1e6, 2),
+                     "roofline_frac": round(t_roof * 1e6 / us, 3), "launch": launch[i]})
+    print("%-6s %-10s %4s %8s %9s %10s %9s %6s %6s  launch" %
+          ("layer", "Cin->Cout", "HW", "us", "denseGF/s", "actGF/s", "effGB/s", "bound", "frac"), file=sys.stderr)
+    for r in rows:
+        print("%-6s %-10s %4d %8.2f %9.0f %10.0f %9.0f %6s %6.3f  %s" %
+              (r["layer"], "%d->%d" % (r["Cin"], r["Cout"]), r["HW"], r["us"], r["dense_equiv_gflops"],
+               r["actual_gflops"], r["effective_gbs"], r["bound"], r["roofline_frac"],
+               "m%d pv%d w%d wg%d lds%d gt%d" % (r["launch"]["mode"], r["launch"]["pv"], r["launch"]["waves"],
+                                                  r["launch"]["workgroups"], r["launch"]["lds_bytes"],
+                                                  r["launch"]["group_tiles"])), file=sys.stderr)
+    sum_us = sum(layer_us)
+    print("sum of per-layer medians %.1f us; step %.1f us; sum of rooflines %.1f us (%.3f of step)" %
+          (sum_us, ms_per_step * 1e3, roof_sum * 1e6, roof_sum * 1e3 / ms_per_step), file=sys.stderr)
+    if args.layers_json:
+        with open(args.layers_json, "w") as f:
+            json.dump(rows, f, indent=1)
+
+    Ld = layers[dom]
+    dom_bytes = layer_bytes(Ld, nnzb[dom])
+    achieved = dom_bytes / (dom_us * 1e-6) / 1e9
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "kernel": "k_pw_resident (layer %s, %d->%d @%dx%d, N=%d)" % (Ld.name, Ld.Cin, Ld.Cout, Ld.H, Ld.W, Ld.N),
+                "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_us": round(dom_us, 2)}
+
+    out = {
+        "metric": "dense-equiv GFLOP/s + achieved HBM GB/s, sparse pointwise conv, 1 MI355X",
+        "value": round(value, 1),
+        "unit": "GFLOP/s (dense-equivalent)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "MobileNetV1-shaped 13 pointwise 1x1 convs @224, batch %d, V=4, block sparsity %s"
+                               % (args.batch, "0.9 fixed" if sp is not None and abs(sp - 0.9) < 1e-9 else
+                                  ("%.2f fixed" % sp if sp is not None else "U(0.7,0.9) per layer")),
+                   "batch": args.batch, "layers": len(layers)},
+        "effective_gbs": round(alg_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+        "actual_gflops": round(alg_flops / (ms_per_step * 1e-3) / 1e9, 1),
+        "roofline_frac_step": round(roof_sum * 1e3 / ms_per_step, 4),
+        "max_rel_err_vs_oracle": float("%.3g" % max_err),
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        nb = max(1, min(args.cpu_sample_batch, args.batch))
+        threads = oracle.max_threads()
+        t_cpu = 0.0
+        fl = 0.0
+        for i, L in enumerate(layers):
+            Wd = oracle.densify(data[i].W, data[i].mask, L.V)
+            xs = np.ascontiguousarray(data[i].X[:nb])
+            c0 = time.perf_counter()
+            oracle.conv(Wd, xs, stride=L.stride, nthreads=threads)
+            t_cpu += time.perf_counter() - c0
+            fl += L.dense_flops() * nb / L.N
+        out["cpu_baseline"] = {"value": round(fl / t_cpu / 1e9, 2), "unit": "GFLOP/s (dense-equivalent)",
+                               "cores": threads, "kind": "oracle",
+                               "sample": "same 13 layers and weights, first %d of %d images, %.1f s of CPU time"
+                                         % (nb, args.batch, t_cpu)}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -11,18 +11,28 @@ namespace alcs {
 
 // Blocks are padded so that a wavefront can fetch the weights of 16 consecutive kept
 // columns of one group with a single coalesced 256-byte load, and so that the inner
-// loop can run in steps of 4 columns without a remainder.
+// loop can run in branch-free batches of 8 columns without a remainder.
 constexpr int kSegAlign = 16;  // every (group, chunk) segment starts at a multiple of 16 blocks
-constexpr int kCntAlign = 4;   // and its padded length is a multiple of 4 blocks
+constexpr int kCntAlign = 8;   // and its padded length is a multiple of 8 blocks
 
 // Geometry of the 3x3 kernels: an 8x8 tile of output pixels per wavefront, staged in
 // LDS with its halo, one plane of kHalo*kHalo floats per input channel.
 constexpr int kTile3 = 8;
 inline constexpr int halo3(int stride) { return (kTile3 - 1) * stride + 3; }
 
+// Bytes per LDS row that the stored 1x1 row selectors assume (a 64-pixel fp32 tile);
+// kernels with 2 or 4 pixels per lane scale the selector by that factor.
+constexpr int kRowBytes1 = 256;
+
 struct Seg {
     int32_t start;  // first padded block of the segment (multiple of kSegAlign)
     int32_t cnt;    // padded number of blocks to process (multiple of kCntAlign, may be 0)
+};
+
+// What a wavefront needs to process one (group, chunk) pair, in the order the kernels
+// hand out work: groups by descending kept-column count.
+struct Work {
+    int32_t start, cnt, group, reserved;
 };
 
 // The layout the kernels read ("tuned layout").  Input channels are cut into chunks
@@ -37,21 +47,21 @@ struct Layout {
     int noff = 0;     // 1 for kernel 1; 2 for kernel 3 (stride 1, stride 2 geometry)
     std::vector<Seg> seg;          // [G * nchunks], index g * nchunks + chunk
     std::vector<float> w;          // [planes][nblk * VV]
-    std::vector<int32_t> off[2];   // [nblk] each; LDS row selector of every block:
-                                   //   kernel 1: input channel c            (pad: c0 + KC)
-                                   //   kernel 3: c*HA + r*halo + s          (pad: (c0 + KC)*HA)
-                                   // with c0 the first channel of the block's chunk
+    std::vector<int32_t> off[2];   // [nblk] each; LDS row selector of every block, in bytes:
+                                   //   kernel 1: c * kRowBytes1             (pad: (c0 + KC) * kRowBytes1)
+                                   //   kernel 3: 4*(c*HA + r*halo + s)      (pad: 4*(c0 + KC)*HA)
+                                   // with c the input channel and c0 the first channel of the block's chunk
     std::vector<int32_t> order;    // [G] groups by descending kept-column count
+    std::vector<Work> work;        // [G * nchunks], index i * nchunks + chunk for the i-th group of `order`
 };
 
 struct DeviceCopy {
     int device = -1;
     void *blob = nullptr;
     size_t bytes = 0;
-    const Seg *seg = nullptr;
+    const Work *work = nullptr;
     const float *w = nullptr;
     const int32_t *off[2] = {nullptr, nullptr};
-    const int32_t *order = nullptr;
 };
 
 }  // namespace alcs
@@ -75,7 +85,7 @@ int upload(alcs_packed *p);
 void release_device(alcs_packed *p);
 
 struct Tuning {
-    int pv = 0, waves = 0, group_tiles = 0, path = 0, kc = 0, ug = 0;
+    int pv = 0, waves = 0, group_tiles = 0, path = 0, kc = 0, ug = 0, debug = 0;
 };
 Tuning &tuning();
 void record_launch(int mode, int pv, int waves, int wgs, int lds, int gtiles, int kc, int path);

@@ -32,18 +32,18 @@ static inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * 
 // Channel of a canonical column index.
 static inline int col_channel(int col, int kk) { return col / kk; }
 
-// LDS row selector of a real block (see Layout::off).
+// LDS row selector of a real block (see Layout::off): a byte offset.
 static inline int32_t off_of(int col, int k, int table) {
-    if (k == 1) return col;
+    if (k == 1) return col * kRowBytes1;
     int c = col / 9, tap = col % 9, r = tap / 3, s = tap % 3;
     int halo = halo3(table + 1);
-    return c * halo * halo + r * halo + s;
+    return (c * halo * halo + r * halo + s) * 4;
 }
 
 static inline int32_t pad_off(int c0, int KC, int k, int table) {
-    if (k == 1) return c0 + KC;
+    if (k == 1) return (c0 + KC) * kRowBytes1;
     int halo = halo3(table + 1);
-    return (c0 + KC) * halo * halo;
+    return (c0 + KC) * halo * halo * 4;
 }
 
 int build_layout(alcs_packed *p, int KC) {
@@ -108,6 +108,12 @@ int build_layout(alcs_packed *p, int KC) {
         std::stable_sort(L.order.begin(), L.order.end(), [&](int a, int b) {
             return p->row_ptr[a + 1] - p->row_ptr[a] > p->row_ptr[b + 1] - p->row_ptr[b];
         });
+        L.work.resize((size_t)G * L.nchunks);
+        for (int i = 0; i < G; ++i)
+            for (int ch = 0; ch < L.nchunks; ++ch) {
+                const Seg sg = L.seg[(size_t)L.order[i] * L.nchunks + ch];
+                L.work[(size_t)i * L.nchunks + ch] = Work{sg.start, sg.cnt, L.order[i], 0};
+            }
     } catch (const std::bad_alloc &) {
         return ALCS_E_ALLOC;
     }
@@ -140,14 +146,12 @@ int upload(alcs_packed *p) {
     }
     int dev = 0;
     if ((e = hipGetDevice(&dev)) != hipSuccess) { set_hip_error((int)e); return ALCS_E_HIP; }
-    const size_t b_seg = L.seg.size() * sizeof(Seg);
+    const size_t b_work = L.work.size() * sizeof(Work);
     const size_t b_w = L.w.size() * sizeof(float);
     const size_t b_off = (size_t)L.nblk * sizeof(int32_t);
-    const size_t b_ord = L.order.size() * sizeof(int32_t);
-    size_t o_seg = 0, o_w = align256(o_seg + b_seg), o_off0 = align256(o_w + b_w);
+    size_t o_work = 0, o_w = align256(o_work + b_work), o_off0 = align256(o_w + b_w);
     size_t o_off1 = align256(o_off0 + b_off);
-    size_t o_ord = L.noff == 2 ? align256(o_off1 + b_off) : o_off1;
-    size_t total = align256(o_ord + b_ord) + 256;
+    size_t total = align256(o_off1 + (L.noff == 2 ? b_off : 0)) + 256;
     void *blob = nullptr;
     if ((e = hipMalloc(&blob, total)) != hipSuccess) {
         set_hip_error((int)e);
@@ -158,11 +162,10 @@ int upload(alcs_packed *p) {
     auto put = [&](size_t o, const void *src, size_t n) -> hipError_t {
         return n ? hipMemcpy(base + o, src, n, hipMemcpyHostToDevice) : hipSuccess;
     };
-    e = put(o_seg, L.seg.data(), b_seg);
+    e = put(o_work, L.work.data(), b_work);
     if (e == hipSuccess) e = put(o_w, L.w.data(), b_w);
     if (e == hipSuccess) e = put(o_off0, L.off[0].data(), b_off);
     if (e == hipSuccess && L.noff == 2) e = put(o_off1, L.off[1].data(), b_off);
-    if (e == hipSuccess) e = put(o_ord, L.order.data(), b_ord);
     if (e != hipSuccess) {
         set_hip_error((int)e);
         (void)hipFree(blob);
@@ -171,11 +174,10 @@ int upload(alcs_packed *p) {
     p->dev.device = dev;
     p->dev.blob = blob;
     p->dev.bytes = total;
-    p->dev.seg = (const Seg *)(base + o_seg);
+    p->dev.work = (const Work *)(base + o_work);
     p->dev.w = (const float *)(base + o_w);
     p->dev.off[0] = (const int32_t *)(base + o_off0);
     p->dev.off[1] = L.noff == 2 ? (const int32_t *)(base + o_off1) : nullptr;
-    p->dev.order = (const int32_t *)(base + o_ord);
     return ALCS_OK;
 }
 
@@ -318,6 +320,13 @@ int alcs_packed_selfcheck(const alcs_packed_t *p) {
             if (p->row_ptr[a + 1] - p->row_ptr[a] < p->row_ptr[g + 1] - p->row_ptr[g]) return ALCS_E_INVALID_ARG;
         }
     }
+    if (L.work.size() != L.seg.size()) return ALCS_E_INVALID_ARG;
+    for (int i = 0; i < p->G; ++i)
+        for (int ch = 0; ch < L.nchunks; ++ch) {
+            const Work wk = L.work[(size_t)i * L.nchunks + ch];
+            const Seg sg = L.seg[(size_t)L.order[i] * L.nchunks + ch];
+            if (wk.start != sg.start || wk.cnt != sg.cnt || wk.group != L.order[i]) return ALCS_E_INVALID_ARG;
+        }
     const uint32_t zero_bits = 0;
     for (int g = 0; g < p->G; ++g) {
         int64_t t = p->row_ptr[g];
@@ -382,6 +391,7 @@ int alcs_set_tuning(const char *name, int value) {
     else if (!std::strcmp(name, "path")) t.path = value;
     else if (!std::strcmp(name, "chunk_channels")) t.kc = value;
     else if (!std::strcmp(name, "groups_per_wave")) t.ug = value;
+    else if (!std::strcmp(name, "debug")) t.debug = value;
     else return ALCS_E_INVALID_ARG;
     return ALCS_OK;
 }

@@ -25,6 +25,7 @@
 #include <cstdint>
 #include <mutex>
 #include <set>
+#include <utility>
 
 #include "alcs_internal.h"
 
@@ -38,10 +39,9 @@ struct ConvArgs {
     const float *X;
     const float *bias;
     float *Y;
-    const Seg *seg;
+    const Work *work;   // [G * nchunks] in hand-out order (longest group first)
     const float *w;
     const int32_t *off;
-    const int32_t *order;
     long long wplane;   // floats between weight planes (nblk * VV)
     int N, Cin, Cout, H, W, Ho, Wo, stride;
     int P, Pin;         // Ho*Wo, H*W
@@ -50,6 +50,7 @@ struct ConvArgs {
     int npt, ngt, gpt;  // pixel tiles, group tiles, groups per group tile
     int tiles_x, tiles_y;  // 3x3: 8x8 tiles per image
     int wg_per_xcd, total_wgs;
+    int debug;  // measurement only: bit 0 skips staging, bit 1 the multiply, bit 2 the stores
 };
 
 constexpr int kXcds = 8;
@@ -65,11 +66,12 @@ __device__ __forceinline__ cptr<T> as_const(const T *p) {
     return (cptr<T>)(uintptr_t)p;
 }
 
-typedef int i2 __attribute__((ext_vector_type(2)));
-static_assert(sizeof(Seg) == 8, "Seg is read as two ints");
-__device__ __forceinline__ Seg load_seg(const Seg *table, size_t idx) {
-    const i2 v = *reinterpret_cast<cptr<i2>>((uintptr_t)(table + idx));
-    return Seg{__builtin_amdgcn_readfirstlane(v[0]), __builtin_amdgcn_readfirstlane(v[1])};
+static_assert(sizeof(Work) == 16, "Work is read as four ints");
+// One scalar 16-byte load; the values end up in SGPRs.
+__device__ __forceinline__ Work load_work(const Work *table, size_t idx) {
+    const i4 v = *reinterpret_cast<cptr<i4>>((uintptr_t)(table + idx));
+    return Work{__builtin_amdgcn_readfirstlane(v[0]), __builtin_amdgcn_readfirstlane(v[1]),
+                __builtin_amdgcn_readfirstlane(v[2]), 0};
 }
 
 // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Renumber
@@ -87,14 +89,23 @@ struct Acc;
 
 template <int V, int PV>
 struct Acc<V, PV, true> {  // MFMA: a[q][pv][i] = channel 4q+i, pixel pv of the lane
+    // With a single accumulator every MFMA would wait for the one before it; in that
+    // case even and odd columns go to two accumulators that are added at the end.
+    static constexpr bool DUAL = (V / 4) * PV == 1;
     f4 a[V / 4][PV];
+    f4 alt[V / 4][PV];
     __device__ __forceinline__ void zero() {
 #pragma unroll
         for (int q = 0; q < V / 4; ++q)
 #pragma unroll
-            for (int pv = 0; pv < PV; ++pv) a[q][pv] = f4{0.f, 0.f, 0.f, 0.f};
+            for (int pv = 0; pv < PV; ++pv) {
+                a[q][pv] = f4{0.f, 0.f, 0.f, 0.f};
+                if (DUAL) alt[q][pv] = f4{0.f, 0.f, 0.f, 0.f};
+            }
     }
-    __device__ __forceinline__ float get(int v, int pv) const { return a[v >> 2][pv][v & 3]; }
+    __device__ __forceinline__ float get(int v, int pv) const {
+        return DUAL ? a[v >> 2][pv][v & 3] + alt[v >> 2][pv][v & 3] : a[v >> 2][pv][v & 3];
+    }
 };
 
 template <int V, int PV>
@@ -122,74 +133,115 @@ __device__ __forceinline__ void lds_read(const float *p, float (&x)[PV]) {
     }
 }
 
-// One kept column, MFMA form: all 16 blocks take their 4 weights from block ABID of
-// the weight register (cbsz = 4), the other operand is the lane's pixel value(s).
-template <int ABID, int V, int PV>
-__device__ __forceinline__ void mfma_column(const float (&aw)[V / 4], const float *xp,
-                                            Acc<V, PV, true> &acc) {
-    float x[PV];
-    lds_read<PV>(xp, x);
+// Weights and row selectors of one run of 16 consecutive kept columns, as fetched by
+// two coalesced vector loads: lane l holds weight (column l/4, row l%4) of every
+// 4-row plane, and lanes 0..15 (repeated) hold the 16 selectors.
+template <int V, bool MF>
+struct Run {
+    float a[MF ? V / 4 : 1];
+    int o;
+};
+
+template <int V, bool MF>
+__device__ __forceinline__ Run<V, MF> load_run(const ConvArgs &a, int blk, int lane) {
+    Run<V, MF> r;
+    if constexpr (MF) {
+        const float *wp = a.w + (size_t)blk * 4 + lane;
 #pragma unroll
-    for (int q = 0; q < V / 4; ++q)
-#pragma unroll
-        for (int pv = 0; pv < PV; ++pv)
-            acc.a[q][pv] = __builtin_amdgcn_mfma_f32_4x4x1f32(aw[q], x[pv], acc.a[q][pv], 4, ABID, 0);
+        for (int q = 0; q < V / 4; ++q) r.a[q] = wp[(size_t)q * a.wplane];
+        r.o = a.off[blk + (lane & 15)];
+    } else {
+        r.a[0] = 0.f;
+        r.o = 0;
+    }
+    return r;
 }
 
-// Columns JJ .. JJ+3 of the current run of 16.  The run's 16 row selectors sit in
-// lanes 0..15 of `ov`; v_readlane moves the one that is needed into an SGPR, so the
-// LDS address costs one v_lshl_add per column and no scalar-memory wait.
-template <int JJ, int V, int PV, int SH>
-__device__ __forceinline__ void mfma_quad(const float (&aw)[V / 4], int ov, const float *lds,
-                                          int base, Acc<V, PV, true> &acc) {
-    mfma_column<JJ + 0, V, PV>(aw, lds + base + (__builtin_amdgcn_readlane(ov, JJ + 0) << SH), acc);
-    mfma_column<JJ + 1, V, PV>(aw, lds + base + (__builtin_amdgcn_readlane(ov, JJ + 1) << SH), acc);
-    mfma_column<JJ + 2, V, PV>(aw, lds + base + (__builtin_amdgcn_readlane(ov, JJ + 2) << SH), acc);
-    mfma_column<JJ + 3, V, PV>(aw, lds + base + (__builtin_amdgcn_readlane(ov, JJ + 3) << SH), acc);
+// Compile-time loop: f(std::integral_constant<int, 0>{}), ..., f(<N-1>); the MFMA
+// block-select modifier has to be an immediate.
+template <class F, int... Is>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, Is...>) {
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f) {
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+// Selector of column C of the current run, in every lane: the run's 16 selectors
+// sit in lanes 0..15 of each 16-lane row of `ov`, and the DPP control row_newbcast:C
+// hands lane C of its own row to every lane - no SGPR round trip, and the compiler
+// folds the move into the address add.
+template <int C>
+__device__ __forceinline__ int bcast_sel(int ov) {
+    return __builtin_amdgcn_update_dpp(0, ov, 0x150 + C, 0xF, 0xF, false);
+}
+
+// B consecutive kept columns of the current run, starting at column B0 of the run.
+// All B LDS row reads are issued first, then the MFMAs: for column c all 16 blocks
+// take their 4 weights from block c of the weight register (cbsz = 4, abid = c) and
+// multiply them with the lane's pixel value(s).  Segment lengths are padded to a
+// multiple of B (zero weights, selector of the all-zero row), so a batch never
+// branches: the compiler keeps all B reads in flight ahead of the MFMAs.
+// base is the lane's byte offset inside an LDS row (minus the chunk's first row);
+// selectors are byte offsets for 64-pixel rows, scaled by 1 << SH for wider rows.
+template <int B0, int B, int V, int PV, int SH>
+__device__ __forceinline__ void mfma_batch(const float (&aw)[V / 4], int ov, const char *lds,
+                                           int base, Acc<V, PV, true> &acc) {
+    float x[B][PV];
+    static_for<B>([&](auto c) {
+        constexpr int C = decltype(c)::value;
+        lds_read<PV>(reinterpret_cast<const float *>(lds + base + (bcast_sel<B0 + C>(ov) << SH)), x[C]);
+    });
+    static_for<B>([&](auto c) {
+        constexpr int C = decltype(c)::value;
+        constexpr int ABID = B0 + C;
+#pragma unroll
+        for (int q = 0; q < V / 4; ++q)
+#pragma unroll
+            for (int pv = 0; pv < PV; ++pv) {
+                if (Acc<V, PV, true>::DUAL && (ABID & 1))
+                    acc.alt[q][pv] = __builtin_amdgcn_mfma_f32_4x4x1f32(aw[q], x[C][pv], acc.alt[q][pv], 4, ABID, 0);
+                else
+                    acc.a[q][pv] = __builtin_amdgcn_mfma_f32_4x4x1f32(aw[q], x[C][pv], acc.a[q][pv], 4, ABID, 0);
+            }
+    });
 }
 
 // One segment (the kept columns of one group inside one channel chunk), MFMA form.
-// start/cnt are wave-uniform; base is the lane's float index inside an LDS row
-// (minus the chunk's first row); SH = log2(row length) for 1x1, 0 for 3x3 where the
-// stored selector is already a float index.  Weights and selectors of the next run
-// of 16 columns are fetched (two coalesced vector loads) while the current run is
-// being multiplied.
+// start/cnt are wave-uniform; base is the lane's byte offset inside an LDS row
+// (minus the chunk's first row); SH = log2(pixels per lane) for 1x1, 0 for 3x3.
+// `first` is the segment's first run,
+// loaded by the caller (early enough that it is not queued behind output stores);
+// the following runs are fetched while the current one is being multiplied.
 template <int V, int PV, int SH>
 __device__ __forceinline__ void mac_segment(const ConvArgs &a, int start, int cnt,
-                                            const float *lds, int base, int lane,
-                                            Acc<V, PV, true> &acc) {
+                                            const char *lds, int base, int lane,
+                                            Run<V, true> first, Acc<V, PV, true> &acc) {
     constexpr int Q = V / 4;
-    if (cnt <= 0) return;
-    const float *wp = a.w + (size_t)start * 4 + lane;
-    const int32_t *op = a.off + start + (lane & 15);
-    float a_nxt[Q];
-#pragma unroll
-    for (int q = 0; q < Q; ++q) a_nxt[q] = wp[(size_t)q * a.wplane];
-    int o_nxt = op[0];
+    constexpr int B = kCntAlign;  // columns whose LDS reads are in flight together
+    static_assert(B == 8, "a run of 16 columns is two batches");
+    Run<V, true> nxt = first;
     for (int j0 = 0; j0 < cnt; j0 += 16) {
         float aw[Q];
 #pragma unroll
-        for (int q = 0; q < Q; ++q) aw[q] = a_nxt[q];
-        const int ov = o_nxt;
-        if (j0 + 16 < cnt) {
-#pragma unroll
-            for (int q = 0; q < Q; ++q) a_nxt[q] = wp[(size_t)q * a.wplane + (size_t)(j0 + 16) * 4];
-            o_nxt = op[j0 + 16];
-        }
-        mfma_quad<0, V, PV, SH>(aw, ov, lds, base, acc);
-        if (j0 + 4 < cnt) mfma_quad<4, V, PV, SH>(aw, ov, lds, base, acc);
-        if (j0 + 8 < cnt) mfma_quad<8, V, PV, SH>(aw, ov, lds, base, acc);
-        if (j0 + 12 < cnt) mfma_quad<12, V, PV, SH>(aw, ov, lds, base, acc);
+        for (int q = 0; q < Q; ++q) aw[q] = nxt.a[q];
+        const int ov = nxt.o;
+        if (j0 + 16 < cnt) nxt = load_run<V, true>(a, start + j0 + 16, lane);
+        mfma_batch<0, B, V, PV, SH>(aw, ov, lds, base, acc);
+        if (j0 + 8 < cnt) mfma_batch<8, B, V, PV, SH>(aw, ov, lds, base, acc);
     }
 }
 
-// Same segment with plain FMAs; the V weights of a column come from scalar loads.
+// Same segment with plain FMAs; selectors and the V weights of a column come from
+// scalar loads.
 template <int V, int PV, int SH>
 __device__ __forceinline__ void mac_segment(const ConvArgs &a, int start, int cnt,
-                                            const float *lds, int base, int lane,
-                                            Acc<V, PV, false> &acc) {
+                                            const char *lds, int base, int lane,
+                                            Run<V, false> first, Acc<V, PV, false> &acc) {
     static_assert(V <= 4, "FMA path is built for V <= 4");
     (void)lane;
+    (void)first;
     cptr<float> wp = as_const(a.w) + (size_t)start * V;
     cptr<int32_t> op = as_const(a.off) + start;
     for (int j = 0; j < cnt; j += 4) {
@@ -197,7 +249,7 @@ __device__ __forceinline__ void mac_segment(const ConvArgs &a, int start, int cn
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             float x[PV];
-            lds_read<PV>(lds + base + (o[u] << SH), x);
+            lds_read<PV>(reinterpret_cast<const float *>(lds + base + (o[u] << SH)), x);
 #pragma unroll
             for (int v = 0; v < V; ++v) {
                 const float wv = wp[(j + u) * V + v];
@@ -226,19 +278,17 @@ __device__ __forceinline__ void stage_pw(const ConvArgs &a, float *lds, int q0, 
         const float *src = a.X + ((size_t)n * a.Cin + c0) * a.P + p;
         float *dst = lds + quad * 4;
         const int rows = c1 - c0;
+        constexpr int U = 8;  // independent 16-byte loads in flight per thread
         int r = r0;
-        for (; r + 3 * rpp < rows; r += 4 * rpp) {
-            f4 v0 = f4{0, 0, 0, 0}, v1 = v0, v2 = v0, v3 = v0;
-            if (valid) {
-                v0 = *reinterpret_cast<const f4 *>(src + (size_t)r * a.P);
-                v1 = *reinterpret_cast<const f4 *>(src + (size_t)(r + rpp) * a.P);
-                v2 = *reinterpret_cast<const f4 *>(src + (size_t)(r + 2 * rpp) * a.P);
-                v3 = *reinterpret_cast<const f4 *>(src + (size_t)(r + 3 * rpp) * a.P);
+        for (; r + (U - 1) * rpp < rows; r += U * rpp) {
+            f4 v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                v[u] = f4{0, 0, 0, 0};
+                if (valid) v[u] = *reinterpret_cast<const f4 *>(src + (size_t)(r + u * rpp) * a.P);
             }
-            *reinterpret_cast<f4 *>(dst + r * TP) = v0;
-            *reinterpret_cast<f4 *>(dst + (r + rpp) * TP) = v1;
-            *reinterpret_cast<f4 *>(dst + (r + 2 * rpp) * TP) = v2;
-            *reinterpret_cast<f4 *>(dst + (r + 3 * rpp) * TP) = v3;
+#pragma unroll
+            for (int u = 0; u < U; ++u) *reinterpret_cast<f4 *>(dst + (r + u * rpp) * TP) = v[u];
         }
         for (; r < rows; r += rpp) {
             f4 v0 = f4{0, 0, 0, 0};
@@ -254,19 +304,14 @@ __device__ __forceinline__ void stage_pw(const ConvArgs &a, float *lds, int q0, 
         const int ho = po / a.Wo, wo = po - ho * a.Wo;
         const float *src = a.X + ((size_t)n * a.Cin + c0) * a.Pin + (size_t)(ho * a.stride) * a.W + wo * a.stride;
         const int rows = c1 - c0;
+        constexpr int U = 16;  // independent 4-byte loads in flight per thread
         int r = r0;
-        for (; r + 3 * rpp < rows; r += 4 * rpp) {
-            float v0 = 0, v1 = 0, v2 = 0, v3 = 0;
-            if (valid) {
-                v0 = src[(size_t)r * a.Pin];
-                v1 = src[(size_t)(r + rpp) * a.Pin];
-                v2 = src[(size_t)(r + 2 * rpp) * a.Pin];
-                v3 = src[(size_t)(r + 3 * rpp) * a.Pin];
-            }
-            lds[r * TP + e] = v0;
-            lds[(r + rpp) * TP + e] = v1;
-            lds[(r + 2 * rpp) * TP + e] = v2;
-            lds[(r + 3 * rpp) * TP + e] = v3;
+        for (; r + (U - 1) * rpp < rows; r += U * rpp) {
+            float v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) v[u] = valid ? src[(size_t)(r + u * rpp) * a.Pin] : 0.f;
+#pragma unroll
+            for (int u = 0; u < U; ++u) lds[(r + u * rpp) * TP + e] = v[u];
         }
         for (; r < rows; r += rpp) lds[r * TP + e] = valid ? src[(size_t)r * a.Pin] : 0.f;
     }
@@ -324,35 +369,59 @@ __device__ __forceinline__ void store_group(const ConvArgs &a, const Acc<V, PV, 
 
 // Mode 1: all input channels of the pixel tile are resident in LDS (one chunk); each
 // wavefront walks through the groups of the workgroup's group tile, longest first.
+// The walk is software-pipelined two groups deep: the work record of group k+2 and the
+// first run of group k+1 are fetched while group k is multiplied, and always before
+// group k's output stores are issued (memory operations retire in order, so a load
+// queued behind stores would wait for them).
 template <int V, int PV, bool MF, bool VEC>
 __global__ void __launch_bounds__(1024) k_pw_resident(const ConvArgs a) {
     extern __shared__ float lds[];
     constexpr int TP = 64 * PV;
-    constexpr int SH = 6 + (PV == 4 ? 2 : PV == 2 ? 1 : 0);
+    constexpr int SH = PV == 4 ? 2 : PV == 2 ? 1 : 0;
     const int logical = logical_wg(a);
-    if (logical >= a.total_wgs) return;
+    if (logical >= a.total_wgs || (a.debug & 8)) return;
     const int pt = logical / a.ngt, gt = logical - pt * a.ngt;
     const int q0 = pt * TP;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), nw = blockDim.x >> 6;
+    const int g_begin = gt * a.gpt;
+    const int ng = min(a.G, g_begin + a.gpt) - g_begin;
+    // The wavefront's k-th group is entry k*nw + (wave, or mirrored in odd rounds) of
+    // the length-sorted list: a snake order that evens out the work per wavefront.
+    auto nth = [&](int k) { return k * nw + ((k & 1) ? nw - 1 - wave : wave); };
+    const bool any = nth(0) < ng;
+    Work w0{0, 0, 0, 0}, w1{0, 0, 0, 0};
+    Run<V, MF> run0, run1;
+    if (any) {
+        w0 = load_work(a.work, g_begin + nth(0));
+        run0 = load_run<V, MF>(a, w0.start, lane);
+        if (nth(1) < ng) w1 = load_work(a.work, g_begin + nth(1));
+    }
 
-    stage_pw<TP, VEC>(a, lds, q0, 0, a.Cin);
+    if (!(a.debug & 1)) stage_pw<TP, VEC>(a, lds, q0, 0, a.Cin);
     for (int t = tid; t < TP; t += blockDim.x) lds[a.KC * TP + t] = 0.f;  // the all-zero row
     __syncthreads();
+    if (!any) return;
 
     PixOut<PV> px;
     pix_out<PV, VEC>(a, q0, lane, px);
-    const int g_begin = gt * a.gpt;
-    const int ng = min(a.G, g_begin + a.gpt) - g_begin;
-    for (int r = 0; r * nw < ng; ++r) {
-        const int idx = r * nw + ((r & 1) ? nw - 1 - wave : wave);  // snake order evens the load
-        if (idx >= ng) continue;
-        const int g = __builtin_amdgcn_readfirstlane(as_const(a.order)[g_begin + idx]);
-        const Seg s = load_seg(a.seg, g);
+    const char *ldsb = reinterpret_cast<const char *>(lds);
+    const int base = lane * PV * 4;
+    for (int k = 0;; ++k) {
+        const bool more = nth(k + 1) < ng;
+        Work w2{0, 0, 0, 0};
+        if (more) {
+            run1 = load_run<V, MF>(a, w1.start, lane);
+            if (nth(k + 2) < ng) w2 = load_work(a.work, g_begin + nth(k + 2));
+        }
         Acc<V, PV, MF> acc;
         acc.zero();
-        mac_segment<V, PV, SH>(a, s.start, s.cnt, lds, lane * PV, lane, acc);
-        store_group<V, PV, MF, VEC>(a, acc, g, px);
+        if (!(a.debug & 2)) mac_segment<V, PV, SH>(a, w0.start, w0.cnt, ldsb, base, lane, run0, acc);
+        if (!(a.debug & 4)) store_group<V, PV, MF, VEC>(a, acc, w0.group, px);
+        if (!more) break;
+        w0 = w1;
+        w1 = w2;
+        run0 = run1;
     }
 }
 
@@ -362,7 +431,7 @@ template <int V, int PV, int UG, bool MF, bool VEC>
 __global__ void __launch_bounds__(512) k_pw_chunked(const ConvArgs a) {
     extern __shared__ float lds[];
     constexpr int TP = 64 * PV;
-    constexpr int SH = 6 + (PV == 4 ? 2 : PV == 2 ? 1 : 0);
+    constexpr int SH = PV == 4 ? 2 : PV == 2 ? 1 : 0;
     const int logical = logical_wg(a);
     if (logical >= a.total_wgs) return;
     const int pt = logical / a.ngt, gt = logical - pt * a.ngt;
@@ -371,13 +440,14 @@ __global__ void __launch_bounds__(512) k_pw_chunked(const ConvArgs a) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g_begin = gt * a.gpt;
     const int ng = min(a.G, g_begin + a.gpt) - g_begin;
+    const char *ldsb = reinterpret_cast<const char *>(lds);
 
-    int gid[UG];
+    int slot[UG];  // position of the wavefront's u-th group in the hand-out order, or -1
     Acc<V, PV, MF> acc[UG];
 #pragma unroll
     for (int u = 0; u < UG; ++u) {
         const int idx = wave * UG + u;
-        gid[u] = idx < ng ? __builtin_amdgcn_readfirstlane(as_const(a.order)[g_begin + idx]) : -1;
+        slot[u] = idx < ng ? g_begin + idx : -1;
         acc[u].zero();
     }
     for (int t = tid; t < TP; t += blockDim.x) lds[a.KC * TP + t] = 0.f;
@@ -386,19 +456,20 @@ __global__ void __launch_bounds__(512) k_pw_chunked(const ConvArgs a) {
         if (ch) __syncthreads();
         stage_pw<TP, VEC>(a, lds, q0, c0, c1);
         __syncthreads();
-        const int base = lane * PV - (c0 << SH);
+        const int base = lane * PV * 4 - c0 * (kRowBytes1 << SH);
 #pragma unroll
         for (int u = 0; u < UG; ++u) {
-            if (gid[u] < 0) continue;
-            const Seg s = load_seg(a.seg, (size_t)gid[u] * a.nchunks + ch);
-            mac_segment<V, PV, SH>(a, s.start, s.cnt, lds, base, lane, acc[u]);
+            if (slot[u] < 0) continue;
+            const Work s = load_work(a.work, (size_t)slot[u] * a.nchunks + ch);
+            mac_segment<V, PV, SH>(a, s.start, s.cnt, ldsb, base, lane, load_run<V, MF>(a, s.start, lane), acc[u]);
         }
     }
     PixOut<PV> px;
     pix_out<PV, VEC>(a, q0, lane, px);
 #pragma unroll
     for (int u = 0; u < UG; ++u)
-        if (gid[u] >= 0) store_group<V, PV, MF, VEC>(a, acc[u], gid[u], px);
+        if (slot[u] >= 0)
+            store_group<V, PV, MF, VEC>(a, acc[u], load_work(a.work, (size_t)slot[u] * a.nchunks).group, px);
 }
 
 // ------------------------------------------------------------------ 3x3 kernel
@@ -425,12 +496,13 @@ __global__ void __launch_bounds__(512) k_conv3(const ConvArgs a) {
     const int g_begin = gt * a.gpt;
     const int ng = min(a.G, g_begin + a.gpt) - g_begin;
 
-    int gid[UG];
+    const char *ldsb = reinterpret_cast<const char *>(lds);
+    int slot[UG];
     Acc<V, 1, MF> acc[UG];
 #pragma unroll
     for (int u = 0; u < UG; ++u) {
         const int idx = wave * UG + u;
-        gid[u] = idx < ng ? __builtin_amdgcn_readfirstlane(as_const(a.order)[g_begin + idx]) : -1;
+        slot[u] = idx < ng ? g_begin + idx : -1;
         acc[u].zero();
     }
     for (int t = tid; t < HA; t += nt) lds[a.KC * HA + t] = 0.f;
@@ -465,12 +537,12 @@ __global__ void __launch_bounds__(512) k_conv3(const ConvArgs a) {
             }
         }
         __syncthreads();
-        const int base = lane_base - c0 * HA;
+        const int base = (lane_base - c0 * HA) * 4;
 #pragma unroll
         for (int u = 0; u < UG; ++u) {
-            if (gid[u] < 0) continue;
-            const Seg s = load_seg(a.seg, (size_t)gid[u] * a.nchunks + ch);
-            mac_segment<V, 1, 0>(a, s.start, s.cnt, lds, base, lane, acc[u]);
+            if (slot[u] < 0) continue;
+            const Work s = load_work(a.work, (size_t)slot[u] * a.nchunks + ch);
+            mac_segment<V, 1, 0>(a, s.start, s.cnt, ldsb, base, lane, load_run<V, MF>(a, s.start, lane), acc[u]);
         }
     }
     const int oy = oy0 + ly, ox = ox0 + lx;
@@ -479,7 +551,8 @@ __global__ void __launch_bounds__(512) k_conv3(const ConvArgs a) {
     px.yoff[0] = (long long)n * a.Cout * a.P + (long long)oy * a.Wo + ox;
 #pragma unroll
     for (int u = 0; u < UG; ++u)
-        if (gid[u] >= 0) store_group<V, 1, MF, false>(a, acc[u], gid[u], px);
+        if (slot[u] >= 0)
+            store_group<V, 1, MF, false>(a, acc[u], load_work(a.work, (size_t)slot[u] * a.nchunks).group, px);
 }
 
 // ------------------------------------------------------------------ launcher
@@ -557,7 +630,7 @@ extern "C" int alcs_sparse_conv(const alcs_packed_t *Wp, const float *X_dev, con
     const int V = Wp->V, G = Wp->G;
     ConvArgs a{};
     a.X = X_dev; a.bias = bias_dev; a.Y = Y_dev;
-    a.seg = Wp->dev.seg; a.w = Wp->dev.w; a.order = Wp->dev.order;
+    a.work = Wp->dev.work; a.w = Wp->dev.w;
     a.off = Wp->dev.off[kernel == 3 && stride == 2 ? 1 : 0];
     a.wplane = (long long)L.nblk * L.VV;
     a.N = N; a.Cin = Cin; a.Cout = Cout; a.H = H; a.W = W; a.Ho = Ho; a.Wo = Wo; a.stride = stride;
@@ -565,6 +638,7 @@ extern "C" int alcs_sparse_conv(const alcs_packed_t *Wp, const float *X_dev, con
     if ((long long)N * P > INT32_MAX - 1024) return ALCS_E_UNSUPPORTED;
     a.NP = (int)((long long)N * P);
     a.G = G; a.nchunks = L.nchunks; a.KC = L.KC;
+    a.debug = T.debug;
 
     bool mfma = V >= 4;
     if (V == 4 && T.path == 1) mfma = false;
@@ -591,8 +665,10 @@ extern "C" int alcs_sparse_conv(const alcs_packed_t *Wp, const float *X_dev, con
             if (lds > kMaxLds) return ALCS_E_UNSUPPORTED;
             a.npt = ceil_div(a.NP, TP);
             // split the groups over several workgroups only when there are too few pixel tiles
+            // (one workgroup per compute unit is the aim: every extra group tile re-stages the
+            // pixel tile's rows)
             int ngt = 1;
-            if (a.npt < 2 * kCUs) ngt = std::min(std::max(1, G / 8), ceil_div(2 * kCUs, a.npt));
+            if (a.npt < kCUs) ngt = std::min(std::max(1, G / 4), std::max(1, kCUs / a.npt));
             if (T.group_tiles > 0) ngt = std::min(T.group_tiles, G);
             a.gpt = ceil_div(G, ngt);
             a.ngt = ceil_div(G, a.gpt);
