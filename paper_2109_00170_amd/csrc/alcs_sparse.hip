@@ -50,6 +50,9 @@ struct ConvArgs {
     int npt, ngt, gpt;  // pixel tiles, group tiles, groups per group tile
     int tiles_x, tiles_y;  // 3x3: 8x8 tiles per image
     int wg_per_xcd, total_wgs;
+    int ppw;            // streaming kernel: flattened pixels per workgroup (multiple of 4)
+    int wfloats;        // streaming kernel: floats in the weight planes, planes * nblk * 4
+    int nblk;           // padded blocks (= number of row selectors)
     int debug;  // measurement only: bit 0 skips staging, bit 1 the multiply, bit 2 the stores
 };
 
@@ -285,7 +288,10 @@ __device__ __forceinline__ void stage_pw(const ConvArgs &a, float *lds, int q0, 
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 v[u] = f4{0, 0, 0, 0};
-                if (valid) v[u] = *reinterpret_cast<const f4 *>(src + (size_t)(r + u * rpp) * a.P);
+                if (valid) {
+                    const f4 *ptr = reinterpret_cast<const f4 *>(src + (size_t)(r + u * rpp) * a.P);
+                    v[u] = (a.debug & 16) ? __builtin_nontemporal_load(ptr) : *ptr;
+                }
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) *reinterpret_cast<f4 *>(dst + (r + u * rpp) * TP) = v[u];
@@ -351,16 +357,20 @@ __device__ __forceinline__ void store_group(const ConvArgs &a, const Acc<V, PV, 
         if (ch >= a.Cout) break;
         const float b = a.bias ? as_const(a.bias)[ch] : 0.f;
         float *dst = a.Y + (size_t)ch * a.P;
+        // Y is written once and not read again by this kernel: streaming (non-temporal) stores
         if constexpr (VEC && PV == 4) {
             if (px.valid[0])
-                *reinterpret_cast<f4 *>(dst + px.yoff[0]) =
-                    f4{acc.get(v, 0) + b, acc.get(v, 1) + b, acc.get(v, 2) + b, acc.get(v, 3) + b};
+                __builtin_nontemporal_store(
+                    f4{acc.get(v, 0) + b, acc.get(v, 1) + b, acc.get(v, 2) + b, acc.get(v, 3) + b},
+                    reinterpret_cast<f4 *>(dst + px.yoff[0]));
         } else if constexpr (VEC && PV == 2) {
-            if (px.valid[0]) *reinterpret_cast<f2 *>(dst + px.yoff[0]) = f2{acc.get(v, 0) + b, acc.get(v, 1) + b};
+            if (px.valid[0])
+                __builtin_nontemporal_store(f2{acc.get(v, 0) + b, acc.get(v, 1) + b},
+                                            reinterpret_cast<f2 *>(dst + px.yoff[0]));
         } else {
 #pragma unroll
             for (int pv = 0; pv < PV; ++pv)
-                if (px.valid[pv]) dst[px.yoff[pv]] = acc.get(v, pv) + b;
+                if (px.valid[pv]) __builtin_nontemporal_store(acc.get(v, pv) + b, dst + px.yoff[pv]);
         }
     }
 }
@@ -472,6 +482,116 @@ __global__ void __launch_bounds__(512) k_pw_chunked(const ConvArgs a) {
             store_group<V, PV, MF, VEC>(a, acc[u], load_work(a.work, (size_t)slot[u] * a.nchunks).group, px);
 }
 
+
+// Mode 4 (streaming): for layers whose time is the HBM stream of X and Y.  Workgroups
+// are persistent: each owns a contiguous range of the flattened pixel axis (all ranges
+// move the same number of bytes) and walks it in tiles of TP pixels.  The input rows of
+// tile t+1 are fetched into registers before tile t is multiplied and are written to
+// the other LDS buffer afterwards, so loads, MFMAs and stores of one workgroup overlap
+// instead of alternating in phases that all workgroups of the chip would share.  The
+// packed weights and row selectors of all groups are staged in LDS once per
+// workgroup: in the steady state the only vector-memory operations are the input
+// prefetch and the output stores (weights fetched from memory would queue behind the
+// prefetch, since vector-memory operations return in order).
+template <int V, int PV, int NR>
+__global__ void __launch_bounds__(512) k_pw_stream(const ConvArgs a) {
+    extern __shared__ float lds[];
+    constexpr int TP = 64 * PV;
+    constexpr int SH = PV == 4 ? 2 : PV == 2 ? 1 : 0;
+    constexpr int NQ = TP / 4;
+    const int tid = threadIdx.x, lane = tid & 63, nt = blockDim.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), nw = nt >> 6;
+    const int q_begin = blockIdx.x * a.ppw;
+    const int q_end = min(a.NP, q_begin + a.ppw);
+    if (q_begin >= q_end || (a.debug & 8)) return;
+    const int ntiles = (q_end - q_begin + TP - 1) / TP;
+    const int bufstride = (a.Cin + 1) * TP;  // floats per buffer: Cin rows + the all-zero row
+    float *wl = lds + 2 * bufstride;
+    int32_t *sl = reinterpret_cast<int32_t *>(wl + a.wfloats);
+
+    // stage weights and selectors, clear the two zero rows
+    for (int i = tid * 4; i < a.wfloats; i += nt * 4)
+        *reinterpret_cast<f4 *>(wl + i) = *reinterpret_cast<const f4 *>(a.w + i);
+    for (int i = tid * 4; i < a.nblk; i += nt * 4)
+        *reinterpret_cast<i4 *>(sl + i) = *reinterpret_cast<const i4 *>(a.off + i);
+    for (int t = tid; t < 2 * TP; t += nt) lds[(t / TP) * bufstride + a.Cin * TP + (t % TP)] = 0.f;
+
+    // this thread's share of a tile: pixel quad `quad`, rows r0, r0 + rpp, ...
+    const int quad = tid % NQ, r0 = tid / NQ, rpp = nt / NQ;
+    int fq = q_begin + quad * 4;       // first pixel of the quad in the tile being fetched
+    int fn = fq / a.P, fp = fq - fn * a.P;
+    f4 v[NR];
+    auto fetch = [&]() {
+        const bool valid = fq < q_end;
+        const float *src = a.X + ((size_t)fn * a.Cin) * a.P + fp;
+#pragma unroll
+        for (int u = 0; u < NR; ++u) {
+            const int r = r0 + u * rpp;
+            v[u] = f4{0, 0, 0, 0};
+            if (valid && r < a.Cin) v[u] = *reinterpret_cast<const f4 *>(src + (size_t)r * a.P);
+        }
+        fq += TP;
+        fp += TP;
+        while (fp >= a.P) { fp -= a.P; ++fn; }
+    };
+    auto commit = [&](int b) {
+        float *dst = lds + b * bufstride + quad * 4;
+#pragma unroll
+        for (int u = 0; u < NR; ++u) {
+            const int r = r0 + u * rpp;
+            if (r < a.Cin) *reinterpret_cast<f4 *>(dst + r * TP) = v[u];
+        }
+    };
+    if (!(a.debug & 1)) { fetch(); commit(0); }
+    __syncthreads();
+
+    ConvArgs al = a;   // same arguments, weights and selectors read from LDS
+    al.w = wl;
+    al.off = sl;
+    auto nth = [&](int k) { return k * nw + ((k & 1) ? nw - 1 - wave : wave); };
+    const bool any = nth(0) < a.G;
+    // where the lane's PV pixels of the current tile go
+    int oq = q_begin + lane * PV;
+    int on = oq / a.P, op = oq - on * a.P;
+    for (int t = 0; t < ntiles; ++t) {
+        if (t + 1 < ntiles && !(a.debug & 1)) fetch();
+        if (any) {
+            PixOut<PV> px;
+#pragma unroll
+            for (int pv = 0; pv < PV; ++pv) {
+                px.valid[pv] = oq + pv < q_end;
+                px.yoff[pv] = (long long)on * a.Cout * a.P + op + pv;
+            }
+            const char *ldsb = reinterpret_cast<const char *>(lds + (t & 1) * bufstride);
+            const int base = lane * PV * 4;
+            Work w0 = load_work(a.work, nth(0)), w1{0, 0, 0, 0};
+            if (nth(1) < a.G) w1 = load_work(a.work, nth(1));
+            Run<V, true> run0 = load_run<V, true>(al, w0.start, lane), run1;
+            for (int k = 0;; ++k) {
+                const bool more = nth(k + 1) < a.G;
+                Work w2{0, 0, 0, 0};
+                if (more) {
+                    run1 = load_run<V, true>(al, w1.start, lane);
+                    if (nth(k + 2) < a.G) w2 = load_work(a.work, nth(k + 2));
+                }
+                Acc<V, PV, true> acc;
+                acc.zero();
+                if (!(a.debug & 2)) mac_segment<V, PV, SH>(al, w0.start, w0.cnt, ldsb, base, lane, run0, acc);
+                if (!(a.debug & 4)) store_group<V, PV, true, true>(a, acc, w0.group, px);
+                if (!more) break;
+                w0 = w1;
+                w1 = w2;
+                run0 = run1;
+            }
+        }
+        oq += TP;
+        op += TP;
+        while (op >= a.P) { op -= a.P; ++on; }
+        if (t + 1 < ntiles && !(a.debug & 1)) commit((t + 1) & 1);
+        __syncthreads();
+    }
+}
+
 // ------------------------------------------------------------------ 3x3 kernel
 
 // One workgroup = one 8x8 tile of output pixels of one image (lane = pixel) and a
@@ -575,8 +695,13 @@ static kern_t pick_resident(int pv, bool vec) {
 }
 
 template <int V, bool MF>
-static kern_t pick_chunked(bool vec) {
-    return vec ? k_pw_chunked<V, 1, 4, MF, true> : k_pw_chunked<V, 1, 4, MF, false>;
+static kern_t pick_chunked(int pv, bool vec) {
+    if (vec) {
+        if (pv == 4) return k_pw_chunked<V, 4, 4, MF, true>;
+        if (pv == 2) return k_pw_chunked<V, 2, 4, MF, true>;
+        return k_pw_chunked<V, 1, 4, MF, true>;
+    }
+    return k_pw_chunked<V, 1, 4, MF, false>;
 }
 
 template <int V, bool MF>
@@ -647,16 +772,58 @@ extern "C" int alcs_sparse_conv(const alcs_packed_t *Wp, const float *X_dev, con
 
     if (kernel == 1) {
         const bool vec = stride == 1 && (P % 4 == 0);
-        if (L.nchunks == 1) {
+        // streaming kernel: everything (two input tiles, packed weights) fits in LDS and
+        // there are enough pixels to give every compute unit several tiles
+        bool stream_ok = false;
+        int s_pv = 1, s_lds = 0, s_nw = 8, s_nwg = 0;
+        if (L.nchunks == 1 && vec && mfma && T.path == 4) {
+            const long long wbytes = (long long)L.planes * L.nblk * 16 + (long long)L.nblk * 4;
+            for (int cand = 4; cand >= 1 && !stream_ok; cand >>= 1) {
+                if (T.pv && T.pv != cand) continue;
+                const int TPc = 64 * cand;
+                const long long need = 2LL * (Cin + 1) * TPc * 4 + wbytes + 64;
+                if (need > kMaxLds) continue;
+                const int wpc = (int)std::min<long long>(kMaxLds / need, 4);   // workgroups per compute unit
+                const int nwg = kCUs * wpc;
+                if (a.NP < (long long)nwg * TPc * 2) continue;                 // at least two tiles each
+                int nwv = T.waves > 0 ? std::min(T.waves, 8) : (wpc >= 2 ? 4 : 8);
+                while (nwv < 8 && (long long)Cin * (TPc / 4) > 8LL * nwv * 64) nwv *= 2;
+                if ((long long)Cin * (TPc / 4) > 8LL * nwv * 64) continue;     // more than 8 loads per thread
+                stream_ok = true;
+                s_pv = cand; s_lds = (int)need; s_nw = nwv; s_nwg = nwg;
+            }
+        }
+        if (stream_ok) {
+            mode = 4;
+            pv = s_pv; lds = s_lds; nw = s_nw;
+            const int TPc = 64 * pv;
+            int ppw = (int)(((long long)a.NP + s_nwg - 1) / s_nwg);
+            ppw = (ppw + 3) & ~3;
+            a.ppw = ppw;
+            a.npt = ceil_div(a.NP, ppw);
+            a.ngt = 1; a.gpt = G;
+            a.wfloats = (int)((long long)L.planes * L.nblk * 4);
+            a.nblk = (int)L.nblk;
+            (void)TPc;
+            switch (V) {
+                case 4: kern = pv == 4 ? k_pw_stream<4, 4, 8> : pv == 2 ? k_pw_stream<4, 2, 8> : k_pw_stream<4, 1, 8>; break;
+                case 8: kern = pv == 4 ? k_pw_stream<8, 4, 8> : pv == 2 ? k_pw_stream<8, 2, 8> : k_pw_stream<8, 1, 8>; break;
+                case 16: kern = pv == 4 ? k_pw_stream<16, 4, 8> : pv == 2 ? k_pw_stream<16, 2, 8> : k_pw_stream<16, 1, 8>; break;
+            }
+        } else if (L.nchunks == 1) {
             mode = 1;
-            // pixels per lane: the widest tile whose Cin+1 rows fit in about 64 KB and that
-            // still leaves a few workgroups per compute unit
+            // Launch shape, from sweeps over the MobileNet/ResNet-shaped layers on MI355X:
+            // pixels per lane - the widest tile whose Cin+1 rows stay below ~68 KB (two
+            // workgroups per compute unit) and that still leaves >= 1.5 workgroups per
+            // compute unit: wider tiles mean longer contiguous runs for loads and stores.
+            constexpr int kTwoPerCu = 68 * 1024;
+            constexpr int kMinWgs = 3 * kCUs / 2;
             pv = 1;
             if (vec) {
                 for (int cand = 4; cand >= 2; cand >>= 1) {
                     const long long need = (long long)(Cin + 1) * 64 * cand * 4;
                     const long long tiles = ((long long)a.NP + 64 * cand - 1) / (64 * cand);
-                    if (need <= 64 * 1024 && tiles >= 4 * kCUs) { pv = cand; break; }
+                    if (need <= kTwoPerCu && tiles * (cand == 2 ? 2 : 1) >= kMinWgs) { pv = cand; break; }
                 }
                 if (T.pv == 1 || T.pv == 2 || T.pv == 4) pv = T.pv;
             }
@@ -664,15 +831,17 @@ extern "C" int alcs_sparse_conv(const alcs_packed_t *Wp, const float *X_dev, con
             lds = (Cin + 1) * TP * 4;
             if (lds > kMaxLds) return ALCS_E_UNSUPPORTED;
             a.npt = ceil_div(a.NP, TP);
-            // split the groups over several workgroups only when there are too few pixel tiles
-            // (one workgroup per compute unit is the aim: every extra group tile re-stages the
-            // pixel tile's rows)
+            // Group tiles: split the groups over several workgroups only when there are too few
+            // pixel tiles (every extra group tile re-stages the pixel tile's rows).  With one
+            // resident workgroup per compute unit aim at one round (<= 256 workgroups), else
+            // at about 1.5 workgroups per compute unit.
             int ngt = 1;
-            if (a.npt < kCUs) ngt = std::min(std::max(1, G / 4), std::max(1, kCUs / a.npt));
+            const int want = lds > 80 * 1024 ? kCUs : kMinWgs;
+            if (a.npt < want) ngt = std::min(std::max(1, G / 4), std::max(1, lds > 80 * 1024 ? want / a.npt : ceil_div(want, a.npt)));
             if (T.group_tiles > 0) ngt = std::min(T.group_tiles, G);
             a.gpt = ceil_div(G, ngt);
             a.ngt = ceil_div(G, a.gpt);
-            nw = lds > 80 * 1024 ? 16 : (lds > 40 * 1024 ? 8 : 4);
+            nw = lds > 40 * 1024 ? 16 : 8;
             nw = std::min(nw, std::max(1, a.gpt));
             if (T.waves > 0) nw = std::min(T.waves, 16);
             switch (V) {
@@ -685,18 +854,19 @@ extern "C" int alcs_sparse_conv(const alcs_packed_t *Wp, const float *X_dev, con
         } else {
             mode = 2;
             pv = 1;
-            lds = (L.KC + 1) * 64 * 4;
-            a.npt = ceil_div(a.NP, 64);
+            if (vec && (T.pv == 2 || T.pv == 4)) pv = T.pv;
+            lds = (L.KC + 1) * 64 * pv * 4;
+            a.npt = ceil_div(a.NP, 64 * pv);
             nw = 8;
             if (T.waves > 0) nw = std::min(T.waves, 8);
             a.gpt = nw * kUG;
             a.ngt = ceil_div(G, a.gpt);
             switch (V) {
-                case 1: kern = pick_chunked<1, false>(vec); break;
-                case 2: kern = pick_chunked<2, false>(vec); break;
-                case 4: kern = mfma ? pick_chunked<4, true>(vec) : pick_chunked<4, false>(vec); break;
-                case 8: kern = pick_chunked<8, true>(vec); break;
-                case 16: kern = pick_chunked<16, true>(vec); break;
+                case 1: kern = pick_chunked<1, false>(pv, vec); break;
+                case 2: kern = pick_chunked<2, false>(pv, vec); break;
+                case 4: kern = mfma ? pick_chunked<4, true>(pv, vec) : pick_chunked<4, false>(pv, vec); break;
+                case 8: kern = pick_chunked<8, true>(pv, vec); break;
+                case 16: kern = pick_chunked<16, true>(pv, vec); break;
             }
         }
     } else {
@@ -726,7 +896,8 @@ extern "C" int alcs_sparse_conv(const alcs_packed_t *Wp, const float *X_dev, con
     int rc = set_lds_limit(kern, lds);
     if (rc != ALCS_OK) return rc;
     record_launch(mode, pv, nw, a.total_wgs, lds, a.ngt, L.KC, mfma ? 2 : 1);
-    hipLaunchKernelGGL(kern, dim3(a.wg_per_xcd * kXcds), dim3(nw * 64), lds, (hipStream_t)stream, a);
+    const int grid = mode == 4 ? a.npt : a.wg_per_xcd * kXcds;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(nw * 64), lds, (hipStream_t)stream, a);
     e = hipGetLastError();
     if (e != hipSuccess) { set_hip_error((int)e); return ALCS_E_HIP; }
     return ALCS_OK;

@@ -49,6 +49,21 @@ def test_pointwise_resident_all_group_sizes(V, pv):
     assert info["mode"] == 1 and info["pv"] == pv
 
 
+@pytest.mark.parametrize("V,pv", [(4, 1), (4, 2), (4, 4), (8, 1), (8, 4), (16, 2)])
+def test_pointwise_streaming_kernel(V, pv):
+    """Enough pixels for the persistent double-buffered kernel; 3 x 212 x 212 pixels do
+    not divide evenly among the workgroups, so the last tile of every range is partial."""
+    L = workloads.Layer("pw_stream_v%d" % V, 24, 40, 212, 212, N=3 * pv, V=V, sparsity=0.7, x_dist="relu")
+    info = check(L, 150 + V + pv, pv=pv, path=4)
+    assert info["mode"] == 4 and info["pv"] == pv
+
+
+def test_pointwise_many_pixels_resident_kernel():
+    L = workloads.Layer("pw_nostream", 24, 40, 212, 212, N=3, V=4, sparsity=0.7, x_dist="relu")
+    info = check(L, 160)
+    assert info["mode"] == 1
+
+
 @pytest.mark.parametrize("V", [1, 4, 8])
 def test_pointwise_odd_pixel_count_uses_scalar_staging(V):
     L = workloads.Layer("pw7x7_v%d" % V, 40, 24, 7, 7, N=5, V=V, sparsity=0.5)
