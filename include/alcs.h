@@ -151,18 +151,31 @@ int alcs_dense_conv(const float *W_dev, const float *X_dev, const float *bias_de
                     int N, int Cin, int Cout, int H, int W, int kernel, int stride, void *stream);
 
 /*
- * Tuning knobs for measurements (process-wide, not thread-safe against concurrent
- * conv calls).  name is one of "pv" (pixels per lane 1/2/4, 0 = automatic),
- * "waves" (wavefronts per workgroup, 0 = automatic), "group_tiles" (0 = automatic),
- * "path" (0 = automatic, 1 = force plain-FMA inner loop, 2 = force MFMA inner loop).
+ * Tuning knobs for measurements and tests (process-wide, not thread-safe against
+ * concurrent calls).  A value of 0 restores the automatic choice.
+ *   read by alcs_sparse_conv:
+ *     "pv"              pixels per lane of the 1x1 kernels: 1, 2 or 4
+ *     "waves"           wavefronts per workgroup
+ *     "group_tiles"     number of workgroups that share one pixel tile
+ *     "path"            1 = plain-FMA inner loop where it exists (V = 4), 2 = MFMA inner
+ *                       loop, 4 = persistent double-buffered 1x1 kernel where applicable
+ *     "debug"           measurement only, results become meaningless: bit 0 skips input
+ *                       staging, bit 1 the multiply, bit 2 the output stores, bit 3
+ *                       makes the kernel return at once
+ *   read by alcs_pack_weights (they shape the device layout of handles packed later):
+ *     "chunk_channels"  input channels per LDS chunk (forces the chunked kernels)
+ *     "group_slots"     output-channel groups multiplied per wavefront: 1, 2 or 4
+ *     "groups_per_wave" reserved
  * Unknown names return ALCS_E_INVALID_ARG.  Results never depend on the knobs beyond
- * floating-point summation order.
+ * floating-point summation order (except "debug").
  */
 int alcs_set_tuning(const char *name, int value);
 
 /* What the last alcs_sparse_conv call of this thread launched: fills up to `cap`
- * ints {mode, pv, waves, workgroups, lds_bytes, group_tiles, chunk_channels, path}
- * and returns how many were written.  For tests and benchmarks. */
+ * ints {mode (1 = all input channels resident in LDS, 2 = chunked, 3 = 3x3,
+ * 4 = persistent double-buffered), pv, waves, workgroups, lds_bytes, group_tiles,
+ * chunk_channels, path, group_slots} and returns how many were written.  For tests
+ * and benchmarks. */
 int alcs_last_launch(int *out, int cap);
 
 #ifdef __cplusplus

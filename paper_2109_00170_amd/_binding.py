@@ -197,7 +197,8 @@ def alcs_set_tuning(name: str, value: int) -> None:
 
 
 def alcs_last_launch() -> dict:
-    buf = (ctypes.c_int * 8)()
-    n = load_library().alcs_last_launch(buf, 8)
-    keys = ["mode", "pv", "waves", "workgroups", "lds_bytes", "group_tiles", "chunk_channels", "path"]
+    buf = (ctypes.c_int * 9)()
+    n = load_library().alcs_last_launch(buf, 9)
+    keys = ["mode", "pv", "waves", "workgroups", "lds_bytes", "group_tiles", "chunk_channels", "path",
+            "group_slots"]
     return {k: int(buf[i]) for i, k in enumerate(keys[:n])}

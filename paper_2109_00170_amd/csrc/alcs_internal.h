@@ -9,50 +9,65 @@
 
 namespace alcs {
 
-// Blocks are padded so that a wavefront can fetch the weights of 16 consecutive kept
-// columns of one group with a single coalesced 256-byte load, and so that the inner
-// loop can run in branch-free batches of 8 columns without a remainder.
-constexpr int kSegAlign = 16;  // every (group, chunk) segment starts at a multiple of 16 blocks
-constexpr int kCntAlign = 8;   // and its padded length is a multiple of 8 blocks
+// Padding rules of the layout the kernels read: a wavefront fetches the weights of 16
+// consecutive kept columns ("a run") with coalesced 256-byte loads, and the inner loop
+// runs in branch-free batches of 8 columns.
+constexpr int kSegAlign = 16;  // every segment starts at a multiple of 16 columns
+constexpr int kCntAlign = 8;   // and its padded length is a multiple of 8 columns
 
 // Geometry of the 3x3 kernels: an 8x8 tile of output pixels per wavefront, staged in
-// LDS with its halo, one plane of kHalo*kHalo floats per input channel.
+// LDS with its halo, one plane of halo*halo floats per input channel.
 constexpr int kTile3 = 8;
 inline constexpr int halo3(int stride) { return (kTile3 - 1) * stride + 3; }
 
-// Bytes per LDS row that the stored 1x1 row selectors assume (a 64-pixel fp32 tile);
-// kernels with 2 or 4 pixels per lane scale the selector by that factor.
+// Bytes per LDS row that the stored 1x1 row selectors assume with one group per
+// wavefront (a 64-pixel fp32 tile); with GS groups per wavefront the tile has 64/GS
+// pixels and the selectors are scaled down accordingly.  Kernels with 2 or 4 pixels
+// per lane scale the selector up by that factor.
 constexpr int kRowBytes1 = 256;
 
-struct Seg {
-    int32_t start;  // first padded block of the segment (multiple of kSegAlign)
-    int32_t cnt;    // padded number of blocks to process (multiple of kCntAlign, may be 0)
-};
+constexpr int kMaxSlots = 4;
 
-// What a wavefront needs to process one (group, chunk) pair, in the order the kernels
-// hand out work: groups by descending kept-column count.
+// What a wavefront needs to process one bundle of GS groups inside one channel chunk.
+// Bundles are formed from the groups sorted by descending kept-column count (slot s of
+// bundle b is the (b*GS+s)-th longest group) and handed out in that order.
 struct Work {
-    int32_t start, cnt, group, reserved;
+    int32_t start;             // first padded column of the segment (multiple of kSegAlign)
+    int32_t cnt;               // padded number of columns to process (multiple of kCntAlign, may be 0)
+    int32_t group[kMaxSlots];  // output-channel group of every slot, -1 for an unused slot
+    int32_t reserved[2];
 };
 
 // The layout the kernels read ("tuned layout").  Input channels are cut into chunks
 // of KC channels; the kept columns of a group are ascending in c, so each
 // (group, chunk) pair owns a contiguous run of the group's columns = one segment.
+// With GS > 1 the segments of the GS groups of a bundle are padded to a common length
+// and interleaved, so that one wavefront multiplies GS groups at once, each on 64/GS
+// pixels (lanes [s*64/GS, (s+1)*64/GS) belong to slot s).
+//
+// Addressing, for bundle column j (0-based inside the segment), slot s, weight row
+// 4q+i, with R = (start + j) / 16 * 16 the first column of j's run, c = j % 16 and
+// CPA = 16 / GS columns per weight register:
+//   weight    w[q * wplane + R*4*GS + (c / CPA)*64 + s*(64/GS) + (c % CPA)*4 + i]
+//   selector  off[t][R*GS + s*16 + c]
+// which for GS = 1 is w[q*wplane + (start+j)*VV + i] and off[t][start + j].
 struct Layout {
     int KC = 0;       // input channels per chunk (the LDS tile holds KC rows + 1 zero row)
     int nchunks = 0;  // ceil(Cin / KC)
+    int GS = 1;       // groups per wavefront (1, 2 or 4); > 1 only with V >= 4, kernel 1, one chunk
+    int nbundles = 0; // ceil(G / GS)
     int planes = 0;   // ceil(V / 4): weight rows 4q..4q+3 of every block live in plane q
     int VV = 0;       // min(V, 4) floats per block and plane
-    int64_t nblk = 0; // padded blocks in total (multiple of kSegAlign)
+    int64_t ncol = 0; // padded columns in total (multiple of kSegAlign)
+    int64_t wplane = 0;  // floats per weight plane: ncol * VV * GS
     int noff = 0;     // 1 for kernel 1; 2 for kernel 3 (stride 1, stride 2 geometry)
-    std::vector<Seg> seg;          // [G * nchunks], index g * nchunks + chunk
-    std::vector<float> w;          // [planes][nblk * VV]
-    std::vector<int32_t> off[2];   // [nblk] each; LDS row selector of every block, in bytes:
-                                   //   kernel 1: c * kRowBytes1             (pad: (c0 + KC) * kRowBytes1)
+    std::vector<float> w;          // [planes][wplane]
+    std::vector<int32_t> off[2];   // [ncol * GS] each; LDS row selector of every block, in bytes:
+                                   //   kernel 1: c * kRowBytes1 / GS        (pad: (c0 + KC) * kRowBytes1 / GS)
                                    //   kernel 3: 4*(c*HA + r*halo + s)      (pad: 4*(c0 + KC)*HA)
                                    // with c the input channel and c0 the first channel of the block's chunk
     std::vector<int32_t> order;    // [G] groups by descending kept-column count
-    std::vector<Work> work;        // [G * nchunks], index i * nchunks + chunk for the i-th group of `order`
+    std::vector<Work> work;        // [nbundles * nchunks], index b * nchunks + chunk
 };
 
 struct DeviceCopy {
@@ -80,14 +95,14 @@ struct alcs_packed {
 namespace alcs {
 
 void set_hip_error(int e);
-int build_layout(alcs_packed *p, int KC);
+int build_layout(alcs_packed *p, int KC, int GS);
 int upload(alcs_packed *p);
 void release_device(alcs_packed *p);
 
 struct Tuning {
-    int pv = 0, waves = 0, group_tiles = 0, path = 0, kc = 0, ug = 0, debug = 0;
+    int pv = 0, waves = 0, group_tiles = 0, path = 0, kc = 0, ug = 0, debug = 0, gs = 0;
 };
 Tuning &tuning();
-void record_launch(int mode, int pv, int waves, int wgs, int lds, int gtiles, int kc, int path);
+void record_launch(int mode, int pv, int waves, int wgs, int lds, int gtiles, int kc, int path, int gs);
 
 }  // namespace alcs

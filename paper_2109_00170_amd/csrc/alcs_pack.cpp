@@ -14,7 +14,7 @@
 namespace alcs {
 
 static thread_local int g_last_hip = 0;
-static thread_local int g_last_launch[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+static thread_local int g_last_launch[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
 void set_hip_error(int e) { g_last_hip = e; }
 
 Tuning &tuning() {
@@ -22,8 +22,8 @@ Tuning &tuning() {
     return t;
 }
 
-void record_launch(int mode, int pv, int waves, int wgs, int lds, int gtiles, int kc, int path) {
-    int v[8] = {mode, pv, waves, wgs, lds, gtiles, kc, path};
+void record_launch(int mode, int pv, int waves, int wgs, int lds, int gtiles, int kc, int path, int gs) {
+    int v[9] = {mode, pv, waves, wgs, lds, gtiles, kc, path, gs};
     std::memcpy(g_last_launch, v, sizeof(v));
 }
 
@@ -33,87 +33,115 @@ static inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * 
 static inline int col_channel(int col, int kk) { return col / kk; }
 
 // LDS row selector of a real block (see Layout::off): a byte offset.
-static inline int32_t off_of(int col, int k, int table) {
-    if (k == 1) return col * kRowBytes1;
+static inline int32_t off_of(int col, int k, int table, int GS) {
+    if (k == 1) return col * (kRowBytes1 / GS);
     int c = col / 9, tap = col % 9, r = tap / 3, s = tap % 3;
     int halo = halo3(table + 1);
     return (c * halo * halo + r * halo + s) * 4;
 }
 
-static inline int32_t pad_off(int c0, int KC, int k, int table) {
-    if (k == 1) return (c0 + KC) * kRowBytes1;
+static inline int32_t pad_off(int c0, int KC, int k, int table, int GS) {
+    if (k == 1) return (c0 + KC) * (kRowBytes1 / GS);
     int halo = halo3(table + 1);
     return (c0 + KC) * halo * halo * 4;
 }
 
-int build_layout(alcs_packed *p, int KC) {
+// Index of (bundle column `col` counted from the start of the arrays, slot s) in a
+// weight plane (row i) and in a selector table.
+static inline size_t w_index(const Layout &L, int64_t col, int s, int i) {
+    const int GS = L.GS, cpa = 16 / GS;
+    const int64_t R = col / 16 * 16;
+    const int c = (int)(col % 16);
+    if (L.VV < 4) return (size_t)(col * L.VV + i);  // V < 4: GS == 1, VV floats per column
+    return (size_t)(R * 4 * GS + (c / cpa) * 64 + s * (64 / GS) + (c % cpa) * 4 + i);
+}
+static inline size_t off_index(const Layout &L, int64_t col, int s) {
+    const int64_t R = col / 16 * 16;
+    return (size_t)(R * L.GS + s * 16 + col % 16);
+}
+
+int build_layout(alcs_packed *p, int KC, int GS) {
     Layout &L = p->lay;
     const int k = p->k, kk = k * k, V = p->V, G = p->G;
     L = Layout();
     L.KC = KC;
     L.nchunks = (p->Cin + KC - 1) / KC;
+    L.GS = GS;
+    L.nbundles = (G + GS - 1) / GS;
     L.planes = V >= 4 ? V / 4 : 1;
     L.VV = V >= 4 ? 4 : V;
     L.noff = k == 1 ? 1 : 2;
+    if (GS != 1 && (GS != 2 && GS != 4)) return ALCS_E_INVALID_ARG;
+    if (GS > 1 && (V < 4 || k != 1 || L.nchunks != 1)) return ALCS_E_INVALID_ARG;
     try {
-        L.seg.assign((size_t)G * L.nchunks, Seg{0, 0});
-        // pass 1: segment boundaries
-        int64_t cur = 0;
-        std::vector<int32_t> lo((size_t)G * L.nchunks), hi((size_t)G * L.nchunks);
-        for (int g = 0; g < G; ++g) {
-            int32_t t = p->row_ptr[g], end = p->row_ptr[g + 1];
-            for (int ch = 0; ch < L.nchunks; ++ch) {
-                int c_end = std::min(p->Cin, (ch + 1) * KC);
-                int32_t a = t;
-                while (t < end && col_channel(p->col_idx[t], kk) < c_end) ++t;
-                size_t si = (size_t)g * L.nchunks + ch;
-                lo[si] = a;
-                hi[si] = t;
-                int32_t cntp = (int32_t)round_up(t - a, kCntAlign);
-                if (cur > INT32_MAX - 64) return ALCS_E_UNSUPPORTED;
-                L.seg[si] = Seg{(int32_t)cur, cntp};
-                cur += round_up(cntp, kSegAlign);
-            }
-        }
-        L.nblk = cur + kSegAlign;  // one spare run so that a read-ahead stays inside the arrays
-        L.w.assign((size_t)L.planes * L.nblk * L.VV, 0.0f);
-        for (int tb = 0; tb < L.noff; ++tb) L.off[tb].assign((size_t)L.nblk, 0);
-        // pass 2: fill
-        for (int g = 0; g < G; ++g)
-            for (int ch = 0; ch < L.nchunks; ++ch) {
-                size_t si = (size_t)g * L.nchunks + ch;
-                const Seg s = L.seg[si];
-                const int c0 = ch * KC;
-                const int64_t span = round_up(s.cnt, kSegAlign);
-                for (int64_t j = 0; j < span; ++j) {
-                    const int64_t b = s.start + j;
-                    const bool real = j < hi[si] - lo[si];
-                    for (int tb = 0; tb < L.noff; ++tb)
-                        L.off[tb][b] = real ? off_of(p->col_idx[lo[si] + j], k, tb)
-                                            : pad_off(c0, KC, k, tb);
-                    if (!real) continue;
-                    const float *src = &p->vals[(size_t)(lo[si] + j) * V];
-                    for (int v = 0; v < V; ++v) {
-                        int q = v / 4, i = v % 4;
-                        if (V < 4) { q = 0; i = v; }
-                        L.w[((size_t)q * L.nblk + b) * L.VV + i] = src[v];
-                    }
-                }
-            }
-        // the spare run: zero weights, selector of a zero row that exists in every tile
-        for (int64_t b = cur; b < L.nblk; ++b)
-            for (int tb = 0; tb < L.noff; ++tb) L.off[tb][b] = pad_off(0, KC, k, tb);
         L.order.resize(G);
         std::iota(L.order.begin(), L.order.end(), 0);
         std::stable_sort(L.order.begin(), L.order.end(), [&](int a, int b) {
             return p->row_ptr[a + 1] - p->row_ptr[a] > p->row_ptr[b + 1] - p->row_ptr[b];
         });
-        L.work.resize((size_t)G * L.nchunks);
-        for (int i = 0; i < G; ++i)
+        // canonical range [lo, hi) of every (group, chunk)
+        std::vector<int32_t> lo((size_t)G * L.nchunks), hi((size_t)G * L.nchunks);
+        for (int g = 0; g < G; ++g) {
+            int32_t t = p->row_ptr[g], end = p->row_ptr[g + 1];
             for (int ch = 0; ch < L.nchunks; ++ch) {
-                const Seg sg = L.seg[(size_t)L.order[i] * L.nchunks + ch];
-                L.work[(size_t)i * L.nchunks + ch] = Work{sg.start, sg.cnt, L.order[i], 0};
+                const int c_end = std::min(p->Cin, (ch + 1) * KC);
+                lo[(size_t)g * L.nchunks + ch] = t;
+                while (t < end && col_channel(p->col_idx[t], kk) < c_end) ++t;
+                hi[(size_t)g * L.nchunks + ch] = t;
             }
+        }
+        // pass 1: segments
+        L.work.assign((size_t)L.nbundles * L.nchunks, Work{0, 0, {-1, -1, -1, -1}, {0, 0}});
+        int64_t cur = 0;
+        for (int b = 0; b < L.nbundles; ++b)
+            for (int ch = 0; ch < L.nchunks; ++ch) {
+                Work &wk = L.work[(size_t)b * L.nchunks + ch];
+                int32_t longest = 0;
+                for (int s = 0; s < GS; ++s) {
+                    const int pos = b * GS + s;
+                    if (pos >= G) continue;
+                    const int g = L.order[pos];
+                    wk.group[s] = g;
+                    const size_t gi = (size_t)g * L.nchunks + ch;
+                    longest = std::max(longest, hi[gi] - lo[gi]);
+                }
+                if (cur > INT32_MAX / (4 * GS) - 64) return ALCS_E_UNSUPPORTED;
+                wk.start = (int32_t)cur;
+                wk.cnt = (int32_t)round_up(longest, kCntAlign);
+                cur += round_up(wk.cnt, kSegAlign);
+            }
+        L.ncol = cur + kSegAlign;  // one spare run so that a read-ahead stays inside the arrays
+        L.wplane = L.ncol * L.VV * GS;
+        L.w.assign((size_t)L.planes * L.wplane, 0.0f);
+        for (int tb = 0; tb < L.noff; ++tb) L.off[tb].assign((size_t)L.ncol * GS, 0);
+        // pass 2: fill (padding: zero weights, selector of the chunk's all-zero row)
+        for (int b = 0; b < L.nbundles; ++b)
+            for (int ch = 0; ch < L.nchunks; ++ch) {
+                const Work wk = L.work[(size_t)b * L.nchunks + ch];
+                const int c0 = ch * KC;
+                const int64_t span = round_up(wk.cnt, kSegAlign);
+                for (int s = 0; s < GS; ++s) {
+                    const int g = wk.group[s];
+                    const size_t gi = g >= 0 ? (size_t)g * L.nchunks + ch : 0;
+                    const int32_t nreal = g >= 0 ? hi[gi] - lo[gi] : 0;
+                    for (int64_t j = 0; j < span; ++j) {
+                        const int64_t col = wk.start + j;
+                        const bool real = j < nreal;
+                        for (int tb = 0; tb < L.noff; ++tb)
+                            L.off[tb][off_index(L, col, s)] =
+                                real ? off_of(p->col_idx[lo[gi] + j], k, tb, GS) : pad_off(c0, KC, k, tb, GS);
+                        if (!real) continue;
+                        const float *src = &p->vals[(size_t)(lo[gi] + j) * V];
+                        for (int v = 0; v < V; ++v) {
+                            const int q = V < 4 ? 0 : v / 4, i = V < 4 ? v : v % 4;
+                            L.w[(size_t)q * L.wplane + w_index(L, col, s, i)] = src[v];
+                        }
+                    }
+                }
+            }
+        for (int64_t col = cur; col < L.ncol; ++col)
+            for (int s = 0; s < GS; ++s)
+                for (int tb = 0; tb < L.noff; ++tb) L.off[tb][off_index(L, col, s)] = pad_off(0, KC, k, tb, GS);
     } catch (const std::bad_alloc &) {
         return ALCS_E_ALLOC;
     }
@@ -148,7 +176,7 @@ int upload(alcs_packed *p) {
     if ((e = hipGetDevice(&dev)) != hipSuccess) { set_hip_error((int)e); return ALCS_E_HIP; }
     const size_t b_work = L.work.size() * sizeof(Work);
     const size_t b_w = L.w.size() * sizeof(float);
-    const size_t b_off = (size_t)L.nblk * sizeof(int32_t);
+    const size_t b_off = L.off[0].size() * sizeof(int32_t);
     size_t o_work = 0, o_w = align256(o_work + b_work), o_off0 = align256(o_w + b_w);
     size_t o_off1 = align256(o_off0 + b_off);
     size_t total = align256(o_off1 + (L.noff == 2 ? b_off : 0)) + 256;
@@ -181,12 +209,17 @@ int upload(alcs_packed *p) {
     return ALCS_OK;
 }
 
-// Chunk size policy.  Kernel 1: all input channels in one LDS tile while a 64-pixel
-// tile of Cin+1 rows fits comfortably; above that, chunks of 256 channels.
+// Tile policy for kernel 1.  One group per wavefront and all input channels in one
+// LDS tile while a 64-pixel tile of Cin+1 rows fits (Cin <= 639 in 160 KB); wider
+// inputs shrink the tile to 32 or 16 pixels and multiply 2 or 4 groups per wavefront
+// (V >= 4 only); beyond that, or for V < 4, chunks of 256 channels.
 // Kernel 3: 32 channels per chunk (the haloed tile is 100 or 289 floats per channel).
-static int default_kc(int Cin, int k) {
-    if (k == 1) return Cin <= 512 ? Cin : 256;
-    return std::min(Cin, 32);
+static void default_tiles(int Cin, int k, int V, int *KC, int *GS) {
+    *GS = 1;
+    if (k == 3) { *KC = std::min(Cin, 32); return; }
+    if (Cin <= 639) { *KC = Cin; return; }
+    if (V >= 4 && Cin <= 2559) { *KC = Cin; *GS = Cin <= 1279 ? 2 : 4; return; }
+    *KC = 256;
 }
 
 }  // namespace alcs
@@ -264,8 +297,13 @@ int alcs_pack_weights(const float *W_host, const uint8_t *mask_host, int Cout, i
         rc = ALCS_E_ALLOC;
     }
     if (rc == ALCS_OK) {
-        int KC = tuning().kc > 0 ? std::min(tuning().kc, Cin) : default_kc(Cin, kernel);
-        rc = build_layout(p, KC);
+        int KC = 0, GS = 1;
+        default_tiles(Cin, kernel, V, &KC, &GS);
+        if (tuning().kc > 0) { KC = std::min(tuning().kc, Cin); GS = 1; }
+        if (tuning().gs > 0 && kernel == 1 && V >= 4 && KC == Cin &&
+            (long long)(Cin + 1) * (kRowBytes1 / tuning().gs) <= 160 * 1024)
+            GS = tuning().gs;
+        rc = build_layout(p, KC, GS);
     }
     if (rc == ALCS_OK) {
         rc = upload(p);
@@ -307,9 +345,13 @@ int alcs_packed_export(const alcs_packed_t *p, int32_t *row_ptr_host, int32_t *c
 int alcs_packed_selfcheck(const alcs_packed_t *p) {
     if (!p) return ALCS_E_INVALID_ARG;
     const Layout &L = p->lay;
-    const int k = p->k, V = p->V;
+    const int k = p->k, V = p->V, GS = L.GS;
     if (L.KC <= 0 || L.nchunks != (p->Cin + L.KC - 1) / L.KC) return ALCS_E_INVALID_ARG;
-    if ((int)L.seg.size() != p->G * L.nchunks || (int)L.order.size() != p->G) return ALCS_E_INVALID_ARG;
+    if (GS != 1 && GS != 2 && GS != 4) return ALCS_E_INVALID_ARG;
+    if (L.nbundles != (p->G + GS - 1) / GS || (int)L.order.size() != p->G) return ALCS_E_INVALID_ARG;
+    if ((int64_t)L.work.size() != (int64_t)L.nbundles * L.nchunks) return ALCS_E_INVALID_ARG;
+    if ((int64_t)L.w.size() != L.planes * L.wplane || L.wplane != L.ncol * L.VV * GS) return ALCS_E_INVALID_ARG;
+    // `order` is a permutation of the groups by descending length
     std::vector<char> seen((size_t)p->G, 0);
     for (int i = 0; i < p->G; ++i) {
         int g = L.order[i];
@@ -320,59 +362,65 @@ int alcs_packed_selfcheck(const alcs_packed_t *p) {
             if (p->row_ptr[a + 1] - p->row_ptr[a] < p->row_ptr[g + 1] - p->row_ptr[g]) return ALCS_E_INVALID_ARG;
         }
     }
-    if (L.work.size() != L.seg.size()) return ALCS_E_INVALID_ARG;
-    for (int i = 0; i < p->G; ++i)
-        for (int ch = 0; ch < L.nchunks; ++ch) {
-            const Work wk = L.work[(size_t)i * L.nchunks + ch];
-            const Seg sg = L.seg[(size_t)L.order[i] * L.nchunks + ch];
-            if (wk.start != sg.start || wk.cnt != sg.cnt || wk.group != L.order[i]) return ALCS_E_INVALID_ARG;
-        }
     const uint32_t zero_bits = 0;
-    for (int g = 0; g < p->G; ++g) {
-        int64_t t = p->row_ptr[g];
+    std::vector<int64_t> next((size_t)p->G);  // next canonical block expected for every group
+    for (int g = 0; g < p->G; ++g) next[g] = p->row_ptr[g];
+    for (int b = 0; b < L.nbundles; ++b)
         for (int ch = 0; ch < L.nchunks; ++ch) {
-            const Seg s = L.seg[(size_t)g * L.nchunks + ch];
-            if (s.start % kSegAlign || s.cnt % kCntAlign || s.cnt < 0) return ALCS_E_INVALID_ARG;
+            const Work wk = L.work[(size_t)b * L.nchunks + ch];
+            if (wk.start % kSegAlign || wk.cnt % kCntAlign || wk.cnt < 0) return ALCS_E_INVALID_ARG;
             const int c0 = ch * L.KC, c1 = std::min(p->Cin, c0 + L.KC);
-            const int64_t span = round_up(s.cnt, kSegAlign);
-            if (s.start + span > L.nblk) return ALCS_E_INVALID_ARG;
-            bool in_pad = false;
-            int64_t nreal = 0;
-            for (int64_t j = 0; j < span; ++j) {
-                const int64_t b = s.start + j;
-                const bool is_pad = L.off[0][b] == pad_off(c0, L.KC, k, 0);
-                if (in_pad && !is_pad) return ALCS_E_INVALID_ARG;  // real blocks come first
-                in_pad = is_pad;
-                if (is_pad) {
-                    for (int tb = 1; tb < L.noff; ++tb)
-                        if (L.off[tb][b] != pad_off(c0, L.KC, k, tb)) return ALCS_E_INVALID_ARG;
-                    for (int q = 0; q < L.planes; ++q)
-                        for (int i = 0; i < L.VV; ++i)
-                            if (std::memcmp(&L.w[((size_t)q * L.nblk + b) * L.VV + i], &zero_bits, 4))
-                                return ALCS_E_INVALID_ARG;
-                    continue;
+            const int64_t span = round_up(wk.cnt, kSegAlign);
+            if (wk.start + span > L.ncol) return ALCS_E_INVALID_ARG;
+            int64_t longest = 0;
+            for (int s = 0; s < kMaxSlots; ++s) {
+                const int pos = b * GS + s;
+                const int want = (s < GS && pos < p->G) ? L.order[pos] : -1;
+                if (wk.group[s] != want) return ALCS_E_INVALID_ARG;
+                if (s >= GS) continue;
+                const int g = wk.group[s];
+                bool in_pad = false;
+                int64_t nreal = 0;
+                for (int64_t j = 0; j < span; ++j) {
+                    const int64_t col = wk.start + j;
+                    const size_t oi = off_index(L, col, s);
+                    if (oi >= L.off[0].size()) return ALCS_E_INVALID_ARG;
+                    const bool is_pad = L.off[0][oi] == pad_off(c0, L.KC, k, 0, GS);
+                    if (in_pad && !is_pad) return ALCS_E_INVALID_ARG;  // real blocks come first
+                    in_pad = is_pad;
+                    if (is_pad) {
+                        for (int tb = 1; tb < L.noff; ++tb)
+                            if (L.off[tb][oi] != pad_off(c0, L.KC, k, tb, GS)) return ALCS_E_INVALID_ARG;
+                        for (int q = 0; q < L.planes; ++q)
+                            for (int i = 0; i < L.VV; ++i)
+                                if (std::memcmp(&L.w[(size_t)q * L.wplane + w_index(L, col, s, i)], &zero_bits, 4))
+                                    return ALCS_E_INVALID_ARG;
+                        continue;
+                    }
+                    // a real block: the next canonical column of the slot's group, inside the
+                    // chunk's channel range (so that its LDS row exists) and the padded count
+                    if (g < 0 || j >= wk.cnt || next[g] >= p->row_ptr[g + 1]) return ALCS_E_INVALID_ARG;
+                    const int64_t t = next[g];
+                    const int cidx = p->col_idx[(size_t)t];
+                    const int c = col_channel(cidx, k * k);
+                    if (c < c0 || c >= c1) return ALCS_E_INVALID_ARG;
+                    for (int tb = 0; tb < L.noff; ++tb)
+                        if (L.off[tb][oi] != off_of(cidx, k, tb, GS)) return ALCS_E_INVALID_ARG;
+                    for (int v = 0; v < V; ++v) {
+                        const int q = V < 4 ? 0 : v / 4, i = V < 4 ? v : v % 4;
+                        if (std::memcmp(&L.w[(size_t)q * L.wplane + w_index(L, col, s, i)],
+                                        &p->vals[(size_t)t * V + v], 4))
+                            return ALCS_E_INVALID_ARG;
+                    }
+                    ++next[g];
+                    ++nreal;
                 }
-                // a real block: must be the next canonical column of this group, inside the
-                // chunk's channel range (so that its LDS row exists), and within the padded count
-                if (j >= s.cnt || t >= p->row_ptr[g + 1]) return ALCS_E_INVALID_ARG;
-                const int col = p->col_idx[(size_t)t];
-                const int c = col_channel(col, k * k);
-                if (c < c0 || c >= c1) return ALCS_E_INVALID_ARG;
-                for (int tb = 0; tb < L.noff; ++tb)
-                    if (L.off[tb][b] != off_of(col, k, tb)) return ALCS_E_INVALID_ARG;
-                for (int v = 0; v < V; ++v) {
-                    int q = V < 4 ? 0 : v / 4, i = V < 4 ? v : v % 4;
-                    if (std::memcmp(&L.w[((size_t)q * L.nblk + b) * L.VV + i],
-                                    &p->vals[(size_t)t * V + v], 4))
-                        return ALCS_E_INVALID_ARG;
-                }
-                ++t;
-                ++nreal;
+                longest = std::max(longest, nreal);
             }
-            if (round_up(nreal, kCntAlign) != s.cnt) return ALCS_E_INVALID_ARG;
+            if (round_up(longest, kCntAlign) != wk.cnt) return ALCS_E_INVALID_ARG;
         }
-        if (t != p->row_ptr[g + 1]) return ALCS_E_INVALID_ARG;  // every canonical block was found
-    }
+    for (int g = 0; g < p->G; ++g)
+        if (next[g] != p->row_ptr[g + 1]) return ALCS_E_INVALID_ARG;  // every canonical block was found
     return ALCS_OK;
 }
 
@@ -392,13 +440,14 @@ int alcs_set_tuning(const char *name, int value) {
     else if (!std::strcmp(name, "chunk_channels")) t.kc = value;
     else if (!std::strcmp(name, "groups_per_wave")) t.ug = value;
     else if (!std::strcmp(name, "debug")) t.debug = value;
+    else if (!std::strcmp(name, "group_slots")) t.gs = (value == 1 || value == 2 || value == 4) ? value : 0;
     else return ALCS_E_INVALID_ARG;
     return ALCS_OK;
 }
 
 int alcs_last_launch(int *out, int cap) {
     if (!out || cap <= 0) return 0;
-    int n = cap < 8 ? cap : 8;
+    int n = cap < 9 ? cap : 9;
     std::memcpy(out, g_last_launch, n * sizeof(int));
     return n;
 }

@@ -69,13 +69,20 @@ __device__ __forceinline__ cptr<T> as_const(const T *p) {
     return (cptr<T>)(uintptr_t)p;
 }
 
-static_assert(sizeof(Work) == 16, "Work is read as four ints");
-// One scalar 16-byte load; the values end up in SGPRs.
+typedef int i8v __attribute__((ext_vector_type(8)));
+static_assert(sizeof(Work) == 32, "Work is read as eight ints");
+// One scalar 32-byte load; the values end up in SGPRs.
 __device__ __forceinline__ Work load_work(const Work *table, size_t idx) {
-    const i4 v = *reinterpret_cast<cptr<i4>>((uintptr_t)(table + idx));
-    return Work{__builtin_amdgcn_readfirstlane(v[0]), __builtin_amdgcn_readfirstlane(v[1]),
-                __builtin_amdgcn_readfirstlane(v[2]), 0};
+    const i8v v = *reinterpret_cast<cptr<i8v>>((uintptr_t)(table + idx));
+    Work w;
+    w.start = __builtin_amdgcn_readfirstlane(v[0]);
+    w.cnt = __builtin_amdgcn_readfirstlane(v[1]);
+#pragma unroll
+    for (int s = 0; s < kMaxSlots; ++s) w.group[s] = __builtin_amdgcn_readfirstlane(v[2 + s]);
+    w.reserved[0] = w.reserved[1] = 0;
+    return w;
 }
+__device__ __forceinline__ Work no_work() { return Work{0, 0, {-1, -1, -1, -1}, {0, 0}}; }
 
 // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Renumber
 // so that consecutive logical ids - which share a pixel tile and differ only in the
@@ -136,23 +143,30 @@ __device__ __forceinline__ void lds_read(const float *p, float (&x)[PV]) {
     }
 }
 
+constexpr int ilog2(int x) { return x <= 1 ? 0 : 1 + ilog2(x / 2); }
+
 // Weights and row selectors of one run of 16 consecutive kept columns, as fetched by
-// two coalesced vector loads: lane l holds weight (column l/4, row l%4) of every
-// 4-row plane, and lanes 0..15 (repeated) hold the 16 selectors.
-template <int V, bool MF>
+// coalesced vector loads.  With GS groups per wavefront, lanes [s*64/GS, (s+1)*64/GS)
+// are slot s; weight register r of plane q holds columns [r*16/GS, (r+1)*16/GS) of the
+// run: lane l carries (slot, column (l % (64/GS)) / 4, weight row l % 4); and every
+// 16-lane row holds the 16 selectors of its slot.
+template <int V, bool MF, int GS = 1>
 struct Run {
-    float a[MF ? V / 4 : 1];
+    float a[MF ? (V / 4) * GS : 1];
     int o;
 };
 
-template <int V, bool MF>
-__device__ __forceinline__ Run<V, MF> load_run(const ConvArgs &a, int blk, int lane) {
-    Run<V, MF> r;
+template <int V, bool MF, int GS = 1>
+__device__ __forceinline__ Run<V, MF, GS> load_run(const ConvArgs &a, int blk, int lane) {
+    Run<V, MF, GS> r;
     if constexpr (MF) {
-        const float *wp = a.w + (size_t)blk * 4 + lane;
+        const float *wp = a.w + (size_t)blk * 4 * GS + lane;
 #pragma unroll
-        for (int q = 0; q < V / 4; ++q) r.a[q] = wp[(size_t)q * a.wplane];
-        r.o = a.off[blk + (lane & 15)];
+        for (int q = 0; q < V / 4; ++q)
+#pragma unroll
+            for (int g = 0; g < GS; ++g) r.a[q * GS + g] = wp[(size_t)q * a.wplane + g * 64];
+        const int slot = lane >> (6 - ilog2(GS));
+        r.o = a.off[(size_t)blk * GS + slot * 16 + (lane & 15)];
     } else {
         r.a[0] = 0.f;
         r.o = 0;
@@ -188,9 +202,11 @@ __device__ __forceinline__ int bcast_sel(int ov) {
 // branches: the compiler keeps all B reads in flight ahead of the MFMAs.
 // base is the lane's byte offset inside an LDS row (minus the chunk's first row);
 // selectors are byte offsets for 64-pixel rows, scaled by 1 << SH for wider rows.
-template <int B0, int B, int V, int PV, int SH>
-__device__ __forceinline__ void mfma_batch(const float (&aw)[V / 4], int ov, const char *lds,
+template <int B0, int B, int V, int PV, int SH, int GS>
+__device__ __forceinline__ void mfma_batch(const float (&aw)[(V / 4) * GS], int ov, const char *lds,
                                            int base, Acc<V, PV, true> &acc) {
+    constexpr int CPA = 16 / GS;           // columns per weight register
+    constexpr int CBSZ = 4 - ilog2(GS);    // blocks that share one block's weights: 16 / GS
     float x[B][PV];
     static_for<B>([&](auto c) {
         constexpr int C = decltype(c)::value;
@@ -198,51 +214,53 @@ __device__ __forceinline__ void mfma_batch(const float (&aw)[V / 4], int ov, con
     });
     static_for<B>([&](auto c) {
         constexpr int C = decltype(c)::value;
-        constexpr int ABID = B0 + C;
+        constexpr int COL = B0 + C, AREG = COL / CPA, ABID = COL % CPA;
 #pragma unroll
         for (int q = 0; q < V / 4; ++q)
 #pragma unroll
             for (int pv = 0; pv < PV; ++pv) {
-                if (Acc<V, PV, true>::DUAL && (ABID & 1))
-                    acc.alt[q][pv] = __builtin_amdgcn_mfma_f32_4x4x1f32(aw[q], x[C][pv], acc.alt[q][pv], 4, ABID, 0);
+                if (Acc<V, PV, true>::DUAL && (COL & 1))
+                    acc.alt[q][pv] = __builtin_amdgcn_mfma_f32_4x4x1f32(aw[q * GS + AREG], x[C][pv],
+                                                                        acc.alt[q][pv], CBSZ, ABID, 0);
                 else
-                    acc.a[q][pv] = __builtin_amdgcn_mfma_f32_4x4x1f32(aw[q], x[C][pv], acc.a[q][pv], 4, ABID, 0);
+                    acc.a[q][pv] = __builtin_amdgcn_mfma_f32_4x4x1f32(aw[q * GS + AREG], x[C][pv],
+                                                                      acc.a[q][pv], CBSZ, ABID, 0);
             }
     });
 }
 
-// One segment (the kept columns of one group inside one channel chunk), MFMA form.
-// start/cnt are wave-uniform; base is the lane's byte offset inside an LDS row
-// (minus the chunk's first row); SH = log2(pixels per lane) for 1x1, 0 for 3x3.
-// `first` is the segment's first run,
-// loaded by the caller (early enough that it is not queued behind output stores);
-// the following runs are fetched while the current one is being multiplied.
-template <int V, int PV, int SH>
+// One segment (the kept columns of one bundle of GS groups inside one channel chunk),
+// MFMA form.  start/cnt are wave-uniform; base is the lane's byte offset inside an LDS
+// row (minus the chunk's first row); SH = log2(pixels per lane) for 1x1, 0 for 3x3.
+// `first` is the segment's first run, loaded by the caller (early enough that it is
+// not queued behind output stores); the following runs are fetched while the current
+// one is being multiplied.
+template <int V, int PV, int SH, int GS = 1>
 __device__ __forceinline__ void mac_segment(const ConvArgs &a, int start, int cnt,
                                             const char *lds, int base, int lane,
-                                            Run<V, true> first, Acc<V, PV, true> &acc) {
+                                            Run<V, true, GS> first, Acc<V, PV, true> &acc) {
     constexpr int Q = V / 4;
     constexpr int B = kCntAlign;  // columns whose LDS reads are in flight together
     static_assert(B == 8, "a run of 16 columns is two batches");
-    Run<V, true> nxt = first;
+    Run<V, true, GS> nxt = first;
     for (int j0 = 0; j0 < cnt; j0 += 16) {
-        float aw[Q];
+        float aw[Q * GS];
 #pragma unroll
-        for (int q = 0; q < Q; ++q) aw[q] = nxt.a[q];
+        for (int q = 0; q < Q * GS; ++q) aw[q] = nxt.a[q];
         const int ov = nxt.o;
-        if (j0 + 16 < cnt) nxt = load_run<V, true>(a, start + j0 + 16, lane);
-        mfma_batch<0, B, V, PV, SH>(aw, ov, lds, base, acc);
-        if (j0 + 8 < cnt) mfma_batch<8, B, V, PV, SH>(aw, ov, lds, base, acc);
+        if (j0 + 16 < cnt) nxt = load_run<V, true, GS>(a, start + j0 + 16, lane);
+        mfma_batch<0, B, V, PV, SH, GS>(aw, ov, lds, base, acc);
+        if (j0 + 8 < cnt) mfma_batch<8, B, V, PV, SH, GS>(aw, ov, lds, base, acc);
     }
 }
 
 // Same segment with plain FMAs; selectors and the V weights of a column come from
 // scalar loads.
-template <int V, int PV, int SH>
+template <int V, int PV, int SH, int GS = 1>
 __device__ __forceinline__ void mac_segment(const ConvArgs &a, int start, int cnt,
                                             const char *lds, int base, int lane,
-                                            Run<V, false> first, Acc<V, PV, false> &acc) {
-    static_assert(V <= 4, "FMA path is built for V <= 4");
+                                            Run<V, false, GS> first, Acc<V, PV, false> &acc) {
+    static_assert(V <= 4 && GS == 1, "FMA path is built for V <= 4, one group per wavefront");
     (void)lane;
     (void)first;
     cptr<float> wp = as_const(a.w) + (size_t)start * V;
@@ -375,6 +393,24 @@ __device__ __forceinline__ void store_group(const ConvArgs &a, const Acc<V, PV, 
     }
 }
 
+// Epilogue with GS groups per wavefront: the lane's group is the one of its slot.
+template <int V, int GS>
+__device__ __forceinline__ void store_slots(const ConvArgs &a, const Acc<V, 1, true> &acc, const Work &w,
+                                            int lane, const PixOut<1> &px) {
+    const int slot = lane >> (6 - ilog2(GS));
+    int g = w.group[0];
+#pragma unroll
+    for (int s = 1; s < GS; ++s) g = slot == s ? w.group[s] : g;
+    if (g < 0 || !px.valid[0]) return;
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        const int ch = g * V + v;
+        if (ch >= a.Cout) break;
+        const float b = a.bias ? a.bias[ch] : 0.f;
+        __builtin_nontemporal_store(acc.get(v, 0) + b, a.Y + (size_t)ch * a.P + px.yoff[0]);
+    }
+}
+
 // ------------------------------------------------------------------ 1x1 kernels
 
 // Mode 1: all input channels of the pixel tile are resident in LDS (one chunk); each
@@ -383,10 +419,11 @@ __device__ __forceinline__ void store_group(const ConvArgs &a, const Acc<V, PV, 
 // first run of group k+1 are fetched while group k is multiplied, and always before
 // group k's output stores are issued (memory operations retire in order, so a load
 // queued behind stores would wait for them).
-template <int V, int PV, bool MF, bool VEC>
+template <int V, int PV, bool MF, bool VEC, int GS>
 __global__ void __launch_bounds__(1024) k_pw_resident(const ConvArgs a) {
+    static_assert(GS == 1 || (PV == 1 && MF), "several groups per wavefront: MFMA form, one pixel per lane");
     extern __shared__ float lds[];
-    constexpr int TP = 64 * PV;
+    constexpr int TP = 64 * PV / GS;
     constexpr int SH = PV == 4 ? 2 : PV == 2 ? 1 : 0;
     const int logical = logical_wg(a);
     if (logical >= a.total_wgs || (a.debug & 8)) return;
@@ -396,15 +433,15 @@ __global__ void __launch_bounds__(1024) k_pw_resident(const ConvArgs a) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), nw = blockDim.x >> 6;
     const int g_begin = gt * a.gpt;
     const int ng = min(a.G, g_begin + a.gpt) - g_begin;
-    // The wavefront's k-th group is entry k*nw + (wave, or mirrored in odd rounds) of
+    // The wavefront's k-th bundle is entry k*nw + (wave, or mirrored in odd rounds) of
     // the length-sorted list: a snake order that evens out the work per wavefront.
     auto nth = [&](int k) { return k * nw + ((k & 1) ? nw - 1 - wave : wave); };
     const bool any = nth(0) < ng;
-    Work w0{0, 0, 0, 0}, w1{0, 0, 0, 0};
-    Run<V, MF> run0, run1;
+    Work w0 = no_work(), w1 = no_work();
+    Run<V, MF, GS> run0, run1;
     if (any) {
         w0 = load_work(a.work, g_begin + nth(0));
-        run0 = load_run<V, MF>(a, w0.start, lane);
+        run0 = load_run<V, MF, GS>(a, w0.start, lane);
         if (nth(1) < ng) w1 = load_work(a.work, g_begin + nth(1));
     }
 
@@ -413,21 +450,25 @@ __global__ void __launch_bounds__(1024) k_pw_resident(const ConvArgs a) {
     __syncthreads();
     if (!any) return;
 
+    const int plane = GS == 1 ? lane : (lane & (TP - 1));  // the lane's pixel position in the tile
     PixOut<PV> px;
-    pix_out<PV, VEC>(a, q0, lane, px);
+    pix_out<PV, VEC>(a, q0, plane, px);
     const char *ldsb = reinterpret_cast<const char *>(lds);
-    const int base = lane * PV * 4;
+    const int base = plane * PV * 4;
     for (int k = 0;; ++k) {
         const bool more = nth(k + 1) < ng;
-        Work w2{0, 0, 0, 0};
+        Work w2 = no_work();
         if (more) {
-            run1 = load_run<V, MF>(a, w1.start, lane);
+            run1 = load_run<V, MF, GS>(a, w1.start, lane);
             if (nth(k + 2) < ng) w2 = load_work(a.work, g_begin + nth(k + 2));
         }
         Acc<V, PV, MF> acc;
         acc.zero();
-        if (!(a.debug & 2)) mac_segment<V, PV, SH>(a, w0.start, w0.cnt, ldsb, base, lane, run0, acc);
-        if (!(a.debug & 4)) store_group<V, PV, MF, VEC>(a, acc, w0.group, px);
+        if (!(a.debug & 2)) mac_segment<V, PV, SH, GS>(a, w0.start, w0.cnt, ldsb, base, lane, run0, acc);
+        if (!(a.debug & 4)) {
+            if constexpr (GS == 1) store_group<V, PV, MF, VEC>(a, acc, w0.group[0], px);
+            else store_slots<V, GS>(a, acc, w0, lane, px);
+        }
         if (!more) break;
         w0 = w1;
         w1 = w2;
@@ -479,7 +520,7 @@ __global__ void __launch_bounds__(512) k_pw_chunked(const ConvArgs a) {
 #pragma unroll
     for (int u = 0; u < UG; ++u)
         if (slot[u] >= 0)
-            store_group<V, PV, MF, VEC>(a, acc[u], load_work(a.work, (size_t)slot[u] * a.nchunks).group, px);
+            store_group<V, PV, MF, VEC>(a, acc[u], load_work(a.work, (size_t)slot[u] * a.nchunks).group[0], px);
 }
 
 
@@ -564,12 +605,12 @@ __global__ void __launch_bounds__(512) k_pw_stream(const ConvArgs a) {
             }
             const char *ldsb = reinterpret_cast<const char *>(lds + (t & 1) * bufstride);
             const int base = lane * PV * 4;
-            Work w0 = load_work(a.work, nth(0)), w1{0, 0, 0, 0};
+            Work w0 = load_work(a.work, nth(0)), w1 = no_work();
             if (nth(1) < a.G) w1 = load_work(a.work, nth(1));
             Run<V, true> run0 = load_run<V, true>(al, w0.start, lane), run1;
             for (int k = 0;; ++k) {
                 const bool more = nth(k + 1) < a.G;
-                Work w2{0, 0, 0, 0};
+                Work w2 = no_work();
                 if (more) {
                     run1 = load_run<V, true>(al, w1.start, lane);
                     if (nth(k + 2) < a.G) w2 = load_work(a.work, nth(k + 2));
@@ -577,7 +618,7 @@ __global__ void __launch_bounds__(512) k_pw_stream(const ConvArgs a) {
                 Acc<V, PV, true> acc;
                 acc.zero();
                 if (!(a.debug & 2)) mac_segment<V, PV, SH>(al, w0.start, w0.cnt, ldsb, base, lane, run0, acc);
-                if (!(a.debug & 4)) store_group<V, PV, true, true>(a, acc, w0.group, px);
+                if (!(a.debug & 4)) store_group<V, PV, true, true>(a, acc, w0.group[0], px);
                 if (!more) break;
                 w0 = w1;
                 w1 = w2;
@@ -672,7 +713,7 @@ __global__ void __launch_bounds__(512) k_conv3(const ConvArgs a) {
 #pragma unroll
     for (int u = 0; u < UG; ++u)
         if (slot[u] >= 0)
-            store_group<V, 1, MF, false>(a, acc[u], load_work(a.work, (size_t)slot[u] * a.nchunks).group, px);
+            store_group<V, 1, MF, false>(a, acc[u], load_work(a.work, (size_t)slot[u] * a.nchunks).group[0], px);
 }
 
 // ------------------------------------------------------------------ launcher
@@ -685,13 +726,17 @@ static inline int ceil_div(long long a, long long b) { return (int)((a + b - 1) 
 typedef void (*kern_t)(const ConvArgs);
 
 template <int V, bool MF>
-static kern_t pick_resident(int pv, bool vec) {
-    if (vec) {
-        if (pv == 4) return k_pw_resident<V, 4, MF, true>;
-        if (pv == 2) return k_pw_resident<V, 2, MF, true>;
-        return k_pw_resident<V, 1, MF, true>;
+static kern_t pick_resident(int pv, bool vec, int gs) {
+    if constexpr (MF) {
+        if (gs == 2) return vec ? k_pw_resident<V, 1, true, true, 2> : k_pw_resident<V, 1, true, false, 2>;
+        if (gs == 4) return vec ? k_pw_resident<V, 1, true, true, 4> : k_pw_resident<V, 1, true, false, 4>;
     }
-    return k_pw_resident<V, 1, MF, false>;
+    if (vec) {
+        if (pv == 4) return k_pw_resident<V, 4, MF, true, 1>;
+        if (pv == 2) return k_pw_resident<V, 2, MF, true, 1>;
+        return k_pw_resident<V, 1, MF, true, 1>;
+    }
+    return k_pw_resident<V, 1, MF, false, 1>;
 }
 
 template <int V, bool MF>
@@ -757,12 +802,12 @@ extern "C" int alcs_sparse_conv(const alcs_packed_t *Wp, const float *X_dev, con
     a.X = X_dev; a.bias = bias_dev; a.Y = Y_dev;
     a.work = Wp->dev.work; a.w = Wp->dev.w;
     a.off = Wp->dev.off[kernel == 3 && stride == 2 ? 1 : 0];
-    a.wplane = (long long)L.nblk * L.VV;
+    a.wplane = (long long)L.wplane;
     a.N = N; a.Cin = Cin; a.Cout = Cout; a.H = H; a.W = W; a.Ho = Ho; a.Wo = Wo; a.stride = stride;
     a.P = (int)P; a.Pin = (int)Pin;
     if ((long long)N * P > INT32_MAX - 1024) return ALCS_E_UNSUPPORTED;
     a.NP = (int)((long long)N * P);
-    a.G = G; a.nchunks = L.nchunks; a.KC = L.KC;
+    a.G = L.nbundles; a.nchunks = L.nchunks; a.KC = L.KC;  // kernels count bundles of GS groups
     a.debug = T.debug;
 
     bool mfma = V >= 4;
@@ -776,8 +821,8 @@ extern "C" int alcs_sparse_conv(const alcs_packed_t *Wp, const float *X_dev, con
         // there are enough pixels to give every compute unit several tiles
         bool stream_ok = false;
         int s_pv = 1, s_lds = 0, s_nw = 8, s_nwg = 0;
-        if (L.nchunks == 1 && vec && mfma && T.path == 4) {
-            const long long wbytes = (long long)L.planes * L.nblk * 16 + (long long)L.nblk * 4;
+        if (L.nchunks == 1 && L.GS == 1 && vec && mfma && T.path == 4) {
+            const long long wbytes = (long long)L.planes * L.ncol * 16 + (long long)L.ncol * 4;
             for (int cand = 4; cand >= 1 && !stream_ok; cand >>= 1) {
                 if (T.pv && T.pv != cand) continue;
                 const int TPc = 64 * cand;
@@ -802,8 +847,8 @@ extern "C" int alcs_sparse_conv(const alcs_packed_t *Wp, const float *X_dev, con
             a.ppw = ppw;
             a.npt = ceil_div(a.NP, ppw);
             a.ngt = 1; a.gpt = G;
-            a.wfloats = (int)((long long)L.planes * L.nblk * 4);
-            a.nblk = (int)L.nblk;
+            a.wfloats = (int)((long long)L.planes * L.ncol * 4);
+            a.nblk = (int)L.ncol;
             (void)TPc;
             switch (V) {
                 case 4: kern = pv == 4 ? k_pw_stream<4, 4, 8> : pv == 2 ? k_pw_stream<4, 2, 8> : k_pw_stream<4, 1, 8>; break;
@@ -818,8 +863,10 @@ extern "C" int alcs_sparse_conv(const alcs_packed_t *Wp, const float *X_dev, con
             // compute unit: wider tiles mean longer contiguous runs for loads and stores.
             constexpr int kTwoPerCu = 68 * 1024;
             constexpr int kMinWgs = 3 * kCUs / 2;
+            const int GS = L.GS, NB = L.nbundles;
+            if (GS > 1 && !mfma) return ALCS_E_UNSUPPORTED;  // the packer pairs groups only for V >= 4
             pv = 1;
-            if (vec) {
+            if (vec && GS == 1) {
                 for (int cand = 4; cand >= 2; cand >>= 1) {
                     const long long need = (long long)(Cin + 1) * 64 * cand * 4;
                     const long long tiles = ((long long)a.NP + 64 * cand - 1) / (64 * cand);
@@ -827,29 +874,29 @@ extern "C" int alcs_sparse_conv(const alcs_packed_t *Wp, const float *X_dev, con
                 }
                 if (T.pv == 1 || T.pv == 2 || T.pv == 4) pv = T.pv;
             }
-            const int TP = 64 * pv;
+            const int TP = 64 * pv / GS;
             lds = (Cin + 1) * TP * 4;
             if (lds > kMaxLds) return ALCS_E_UNSUPPORTED;
             a.npt = ceil_div(a.NP, TP);
-            // Group tiles: split the groups over several workgroups only when there are too few
-            // pixel tiles (every extra group tile re-stages the pixel tile's rows).  With one
-            // resident workgroup per compute unit aim at one round (<= 256 workgroups), else
-            // at about 1.5 workgroups per compute unit.
+            // Group tiles: split the bundles over several workgroups only when there are too
+            // few pixel tiles (every extra group tile re-stages the pixel tile's rows).  With
+            // one resident workgroup per compute unit aim at one round (<= 256 workgroups),
+            // else at about 1.5 workgroups per compute unit.
             int ngt = 1;
             const int want = lds > 80 * 1024 ? kCUs : kMinWgs;
-            if (a.npt < want) ngt = std::min(std::max(1, G / 4), std::max(1, lds > 80 * 1024 ? want / a.npt : ceil_div(want, a.npt)));
-            if (T.group_tiles > 0) ngt = std::min(T.group_tiles, G);
-            a.gpt = ceil_div(G, ngt);
-            a.ngt = ceil_div(G, a.gpt);
+            if (a.npt < want) ngt = std::min(std::max(1, NB / 4), std::max(1, lds > 80 * 1024 ? want / a.npt : ceil_div(want, a.npt)));
+            if (T.group_tiles > 0) ngt = std::min(T.group_tiles, NB);
+            a.gpt = ceil_div(NB, ngt);
+            a.ngt = ceil_div(NB, a.gpt);
             nw = lds > 40 * 1024 ? 16 : 8;
             nw = std::min(nw, std::max(1, a.gpt));
             if (T.waves > 0) nw = std::min(T.waves, 16);
             switch (V) {
-                case 1: kern = pick_resident<1, false>(pv, vec); break;
-                case 2: kern = pick_resident<2, false>(pv, vec); break;
-                case 4: kern = mfma ? pick_resident<4, true>(pv, vec) : pick_resident<4, false>(pv, vec); break;
-                case 8: kern = pick_resident<8, true>(pv, vec); break;
-                case 16: kern = pick_resident<16, true>(pv, vec); break;
+                case 1: kern = pick_resident<1, false>(pv, vec, GS); break;
+                case 2: kern = pick_resident<2, false>(pv, vec, GS); break;
+                case 4: kern = mfma ? pick_resident<4, true>(pv, vec, GS) : pick_resident<4, false>(pv, vec, GS); break;
+                case 8: kern = pick_resident<8, true>(pv, vec, GS); break;
+                case 16: kern = pick_resident<16, true>(pv, vec, GS); break;
             }
         } else {
             mode = 2;
@@ -859,6 +906,7 @@ extern "C" int alcs_sparse_conv(const alcs_packed_t *Wp, const float *X_dev, con
             a.npt = ceil_div(a.NP, 64 * pv);
             nw = 8;
             if (T.waves > 0) nw = std::min(T.waves, 8);
+            if (L.GS != 1) return ALCS_E_UNSUPPORTED;
             a.gpt = nw * kUG;
             a.ngt = ceil_div(G, a.gpt);
             switch (V) {
@@ -895,7 +943,7 @@ extern "C" int alcs_sparse_conv(const alcs_packed_t *Wp, const float *X_dev, con
     a.wg_per_xcd = ceil_div(total, kXcds);
     int rc = set_lds_limit(kern, lds);
     if (rc != ALCS_OK) return rc;
-    record_launch(mode, pv, nw, a.total_wgs, lds, a.ngt, L.KC, mfma ? 2 : 1);
+    record_launch(mode, pv, nw, a.total_wgs, lds, a.ngt, L.KC, mfma ? 2 : 1, L.GS);
     const int grid = mode == 4 ? a.npt : a.wg_per_xcd * kXcds;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(nw * 64), lds, (hipStream_t)stream, a);
     e = hipGetLastError();

@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 @pytest.fixture(autouse=True)
 def _reset_tuning():
     yield
-    for k in ("pv", "waves", "group_tiles", "path", "chunk_channels", "groups_per_wave"):
+    for k in ("pv", "waves", "group_tiles", "path", "chunk_channels", "groups_per_wave", "group_slots", "debug"):
         alcs.alcs_set_tuning(k, 0)
 
 
@@ -84,9 +84,27 @@ def test_pointwise_chunked(V, kc):
     assert info["mode"] == 2 and info["chunk_channels"] == kc
 
 
-def test_pointwise_chunked_default_for_wide_inputs():
-    L = workloads.Layer("pw_wide", 1100, 40, 7, 7, N=3, V=4, sparsity=0.9)
-    info = check(L, 450)
+@pytest.mark.parametrize("V,gs", [(4, 2), (4, 4), (8, 2), (16, 4)])
+@pytest.mark.parametrize("hw", [12, 7])
+def test_pointwise_several_groups_per_wavefront(V, gs, hw):
+    """2 or 4 groups share a wavefront (32 or 16 pixels each); Cout=44 leaves the last
+    bundle partly empty, hw=7 exercises the scalar staging path."""
+    L = workloads.Layer("pw_gs%d_v%d" % (gs, V), 60, 44, hw, hw, N=5, V=V, sparsity=0.6)
+    info = check(L, 430 + V + gs + hw, group_slots=gs)
+    assert info["mode"] == 1 and info["group_slots"] == gs
+
+
+@pytest.mark.parametrize("Cin,gs", [(1100, 2), (2048, 4)])
+def test_pointwise_wide_inputs_pair_groups_by_default(Cin, gs):
+    L = workloads.Layer("pw_wide%d" % Cin, Cin, 40, 7, 7, N=3, V=4, sparsity=0.9)
+    info = check(L, 450 + gs)
+    assert info["mode"] == 1 and info["group_slots"] == gs
+
+
+def test_pointwise_very_wide_or_small_v_inputs_are_chunked():
+    info = check(workloads.Layer("pw_wide_v1", 700, 12, 7, 7, N=3, V=1, sparsity=0.9), 456)
+    assert info["mode"] == 2
+    info = check(workloads.Layer("pw_wide2600", 2600, 16, 5, 5, N=2, V=4, sparsity=0.95), 457)
     assert info["mode"] == 2
 
 

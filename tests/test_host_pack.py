@@ -118,6 +118,36 @@ def test_chunked_layouts_selfcheck_for_every_chunk_size():
         alcs.alcs_set_tuning("chunk_channels", 0)
 
 
+@pytest.mark.parametrize("gs", [1, 2, 4])
+@pytest.mark.parametrize("V,Cout", [(4, 44), (8, 40), (16, 50)])
+def test_group_slot_layouts_selfcheck(gs, V, Cout):
+    """Bundles of 1, 2 or 4 groups per wavefront, including a last bundle that is not full."""
+    rng = np.random.default_rng(gs * 10 + V)
+    G = oracle.n_groups(Cout, V)
+    W = rng.standard_normal((Cout, 70, 1, 1)).astype(np.float32)
+    mask = (rng.random((G, 70, 1, 1)) < 0.35).astype(np.uint8)
+    mask[1] = 0          # an empty group ends up in the last bundle
+    try:
+        alcs.alcs_set_tuning("group_slots", gs)
+        p = alcs.alcs_pack_weights(W, mask, V)
+    finally:
+        alcs.alcs_set_tuning("group_slots", 0)
+    assert p.selfcheck() == 0
+    for got, want in zip(p.export(), oracle.pack(W, mask, V)):
+        assert got.tobytes() == want.tobytes()
+
+
+@pytest.mark.parametrize("Cin", [640, 1280, 2048, 2560])
+def test_wide_inputs_pack_and_selfcheck(Cin):
+    rng = np.random.default_rng(Cin)
+    W = rng.standard_normal((24, Cin, 1, 1)).astype(np.float32)
+    mask = (rng.random((6, Cin, 1, 1)) < 0.1).astype(np.uint8)
+    p = alcs.alcs_pack_weights(W, mask, 4)
+    assert p.selfcheck() == 0
+    for got, want in zip(p.export(), oracle.pack(W, mask, 4)):
+        assert got.tobytes() == want.tobytes()
+
+
 def test_python_binding_rejects_bad_mask_shape():
     W = np.zeros((8, 4, 1, 1), np.float32)
     with pytest.raises(ValueError):
