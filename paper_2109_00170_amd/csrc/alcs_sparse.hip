@@ -156,7 +156,28 @@ struct Run {
     int o;
 };
 
+// The first two runs of a segment: fetched together, two runs ahead of their use, so
+// that the latency of the weight fetch (an L2 hit at best) is covered by 32 columns of
+// multiplies instead of 16.
 template <int V, bool MF, int GS = 1>
+struct Run2 {
+    Run<V, MF, GS> r0, r1;
+};
+
+template <int V, bool MF, int GS = 1>
+__device__ __forceinline__ Run<V, MF, GS> load_run(const ConvArgs &a, int blk, int lane);
+
+// Runs at columns blk and blk + 16 (the second may lie beyond the segment: the arrays
+// end with a spare run, so the read stays in bounds and the data is not used).
+template <int V, bool MF, int GS = 1>
+__device__ __forceinline__ Run2<V, MF, GS> load_run2(const ConvArgs &a, int blk, int lane) {
+    Run2<V, MF, GS> r;
+    r.r0 = load_run<V, MF, GS>(a, blk, lane);
+    r.r1 = load_run<V, MF, GS>(a, blk + 16, lane);
+    return r;
+}
+
+template <int V, bool MF, int GS>
 __device__ __forceinline__ Run<V, MF, GS> load_run(const ConvArgs &a, int blk, int lane) {
     Run<V, MF, GS> r;
     if constexpr (MF) {
@@ -232,23 +253,23 @@ __device__ __forceinline__ void mfma_batch(const float (&aw)[(V / 4) * GS], int 
 // One segment (the kept columns of one bundle of GS groups inside one channel chunk),
 // MFMA form.  start/cnt are wave-uniform; base is the lane's byte offset inside an LDS
 // row (minus the chunk's first row); SH = log2(pixels per lane) for 1x1, 0 for 3x3.
-// `first` is the segment's first run, loaded by the caller (early enough that it is
-// not queued behind output stores); the following runs are fetched while the current
-// one is being multiplied.
+// `first` holds the segment's first two runs, loaded by the caller (early enough that
+// they are not queued behind output stores); later runs are fetched two runs ahead.
 template <int V, int PV, int SH, int GS = 1>
 __device__ __forceinline__ void mac_segment(const ConvArgs &a, int start, int cnt,
                                             const char *lds, int base, int lane,
-                                            Run<V, true, GS> first, Acc<V, PV, true> &acc) {
+                                            Run2<V, true, GS> first, Acc<V, PV, true> &acc) {
     constexpr int Q = V / 4;
     constexpr int B = kCntAlign;  // columns whose LDS reads are in flight together
     static_assert(B == 8, "a run of 16 columns is two batches");
-    Run<V, true, GS> nxt = first;
+    Run<V, true, GS> r0 = first.r0, r1 = first.r1;
     for (int j0 = 0; j0 < cnt; j0 += 16) {
         float aw[Q * GS];
 #pragma unroll
-        for (int q = 0; q < Q * GS; ++q) aw[q] = nxt.a[q];
-        const int ov = nxt.o;
-        if (j0 + 16 < cnt) nxt = load_run<V, true, GS>(a, start + j0 + 16, lane);
+        for (int q = 0; q < Q * GS; ++q) aw[q] = r0.a[q];
+        const int ov = r0.o;
+        r0 = r1;
+        if (j0 + 32 < cnt) r1 = load_run<V, true, GS>(a, start + j0 + 32, lane);
         mfma_batch<0, B, V, PV, SH, GS>(aw, ov, lds, base, acc);
         if (j0 + 8 < cnt) mfma_batch<8, B, V, PV, SH, GS>(aw, ov, lds, base, acc);
     }
@@ -259,7 +280,7 @@ __device__ __forceinline__ void mac_segment(const ConvArgs &a, int start, int cn
 template <int V, int PV, int SH, int GS = 1>
 __device__ __forceinline__ void mac_segment(const ConvArgs &a, int start, int cnt,
                                             const char *lds, int base, int lane,
-                                            Run<V, false, GS> first, Acc<V, PV, false> &acc) {
+                                            Run2<V, false, GS> first, Acc<V, PV, false> &acc) {
     static_assert(V <= 4 && GS == 1, "FMA path is built for V <= 4, one group per wavefront");
     (void)lane;
     (void)first;
@@ -438,10 +459,10 @@ __global__ void __launch_bounds__(1024) k_pw_resident(const ConvArgs a) {
     auto nth = [&](int k) { return k * nw + ((k & 1) ? nw - 1 - wave : wave); };
     const bool any = nth(0) < ng;
     Work w0 = no_work(), w1 = no_work();
-    Run<V, MF, GS> run0, run1;
+    Run2<V, MF, GS> run0, run1;
     if (any) {
         w0 = load_work(a.work, g_begin + nth(0));
-        run0 = load_run<V, MF, GS>(a, w0.start, lane);
+        run0 = load_run2<V, MF, GS>(a, w0.start, lane);
         if (nth(1) < ng) w1 = load_work(a.work, g_begin + nth(1));
     }
 
@@ -459,7 +480,7 @@ __global__ void __launch_bounds__(1024) k_pw_resident(const ConvArgs a) {
         const bool more = nth(k + 1) < ng;
         Work w2 = no_work();
         if (more) {
-            run1 = load_run<V, MF, GS>(a, w1.start, lane);
+            run1 = load_run2<V, MF, GS>(a, w1.start, lane);
             if (nth(k + 2) < ng) w2 = load_work(a.work, g_begin + nth(k + 2));
         }
         Acc<V, PV, MF> acc;
@@ -512,7 +533,7 @@ __global__ void __launch_bounds__(512) k_pw_chunked(const ConvArgs a) {
         for (int u = 0; u < UG; ++u) {
             if (slot[u] < 0) continue;
             const Work s = load_work(a.work, (size_t)slot[u] * a.nchunks + ch);
-            mac_segment<V, PV, SH>(a, s.start, s.cnt, ldsb, base, lane, load_run<V, MF>(a, s.start, lane), acc[u]);
+            mac_segment<V, PV, SH>(a, s.start, s.cnt, ldsb, base, lane, load_run2<V, MF>(a, s.start, lane), acc[u]);
         }
     }
     PixOut<PV> px;
@@ -607,12 +628,12 @@ __global__ void __launch_bounds__(512) k_pw_stream(const ConvArgs a) {
             const int base = lane * PV * 4;
             Work w0 = load_work(a.work, nth(0)), w1 = no_work();
             if (nth(1) < a.G) w1 = load_work(a.work, nth(1));
-            Run<V, true> run0 = load_run<V, true>(al, w0.start, lane), run1;
+            Run2<V, true> run0 = load_run2<V, true>(al, w0.start, lane), run1;
             for (int k = 0;; ++k) {
                 const bool more = nth(k + 1) < a.G;
                 Work w2 = no_work();
                 if (more) {
-                    run1 = load_run<V, true>(al, w1.start, lane);
+                    run1 = load_run2<V, true>(al, w1.start, lane);
                     if (nth(k + 2) < a.G) w2 = load_work(a.work, nth(k + 2));
                 }
                 Acc<V, PV, true> acc;
@@ -703,7 +724,7 @@ __global__ void __launch_bounds__(512) k_conv3(const ConvArgs a) {
         for (int u = 0; u < UG; ++u) {
             if (slot[u] < 0) continue;
             const Work s = load_work(a.work, (size_t)slot[u] * a.nchunks + ch);
-            mac_segment<V, 1, 0>(a, s.start, s.cnt, ldsb, base, lane, load_run<V, MF>(a, s.start, lane), acc[u]);
+            mac_segment<V, 1, 0>(a, s.start, s.cnt, ldsb, base, lane, load_run2<V, MF>(a, s.start, lane), acc[u]);
         }
     }
     const int oy = oy0 + ly, ox = ox0 + lx;
