@@ -37,6 +37,39 @@ def layer_flops(L, nnzb):
     return 2.0 * L.N * L.Ho * L.Wo * L.V * nnzb
 
 
+def kernel_symbol(L, info):
+    """Name of the kernel template instance a launch used, as rocprofv3 prints it."""
+    b = lambda x: "true" if x else "false"
+    mf = info["path"] == 2
+    vec = L.stride == 1 and (L.Ho * L.Wo) % 4 == 0
+    if info["mode"] == 1:
+        return "alcs::k_pw_resident<%d, %d, %s, %s, %d>" % (L.V, info["pv"], b(mf), b(vec), info["group_slots"])
+    if info["mode"] == 2:
+        return "alcs::k_pw_chunked<%d, %d, 4, %s, %s>" % (L.V, info["pv"], b(mf), b(vec))
+    if info["mode"] == 3:
+        return "alcs::k_conv3<%d, %d, 4, %s>" % (L.V, L.stride, b(mf))
+    return "alcs::k_pw_stream<%d, %d, 8>" % (L.V, info["pv"])
+
+
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_mobilenetv1_pointwise_b32.txt")
+
+
+def read_traffic(symbol):
+    """HBM bytes per launch of `symbol` from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE + WRITE_SIZE, each scaled by a plain copy of known size), or None."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            for line in f:
+                if line.startswith("#") or "|" not in line:
+                    continue
+                name, fetch_b, write_b = [t.strip() for t in line.split("|")[:3]]
+                if name == symbol:
+                    return int(float(fetch_b) + float(write_b))
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -48,6 +81,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-batch", type=int, default=32)
     ap.add_argument("--layers-json", default=None, help="also write the per-layer table to this file")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="for rocprofv3 --pmc runs only: put a plain 256 MiB device copy in front of every "
+                         "step, so that the HBM byte counters can be scaled by a kernel of known traffic "
+                         "(the printed timings are then not a benchmark result)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (the path needs no exchange between GPUs); "
@@ -93,45 +130,52 @@ def main():
         run_step()
     torch.cuda.synchronize()
 
-    # untimed pass with an event pair around every launch: per-layer durations in the
-    # same launch order and with the same buffers as the timed steps
-    nprof = max(5, min(args.steps, 20))
-    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-           for _ in layers] for _ in range(nprof)]
-    torch.cuda._sleep(100_000_000)  # keep the GPU busy (~40 ms) so that the host runs ahead of it:
-    # otherwise an event pair around a short kernel measures the host's submission time
-    for s in range(nprof):
-        for i in range(len(layers)):
-            ev[s][i][0].record(stream)
-            run_layer(i)
-            ev[s][i][1].record(stream)
-    torch.cuda.synchronize()
-    layer_us = [float(np.median([ev[s][i][0].elapsed_time(ev[s][i][1]) * 1e3 for s in range(nprof)]))
-                for i in range(len(layers))]
+    def run_layer_timed(i, pair):
+        alcs.alcs_sparse_conv(packed[i], Xs[i], None, Ys[i], stride=layers[i].stride, stream=stream_ptr,
+                              events=pair)
+
     launch = []
     for i in range(len(layers)):
         run_layer(i)
         launch.append(alcs.alcs_last_launch())
     torch.cuda.synchronize()
-    dom = int(np.argmax(layer_us))
+    symbols = [kernel_symbol(layers[i], launch[i]) for i in range(len(layers))]
 
-    # ---- timed region: exactly `steps` steps; events bracket the dominant layer's launch ----
-    dom_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-              for _ in range(args.steps)]
+    calib = None
+    if args.calib_copy:
+        calib = (torch.zeros(64 * 1024 * 1024, device=dev), torch.empty(64 * 1024 * 1024, device=dev))
+
+    # ---- timed region: exactly `steps` steps, nothing but the 13 launches per step ----
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(args.steps):
-        for i in range(len(layers)):
-            if i == dom:
-                dom_ev[s][0].record(stream)
-                run_layer(i)
-                dom_ev[s][1].record(stream)
-            else:
-                run_layer(i)
+        if calib is not None:
+            calib[1].copy_(calib[0])
+        run_step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    dom_us = float(np.mean([a.elapsed_time(b) * 1e3 for a, b in dom_ev]))
+
+    # ---- the same `steps` steps once more, every launch carrying a pair of HIP events that
+    # take the kernel's own begin/end time stamps (alcs_sparse_conv_timed): per-launch
+    # durations in the launch order and on the buffers of the timed steps ----
+    evs = alcs.HipEvents(args.steps * len(layers))
+    torch.cuda.synchronize()
+    for s in range(args.steps):
+        for i in range(len(layers)):
+            run_layer_timed(i, evs.pairs[s * len(layers) + i])
+    torch.cuda.synchronize()
+    dur = np.array([[evs.elapsed_us(s * len(layers) + i) for i in range(len(layers))]
+                    for s in range(args.steps)])
+    evs.close()
+    layer_us = [float(np.mean(dur[:, i])) for i in range(len(layers))]
+    # the dominant kernel: the kernel symbol (template instance) with the largest total time per step
+    per_symbol = {}
+    for i, sname in enumerate(symbols):
+        per_symbol[sname] = per_symbol.get(sname, 0.0) + layer_us[i]
+    dom_symbol = max(per_symbol, key=per_symbol.get)
+    dom_layers = [i for i, sname in enumerate(symbols) if sname == dom_symbol]
+    dom_us = float(np.mean(dur[:, dom_layers]))
 
     dense_flops = sum(L.dense_flops() for L in layers)
     alg_flops = sum(layer_flops(L, n) for L, n in zip(layers, nnzb))
@@ -179,19 +223,20 @@ def main():
                                                   r["launch"]["workgroups"], r["launch"]["lds_bytes"],
                                                   r["launch"]["group_tiles"])), file=sys.stderr)
     sum_us = sum(layer_us)
-    print("sum of per-layer medians %.1f us; step %.1f us; sum of rooflines %.1f us (%.3f of step)" %
+    print("sum of per-launch kernel times %.1f us; step %.1f us; sum of rooflines %.1f us (%.3f of step)" %
           (sum_us, ms_per_step * 1e3, roof_sum * 1e6, roof_sum * 1e3 / ms_per_step), file=sys.stderr)
     if args.layers_json:
         with open(args.layers_json, "w") as f:
             json.dump(rows, f, indent=1)
 
-    Ld = layers[dom]
-    dom_bytes = layer_bytes(Ld, nnzb[dom])
+    dom_bytes = float(np.mean([layer_bytes(layers[i], nnzb[i]) for i in dom_layers]))
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                "kernel": "k_pw_resident (layer %s, %d->%d @%dx%d, N=%d)" % (Ld.name, Ld.Cin, Ld.Cout, Ld.H, Ld.W, Ld.N),
-                "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_us": round(dom_us, 2)}
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic(dom_symbol),
+                "kernel": dom_symbol,
+                "layers": [layers[i].name for i in dom_layers],
+                "algorithmic_bytes_per_launch": int(dom_bytes), "avg_launch_us": round(dom_us, 2),
+                "share_of_step": round(per_symbol[dom_symbol] / sum(layer_us), 3)}
 
     out = {
         "metric": "dense-equiv GFLOP/s + achieved HBM GB/s, sparse pointwise conv, 1 MI355X",
@@ -228,6 +273,8 @@ def main():
                                "cores": threads, "kind": "oracle",
                                "sample": "same 13 layers and weights, first %d of %d images, %.1f s of CPU time"
                                          % (nb, args.batch, t_cpu)}
+    if args.calib_copy:
+        out["calibration_run"] = True
     print(json.dumps(out))
 
 

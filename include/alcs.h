@@ -142,6 +142,18 @@ int alcs_sparse_conv(const alcs_packed_t *Wp, const float *X_dev, const float *b
                      void *stream);
 
 /*
+ * alcs_sparse_conv with the kernel's own begin and end time stamps recorded on two
+ * caller-created hipEvent_t (passed as void*, either may be NULL): the pair measures
+ * the launch itself (hipEventElapsedTime after synchronising on stop_event), without
+ * the gaps that event packets put on a stream around a short kernel.  For benchmarks;
+ * arguments, results and errors are those of alcs_sparse_conv (Section 3.2.2,
+ * "Efficient multiplication computation").
+ */
+int alcs_sparse_conv_timed(const alcs_packed_t *Wp, const float *X_dev, const float *bias_dev,
+                           float *Y_dev, int N, int Cin, int Cout, int H, int W, int kernel,
+                           int stride, void *stream, void *start_event, void *stop_event);
+
+/*
  * Dense convolution with the same conventions: the sparsity-0 case of the
  * operation above and the same-GPU baseline (the role the dense models play in the
  * paper's Section 4.1 timing protocol).

@@ -6,6 +6,7 @@ built, loading fails with an ImportError.
 """
 from ._binding import (  # noqa: F401
     AlcsError,
+    HipEvents,
     Packed,
     alcs_dense_conv,
     alcs_last_launch,

@@ -14,7 +14,7 @@ _lib = None
 EXPORTS = [
     "alcs_strerror", "alcs_last_hip_error", "alcs_version", "alcs_pack_weights", "alcs_packed_info",
     "alcs_packed_on_device", "alcs_packed_export", "alcs_packed_selfcheck", "alcs_packed_free",
-    "alcs_sparse_conv", "alcs_dense_conv", "alcs_set_tuning", "alcs_last_launch",
+    "alcs_sparse_conv", "alcs_sparse_conv_timed", "alcs_dense_conv", "alcs_set_tuning", "alcs_last_launch",
 ]
 
 
@@ -52,6 +52,7 @@ def load_library():
     lib.alcs_packed_free.argtypes = [vp]
     lib.alcs_packed_free.restype = None
     lib.alcs_sparse_conv.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp]
+    lib.alcs_sparse_conv_timed.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp, vp, vp]
     lib.alcs_dense_conv.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp]
     lib.alcs_set_tuning.argtypes = [ctypes.c_char_p, ci]
     lib.alcs_last_launch.argtypes = [cip, ci]
@@ -160,18 +161,59 @@ def _dev_ptr(t, name, dtype_name="torch.float32"):
     return ctypes.c_void_p(t.data_ptr())
 
 
-def alcs_sparse_conv(packed: Packed, X, bias, Y, stride: int = 1, stream=None) -> None:
-    """Y[N,Cout,Ho,Wo] = sparse_conv(packed, X[N,Cin,H,W]) + bias; device tensors, async on stream."""
+def alcs_sparse_conv(packed: Packed, X, bias, Y, stride: int = 1, stream=None, events=None) -> None:
+    """Y[N,Cout,Ho,Wo] = sparse_conv(packed, X[N,Cin,H,W]) + bias; device tensors, async on stream.
+    events = (start, stop) hipEvent_t handles (ints) routes the call to alcs_sparse_conv_timed."""
     N, Cin, H, W = X.shape
     k = packed.kernel
     exp = (N, packed.Cout, out_size(H, k, stride), out_size(W, k, stride))
     if tuple(Y.shape) != exp:
         raise ValueError("Y must have shape %r, got %r" % (exp, tuple(Y.shape)))
-    rc = load_library().alcs_sparse_conv(packed.handle, _dev_ptr(X, "X"), _dev_ptr(bias, "bias"),
-                                         _dev_ptr(Y, "Y"), N, Cin, packed.Cout, H, W, k, int(stride),
-                                         _stream_ptr(stream))
+    lib = load_library()
+    if events is None:
+        rc = lib.alcs_sparse_conv(packed.handle, _dev_ptr(X, "X"), _dev_ptr(bias, "bias"), _dev_ptr(Y, "Y"),
+                                  N, Cin, packed.Cout, H, W, k, int(stride), _stream_ptr(stream))
+    else:
+        rc = lib.alcs_sparse_conv_timed(packed.handle, _dev_ptr(X, "X"), _dev_ptr(bias, "bias"),
+                                        _dev_ptr(Y, "Y"), N, Cin, packed.Cout, H, W, k, int(stride),
+                                        _stream_ptr(stream), ctypes.c_void_p(events[0]),
+                                        ctypes.c_void_p(events[1]))
     if rc != 0:
         raise AlcsError(rc, "alcs_sparse_conv")
+
+
+class HipEvents:
+    """A pool of raw hipEvent_t pairs from the HIP runtime that is already in the process
+    (PyTorch's), for timing launches with alcs_sparse_conv_timed."""
+
+    def __init__(self, n_pairs: int):
+        import torch
+        path = os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so")
+        self._hip = ctypes.CDLL(path)
+        self._hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self._hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self._hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.pairs = []
+        for _ in range(n_pairs):
+            a, b = ctypes.c_void_p(), ctypes.c_void_p()
+            if self._hip.hipEventCreate(ctypes.byref(a)) or self._hip.hipEventCreate(ctypes.byref(b)):
+                raise RuntimeError("hipEventCreate failed")
+            self.pairs.append((a.value, b.value))
+
+    def elapsed_us(self, i: int) -> float:
+        a, b = self.pairs[i]
+        self._hip.hipEventSynchronize(ctypes.c_void_p(b))
+        ms = ctypes.c_float()
+        rc = self._hip.hipEventElapsedTime(ctypes.byref(ms), ctypes.c_void_p(a), ctypes.c_void_p(b))
+        if rc:
+            raise RuntimeError("hipEventElapsedTime failed (%d)" % rc)
+        return ms.value * 1e3
+
+    def close(self):
+        for a, b in self.pairs:
+            self._hip.hipEventDestroy(ctypes.c_void_p(a))
+            self._hip.hipEventDestroy(ctypes.c_void_p(b))
+        self.pairs = []
 
 
 def alcs_dense_conv(W_dev, X, bias, Y, stride: int = 1, stream=None) -> None:

@@ -20,6 +20,7 @@
 // a useful one (nothing is densified).  For V in {1, 2} (and optionally 4) plain
 // v_fma_f32 with scalar-register weights is used.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <algorithm>
 #include <cstdint>
@@ -795,9 +796,9 @@ static int set_lds_limit(kern_t k, int lds) {
 
 using namespace alcs;
 
-extern "C" int alcs_sparse_conv(const alcs_packed_t *Wp, const float *X_dev, const float *bias_dev,
-                                float *Y_dev, int N, int Cin, int Cout, int H, int W, int kernel,
-                                int stride, void *stream) {
+static int launch_sparse(const alcs_packed_t *Wp, const float *X_dev, const float *bias_dev,
+                         float *Y_dev, int N, int Cin, int Cout, int H, int W, int kernel,
+                         int stride, void *stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
     if (!Wp || N < 0 || H <= 0 || W <= 0) return ALCS_E_INVALID_ARG;
     if (Cin != Wp->Cin || Cout != Wp->Cout || kernel != Wp->k) return ALCS_E_INVALID_ARG;
     if (stride != 1 && stride != 2) return ALCS_E_UNSUPPORTED;
@@ -966,8 +967,29 @@ extern "C" int alcs_sparse_conv(const alcs_packed_t *Wp, const float *X_dev, con
     if (rc != ALCS_OK) return rc;
     record_launch(mode, pv, nw, a.total_wgs, lds, a.ngt, L.KC, mfma ? 2 : 1, L.GS);
     const int grid = mode == 4 ? a.npt : a.wg_per_xcd * kXcds;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(nw * 64), lds, (hipStream_t)stream, a);
-    e = hipGetLastError();
+    if (ev_start || ev_stop) {
+        // the events take the kernel's own begin and end time stamps (no gap for event
+        // packets on the stream): for benchmarks that time single launches
+        void *kargs[] = {(void *)&a};
+        e = hipExtLaunchKernel((const void *)kern, dim3(grid), dim3(nw * 64), kargs, lds, (hipStream_t)stream,
+                               ev_start, ev_stop, 0);
+    } else {
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(nw * 64), lds, (hipStream_t)stream, a);
+        e = hipGetLastError();
+    }
     if (e != hipSuccess) { set_hip_error((int)e); return ALCS_E_HIP; }
     return ALCS_OK;
+}
+
+extern "C" int alcs_sparse_conv(const alcs_packed_t *Wp, const float *X_dev, const float *bias_dev,
+                                float *Y_dev, int N, int Cin, int Cout, int H, int W, int kernel,
+                                int stride, void *stream) {
+    return launch_sparse(Wp, X_dev, bias_dev, Y_dev, N, Cin, Cout, H, W, kernel, stride, stream, nullptr, nullptr);
+}
+
+extern "C" int alcs_sparse_conv_timed(const alcs_packed_t *Wp, const float *X_dev, const float *bias_dev,
+                                      float *Y_dev, int N, int Cin, int Cout, int H, int W, int kernel,
+                                      int stride, void *stream, void *start_event, void *stop_event) {
+    return launch_sparse(Wp, X_dev, bias_dev, Y_dev, N, Cin, Cout, H, W, kernel, stride, stream,
+                         (hipEvent_t)start_event, (hipEvent_t)stop_event);
 }
