@@ -8,7 +8,7 @@ from typing import Optional
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libalcs.so")
+_LIB_PATH = os.environ.get("ALCS_LIBRARY") or os.path.join(_HERE, "libalcs.so")
 _lib = None
 
 EXPORTS = [

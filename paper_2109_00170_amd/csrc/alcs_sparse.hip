@@ -95,27 +95,37 @@ __device__ __forceinline__ int logical_wg(const ConvArgs &a) {
 
 // ------------------------------------------------------------------ accumulators
 
+#ifndef ALCS_NACC1
+#define ALCS_NACC1 2
+#endif
+#ifndef ALCS_NACC2
+#define ALCS_NACC2 1
+#endif
+#define ALCS_NACC_FOR(n) ((n) == 1 ? ALCS_NACC1 : (n) == 2 ? ALCS_NACC2 : 1)
+
 template <int V, int PV, bool MF>
 struct Acc;
 
 template <int V, int PV>
-struct Acc<V, PV, true> {  // MFMA: a[q][pv][i] = channel 4q+i, pixel pv of the lane
-    // With a single accumulator every MFMA would wait for the one before it; in that
-    // case even and odd columns go to two accumulators that are added at the end.
-    static constexpr bool DUAL = (V / 4) * PV == 1;
-    f4 a[V / 4][PV];
-    f4 alt[V / 4][PV];
+struct Acc<V, PV, true> {  // MFMA: a[k][q][pv][i] = channel 4q+i, pixel pv of the lane, partial sum k
+    // An MFMA that accumulates into the register of the one before it has to wait for its
+    // result.  With few independent accumulators per lane (V/4 * PV), consecutive columns
+    // therefore go round-robin to NACC partial accumulators that are added at the end.
+    static constexpr int NACC = ALCS_NACC_FOR((V / 4) * PV);
+    f4 a[NACC][V / 4][PV];
     __device__ __forceinline__ void zero() {
 #pragma unroll
-        for (int q = 0; q < V / 4; ++q)
+        for (int k = 0; k < NACC; ++k)
 #pragma unroll
-            for (int pv = 0; pv < PV; ++pv) {
-                a[q][pv] = f4{0.f, 0.f, 0.f, 0.f};
-                if (DUAL) alt[q][pv] = f4{0.f, 0.f, 0.f, 0.f};
-            }
+            for (int q = 0; q < V / 4; ++q)
+#pragma unroll
+                for (int pv = 0; pv < PV; ++pv) a[k][q][pv] = f4{0.f, 0.f, 0.f, 0.f};
     }
     __device__ __forceinline__ float get(int v, int pv) const {
-        return DUAL ? a[v >> 2][pv][v & 3] + alt[v >> 2][pv][v & 3] : a[v >> 2][pv][v & 3];
+        float r = a[0][v >> 2][pv][v & 3];
+#pragma unroll
+        for (int k = 1; k < NACC; ++k) r += a[k][v >> 2][pv][v & 3];
+        return r;
     }
 };
 
@@ -241,12 +251,9 @@ __device__ __forceinline__ void mfma_batch(const float (&aw)[(V / 4) * GS], int 
         for (int q = 0; q < V / 4; ++q)
 #pragma unroll
             for (int pv = 0; pv < PV; ++pv) {
-                if (Acc<V, PV, true>::DUAL && (COL & 1))
-                    acc.alt[q][pv] = __builtin_amdgcn_mfma_f32_4x4x1f32(aw[q * GS + AREG], x[C][pv],
-                                                                        acc.alt[q][pv], CBSZ, ABID, 0);
-                else
-                    acc.a[q][pv] = __builtin_amdgcn_mfma_f32_4x4x1f32(aw[q * GS + AREG], x[C][pv],
-                                                                      acc.a[q][pv], CBSZ, ABID, 0);
+                constexpr int K = COL % Acc<V, PV, true>::NACC;
+                acc.a[K][q][pv] = __builtin_amdgcn_mfma_f32_4x4x1f32(aw[q * GS + AREG], x[C][pv],
+                                                                     acc.a[K][q][pv], CBSZ, ABID, 0);
             }
     });
 }
