@@ -70,6 +70,121 @@ def read_traffic(symbol):
     return None
 
 
+def time_layer(alcs, torch, np, workloads, L, seed, dense=False, iters=10, tuning=None):
+    """Median kernel time of one layer (kernel time stamps), optionally with the dense conv."""
+    import oracle
+    for k, v in (tuning or {}).items():
+        alcs.alcs_set_tuning(k, v)
+    d = workloads.make_layer(L, seed)
+    p = alcs.alcs_pack_weights(d.W, d.mask, L.V)
+    X = torch.from_numpy(d.X).cuda()
+    Y = torch.empty((L.N, L.Cout, L.Ho, L.Wo), dtype=torch.float32, device="cuda")
+    # rotate over enough copies that more than 600 MB is touched before a buffer comes round
+    # again (the Infinity Cache holds 256 MB)
+    R = max(1, min(8, int(600e6 // (L.x_bytes() + L.y_bytes())) + 1))
+    Xr = [X] + [X.clone() for _ in range(R - 1)]
+    Yr = [Y] + [torch.empty_like(Y) for _ in range(R - 1)]
+    for _ in range(2):
+        alcs.alcs_sparse_conv(p, X, None, Y, stride=L.stride)
+    torch.cuda.synchronize()
+    info = alcs.alcs_last_launch()
+    iters = max(iters, R + 1)
+    ev = alcs.HipEvents(iters)
+    for i in range(iters):
+        alcs.alcs_sparse_conv(p, Xr[(i + 1) % R], None, Yr[(i + 1) % R], stride=L.stride, events=ev.pairs[i])
+    torch.cuda.synchronize()
+    t = float(np.median([ev.elapsed_us(i) for i in range(iters)]))
+    ev.close()
+    # sampled parity on the timed buffers
+    y = Y.reshape(-1)
+    rng = np.random.default_rng(seed + 5)
+    idx = rng.integers(0, y.numel(), size=500)
+    got = y[torch.from_numpy(idx).cuda()].cpu().numpy()
+    Wd_host = oracle.densify(d.W, d.mask, L.V)
+    ref = oracle.conv_at(Wd_host, d.X, idx, stride=L.stride)
+    err = float(np.max(np.abs(got - ref)) / max(float(y.abs().max()), 1e-30))
+    td = None
+    if dense:
+        Wd = torch.from_numpy(Wd_host).cuda()
+        for _ in range(2):
+            alcs.alcs_dense_conv(Wd, X, None, Y, stride=L.stride)
+        torch.cuda.synchronize()
+        e = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(5)]
+        for a, b in e:
+            a.record()
+            alcs.alcs_dense_conv(Wd, X, None, Y, stride=L.stride)
+            b.record()
+        torch.cuda.synchronize()
+        td = float(np.median([a.elapsed_time(b) * 1e3 for a, b in e]))
+    nn = p.nnzb
+    by, fl = layer_bytes(L, nn), layer_flops(L, nn)
+    p.free()
+    for k in (tuning or {}):
+        alcs.alcs_set_tuning(k, 0)
+    roof = max(by / (HBM_PEAK_GBS * 1e9), fl / (MFMA_FP32_PEAK_TFLOPS * 1e12)) * 1e6
+    bound = "hbm" if by / (HBM_PEAK_GBS * 1e9) >= fl / (MFMA_FP32_PEAK_TFLOPS * 1e12) else "mfma"
+    return {"us": t, "dense_us": td, "roof_us": roof, "bound": bound, "bytes": by, "flops": fl, "err": err,
+            "info": info}
+
+
+def report(kind, alcs, workloads, torch, np):
+    """Per-layer tables for configurations 3, 4, 5 and the MFMA / FMA comparison (markdown on stdout)."""
+    pr = lambda *a: print(*a, flush=True)
+    if kind == "sweep":
+        pr("| sparsity | sparse us | dense us | speed-up | dense-equiv TFLOP/s | actual TFLOP/s | bound | roofline frac | max rel err |")
+        pr("|---|---|---|---|---|---|---|---|---|")
+        for s in workloads.SWEEP_SPARSITIES:
+            L = workloads.sweep_layer(s)
+            r = time_layer(alcs, torch, np, workloads, L, workloads.seed_for(4, int(round(s * 100))), dense=True)
+            pr("| %.2f | %.1f | %.1f | %.2f | %.1f | %.1f | %s | %.3f | %.1e |" %
+               (s, r["us"], r["dense_us"], r["dense_us"] / r["us"], L.dense_flops() / r["us"] / 1e6,
+                r["flops"] / r["us"] / 1e6, r["bound"], r["roof_us"] / r["us"], r["err"]))
+    elif kind == "resnet":
+        pr("| layer | Cin->Cout | k/s | HxW | x | sparse us | dense us | speed-up | actual TFLOP/s | eff GB/s | bound | roofline frac | max rel err |")
+        pr("|---|---|---|---|---|---|---|---|---|---|---|---|---|")
+        tot = troof = tdense = 0.0
+        for i, L in enumerate(workloads.resnet50_bottlenecks(64)):
+            r = time_layer(alcs, torch, np, workloads, L, workloads.seed_for(3, i), dense=True)
+            tot += r["us"] * L.repeats
+            troof += r["roof_us"] * L.repeats
+            tdense += r["dense_us"] * L.repeats
+            pr("| %s | %d->%d | %d/%d | %d | %d | %.1f | %.1f | %.2f | %.1f | %.0f | %s | %.3f | %.1e |" %
+               (L.name, L.Cin, L.Cout, L.k, L.stride, L.H, L.repeats, r["us"], r["dense_us"],
+                r["dense_us"] / r["us"], r["flops"] / r["us"] / 1e6, r["bytes"] / r["us"] / 1e3, r["bound"],
+                r["roof_us"] / r["us"], r["err"]))
+        pr("\nall 48 convs, batch 64: sparse %.0f us, dense %.0f us (%.2fx), sum of rooflines %.0f us (%.3f)" %
+           (tot, tdense, tdense / tot, troof, troof / tot))
+    elif kind == "mbv2":
+        for V in (1, 4, 8, 16):
+            pr("\nV = %d" % V)
+            pr("| layer | sparse us | eff GB/s | bound | roofline frac | longest/mean group | max rel err |")
+            pr("|---|---|---|---|---|---|---|")
+            tot = troof = 0.0
+            for i, L in enumerate(workloads.mobilenet_v2_pointwise(128, V)):
+                r = time_layer(alcs, torch, np, workloads, L, workloads.seed_for(5, 100 * V + i))
+                tot += r["us"] * L.repeats
+                troof += r["roof_us"] * L.repeats
+                cnt = workloads.zipf_counts(L.G, L.K, 1.0 - L.sparsity)
+                pr("| %s | %.1f | %.0f | %s | %.3f | %.1f | %.1e |" %
+                   (L.name, r["us"], r["bytes"] / r["us"] / 1e3, r["bound"], r["roof_us"] / r["us"],
+                    cnt.max() / max(cnt.mean(), 1e-9), r["err"]))
+            pr("total (with repeats) %.0f us, sum of rooflines %.0f us (%.3f)" % (tot, troof, troof / tot))
+    elif kind == "paths":
+        pr("| layer | MFMA us | FMA us | FMA / MFMA |")
+        pr("|---|---|---|---|")
+        for i, L in enumerate(workloads.mobilenet_v1_pointwise(32, 0.9)):
+            if L.Cin > 639:
+                continue    # wider inputs pair groups per wavefront, which only the MFMA form does
+            a = time_layer(alcs, torch, np, workloads, L, workloads.seed_for(2, i), tuning={"path": 2})
+            b = time_layer(alcs, torch, np, workloads, L, workloads.seed_for(2, i), tuning={"path": 1})
+            pr("| %s | %.1f | %.1f | %.2f |" % (L.name, a["us"], b["us"], b["us"] / a["us"]))
+        for s in (0.5, 0.9):
+            L = workloads.sweep_layer(s)
+            a = time_layer(alcs, torch, np, workloads, L, workloads.seed_for(4, int(s * 100)), tuning={"path": 2})
+            b = time_layer(alcs, torch, np, workloads, L, workloads.seed_for(4, int(s * 100)), tuning={"path": 1})
+            pr("| sweep s=%.2f | %.1f | %.1f | %.2f |" % (s, a["us"], b["us"], b["us"] / a["us"]))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -81,6 +196,11 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-batch", type=int, default=32)
     ap.add_argument("--layers-json", default=None, help="also write the per-layer table to this file")
+    ap.add_argument("--report", choices=["sweep", "resnet", "mbv2", "paths"], default=None,
+                    help="instead of the benchmark line, print a per-layer table for another configuration: "
+                         "the sparsity sweep with the same-GPU dense conv (config 4), the ResNet-50-shaped "
+                         "bottleneck convs (config 3), the MobileNetV2-shaped pointwise convs for V in "
+                         "{1,4,8,16} (config 5), or MFMA against plain-FMA inner loops (V=4)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="for rocprofv3 --pmc runs only: put a plain 256 MiB device copy in front of every "
                          "step, so that the HBM byte counters can be scaled by a kernel of known traffic "
@@ -103,6 +223,10 @@ def main():
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
     alcs.load_library()
+
+    if args.report:
+        report(args.report, alcs, workloads, torch, np)
+        return
 
     sp = None if args.sparsity < 0 else args.sparsity
     layers = workloads.mobilenet_v1_pointwise(args.batch, sp)
