@@ -15,10 +15,21 @@ namespace alcs {
 constexpr int kSegAlign = 16;  // every segment starts at a multiple of 16 columns
 constexpr int kCntAlign = 8;   // and its padded length is a multiple of 8 columns
 
-// Geometry of the 3x3 kernels: an 8x8 tile of output pixels per wavefront, staged in
-// LDS with its halo, one plane of halo*halo floats per input channel.
+// Geometry of the 3x3 kernels: an 8x8 tile of output pixels per wavefront (lane =
+// 8*ly + lx), staged in LDS with its halo of (8-1)*stride+3 rows and columns, one
+// plane per input channel.  The planes are laid out so that the 64 lanes of a read hit
+// distinct LDS banks for every tap (true for 32 and for 64 banks):
+//   stride 1: row pitch 24 floats, halo column hx at hx; lane offset ly*24 + lx;
+//   stride 2: row pitch 28 floats, the 9 even halo columns at [0, 9) and the 8 odd ones
+//             at [12, 20); lane offset 2*ly*28 + lx; tap column s reads {0, 12, 1}[s].
 constexpr int kTile3 = 8;
-inline constexpr int halo3(int stride) { return (kTile3 - 1) * stride + 3; }
+constexpr int kOdd3 = 12;
+inline constexpr int halo_rows3(int stride) { return (kTile3 - 1) * stride + 3; }
+inline constexpr int pitch3(int stride) { return stride == 1 ? 24 : 28; }
+inline constexpr int halo_area3(int stride) { return halo_rows3(stride) * pitch3(stride); }
+inline constexpr int halo_col3(int stride, int hx) {
+    return stride == 1 ? hx : ((hx & 1) ? kOdd3 + (hx >> 1) : (hx >> 1));
+}
 
 // Bytes per LDS row that the stored 1x1 row selectors assume with one group per
 // wavefront (a 64-pixel fp32 tile); with GS groups per wavefront the tile has 64/GS
@@ -64,7 +75,7 @@ struct Layout {
     std::vector<float> w;          // [planes][wplane]
     std::vector<int32_t> off[2];   // [ncol * GS] each; LDS row selector of every block, in bytes:
                                    //   kernel 1: c * kRowBytes1 / GS        (pad: (c0 + KC) * kRowBytes1 / GS)
-                                   //   kernel 3: 4*(c*HA + r*halo + s)      (pad: 4*(c0 + KC)*HA)
+                                   //   kernel 3: 4*(c*HA + r*pitch + col(s)) (pad: 4*(c0 + KC)*HA), see halo_col3
                                    // with c the input channel and c0 the first channel of the block's chunk
     std::vector<int32_t> order;    // [G] groups by descending kept-column count
     std::vector<Work> work;        // [nbundles * nchunks], index b * nchunks + chunk

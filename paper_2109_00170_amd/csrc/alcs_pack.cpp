@@ -35,15 +35,13 @@ static inline int col_channel(int col, int kk) { return col / kk; }
 // LDS row selector of a real block (see Layout::off): a byte offset.
 static inline int32_t off_of(int col, int k, int table, int GS) {
     if (k == 1) return col * (kRowBytes1 / GS);
-    int c = col / 9, tap = col % 9, r = tap / 3, s = tap % 3;
-    int halo = halo3(table + 1);
-    return (c * halo * halo + r * halo + s) * 4;
+    const int c = col / 9, tap = col % 9, r = tap / 3, s = tap % 3, stride = table + 1;
+    return (c * halo_area3(stride) + r * pitch3(stride) + halo_col3(stride, s)) * 4;
 }
 
 static inline int32_t pad_off(int c0, int KC, int k, int table, int GS) {
     if (k == 1) return (c0 + KC) * (kRowBytes1 / GS);
-    int halo = halo3(table + 1);
-    return (c0 + KC) * halo * halo * 4;
+    return (c0 + KC) * halo_area3(table + 1) * 4;
 }
 
 // Index of (bundle column `col` counted from the start of the arrays, slot s) in a
@@ -213,7 +211,7 @@ int upload(alcs_packed *p) {
 // LDS tile while a 64-pixel tile of Cin+1 rows fits (Cin <= 639 in 160 KB); wider
 // inputs shrink the tile to 32 or 16 pixels and multiply 2 or 4 groups per wavefront
 // (V >= 4 only); beyond that, or for V < 4, chunks of 256 channels.
-// Kernel 3: 32 channels per chunk (the haloed tile is 100 or 289 floats per channel).
+// Kernel 3: 32 channels per chunk (the haloed tile plane is 240 or 476 floats per channel).
 static void default_tiles(int Cin, int k, int V, int *KC, int *GS) {
     *GS = 1;
     if (k == 3) { *KC = std::min(Cin, 32); return; }

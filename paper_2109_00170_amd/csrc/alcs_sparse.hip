@@ -533,16 +533,24 @@ __global__ void __launch_bounds__(512) k_pw_chunked(const ConvArgs a) {
     for (int t = tid; t < TP; t += blockDim.x) lds[a.KC * TP + t] = 0.f;
     for (int ch = 0; ch < a.nchunks; ++ch) {
         const int c0 = ch * a.KC, c1 = min(a.Cin, c0 + a.KC);
+        // work records and first weight runs of this chunk: fetched ahead of the input rows
+        Work wk[UG];
+        Run2<V, MF> rn[UG];
+#pragma unroll
+        for (int u = 0; u < UG; ++u) {
+            wk[u] = no_work();
+            if (slot[u] >= 0) {
+                wk[u] = load_work(a.work, (size_t)slot[u] * a.nchunks + ch);
+                rn[u] = load_run2<V, MF>(a, wk[u].start, lane);
+            }
+        }
         if (ch) __syncthreads();
         stage_pw<TP, VEC>(a, lds, q0, c0, c1);
         __syncthreads();
         const int base = lane * PV * 4 - c0 * (kRowBytes1 << SH);
 #pragma unroll
-        for (int u = 0; u < UG; ++u) {
-            if (slot[u] < 0) continue;
-            const Work s = load_work(a.work, (size_t)slot[u] * a.nchunks + ch);
-            mac_segment<V, PV, SH>(a, s.start, s.cnt, ldsb, base, lane, load_run2<V, MF>(a, s.start, lane), acc[u]);
-        }
+        for (int u = 0; u < UG; ++u)
+            if (slot[u] >= 0) mac_segment<V, PV, SH>(a, wk[u].start, wk[u].cnt, ldsb, base, lane, rn[u], acc[u]);
     }
     PixOut<PV> px;
     pix_out<PV, VEC>(a, q0, lane, px);
@@ -665,16 +673,19 @@ __global__ void __launch_bounds__(512) k_pw_stream(const ConvArgs a) {
 // ------------------------------------------------------------------ 3x3 kernel
 
 // One workgroup = one 8x8 tile of output pixels of one image (lane = pixel) and a
-// tile of groups; input channels are streamed in chunks of KC with their halo
-// ((8-1)*stride+3 squared floats per channel).  The selector stored with every kept
-// column is c*HA + r*halo + s, so the tap shift costs nothing at run time.
+// tile of groups; input channels are streamed in chunks of KC, each channel as a haloed
+// plane in the bank-conflict-free layout described with halo_col3.  The selector stored
+// with every kept column is 4*(c*HA + r*pitch + col(s)), so the tap shift costs nothing
+// at run time.
 template <int V, int STRIDE, int UG, bool MF>
 __global__ void __launch_bounds__(512) k_conv3(const ConvArgs a) {
     extern __shared__ float lds[];
-    constexpr int HALO = (kTile3 - 1) * STRIDE + 3;
-    constexpr int HA = HALO * HALO;
+    constexpr int ROWS = halo_rows3(STRIDE);   // halo rows = halo columns
+    constexpr int PITCH = pitch3(STRIDE);
+    constexpr int HA = halo_area3(STRIDE);
+    constexpr int HPOS = ROWS * ROWS;          // halo positions that are actually loaded
     const int logical = logical_wg(a);
-    if (logical >= a.total_wgs) return;
+    if (logical >= a.total_wgs || (a.debug & 8)) return;
     const int pt = logical / a.ngt, gt = logical - pt * a.ngt;
     const int tiles_per_img = a.tiles_x * a.tiles_y;
     const int n = pt / tiles_per_img, trem = pt - n * tiles_per_img;
@@ -695,45 +706,81 @@ __global__ void __launch_bounds__(512) k_conv3(const ConvArgs a) {
         slot[u] = idx < ng ? g_begin + idx : -1;
         acc[u].zero();
     }
-    for (int t = tid; t < HA; t += nt) lds[a.KC * HA + t] = 0.f;
-
-    // staging: a thread keeps one halo position and walks over channels
-    const int rpp = nt / HA > 0 ? nt / HA : 1;  // channel rows per pass (nt >= HA is guaranteed by the launcher for stride 1)
-    const int pos = tid % HA, r0 = tid / HA;
-    const int hy = pos / HALO, hx = pos - hy * HALO;
-    const int iy = iy0 + hy, ix = ix0 + hx;
-    const bool inb = iy >= 0 && iy < a.H && ix >= 0 && ix < a.W;
-    const float *src = a.X + (size_t)n * a.Cin * a.Pin + (inb ? (size_t)iy * a.W + ix : 0);
+    for (int t = tid; t < HA; t += nt) lds[a.KC * HA + t] = 0.f;  // the all-zero plane
 
     const int ly = lane >> 3, lx = lane & 7;
-    const int lane_base = (ly * STRIDE) * HALO + lx * STRIDE;
+    const int lane_base = (ly * STRIDE) * PITCH + lx;
+    // staging map: a thread keeps one halo position and walks over the chunk's channels
+    // (RPP channels are staged side by side; threads beyond RPP*HPOS only help when
+    // HPOS exceeds half the workgroup and the element loop below is used instead)
+    constexpr bool FIXED_POS = HPOS <= 128;
+    const int rpp = nt / HPOS;
+    const int pos = tid % HPOS, r0 = tid / HPOS;
+    const int phy = pos / ROWS, phx = pos - phy * ROWS;
+    const bool pin = iy0 + phy >= 0 && iy0 + phy < a.H && ix0 + phx >= 0 && ix0 + phx < a.W;
+    const float *psrc = a.X + (size_t)n * a.Cin * a.Pin + (pin ? (size_t)(iy0 + phy) * a.W + ix0 + phx : 0);
+    const int pdst = phy * PITCH + halo_col3(STRIDE, phx);
     for (int ch = 0; ch < a.nchunks; ++ch) {
         const int c0 = ch * a.KC, c1 = min(a.Cin, c0 + a.KC);
+        // the chunk's work records and first weight runs: fetched before the input tile, so
+        // that their latency is covered by the staging (vector memory returns in order)
+        Work wk[UG];
+        Run2<V, MF> rn[UG];
+#pragma unroll
+        for (int u = 0; u < UG; ++u) {
+            wk[u] = no_work();
+            if (slot[u] >= 0) {
+                wk[u] = load_work(a.work, (size_t)slot[u] * a.nchunks + ch);
+                rn[u] = load_run2<V, MF>(a, wk[u].start, lane);
+            }
+        }
         if (ch) __syncthreads();
-        if (nt >= HA) {
-            if (r0 < rpp)
-                for (int r = r0; r < c1 - c0; r += rpp)
-                    lds[r * HA + pos] = inb ? src[(size_t)(c0 + r) * a.Pin] : 0.f;
+        if (a.debug & 1) {
+        } else if (FIXED_POS && nt >= HPOS) {
+            if (r0 < rpp) {
+                constexpr int U = 8;
+                const int rows = c1 - c0;
+                int r = r0;
+                for (; r + (U - 1) * rpp < rows; r += U * rpp) {
+                    float v[U];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) v[u] = pin ? psrc[(size_t)(c0 + r + u * rpp) * a.Pin] : 0.f;
+#pragma unroll
+                    for (int u = 0; u < U; ++u) lds[(r + u * rpp) * HA + pdst] = v[u];
+                }
+                for (; r < rows; r += rpp) lds[r * HA + pdst] = pin ? psrc[(size_t)(c0 + r) * a.Pin] : 0.f;
+            }
         } else {
-            // fewer threads than halo positions: loop over positions as well
-            for (int e = tid; e < (c1 - c0) * HA; e += nt) {
-                const int r = e / HA, ps = e - r * HA;
-                const int y = ps / HALO, x = ps - y * HALO;
-                const int yy = iy0 + y, xx = ix0 + x;
-                float v = 0.f;
-                if (yy >= 0 && yy < a.H && xx >= 0 && xx < a.W)
-                    v = a.X[((size_t)n * a.Cin + c0 + r) * a.Pin + (size_t)yy * a.W + xx];
-                lds[e] = v;
+            // element e = (channel row, halo position); a thread's elements are nt apart
+            const int total = (c1 - c0) * HPOS;
+            constexpr int U = 4;
+            for (int e0 = tid; e0 < total; e0 += U * nt) {
+                float v[U];
+                int dst[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int e = e0 + u * nt;
+                    v[u] = 0.f;
+                    dst[u] = -1;
+                    if (e < total) {
+                        const int r = e / HPOS, ps = e - r * HPOS;
+                        const int hy = ps / ROWS, hx = ps - hy * ROWS;
+                        const int yy = iy0 + hy, xx = ix0 + hx;
+                        dst[u] = r * HA + hy * PITCH + halo_col3(STRIDE, hx);
+                        if (yy >= 0 && yy < a.H && xx >= 0 && xx < a.W)
+                            v[u] = a.X[((size_t)n * a.Cin + c0 + r) * a.Pin + (size_t)yy * a.W + xx];
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    if (dst[u] >= 0) lds[dst[u]] = v[u];
             }
         }
         __syncthreads();
         const int base = (lane_base - c0 * HA) * 4;
 #pragma unroll
-        for (int u = 0; u < UG; ++u) {
-            if (slot[u] < 0) continue;
-            const Work s = load_work(a.work, (size_t)slot[u] * a.nchunks + ch);
-            mac_segment<V, 1, 0>(a, s.start, s.cnt, ldsb, base, lane, load_run2<V, MF>(a, s.start, lane), acc[u]);
-        }
+        for (int u = 0; u < UG; ++u)
+            if (slot[u] >= 0 && !(a.debug & 2)) mac_segment<V, 1, 0>(a, wk[u].start, wk[u].cnt, ldsb, base, lane, rn[u], acc[u]);
     }
     const int oy = oy0 + ly, ox = ox0 + lx;
     PixOut<1> px;
@@ -741,7 +788,7 @@ __global__ void __launch_bounds__(512) k_conv3(const ConvArgs a) {
     px.yoff[0] = (long long)n * a.Cout * a.P + (long long)oy * a.Wo + ox;
 #pragma unroll
     for (int u = 0; u < UG; ++u)
-        if (slot[u] >= 0)
+        if (slot[u] >= 0 && !(a.debug & 4))
             store_group<V, 1, MF, false>(a, acc[u], load_work(a.work, (size_t)slot[u] * a.nchunks).group[0], px);
 }
 
@@ -769,21 +816,27 @@ static kern_t pick_resident(int pv, bool vec, int gs) {
 }
 
 template <int V, bool MF>
-static kern_t pick_chunked(int pv, bool vec) {
+static kern_t pick_chunked(int pv, bool vec, int ug) {
     if (vec) {
-        if (pv == 4) return k_pw_chunked<V, 4, 4, MF, true>;
-        if (pv == 2) return k_pw_chunked<V, 2, 4, MF, true>;
-        return k_pw_chunked<V, 1, 4, MF, true>;
+        if (pv == 4) return ug == 2 ? k_pw_chunked<V, 4, 2, MF, true> : k_pw_chunked<V, 4, 4, MF, true>;
+        if (pv == 2) return ug == 2 ? k_pw_chunked<V, 2, 2, MF, true> : k_pw_chunked<V, 2, 4, MF, true>;
+        return ug == 2 ? k_pw_chunked<V, 1, 2, MF, true> : k_pw_chunked<V, 1, 4, MF, true>;
     }
-    return k_pw_chunked<V, 1, 4, MF, false>;
+    return ug == 2 ? k_pw_chunked<V, 1, 2, MF, false> : k_pw_chunked<V, 1, 4, MF, false>;
 }
 
 template <int V, bool MF>
-static kern_t pick_conv3(int stride) {
+static kern_t pick_conv3(int stride, int ug) {
+    if (ug == 2) return stride == 1 ? k_conv3<V, 1, 2, MF> : k_conv3<V, 2, 2, MF>;
     return stride == 1 ? k_conv3<V, 1, 4, MF> : k_conv3<V, 2, 4, MF>;
 }
 
-constexpr int kUG = 4;  // groups per wavefront in the chunked kernels
+// Groups per wavefront in the chunked kernels: 4, or 2 when the layer has too few groups
+// to give every wavefront of a workgroup four of them.
+static int pick_ug(int G, int nw, int forced) {
+    if (forced == 2 || forced == 4) return forced;
+    return G <= 2 * nw ? 2 : 4;
+}
 
 // Dynamic LDS above 64 KB has to be allowed per kernel once; remember which kernels
 // already have the full 160 KB enabled.
@@ -842,7 +895,7 @@ static int launch_sparse(const alcs_packed_t *Wp, const float *X_dev, const floa
     bool mfma = V >= 4;
     if (V == 4 && T.path == 1) mfma = false;
     kern_t kern = nullptr;
-    int lds = 0, nw = 0, pv = 1, mode = 0;
+    int lds = 0, nw = 0, pv = 1, mode = 0, ug = 4;
 
     if (kernel == 1) {
         const bool vec = stride == 1 && (P % 4 == 0);
@@ -936,33 +989,34 @@ static int launch_sparse(const alcs_packed_t *Wp, const float *X_dev, const floa
             nw = 8;
             if (T.waves > 0) nw = std::min(T.waves, 8);
             if (L.GS != 1) return ALCS_E_UNSUPPORTED;
-            a.gpt = nw * kUG;
+            ug = pick_ug(G, nw, T.ug);
+            a.gpt = nw * ug;
             a.ngt = ceil_div(G, a.gpt);
             switch (V) {
-                case 1: kern = pick_chunked<1, false>(pv, vec); break;
-                case 2: kern = pick_chunked<2, false>(pv, vec); break;
-                case 4: kern = mfma ? pick_chunked<4, true>(pv, vec) : pick_chunked<4, false>(pv, vec); break;
-                case 8: kern = pick_chunked<8, true>(pv, vec); break;
-                case 16: kern = pick_chunked<16, true>(pv, vec); break;
+                case 1: kern = pick_chunked<1, false>(pv, vec, ug); break;
+                case 2: kern = pick_chunked<2, false>(pv, vec, ug); break;
+                case 4: kern = mfma ? pick_chunked<4, true>(pv, vec, ug) : pick_chunked<4, false>(pv, vec, ug); break;
+                case 8: kern = pick_chunked<8, true>(pv, vec, ug); break;
+                case 16: kern = pick_chunked<16, true>(pv, vec, ug); break;
             }
         }
     } else {
         mode = 3;
-        const int halo = halo3(stride);
-        lds = (L.KC + 1) * halo * halo * 4;
+        lds = (L.KC + 1) * halo_area3(stride) * 4;
         a.tiles_x = ceil_div(Wo, kTile3);
         a.tiles_y = ceil_div(Ho, kTile3);
         a.npt = a.tiles_x * a.tiles_y * N;
         nw = 8;
         if (T.waves > 0) nw = std::min(T.waves, 8);
-        a.gpt = nw * kUG;
+        ug = pick_ug(G, nw, T.ug);
+        a.gpt = nw * ug;
         a.ngt = ceil_div(G, a.gpt);
         switch (V) {
-            case 1: kern = pick_conv3<1, false>(stride); break;
-            case 2: kern = pick_conv3<2, false>(stride); break;
-            case 4: kern = mfma ? pick_conv3<4, true>(stride) : pick_conv3<4, false>(stride); break;
-            case 8: kern = pick_conv3<8, true>(stride); break;
-            case 16: kern = pick_conv3<16, true>(stride); break;
+            case 1: kern = pick_conv3<1, false>(stride, ug); break;
+            case 2: kern = pick_conv3<2, false>(stride, ug); break;
+            case 4: kern = mfma ? pick_conv3<4, true>(stride, ug) : pick_conv3<4, false>(stride, ug); break;
+            case 8: kern = pick_conv3<8, true>(stride, ug); break;
+            case 16: kern = pick_conv3<16, true>(stride, ug); break;
         }
     }
     if (!kern || lds > kMaxLds) return ALCS_E_UNSUPPORTED;
