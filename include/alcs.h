@@ -171,6 +171,7 @@ int alcs_dense_conv(const float *W_dev, const float *X_dev, const float *bias_de
  *     "group_tiles"     number of workgroups that share one pixel tile
  *     "path"            1 = plain-FMA inner loop where it exists (V = 4), 2 = MFMA inner
  *                       loop, 4 = persistent double-buffered 1x1 kernel where applicable
+ *     "tile_width"      output-tile width of the 3x3 kernel: 8, 16 or 32 (tile height 64/width)
  *     "debug"           measurement only, results become meaningless: bit 0 skips input
  *                       staging, bit 1 the multiply, bit 2 the output stores, bit 3
  *                       makes the kernel return at once
@@ -186,8 +187,8 @@ int alcs_set_tuning(const char *name, int value);
 /* What the last alcs_sparse_conv call of this thread launched: fills up to `cap`
  * ints {mode (1 = all input channels resident in LDS, 2 = chunked, 3 = 3x3,
  * 4 = persistent double-buffered), pv, waves, workgroups, lds_bytes, group_tiles,
- * chunk_channels, path, group_slots} and returns how many were written.  For tests
- * and benchmarks. */
+ * chunk_channels, path, group_slots, tile_width (3x3 only, else 0)} and returns how many were
+ * written.  For tests and benchmarks. */
 int alcs_last_launch(int *out, int cap);
 
 #ifdef __cplusplus

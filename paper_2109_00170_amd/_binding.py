@@ -239,8 +239,8 @@ def alcs_set_tuning(name: str, value: int) -> None:
 
 
 def alcs_last_launch() -> dict:
-    buf = (ctypes.c_int * 9)()
-    n = load_library().alcs_last_launch(buf, 9)
+    buf = (ctypes.c_int * 10)()
+    n = load_library().alcs_last_launch(buf, 10)
     keys = ["mode", "pv", "waves", "workgroups", "lds_bytes", "group_tiles", "chunk_channels", "path",
-            "group_slots"]
+            "group_slots", "tile_width"]
     return {k: int(buf[i]) for i, k in enumerate(keys[:n])}

@@ -15,21 +15,60 @@ namespace alcs {
 constexpr int kSegAlign = 16;  // every segment starts at a multiple of 16 columns
 constexpr int kCntAlign = 8;   // and its padded length is a multiple of 8 columns
 
-// Geometry of the 3x3 kernels: an 8x8 tile of output pixels per wavefront (lane =
-// 8*ly + lx), staged in LDS with its halo of (8-1)*stride+3 rows and columns, one
-// plane per input channel.  The planes are laid out so that the 64 lanes of a read hit
-// distinct LDS banks for every tap (true for 32 and for 64 banks):
-//   stride 1: row pitch 24 floats, halo column hx at hx; lane offset ly*24 + lx;
-//   stride 2: row pitch 28 floats, the 9 even halo columns at [0, 9) and the 8 odd ones
-//             at [12, 20); lane offset 2*ly*28 + lx; tap column s reads {0, 12, 1}[s].
-constexpr int kTile3 = 8;
-constexpr int kOdd3 = 12;
-inline constexpr int halo_rows3(int stride) { return (kTile3 - 1) * stride + 3; }
-inline constexpr int pitch3(int stride) { return stride == 1 ? 24 : 28; }
-inline constexpr int halo_area3(int stride) { return halo_rows3(stride) * pitch3(stride); }
-inline constexpr int halo_col3(int stride, int hx) {
-    return stride == 1 ? hx : ((hx & 1) ? kOdd3 + (hx >> 1) : (hx >> 1));
+// Geometry of the 3x3 kernels: a TH x TW tile of output pixels per wavefront, TW one of
+// 8, 16, 32 ("tile shape" ti = 0, 1, 2) and TH = 64 / TW, lane = TW*ly + lx.  Wide tiles
+// give long contiguous runs for the input loads and output stores of wide images; 8x8 has
+// the smallest halo and fits small images best.  The tile is staged in LDS with its halo
+// of (TH-1)*stride+3 rows and (TW-1)*stride+3 columns, one plane per input channel.  The
+// planes are laid out so that the 64 lanes of a read hit distinct LDS banks for every tap
+// (for 32 and for 64 banks): the row pitch is chosen so that the lane rows ly land on
+// distinct multiples of TW banks,
+//   stride 1: halo column hx at hx; lane offset ly*pitch + lx;
+//   stride 2: even halo columns first, the odd ones from column odd3 on; lane offset
+//             2*ly*pitch + lx; tap column s reads {0, odd3, 1}[s].
+constexpr int kTileShapes3 = 3;
+inline constexpr int tile_w3(int ti) { return 8 << ti; }
+inline constexpr int tile_h3(int ti) { return 8 >> ti; }
+inline constexpr int halo_rows3(int stride, int ti) { return (tile_h3(ti) - 1) * stride + 3; }
+inline constexpr int halo_cols3(int stride, int ti) { return (tile_w3(ti) - 1) * stride + 3; }
+inline constexpr int pitch3(int stride, int ti) {
+    return stride == 1 ? (ti == 0 ? 24 : ti == 1 ? 48 : 96) : (ti == 0 ? 28 : ti == 1 ? 40 : 80);
 }
+inline constexpr int odd3(int ti) { return ti == 0 ? 12 : ti == 1 ? 20 : 40; }
+inline constexpr int halo_area3(int stride, int ti) { return halo_rows3(stride, ti) * pitch3(stride, ti); }
+inline constexpr int halo_col3(int stride, int ti, int hx) {
+    return stride == 1 ? hx : ((hx & 1) ? odd3(ti) + (hx >> 1) : (hx >> 1));
+}
+// Compile-time proof of the two properties the kernels rely on: the 64 lane offsets of a
+// read are distinct modulo 64 (hence also no more than 2 lanes per bank of 32), and the
+// farthest read (last lane, last tap) stays inside the plane.
+inline constexpr bool layout3_ok(int stride, int ti) {
+    const int tw = tile_w3(ti), pitch = pitch3(stride, ti);
+    bool used[64] = {};
+    for (int lane = 0; lane < 64; ++lane) {
+        const int o = (lane / tw) * stride * pitch + lane % tw;
+        if (used[o % 64]) return false;
+        used[o % 64] = true;
+    }
+    int far = 0;
+    for (int s = 0; s < 3; ++s) {
+        const int o = (tile_h3(ti) - 1) * stride * pitch + tw - 1 + 2 * pitch + halo_col3(stride, ti, s);
+        far = o > far ? o : far;
+    }
+    // the staged columns of a row must fit the pitch as well
+    int widest = 0;
+    for (int hx = 0; hx < halo_cols3(stride, ti); ++hx) {
+        const int o = halo_col3(stride, ti, hx);
+        widest = o > widest ? o : widest;
+    }
+    return far < halo_area3(stride, ti) && widest < pitch;
+}
+static_assert(layout3_ok(1, 0) && layout3_ok(1, 1) && layout3_ok(1, 2) && layout3_ok(2, 0) &&
+                  layout3_ok(2, 1) && layout3_ok(2, 2),
+              "3x3 LDS plane layout");
+// index of the selector table of a (stride, tile shape) pair
+inline constexpr int off_table3(int stride, int ti) { return (stride - 1) * kTileShapes3 + ti; }
+constexpr int kMaxOff = 2 * kTileShapes3;
 
 // Bytes per LDS row that the stored 1x1 row selectors assume with one group per
 // wavefront (a 64-pixel fp32 tile); with GS groups per wavefront the tile has 64/GS
@@ -71,9 +110,9 @@ struct Layout {
     int VV = 0;       // min(V, 4) floats per block and plane
     int64_t ncol = 0; // padded columns in total (multiple of kSegAlign)
     int64_t wplane = 0;  // floats per weight plane: ncol * VV * GS
-    int noff = 0;     // 1 for kernel 1; 2 for kernel 3 (stride 1, stride 2 geometry)
+    int noff = 0;     // 1 for kernel 1; kMaxOff for kernel 3 (one table per stride and tile shape)
     std::vector<float> w;          // [planes][wplane]
-    std::vector<int32_t> off[2];   // [ncol * GS] each; LDS row selector of every block, in bytes:
+    std::vector<int32_t> off[kMaxOff];   // [ncol * GS] each; LDS row selector of every block, in bytes:
                                    //   kernel 1: c * kRowBytes1 / GS        (pad: (c0 + KC) * kRowBytes1 / GS)
                                    //   kernel 3: 4*(c*HA + r*pitch + col(s)) (pad: 4*(c0 + KC)*HA), see halo_col3
                                    // with c the input channel and c0 the first channel of the block's chunk
@@ -87,7 +126,7 @@ struct DeviceCopy {
     size_t bytes = 0;
     const Work *work = nullptr;
     const float *w = nullptr;
-    const int32_t *off[2] = {nullptr, nullptr};
+    const int32_t *off[kMaxOff] = {};
 };
 
 }  // namespace alcs
@@ -111,9 +150,10 @@ int upload(alcs_packed *p);
 void release_device(alcs_packed *p);
 
 struct Tuning {
-    int pv = 0, waves = 0, group_tiles = 0, path = 0, kc = 0, ug = 0, debug = 0, gs = 0;
+    int pv = 0, waves = 0, group_tiles = 0, path = 0, kc = 0, ug = 0, debug = 0, gs = 0, tile_w = 0;
 };
 Tuning &tuning();
-void record_launch(int mode, int pv, int waves, int wgs, int lds, int gtiles, int kc, int path, int gs);
+void record_launch(int mode, int pv, int waves, int wgs, int lds, int gtiles, int kc, int path, int gs,
+                   int tile_w);
 
 }  // namespace alcs

@@ -14,7 +14,7 @@
 namespace alcs {
 
 static thread_local int g_last_hip = 0;
-static thread_local int g_last_launch[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+static thread_local int g_last_launch[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 void set_hip_error(int e) { g_last_hip = e; }
 
 Tuning &tuning() {
@@ -22,8 +22,9 @@ Tuning &tuning() {
     return t;
 }
 
-void record_launch(int mode, int pv, int waves, int wgs, int lds, int gtiles, int kc, int path, int gs) {
-    int v[9] = {mode, pv, waves, wgs, lds, gtiles, kc, path, gs};
+void record_launch(int mode, int pv, int waves, int wgs, int lds, int gtiles, int kc, int path, int gs,
+                   int tile_w) {
+    int v[10] = {mode, pv, waves, wgs, lds, gtiles, kc, path, gs, tile_w};
     std::memcpy(g_last_launch, v, sizeof(v));
 }
 
@@ -35,13 +36,14 @@ static inline int col_channel(int col, int kk) { return col / kk; }
 // LDS row selector of a real block (see Layout::off): a byte offset.
 static inline int32_t off_of(int col, int k, int table, int GS) {
     if (k == 1) return col * (kRowBytes1 / GS);
-    const int c = col / 9, tap = col % 9, r = tap / 3, s = tap % 3, stride = table + 1;
-    return (c * halo_area3(stride) + r * pitch3(stride) + halo_col3(stride, s)) * 4;
+    const int c = col / 9, tap = col % 9, r = tap / 3, s = tap % 3;
+    const int stride = table / kTileShapes3 + 1, ti = table % kTileShapes3;
+    return (c * halo_area3(stride, ti) + r * pitch3(stride, ti) + halo_col3(stride, ti, s)) * 4;
 }
 
 static inline int32_t pad_off(int c0, int KC, int k, int table, int GS) {
     if (k == 1) return (c0 + KC) * (kRowBytes1 / GS);
-    return (c0 + KC) * halo_area3(table + 1) * 4;
+    return (c0 + KC) * halo_area3(table / kTileShapes3 + 1, table % kTileShapes3) * 4;
 }
 
 // Index of (bundle column `col` counted from the start of the arrays, slot s) in a
@@ -68,7 +70,7 @@ int build_layout(alcs_packed *p, int KC, int GS) {
     L.nbundles = (G + GS - 1) / GS;
     L.planes = V >= 4 ? V / 4 : 1;
     L.VV = V >= 4 ? 4 : V;
-    L.noff = k == 1 ? 1 : 2;
+    L.noff = k == 1 ? 1 : kMaxOff;
     if (GS != 1 && (GS != 2 && GS != 4)) return ALCS_E_INVALID_ARG;
     if (GS > 1 && (V < 4 || k != 1 || L.nchunks != 1)) return ALCS_E_INVALID_ARG;
     try {
@@ -175,9 +177,13 @@ int upload(alcs_packed *p) {
     const size_t b_work = L.work.size() * sizeof(Work);
     const size_t b_w = L.w.size() * sizeof(float);
     const size_t b_off = L.off[0].size() * sizeof(int32_t);
-    size_t o_work = 0, o_w = align256(o_work + b_work), o_off0 = align256(o_w + b_w);
-    size_t o_off1 = align256(o_off0 + b_off);
-    size_t total = align256(o_off1 + (L.noff == 2 ? b_off : 0)) + 256;
+    size_t o_work = 0, o_w = align256(o_work + b_work), o_off[kMaxOff];
+    size_t total = align256(o_w + b_w);
+    for (int t = 0; t < L.noff; ++t) {
+        o_off[t] = total;
+        total = align256(total + b_off);
+    }
+    total += 256;
     void *blob = nullptr;
     if ((e = hipMalloc(&blob, total)) != hipSuccess) {
         set_hip_error((int)e);
@@ -190,8 +196,7 @@ int upload(alcs_packed *p) {
     };
     e = put(o_work, L.work.data(), b_work);
     if (e == hipSuccess) e = put(o_w, L.w.data(), b_w);
-    if (e == hipSuccess) e = put(o_off0, L.off[0].data(), b_off);
-    if (e == hipSuccess && L.noff == 2) e = put(o_off1, L.off[1].data(), b_off);
+    for (int t = 0; t < L.noff && e == hipSuccess; ++t) e = put(o_off[t], L.off[t].data(), b_off);
     if (e != hipSuccess) {
         set_hip_error((int)e);
         (void)hipFree(blob);
@@ -202,8 +207,7 @@ int upload(alcs_packed *p) {
     p->dev.bytes = total;
     p->dev.work = (const Work *)(base + o_work);
     p->dev.w = (const float *)(base + o_w);
-    p->dev.off[0] = (const int32_t *)(base + o_off0);
-    p->dev.off[1] = L.noff == 2 ? (const int32_t *)(base + o_off1) : nullptr;
+    for (int t = 0; t < kMaxOff; ++t) p->dev.off[t] = t < L.noff ? (const int32_t *)(base + o_off[t]) : nullptr;
     return ALCS_OK;
 }
 
@@ -211,7 +215,7 @@ int upload(alcs_packed *p) {
 // LDS tile while a 64-pixel tile of Cin+1 rows fits (Cin <= 639 in 160 KB); wider
 // inputs shrink the tile to 32 or 16 pixels and multiply 2 or 4 groups per wavefront
 // (V >= 4 only); beyond that, or for V < 4, chunks of 256 channels.
-// Kernel 3: 32 channels per chunk (the haloed tile plane is 240 or 476 floats per channel).
+// Kernel 3: 32 channels per chunk (the haloed tile plane is 240 to 476 floats per channel).
 static void default_tiles(int Cin, int k, int V, int *KC, int *GS) {
     *GS = 1;
     if (k == 3) { *KC = std::min(Cin, 32); return; }
@@ -438,6 +442,7 @@ int alcs_set_tuning(const char *name, int value) {
     else if (!std::strcmp(name, "chunk_channels")) t.kc = value;
     else if (!std::strcmp(name, "groups_per_wave")) t.ug = value;
     else if (!std::strcmp(name, "debug")) t.debug = value;
+    else if (!std::strcmp(name, "tile_width")) t.tile_w = (value == 8 || value == 16 || value == 32) ? value : 0;
     else if (!std::strcmp(name, "group_slots")) t.gs = (value == 1 || value == 2 || value == 4) ? value : 0;
     else return ALCS_E_INVALID_ARG;
     return ALCS_OK;
@@ -445,7 +450,7 @@ int alcs_set_tuning(const char *name, int value) {
 
 int alcs_last_launch(int *out, int cap) {
     if (!out || cap <= 0) return 0;
-    int n = cap < 9 ? cap : 9;
+    int n = cap < 10 ? cap : 10;
     std::memcpy(out, g_last_launch, n * sizeof(int));
     return n;
 }

@@ -672,25 +672,26 @@ __global__ void __launch_bounds__(512) k_pw_stream(const ConvArgs a) {
 
 // ------------------------------------------------------------------ 3x3 kernel
 
-// One workgroup = one 8x8 tile of output pixels of one image (lane = pixel) and a
-// tile of groups; input channels are streamed in chunks of KC, each channel as a haloed
-// plane in the bank-conflict-free layout described with halo_col3.  The selector stored
-// with every kept column is 4*(c*HA + r*pitch + col(s)), so the tap shift costs nothing
-// at run time.
-template <int V, int STRIDE, int UG, bool MF>
+// One workgroup = one TH x TW tile of output pixels of one image (lane = pixel, see the
+// tile shapes in alcs_internal.h) and a tile of groups; input channels are streamed in
+// chunks of KC, each channel as a haloed plane in the bank-conflict-free layout described
+// with halo_col3.  The selector stored with every kept column is
+// 4*(c*HA + r*pitch + col(s)), so the tap shift costs nothing at run time.
+template <int V, int STRIDE, int TI, int UG, bool MF>
 __global__ void __launch_bounds__(512) k_conv3(const ConvArgs a) {
     extern __shared__ float lds[];
-    constexpr int ROWS = halo_rows3(STRIDE);   // halo rows = halo columns
-    constexpr int PITCH = pitch3(STRIDE);
-    constexpr int HA = halo_area3(STRIDE);
-    constexpr int HPOS = ROWS * ROWS;          // halo positions that are actually loaded
+    constexpr int TW = tile_w3(TI), TH = tile_h3(TI);
+    constexpr int ROWS = halo_rows3(STRIDE, TI), COLS = halo_cols3(STRIDE, TI);
+    constexpr int PITCH = pitch3(STRIDE, TI);
+    constexpr int HA = halo_area3(STRIDE, TI);
+    constexpr int HPOS = ROWS * COLS;          // halo positions that are actually loaded
     const int logical = logical_wg(a);
     if (logical >= a.total_wgs || (a.debug & 8)) return;
     const int pt = logical / a.ngt, gt = logical - pt * a.ngt;
     const int tiles_per_img = a.tiles_x * a.tiles_y;
     const int n = pt / tiles_per_img, trem = pt - n * tiles_per_img;
     const int tyi = trem / a.tiles_x, txi = trem - tyi * a.tiles_x;
-    const int oy0 = tyi * kTile3, ox0 = txi * kTile3;
+    const int oy0 = tyi * TH, ox0 = txi * TW;
     const int iy0 = oy0 * STRIDE - 1, ix0 = ox0 * STRIDE - 1;
     const int tid = threadIdx.x, lane = tid & 63, nt = blockDim.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -708,18 +709,17 @@ __global__ void __launch_bounds__(512) k_conv3(const ConvArgs a) {
     }
     for (int t = tid; t < HA; t += nt) lds[a.KC * HA + t] = 0.f;  // the all-zero plane
 
-    const int ly = lane >> 3, lx = lane & 7;
+    const int ly = lane / TW, lx = lane % TW;
     const int lane_base = (ly * STRIDE) * PITCH + lx;
     // staging map: a thread keeps one halo position and walks over the chunk's channels
-    // (RPP channels are staged side by side; threads beyond RPP*HPOS only help when
-    // HPOS exceeds half the workgroup and the element loop below is used instead)
-    constexpr bool FIXED_POS = HPOS <= 128;
+    // (RPP = nt / HPOS channels are staged side by side); a workgroup with fewer threads
+    // than halo positions uses the element loop below instead
     const int rpp = nt / HPOS;
     const int pos = tid % HPOS, r0 = tid / HPOS;
-    const int phy = pos / ROWS, phx = pos - phy * ROWS;
+    const int phy = pos / COLS, phx = pos - phy * COLS;
     const bool pin = iy0 + phy >= 0 && iy0 + phy < a.H && ix0 + phx >= 0 && ix0 + phx < a.W;
     const float *psrc = a.X + (size_t)n * a.Cin * a.Pin + (pin ? (size_t)(iy0 + phy) * a.W + ix0 + phx : 0);
-    const int pdst = phy * PITCH + halo_col3(STRIDE, phx);
+    const int pdst = phy * PITCH + halo_col3(STRIDE, TI, phx);
     for (int ch = 0; ch < a.nchunks; ++ch) {
         const int c0 = ch * a.KC, c1 = min(a.Cin, c0 + a.KC);
         // the chunk's work records and first weight runs: fetched before the input tile, so
@@ -736,7 +736,7 @@ __global__ void __launch_bounds__(512) k_conv3(const ConvArgs a) {
         }
         if (ch) __syncthreads();
         if (a.debug & 1) {
-        } else if (FIXED_POS && nt >= HPOS) {
+        } else if (rpp >= 1) {
             if (r0 < rpp) {
                 constexpr int U = 8;
                 const int rows = c1 - c0;
@@ -764,9 +764,9 @@ __global__ void __launch_bounds__(512) k_conv3(const ConvArgs a) {
                     dst[u] = -1;
                     if (e < total) {
                         const int r = e / HPOS, ps = e - r * HPOS;
-                        const int hy = ps / ROWS, hx = ps - hy * ROWS;
+                        const int hy = ps / COLS, hx = ps - hy * COLS;
                         const int yy = iy0 + hy, xx = ix0 + hx;
-                        dst[u] = r * HA + hy * PITCH + halo_col3(STRIDE, hx);
+                        dst[u] = r * HA + hy * PITCH + halo_col3(STRIDE, TI, hx);
                         if (yy >= 0 && yy < a.H && xx >= 0 && xx < a.W)
                             v[u] = a.X[((size_t)n * a.Cin + c0 + r) * a.Pin + (size_t)yy * a.W + xx];
                     }
@@ -825,10 +825,33 @@ static kern_t pick_chunked(int pv, bool vec, int ug) {
     return ug == 2 ? k_pw_chunked<V, 1, 2, MF, false> : k_pw_chunked<V, 1, 4, MF, false>;
 }
 
+template <int V, int TI, bool MF>
+static kern_t pick_conv3_shape(int stride, int ug) {
+    if (ug == 2) return stride == 1 ? k_conv3<V, 1, TI, 2, MF> : k_conv3<V, 2, TI, 2, MF>;
+    return stride == 1 ? k_conv3<V, 1, TI, 4, MF> : k_conv3<V, 2, TI, 4, MF>;
+}
 template <int V, bool MF>
-static kern_t pick_conv3(int stride, int ug) {
-    if (ug == 2) return stride == 1 ? k_conv3<V, 1, 2, MF> : k_conv3<V, 2, 2, MF>;
-    return stride == 1 ? k_conv3<V, 1, 4, MF> : k_conv3<V, 2, 4, MF>;
+static kern_t pick_conv3(int stride, int ti, int ug) {
+    if (ti == 2) return pick_conv3_shape<V, 2, MF>(stride, ug);
+    if (ti == 1) return pick_conv3_shape<V, 1, MF>(stride, ug);
+    return pick_conv3_shape<V, 0, MF>(stride, ug);
+}
+
+// Tile shape of the 3x3 kernel: the share of lanes that fall on real output pixels decides,
+// with a preference for wide tiles (longer contiguous loads and stores).
+static int pick_tile3(int Ho, int Wo, int forced_w) {
+    if (forced_w == 8) return 0;
+    if (forced_w == 16) return 1;
+    if (forced_w == 32) return 2;
+    static const double bonus[kTileShapes3] = {1.0, 1.2, 1.1};  // from sweeps over ResNet-shaped layers
+    int best = 0;
+    double best_score = 0;
+    for (int ti = 0; ti < kTileShapes3; ++ti) {
+        const double covered = (double)ceil_div(Ho, tile_h3(ti)) * tile_h3(ti) * ceil_div(Wo, tile_w3(ti)) * tile_w3(ti);
+        const double score = (double)Ho * Wo / covered * bonus[ti];
+        if (score > best_score) { best_score = score; best = ti; }
+    }
+    return best;
 }
 
 // Groups per wavefront in the chunked kernels: 4, or 2 when the layer has too few groups
@@ -883,7 +906,7 @@ static int launch_sparse(const alcs_packed_t *Wp, const float *X_dev, const floa
     ConvArgs a{};
     a.X = X_dev; a.bias = bias_dev; a.Y = Y_dev;
     a.work = Wp->dev.work; a.w = Wp->dev.w;
-    a.off = Wp->dev.off[kernel == 3 && stride == 2 ? 1 : 0];
+    a.off = Wp->dev.off[0];
     a.wplane = (long long)L.wplane;
     a.N = N; a.Cin = Cin; a.Cout = Cout; a.H = H; a.W = W; a.Ho = Ho; a.Wo = Wo; a.stride = stride;
     a.P = (int)P; a.Pin = (int)Pin;
@@ -895,7 +918,7 @@ static int launch_sparse(const alcs_packed_t *Wp, const float *X_dev, const floa
     bool mfma = V >= 4;
     if (V == 4 && T.path == 1) mfma = false;
     kern_t kern = nullptr;
-    int lds = 0, nw = 0, pv = 1, mode = 0, ug = 4;
+    int lds = 0, nw = 0, pv = 1, mode = 0, ug = 4, ti = 0;
 
     if (kernel == 1) {
         const bool vec = stride == 1 && (P % 4 == 0);
@@ -1002,9 +1025,11 @@ static int launch_sparse(const alcs_packed_t *Wp, const float *X_dev, const floa
         }
     } else {
         mode = 3;
-        lds = (L.KC + 1) * halo_area3(stride) * 4;
-        a.tiles_x = ceil_div(Wo, kTile3);
-        a.tiles_y = ceil_div(Ho, kTile3);
+        ti = pick_tile3(Ho, Wo, T.tile_w);
+        a.off = Wp->dev.off[off_table3(stride, ti)];
+        lds = (L.KC + 1) * halo_area3(stride, ti) * 4;
+        a.tiles_x = ceil_div(Wo, tile_w3(ti));
+        a.tiles_y = ceil_div(Ho, tile_h3(ti));
         a.npt = a.tiles_x * a.tiles_y * N;
         nw = 8;
         if (T.waves > 0) nw = std::min(T.waves, 8);
@@ -1012,11 +1037,11 @@ static int launch_sparse(const alcs_packed_t *Wp, const float *X_dev, const floa
         a.gpt = nw * ug;
         a.ngt = ceil_div(G, a.gpt);
         switch (V) {
-            case 1: kern = pick_conv3<1, false>(stride, ug); break;
-            case 2: kern = pick_conv3<2, false>(stride, ug); break;
-            case 4: kern = mfma ? pick_conv3<4, true>(stride, ug) : pick_conv3<4, false>(stride, ug); break;
-            case 8: kern = pick_conv3<8, true>(stride, ug); break;
-            case 16: kern = pick_conv3<16, true>(stride, ug); break;
+            case 1: kern = pick_conv3<1, false>(stride, ti, ug); break;
+            case 2: kern = pick_conv3<2, false>(stride, ti, ug); break;
+            case 4: kern = mfma ? pick_conv3<4, true>(stride, ti, ug) : pick_conv3<4, false>(stride, ti, ug); break;
+            case 8: kern = pick_conv3<8, true>(stride, ti, ug); break;
+            case 16: kern = pick_conv3<16, true>(stride, ti, ug); break;
         }
     }
     if (!kern || lds > kMaxLds) return ALCS_E_UNSUPPORTED;
@@ -1026,7 +1051,7 @@ static int launch_sparse(const alcs_packed_t *Wp, const float *X_dev, const floa
     a.wg_per_xcd = ceil_div(total, kXcds);
     int rc = set_lds_limit(kern, lds);
     if (rc != ALCS_OK) return rc;
-    record_launch(mode, pv, nw, a.total_wgs, lds, a.ngt, L.KC, mfma ? 2 : 1, L.GS);
+    record_launch(mode, pv, nw, a.total_wgs, lds, a.ngt, L.KC, mfma ? 2 : 1, L.GS, mode == 3 ? tile_w3(ti) : 0);
     const int grid = mode == 4 ? a.npt : a.wg_per_xcd * kXcds;
     if (ev_start || ev_stop) {
         // the events take the kernel's own begin and end time stamps (no gap for event

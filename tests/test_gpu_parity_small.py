@@ -14,7 +14,8 @@ pytestmark = pytest.mark.gpu
 @pytest.fixture(autouse=True)
 def _reset_tuning():
     yield
-    for k in ("pv", "waves", "group_tiles", "path", "chunk_channels", "groups_per_wave", "group_slots", "debug"):
+    for k in ("pv", "waves", "group_tiles", "path", "chunk_channels", "groups_per_wave", "group_slots", "debug",
+              "tile_width"):
         alcs.alcs_set_tuning(k, 0)
 
 
@@ -131,6 +132,24 @@ def test_conv3x3(V, stride):
                         sparsity=0.7, w_std=0.05)
     info = check(L, 500 + V + stride)
     assert info["mode"] == 3
+
+
+@pytest.mark.parametrize("V", [1, 2, 4, 16])
+@pytest.mark.parametrize("stride", [1, 2])
+@pytest.mark.parametrize("tile_width", [8, 16, 32])
+def test_conv3x3_tile_shapes(V, stride, tile_width):
+    # 37 columns: one full 32-wide tile and a ragged one; 21 rows: ragged for every tile
+    # height; 70 channels = 3 chunks, the last one short; ragged last group for V = 16
+    L = workloads.Layer("c3_tw%d_v%d_s%d" % (tile_width, V, stride), 70, 40, 21, 37, k=3, stride=stride,
+                        N=2, V=V, sparsity=0.75, w_std=0.05)
+    info = check(L, 540 + V + 3 * stride + tile_width, tile_width=tile_width)
+    assert info["mode"] == 3 and info["tile_width"] == tile_width
+
+
+@pytest.mark.parametrize("tile_width", [8, 16, 32])
+def test_conv3x3_tile_shapes_few_waves_use_position_loop(tile_width):
+    L = workloads.Layer("c3_tw%d_small_wg" % tile_width, 16, 16, 11, 35, k=3, stride=2, N=1, V=4, sparsity=0.5)
+    check(L, 560 + tile_width, waves=2, tile_width=tile_width)
 
 
 def test_conv3x3_tap_shared_pattern_and_many_groups():
