@@ -422,14 +422,19 @@ __device__ __forceinline__ void store_group(const ConvArgs &a, const Acc<V, PV, 
     }
 }
 
-// Epilogue with GS groups per wavefront: the lane's group is the one of its slot.
-template <int V, int GS>
-__device__ __forceinline__ void store_slots(const ConvArgs &a, const Acc<V, 1, true> &acc, const Work &w,
-                                            int lane, const PixOut<1> &px) {
+// The group of the lane's slot in bundle idx of the work table, fetched per lane with a
+// vector load (selecting among the record's four scalar fields by lane would be turned
+// into an indexed array in scratch memory by the compiler).
+template <int GS>
+__device__ __forceinline__ int lane_group(const Work *table, size_t idx, int lane) {
     const int slot = lane >> (6 - ilog2(GS));
-    int g = w.group[0];
-#pragma unroll
-    for (int s = 1; s < GS; ++s) g = slot == s ? w.group[s] : g;
+    return reinterpret_cast<const int32_t *>(table + idx)[2 + slot];
+}
+
+// Epilogue with GS groups per wavefront: g is the group of the lane's slot (-1: none).
+template <int V, int GS>
+__device__ __forceinline__ void store_slots(const ConvArgs &a, const Acc<V, 1, true> &acc, int g,
+                                            const PixOut<1> &px) {
     if (g < 0 || !px.valid[0]) return;
 #pragma unroll
     for (int v = 0; v < V; ++v) {
@@ -468,9 +473,11 @@ __global__ void __launch_bounds__(1024) k_pw_resident(const ConvArgs a) {
     const bool any = nth(0) < ng;
     Work w0 = no_work(), w1 = no_work();
     Run2<V, MF, GS> run0, run1;
+    int gl0 = -1, gl1 = -1;  // GS > 1: the group of the lane's slot in the current / next bundle
     if (any) {
         w0 = load_work(a.work, g_begin + nth(0));
         run0 = load_run2<V, MF, GS>(a, w0.start, lane);
+        if constexpr (GS > 1) gl0 = lane_group<GS>(a.work, g_begin + nth(0), lane);
         if (nth(1) < ng) w1 = load_work(a.work, g_begin + nth(1));
     }
 
@@ -489,6 +496,7 @@ __global__ void __launch_bounds__(1024) k_pw_resident(const ConvArgs a) {
         Work w2 = no_work();
         if (more) {
             run1 = load_run2<V, MF, GS>(a, w1.start, lane);
+            if constexpr (GS > 1) gl1 = lane_group<GS>(a.work, g_begin + nth(k + 1), lane);
             if (nth(k + 2) < ng) w2 = load_work(a.work, g_begin + nth(k + 2));
         }
         Acc<V, PV, MF> acc;
@@ -496,12 +504,13 @@ __global__ void __launch_bounds__(1024) k_pw_resident(const ConvArgs a) {
         if (!(a.debug & 2)) mac_segment<V, PV, SH, GS>(a, w0.start, w0.cnt, ldsb, base, lane, run0, acc);
         if (!(a.debug & 4)) {
             if constexpr (GS == 1) store_group<V, PV, MF, VEC>(a, acc, w0.group[0], px);
-            else store_slots<V, GS>(a, acc, w0, lane, px);
+            else store_slots<V, GS>(a, acc, gl0, px);
         }
         if (!more) break;
         w0 = w1;
         w1 = w2;
         run0 = run1;
+        gl0 = gl1;
     }
 }
 
@@ -818,7 +827,11 @@ static kern_t pick_resident(int pv, bool vec, int gs) {
 template <int V, bool MF>
 static kern_t pick_chunked(int pv, bool vec, int ug) {
     if (vec) {
-        if (pv == 4) return ug == 2 ? k_pw_chunked<V, 4, 2, MF, true> : k_pw_chunked<V, 4, 4, MF, true>;
+        if (pv == 4) {
+            // 4 groups x 4 pixels x 16 channels of accumulators do not fit the register file
+            if constexpr (V * 4 * 4 > 128) return k_pw_chunked<V, 4, 2, MF, true>;
+            else return ug == 2 ? k_pw_chunked<V, 4, 2, MF, true> : k_pw_chunked<V, 4, 4, MF, true>;
+        }
         if (pv == 2) return ug == 2 ? k_pw_chunked<V, 2, 2, MF, true> : k_pw_chunked<V, 2, 4, MF, true>;
         return ug == 2 ? k_pw_chunked<V, 1, 2, MF, true> : k_pw_chunked<V, 1, 4, MF, true>;
     }
@@ -1013,6 +1026,7 @@ static int launch_sparse(const alcs_packed_t *Wp, const float *X_dev, const floa
             if (T.waves > 0) nw = std::min(T.waves, 8);
             if (L.GS != 1) return ALCS_E_UNSUPPORTED;
             ug = pick_ug(G, nw, T.ug);
+            if (V * pv * ug > 128) ug = 2;  // accumulators of 4 groups would not fit the register file
             a.gpt = nw * ug;
             a.ngt = ceil_div(G, a.gpt);
             switch (V) {
