@@ -422,13 +422,19 @@ __device__ __forceinline__ void store_group(const ConvArgs &a, const Acc<V, PV, 
     }
 }
 
-// The group of the lane's slot in bundle idx of the work table, fetched per lane with a
-// vector load (selecting among the record's four scalar fields by lane would be turned
-// into an indexed array in scratch memory by the compiler).
+// The group of the lane's slot: a select tree over the record's (scalar) fields by the bits
+// of the slot number.  (A loop of "slot == s ? group[s] : g" is turned into an indexed
+// array in scratch memory by the compiler for four slots.)
 template <int GS>
-__device__ __forceinline__ int lane_group(const Work *table, size_t idx, int lane) {
+__device__ __forceinline__ int lane_group(const Work &w, int lane) {
     const int slot = lane >> (6 - ilog2(GS));
-    return reinterpret_cast<const int32_t *>(table + idx)[2 + slot];
+    if constexpr (GS == 1) return w.group[0];
+    const int g0 = w.group[0], g1 = w.group[1];
+    const int lo = (slot & 1) ? g1 : g0;
+    if constexpr (GS == 2) return lo;
+    const int g2 = w.group[2], g3 = w.group[3];
+    const int hi = (slot & 1) ? g3 : g2;
+    return (slot & 2) ? hi : lo;
 }
 
 // Epilogue with GS groups per wavefront: g is the group of the lane's slot (-1: none).
@@ -473,11 +479,9 @@ __global__ void __launch_bounds__(1024) k_pw_resident(const ConvArgs a) {
     const bool any = nth(0) < ng;
     Work w0 = no_work(), w1 = no_work();
     Run2<V, MF, GS> run0, run1;
-    int gl0 = -1, gl1 = -1;  // GS > 1: the group of the lane's slot in the current / next bundle
     if (any) {
         w0 = load_work(a.work, g_begin + nth(0));
         run0 = load_run2<V, MF, GS>(a, w0.start, lane);
-        if constexpr (GS > 1) gl0 = lane_group<GS>(a.work, g_begin + nth(0), lane);
         if (nth(1) < ng) w1 = load_work(a.work, g_begin + nth(1));
     }
 
@@ -496,7 +500,6 @@ __global__ void __launch_bounds__(1024) k_pw_resident(const ConvArgs a) {
         Work w2 = no_work();
         if (more) {
             run1 = load_run2<V, MF, GS>(a, w1.start, lane);
-            if constexpr (GS > 1) gl1 = lane_group<GS>(a.work, g_begin + nth(k + 1), lane);
             if (nth(k + 2) < ng) w2 = load_work(a.work, g_begin + nth(k + 2));
         }
         Acc<V, PV, MF> acc;
@@ -504,13 +507,12 @@ __global__ void __launch_bounds__(1024) k_pw_resident(const ConvArgs a) {
         if (!(a.debug & 2)) mac_segment<V, PV, SH, GS>(a, w0.start, w0.cnt, ldsb, base, lane, run0, acc);
         if (!(a.debug & 4)) {
             if constexpr (GS == 1) store_group<V, PV, MF, VEC>(a, acc, w0.group[0], px);
-            else store_slots<V, GS>(a, acc, gl0, px);
+            else store_slots<V, GS>(a, acc, lane_group<GS>(w0, lane), px);
         }
         if (!more) break;
         w0 = w1;
         w1 = w2;
         run0 = run1;
-        gl0 = gl1;
     }
 }
 
