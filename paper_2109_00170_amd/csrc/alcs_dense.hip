@@ -6,7 +6,10 @@
 //
 // A workgroup of four wavefronts (2 x 2) owns a BM x 128 tile of Y and walks K in
 // steps of 16: the weight tile is transposed into LDS as As[k][m], the patch tile is
-// gathered as Bs[k][q]; each wavefront owns (BM/64) x 2 MFMA tiles of 32 x 32.
+// gathered as Bs[k][q]; each wavefront owns (BM/64) x 2 MFMA tiles of 32 x 32.  The
+// global loads of step k+1 are issued before the multiplies of step k and written to the
+// other half of a two-deep LDS buffer afterwards, so a step costs one barrier and the
+// load latency is covered by the matrix instructions.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -37,8 +40,10 @@ template <int BM, bool PW_VEC>
 __global__ void __launch_bounds__(256) k_dense(const DenseArgs a) {
     constexpr int LDA = BM + 4;
     constexpr int TM = BM / 64;  // 32x32 tiles per wavefront along M
-    __shared__ float As[BK * LDA];
-    __shared__ float Bs[BK * BN];
+    constexpr int A_ROWS_PER_PASS = 128;  // 256 threads / 2
+    constexpr int NA = (BM + A_ROWS_PER_PASS - 1) / A_ROWS_PER_PASS;  // weight-tile passes per thread
+    __shared__ float As[2][BK * LDA];
+    __shared__ float Bs[2][BK * BN];
     const int id = blockIdx.x;
     const int logical = (id % 8) * a.wg_per_xcd + id / 8;
     if (logical >= a.total_wgs) return;
@@ -58,7 +63,6 @@ __global__ void __launch_bounds__(256) k_dense(const DenseArgs a) {
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     // weight tile: thread -> (row of W, half of the 16 k's)
-    constexpr int A_ROWS_PER_PASS = 128;  // 256 threads / 2
     const int a_row = tid >> 1, a_k = (tid & 1) * 8;
     // patch tile, vector form (1x1, stride 1, P % 4 == 0): thread -> (k row, pixel quad)
     const int bq = tid & 31, bk0 = tid >> 5;  // 32 quads x 8 rows per pass
@@ -76,76 +80,104 @@ __global__ void __launch_bounds__(256) k_dense(const DenseArgs a) {
     const int pad = (a.k - 1) / 2;
     const int giy = gho * a.stride - pad, gix = gwo * a.stride - pad;
     const int kk = a.k * a.k;
+    const float *gx = a.X + (size_t)gn * a.Cin * a.Pin;
+    // channel and tap of the thread's first gather row; advanced by 2 per row and kept
+    // across steps (8 rows * 2 = one step of 16), so no division in the loop
+    int gc = gk0 / kk, gtap = gk0 - gc * kk;
 
-    for (int k0 = 0; k0 < a.K; k0 += BK) {
-        // ---- stage A (transposed) ----
+    float ra[NA][8];   // the step's weights: 8 consecutive k of one row of W per pass
+    f4 rbv[2];         // vector form: two rows of the patch tile
+    float rbg[8];      // gather form: 8 rows of one pixel column
+
+    auto load_tiles = [&](int k0) {
 #pragma unroll
-        for (int rr = 0; rr < BM; rr += A_ROWS_PER_PASS) {
-            const int row = rr + a_row;
-            if (BM >= A_ROWS_PER_PASS || row < BM) {
-                const int o = m0 + row;
-                float v[8];
-                const bool full = o < a.Cout && k0 + a_k + 8 <= a.K && (a.K % 4 == 0);
-                if (full) {
-                    const f4 *src = reinterpret_cast<const f4 *>(a.Wt + (size_t)o * a.K + k0 + a_k);
-                    f4 t0 = src[0], t1 = src[1];
-                    v[0] = t0[0]; v[1] = t0[1]; v[2] = t0[2]; v[3] = t0[3];
-                    v[4] = t1[0]; v[5] = t1[1]; v[6] = t1[2]; v[7] = t1[3];
-                } else {
+        for (int pass = 0; pass < NA; ++pass) {
+            const int row = pass * A_ROWS_PER_PASS + a_row;
+            const int o = m0 + row;
+            const bool full = o < a.Cout && k0 + a_k + 8 <= a.K && (a.K % 4 == 0);
+            if (full) {
+                const f4 *src = reinterpret_cast<const f4 *>(a.Wt + (size_t)o * a.K + k0 + a_k);
+                const f4 t0 = src[0], t1 = src[1];
+                ra[pass][0] = t0[0]; ra[pass][1] = t0[1]; ra[pass][2] = t0[2]; ra[pass][3] = t0[3];
+                ra[pass][4] = t1[0]; ra[pass][5] = t1[1]; ra[pass][6] = t1[2]; ra[pass][7] = t1[3];
+            } else {
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        const int kx = k0 + a_k + i;
-                        v[i] = (o < a.Cout && kx < a.K) ? a.Wt[(size_t)o * a.K + kx] : 0.f;
-                    }
+                for (int i = 0; i < 8; ++i) {
+                    const int kx = k0 + a_k + i;
+                    ra[pass][i] = (o < a.Cout && kx < a.K) ? a.Wt[(size_t)o * a.K + kx] : 0.f;
                 }
-#pragma unroll
-                for (int i = 0; i < 8; ++i) As[(a_k + i) * LDA + row] = v[i];
             }
         }
-        // ---- stage B ----
         if constexpr (PW_VEC) {
 #pragma unroll
             for (int pass = 0; pass < 2; ++pass) {
-                const int kr = bk0 + pass * 8;
-                const int c = k0 + kr;
-                f4 v = f4{0, 0, 0, 0};
+                const int c = k0 + bk0 + pass * 8;
+                rbv[pass] = f4{0, 0, 0, 0};
                 if (vvalid && c < a.K)
-                    v = *reinterpret_cast<const f4 *>(a.X + ((size_t)vn * a.Cin + c) * a.P + vp);
-                *reinterpret_cast<f4 *>(&Bs[kr * BN + bq * 4]) = v;
+                    rbv[pass] = *reinterpret_cast<const f4 *>(a.X + ((size_t)vn * a.Cin + c) * a.P + vp);
             }
         } else {
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                const int kr = gk0 + 2 * i;
-                const int kx = k0 + kr;
                 float v = 0.f;
-                if (gvalid && kx < a.K) {
-                    const int c = kx / kk, tap = kx - c * kk;
-                    const int r = tap / a.k, s = tap - r * a.k;
+                if (gvalid && gc < a.Cin) {
+                    const int r = a.k == 1 ? 0 : gtap / 3, s = a.k == 1 ? 0 : gtap - r * 3;
                     const int iy = giy + r, ix = gix + s;
                     if (iy >= 0 && iy < a.H && ix >= 0 && ix < a.W)
-                        v = a.X[((size_t)gn * a.Cin + c) * a.Pin + (size_t)iy * a.W + ix];
+                        v = gx[(size_t)gc * a.Pin + (size_t)iy * a.W + ix];
                 }
-                Bs[kr * BN + gcol] = v;
+                rbg[i] = v;
+                gtap += 2;   // next row of this thread: k + 2
+                if (gtap >= kk) { gtap -= kk; ++gc; }
+                if (gtap >= kk) { gtap -= kk; ++gc; }   // kk = 1: two channels per row step
             }
         }
-        __syncthreads();
+    };
+    auto store_tiles = [&](int buf) {
+#pragma unroll
+        for (int pass = 0; pass < NA; ++pass) {
+            const int row = pass * A_ROWS_PER_PASS + a_row;
+            if (BM >= A_ROWS_PER_PASS || row < BM) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) As[buf][(a_k + i) * LDA + row] = ra[pass][i];
+            }
+        }
+        if constexpr (PW_VEC) {
+#pragma unroll
+            for (int pass = 0; pass < 2; ++pass)
+                *reinterpret_cast<f4 *>(&Bs[buf][(bk0 + pass * 8) * BN + bq * 4]) = rbv[pass];
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) Bs[buf][(gk0 + 2 * i) * BN + gcol] = rbg[i];
+        }
+    };
+
+    load_tiles(0);
+    store_tiles(0);
+    __syncthreads();
+    int buf = 0;
+    for (int k0 = 0; k0 < a.K; k0 += BK) {
+        const bool more = k0 + BK < a.K;
+        if (more) load_tiles(k0 + BK);   // in flight during the multiplies below
         // ---- multiply ----
 #pragma unroll
         for (int ks = 0; ks < BK; ks += 2) {
             const int kl = ks + (lane >> 5);
             float av[TM], bv[2];
 #pragma unroll
-            for (int i = 0; i < TM; ++i) av[i] = As[kl * LDA + (wm * TM + i) * 32 + (lane & 31)];
+            for (int i = 0; i < TM; ++i) av[i] = As[buf][kl * LDA + (wm * TM + i) * 32 + (lane & 31)];
 #pragma unroll
-            for (int j = 0; j < 2; ++j) bv[j] = Bs[kl * BN + (wn * 2 + j) * 32 + (lane & 31)];
+            for (int j = 0; j < 2; ++j) bv[j] = Bs[buf][kl * BN + (wn * 2 + j) * 32 + (lane & 31)];
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
         }
+        // the other buffer was last read in the previous step, before that step's barrier
+        if (more) store_tiles(buf ^ 1);
         __syncthreads();
+        buf ^= 1;
     }
     // ---- epilogue: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32 ----
 #pragma unroll
