@@ -169,6 +169,24 @@ def report(kind, alcs, workloads, torch, np):
                    (L.name, r["us"], r["bytes"] / r["us"] / 1e3, r["bound"], r["roof_us"] / r["us"],
                     cnt.max() / max(cnt.mean(), 1e-9), r["err"]))
             pr("total (with repeats) %.0f us, sum of rooflines %.0f us (%.3f)" % (tot, troof, troof / tot))
+    elif kind == "mbv1":
+        for N, sp, label in ((32, 0.9, "batch 32, block sparsity 0.9 in every layer"),
+                             (32, None, "batch 32, per-layer block sparsity drawn from U(0.7, 0.9)"),
+                             (1, None, "batch 1, per-layer block sparsity drawn from U(0.7, 0.9)")):
+            pr("\n%s" % label)
+            pr("| layer | Cin->Cout | HxW | sparsity | sparse us | dense us | speed-up | eff GB/s | bound | roofline us | roofline frac | max rel err |")
+            pr("|---|---|---|---|---|---|---|---|---|---|---|---|")
+            tot = troof = tdense = 0.0
+            for i, L in enumerate(workloads.mobilenet_v1_pointwise(N, sp)):
+                r = time_layer(alcs, torch, np, workloads, L, workloads.seed_for(2, i), dense=True)
+                tot += r["us"]
+                troof += r["roof_us"]
+                tdense += r["dense_us"]
+                pr("| %s | %d->%d | %d | %.3f | %.1f | %.1f | %.2f | %.0f | %s | %.2f | %.3f | %.1e |" %
+                   (L.name, L.Cin, L.Cout, L.H, L.sparsity, r["us"], r["dense_us"], r["dense_us"] / r["us"],
+                    r["bytes"] / r["us"] / 1e3, r["bound"], r["roof_us"], r["roof_us"] / r["us"], r["err"]))
+            pr("13 layers: sparse %.0f us, dense %.0f us (%.2fx), sum of rooflines %.0f us (%.3f)" %
+               (tot, tdense, tdense / tot, troof, troof / tot))
     elif kind == "paths":
         pr("| layer | MFMA us | FMA us | FMA / MFMA |")
         pr("|---|---|---|---|")
@@ -196,11 +214,13 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-batch", type=int, default=32)
     ap.add_argument("--layers-json", default=None, help="also write the per-layer table to this file")
-    ap.add_argument("--report", choices=["sweep", "resnet", "mbv2", "paths"], default=None,
+    ap.add_argument("--report", choices=["sweep", "resnet", "mbv2", "paths", "mbv1"], default=None,
                     help="instead of the benchmark line, print a per-layer table for another configuration: "
                          "the sparsity sweep with the same-GPU dense conv (config 4), the ResNet-50-shaped "
                          "bottleneck convs (config 3), the MobileNetV2-shaped pointwise convs for V in "
-                         "{1,4,8,16} (config 5), or MFMA against plain-FMA inner loops (V=4)")
+                         "{1,4,8,16} (config 5), MFMA against plain-FMA inner loops (V=4), or the "
+                         "MobileNetV1-shaped pointwise convs at batch 1 and 32 with fixed and drawn "
+                         "sparsities, beside the dense conv (config 2)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="for rocprofv3 --pmc runs only: put a plain 256 MiB device copy in front of every "
                          "step, so that the HBM byte counters can be scaled by a kernel of known traffic "

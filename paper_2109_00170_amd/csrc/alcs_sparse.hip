@@ -244,6 +244,11 @@ __device__ __forceinline__ void mfma_batch(const float (&aw)[(V / 4) * GS], int 
         constexpr int C = decltype(c)::value;
         lds_read<PV>(reinterpret_cast<const float *>(lds + base + (bcast_sel<B0 + C>(ov) << SH)), x[C]);
     });
+#ifdef ALCS_HOLD_READS
+    // keep the B reads ahead of the MFMAs (the scheduler otherwise trades reads in flight
+    // for registers when a lane has several pixels)
+    if constexpr (PV > 1) __builtin_amdgcn_sched_barrier(0);
+#endif
     static_for<B>([&](auto c) {
         constexpr int C = decltype(c)::value;
         constexpr int COL = B0 + C, AREG = COL / CPA, ABID = COL % CPA;
@@ -524,7 +529,7 @@ __global__ void __launch_bounds__(512) k_pw_chunked(const ConvArgs a) {
     constexpr int TP = 64 * PV;
     constexpr int SH = PV == 4 ? 2 : PV == 2 ? 1 : 0;
     const int logical = logical_wg(a);
-    if (logical >= a.total_wgs) return;
+    if (logical >= a.total_wgs || (a.debug & 8)) return;
     const int pt = logical / a.ngt, gt = logical - pt * a.ngt;
     const int q0 = pt * TP;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -556,18 +561,19 @@ __global__ void __launch_bounds__(512) k_pw_chunked(const ConvArgs a) {
             }
         }
         if (ch) __syncthreads();
-        stage_pw<TP, VEC>(a, lds, q0, c0, c1);
+        if (!(a.debug & 1)) stage_pw<TP, VEC>(a, lds, q0, c0, c1);
         __syncthreads();
         const int base = lane * PV * 4 - c0 * (kRowBytes1 << SH);
 #pragma unroll
         for (int u = 0; u < UG; ++u)
-            if (slot[u] >= 0) mac_segment<V, PV, SH>(a, wk[u].start, wk[u].cnt, ldsb, base, lane, rn[u], acc[u]);
+            if (slot[u] >= 0 && !(a.debug & 2))
+                mac_segment<V, PV, SH>(a, wk[u].start, wk[u].cnt, ldsb, base, lane, rn[u], acc[u]);
     }
     PixOut<PV> px;
     pix_out<PV, VEC>(a, q0, lane, px);
 #pragma unroll
     for (int u = 0; u < UG; ++u)
-        if (slot[u] >= 0)
+        if (slot[u] >= 0 && !(a.debug & 4))
             store_group<V, PV, MF, VEC>(a, acc[u], load_work(a.work, (size_t)slot[u] * a.nchunks).group[0], px);
 }
 
@@ -1009,7 +1015,9 @@ static int launch_sparse(const alcs_packed_t *Wp, const float *X_dev, const floa
             a.gpt = ceil_div(NB, ngt);
             a.ngt = ceil_div(NB, a.gpt);
             nw = lds > 40 * 1024 ? 16 : 8;
-            nw = std::min(nw, std::max(1, a.gpt));
+            // fewer wavefronts when the group tile has fewer bundles, but at least one per 8 KB
+            // of tile: wavefronts without a bundle still help to stage it
+            nw = std::min(nw, std::max(std::max(1, a.gpt), lds / 8192));
             if (T.waves > 0) nw = std::min(T.waves, 16);
             switch (V) {
                 case 1: kern = pick_resident<1, false>(pv, vec, GS); break;
