@@ -49,7 +49,7 @@ struct ConvArgs {
     int NP;             // N * P, flattened output pixels (< 2^31)
     int G, nchunks, KC;
     int npt, ngt, gpt;  // pixel tiles, group tiles, groups per group tile
-    int tiles_x, tiles_y;  // 3x3: 8x8 tiles per image
+    int tiles_x, tiles_y;  // 3x3: output tiles per image
     int wg_per_xcd, total_wgs;
     int ppw;            // streaming kernel: flattened pixels per workgroup (multiple of 4)
     int wfloats;        // streaming kernel: floats in the weight planes, planes * nblk * 4
@@ -95,13 +95,9 @@ __device__ __forceinline__ int logical_wg(const ConvArgs &a) {
 
 // ------------------------------------------------------------------ accumulators
 
-#ifndef ALCS_NACC1
-#define ALCS_NACC1 2
-#endif
-#ifndef ALCS_NACC2
-#define ALCS_NACC2 1
-#endif
-#define ALCS_NACC_FOR(n) ((n) == 1 ? ALCS_NACC1 : (n) == 2 ? ALCS_NACC2 : 1)
+// Partial accumulators per (channel quad, pixel of the lane): 2 when a lane has a single
+// MFMA per column, else 1.
+constexpr int nacc_for(int mfmas_per_column) { return mfmas_per_column == 1 ? 2 : 1; }
 
 template <int V, int PV, bool MF>
 struct Acc;
@@ -109,9 +105,10 @@ struct Acc;
 template <int V, int PV>
 struct Acc<V, PV, true> {  // MFMA: a[k][q][pv][i] = channel 4q+i, pixel pv of the lane, partial sum k
     // An MFMA that accumulates into the register of the one before it has to wait for its
-    // result.  With few independent accumulators per lane (V/4 * PV), consecutive columns
-    // therefore go round-robin to NACC partial accumulators that are added at the end.
-    static constexpr int NACC = ALCS_NACC_FOR((V / 4) * PV);
+    // result (two alternating accumulators already issue at full rate).  With a single
+    // accumulator per lane (V/4 * PV == 1), consecutive columns therefore go round-robin to
+    // NACC partial accumulators that are added at the end.
+    static constexpr int NACC = nacc_for((V / 4) * PV);
     f4 a[NACC][V / 4][PV];
     __device__ __forceinline__ void zero() {
 #pragma unroll
@@ -244,11 +241,10 @@ __device__ __forceinline__ void mfma_batch(const float (&aw)[(V / 4) * GS], int 
         constexpr int C = decltype(c)::value;
         lds_read<PV>(reinterpret_cast<const float *>(lds + base + (bcast_sel<B0 + C>(ov) << SH)), x[C]);
     });
-#ifdef ALCS_HOLD_READS
-    // keep the B reads ahead of the MFMAs (the scheduler otherwise trades reads in flight
-    // for registers when a lane has several pixels)
-    if constexpr (PV > 1) __builtin_amdgcn_sched_barrier(0);
-#endif
+    // With two pixels per lane the scheduler would trade reads in flight for registers and
+    // interleave two reads at a time with the MFMAs; keep all B reads ahead of them.  (With
+    // four pixels per lane the 32 registers this takes cost more occupancy than they gain.)
+    if constexpr (PV == 2) __builtin_amdgcn_sched_barrier(0);
     static_for<B>([&](auto c) {
         constexpr int C = decltype(c)::value;
         constexpr int COL = B0 + C, AREG = COL / CPA, ABID = COL % CPA;
@@ -342,7 +338,7 @@ __device__ __forceinline__ void stage_pw(const ConvArgs &a, float *lds, int q0, 
                 v[u] = f4{0, 0, 0, 0};
                 if (valid) {
                     const f4 *ptr = reinterpret_cast<const f4 *>(src + (size_t)(r + u * rpp) * a.P);
-                    v[u] = (a.debug & 16) ? __builtin_nontemporal_load(ptr) : *ptr;
+                    v[u] = *ptr;
                 }
             }
 #pragma unroll
