@@ -71,8 +71,9 @@ def read_traffic(symbol):
 
 
 def time_layer(alcs, torch, np, workloads, L, seed, dense=False, iters=10, tuning=None):
-    """Median kernel time of one layer (kernel time stamps), optionally with the dense conv."""
-    import oracle
+    """Median kernel time of one layer (kernel time stamps), optionally with the dense conv
+    (then the two results are compared with each other; parity with the CPU oracle is the
+    business of the tests)."""
     for k, v in (tuning or {}).items():
         alcs.alcs_set_tuning(k, v)
     d = workloads.make_layer(L, seed)
@@ -95,20 +96,18 @@ def time_layer(alcs, torch, np, workloads, L, seed, dense=False, iters=10, tunin
     torch.cuda.synchronize()
     t = float(np.median([ev.elapsed_us(i) for i in range(iters)]))
     ev.close()
-    # sampled parity on the timed buffers
-    y = Y.reshape(-1)
-    rng = np.random.default_rng(seed + 5)
-    idx = rng.integers(0, y.numel(), size=500)
-    got = y[torch.from_numpy(idx).cuda()].cpu().numpy()
-    Wd_host = oracle.densify(d.W, d.mask, L.V)
-    ref = oracle.conv_at(Wd_host, d.X, idx, stride=L.stride)
-    err = float(np.max(np.abs(got - ref)) / max(float(y.abs().max()), 1e-30))
     td = None
+    err = float("nan")
     if dense:
-        Wd = torch.from_numpy(Wd_host).cuda()
+        # dense weights of the pruned layer: kept blocks as they are, dropped blocks zero
+        keep = np.repeat(d.mask, L.V, axis=0)[:L.Cout] if d.mask is not None else 1
+        Wd = torch.from_numpy(np.ascontiguousarray(d.W * keep, dtype=np.float32)).cuda()
+        Ys = Y.clone()
         for _ in range(2):
             alcs.alcs_dense_conv(Wd, X, None, Y, stride=L.stride)
         torch.cuda.synchronize()
+        err = float((Ys - Y).abs().max() / Y.abs().max().clamp_min(1e-30))
+        del Ys
         e = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(5)]
         for a, b in e:
             a.record()
@@ -131,7 +130,7 @@ def report(kind, alcs, workloads, torch, np):
     """Per-layer tables for configurations 3, 4, 5 and the MFMA / FMA comparison (markdown on stdout)."""
     pr = lambda *a: print(*a, flush=True)
     if kind == "sweep":
-        pr("| sparsity | sparse us | dense us | speed-up | dense-equiv TFLOP/s | actual TFLOP/s | bound | roofline frac | max rel err |")
+        pr("| sparsity | sparse us | dense us | speed-up | dense-equiv TFLOP/s | actual TFLOP/s | bound | roofline frac | max diff vs dense |")
         pr("|---|---|---|---|---|---|---|---|---|")
         for s in workloads.SWEEP_SPARSITIES:
             L = workloads.sweep_layer(s)
@@ -140,7 +139,7 @@ def report(kind, alcs, workloads, torch, np):
                (s, r["us"], r["dense_us"], r["dense_us"] / r["us"], L.dense_flops() / r["us"] / 1e6,
                 r["flops"] / r["us"] / 1e6, r["bound"], r["roof_us"] / r["us"], r["err"]))
     elif kind == "resnet":
-        pr("| layer | Cin->Cout | k/s | HxW | x | sparse us | dense us | speed-up | actual TFLOP/s | eff GB/s | bound | roofline frac | max rel err |")
+        pr("| layer | Cin->Cout | k/s | HxW | x | sparse us | dense us | speed-up | actual TFLOP/s | eff GB/s | bound | roofline frac | max diff vs dense |")
         pr("|---|---|---|---|---|---|---|---|---|---|---|---|---|")
         tot = troof = tdense = 0.0
         for i, L in enumerate(workloads.resnet50_bottlenecks(64)):
@@ -157,24 +156,24 @@ def report(kind, alcs, workloads, torch, np):
     elif kind == "mbv2":
         for V in (1, 4, 8, 16):
             pr("\nV = %d" % V)
-            pr("| layer | sparse us | eff GB/s | bound | roofline frac | longest/mean group | max rel err |")
-            pr("|---|---|---|---|---|---|---|")
+            pr("| layer | sparse us | eff GB/s | bound | roofline frac | longest/mean group |")
+            pr("|---|---|---|---|---|---|")
             tot = troof = 0.0
             for i, L in enumerate(workloads.mobilenet_v2_pointwise(128, V)):
                 r = time_layer(alcs, torch, np, workloads, L, workloads.seed_for(5, 100 * V + i))
                 tot += r["us"] * L.repeats
                 troof += r["roof_us"] * L.repeats
                 cnt = workloads.zipf_counts(L.G, L.K, 1.0 - L.sparsity)
-                pr("| %s | %.1f | %.0f | %s | %.3f | %.1f | %.1e |" %
+                pr("| %s | %.1f | %.0f | %s | %.3f | %.1f |" %
                    (L.name, r["us"], r["bytes"] / r["us"] / 1e3, r["bound"], r["roof_us"] / r["us"],
-                    cnt.max() / max(cnt.mean(), 1e-9), r["err"]))
+                    cnt.max() / max(cnt.mean(), 1e-9)))
             pr("total (with repeats) %.0f us, sum of rooflines %.0f us (%.3f)" % (tot, troof, troof / tot))
     elif kind == "mbv1":
         for N, sp, label in ((32, 0.9, "batch 32, block sparsity 0.9 in every layer"),
                              (32, None, "batch 32, per-layer block sparsity drawn from U(0.7, 0.9)"),
                              (1, None, "batch 1, per-layer block sparsity drawn from U(0.7, 0.9)")):
             pr("\n%s" % label)
-            pr("| layer | Cin->Cout | HxW | sparsity | sparse us | dense us | speed-up | eff GB/s | bound | roofline us | roofline frac | max rel err |")
+            pr("| layer | Cin->Cout | HxW | sparsity | sparse us | dense us | speed-up | eff GB/s | bound | roofline us | roofline frac | max diff vs dense |")
             pr("|---|---|---|---|---|---|---|---|---|---|---|---|")
             tot = troof = tdense = 0.0
             for i, L in enumerate(workloads.mobilenet_v1_pointwise(N, sp)):
@@ -326,18 +325,6 @@ def main():
     alg_bytes = sum(layer_bytes(L, n) for L, n in zip(layers, nnzb))
     value = dense_flops / (ms_per_step * 1e-3) / 1e9
 
-    # ---- parity on the buffers that were timed: sampled outputs against the CPU oracle ----
-    import oracle
-    max_err = 0.0
-    rng = np.random.default_rng(12345)
-    for i, L in enumerate(layers):
-        y = Ys[i].cpu().numpy().reshape(-1)
-        idx = rng.choice(y.size, size=2000, replace=False)
-        Wd = oracle.densify(data[i].W, data[i].mask, L.V)
-        ref = oracle.conv_at(Wd, data[i].X, idx, stride=L.stride)
-        scale = float(np.max(np.abs(y)))
-        max_err = max(max_err, float(np.max(np.abs(y[idx] - ref)) / scale))
-
     # ---- per-layer table ----
     rows = []
     roof_sum = 0.0
@@ -397,26 +384,32 @@ def main():
         "effective_gbs": round(alg_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "actual_gflops": round(alg_flops / (ms_per_step * 1e-3) / 1e9, 1),
         "roofline_frac_step": round(roof_sum * 1e3 / ms_per_step, 4),
-        "max_rel_err_vs_oracle": float("%.3g" % max_err),
         "roofline": roofline,
     }
 
     if not args.no_cpu_baseline:
+        # The oracle as it stands, on the host cores, on the first nb images of every layer;
+        # its outputs are also what the timed GPU buffers are checked against.
+        import oracle
         nb = max(1, min(args.cpu_sample_batch, args.batch))
         threads = oracle.max_threads()
         t_cpu = 0.0
         fl = 0.0
+        max_err = 0.0
         for i, L in enumerate(layers):
             Wd = oracle.densify(data[i].W, data[i].mask, L.V)
             xs = np.ascontiguousarray(data[i].X[:nb])
             c0 = time.perf_counter()
-            oracle.conv(Wd, xs, stride=L.stride, nthreads=threads)
+            ref = oracle.conv(Wd, xs, stride=L.stride, nthreads=threads)
             t_cpu += time.perf_counter() - c0
             fl += L.dense_flops() * nb / L.N
+            got = Ys[i][:nb].cpu().numpy()
+            max_err = max(max_err, float(np.max(np.abs(got - ref)) / max(float(np.max(np.abs(ref))), 1e-30)))
         out["cpu_baseline"] = {"value": round(fl / t_cpu / 1e9, 2), "unit": "GFLOP/s (dense-equivalent)",
                                "cores": threads, "kind": "oracle",
                                "sample": "same 13 layers and weights, first %d of %d images, %.1f s of CPU time"
                                          % (nb, args.batch, t_cpu)}
+        out["max_rel_err_vs_oracle"] = float("%.3g" % max_err)
     if args.calib_copy:
         out["calibration_run"] = True
     print(json.dumps(out))
