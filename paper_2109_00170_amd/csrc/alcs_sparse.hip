@@ -164,25 +164,35 @@ struct Run {
     int o;
 };
 
-// The first two runs of a segment: fetched together, two runs ahead of their use, so
-// that the latency of the weight fetch (an L2 hit at best) is covered by 32 columns of
-// multiplies instead of 16.
+// The first N runs of a segment, fetched together by the caller well ahead of their use
+// (before the previous group's output stores: vector memory operations complete in
+// order, so a load issued behind stores waits for them).  N = 4 covers segments of up
+// to 64 columns without any load inside the multiply loop; with many weight registers
+// per run (V/4 * GS > 2) N = 2.  The walk over a longer segment re-fills register set i
+// right after its use with the run N places further on: no register is ever copied, so
+// nothing waits for a load before the run that needs it.
+template <int V, bool MF, int GS>
+constexpr int runs_ahead() { return !MF ? 1 : (V / 4) * GS <= 2 ? 4 : 2; }
+
 template <int V, bool MF, int GS = 1>
-struct Run2 {
-    Run<V, MF, GS> r0, r1;
+struct Runs {
+    static constexpr int N = runs_ahead<V, MF, GS>();
+    Run<V, MF, GS> r[N];
 };
 
 template <int V, bool MF, int GS = 1>
 __device__ __forceinline__ Run<V, MF, GS> load_run(const ConvArgs &a, int blk, int lane);
 
-// Runs at columns blk and blk + 16 (the second may lie beyond the segment: the arrays
-// end with a spare run, so the read stays in bounds and the data is not used).
+// Runs at columns blk, blk + 16, ... of a segment of cnt (padded) columns.  All N loads
+// are issued unconditionally; places beyond the segment's last run re-read that run (or
+// run 0 of an empty segment, which exists: the arrays end with a spare run).
 template <int V, bool MF, int GS = 1>
-__device__ __forceinline__ Run2<V, MF, GS> load_run2(const ConvArgs &a, int blk, int lane) {
-    Run2<V, MF, GS> r;
-    r.r0 = load_run<V, MF, GS>(a, blk, lane);
-    r.r1 = load_run<V, MF, GS>(a, blk + 16, lane);
-    return r;
+__device__ __forceinline__ Runs<V, MF, GS> load_runs(const ConvArgs &a, int blk, int cnt, int lane) {
+    Runs<V, MF, GS> rs;
+    const int last = max(0, ((cnt + 15) & ~15) - 16);
+#pragma unroll
+    for (int i = 0; i < Runs<V, MF, GS>::N; ++i) rs.r[i] = load_run<V, MF, GS>(a, blk + min(16 * i, last), lane);
+    return rs;
 }
 
 template <int V, bool MF, int GS>
@@ -262,25 +272,24 @@ __device__ __forceinline__ void mfma_batch(const float (&aw)[(V / 4) * GS], int 
 // One segment (the kept columns of one bundle of GS groups inside one channel chunk),
 // MFMA form.  start/cnt are wave-uniform; base is the lane's byte offset inside an LDS
 // row (minus the chunk's first row); SH = log2(pixels per lane) for 1x1, 0 for 3x3.
-// `first` holds the segment's first two runs, loaded by the caller (early enough that
-// they are not queued behind output stores); later runs are fetched two runs ahead.
+// `rs` holds the segment's first runs, loaded by the caller (see Runs).
 template <int V, int PV, int SH, int GS = 1>
 __device__ __forceinline__ void mac_segment(const ConvArgs &a, int start, int cnt,
                                             const char *lds, int base, int lane,
-                                            Run2<V, true, GS> first, Acc<V, PV, true> &acc) {
-    constexpr int Q = V / 4;
+                                            Runs<V, true, GS> rs, Acc<V, PV, true> &acc) {
     constexpr int B = kCntAlign;  // columns whose LDS reads are in flight together
+    constexpr int N = Runs<V, true, GS>::N;
     static_assert(B == 8, "a run of 16 columns is two batches");
-    Run<V, true, GS> r0 = first.r0, r1 = first.r1;
-    for (int j0 = 0; j0 < cnt; j0 += 16) {
-        float aw[Q * GS];
-#pragma unroll
-        for (int q = 0; q < Q * GS; ++q) aw[q] = r0.a[q];
-        const int ov = r0.o;
-        r0 = r1;
-        if (j0 + 32 < cnt) r1 = load_run<V, true, GS>(a, start + j0 + 32, lane);
-        mfma_batch<0, B, V, PV, SH, GS>(aw, ov, lds, base, acc);
-        if (j0 + 8 < cnt) mfma_batch<8, B, V, PV, SH, GS>(aw, ov, lds, base, acc);
+    for (int j0 = 0; j0 < cnt; j0 += 16 * N) {
+        static_for<N>([&](auto ii) {
+            constexpr int I = decltype(ii)::value;
+            const int j = j0 + 16 * I;
+            if (j < cnt) {
+                mfma_batch<0, B, V, PV, SH, GS>(rs.r[I].a, rs.r[I].o, lds, base, acc);
+                if (j + 8 < cnt) mfma_batch<8, B, V, PV, SH, GS>(rs.r[I].a, rs.r[I].o, lds, base, acc);
+                if (j + 16 * N < cnt) rs.r[I] = load_run<V, true, GS>(a, start + j + 16 * N, lane);
+            }
+        });
     }
 }
 
@@ -289,7 +298,7 @@ __device__ __forceinline__ void mac_segment(const ConvArgs &a, int start, int cn
 template <int V, int PV, int SH, int GS = 1>
 __device__ __forceinline__ void mac_segment(const ConvArgs &a, int start, int cnt,
                                             const char *lds, int base, int lane,
-                                            Run2<V, false, GS> first, Acc<V, PV, false> &acc) {
+                                            Runs<V, false, GS> first, Acc<V, PV, false> &acc) {
     static_assert(V <= 4 && GS == 1, "FMA path is built for V <= 4, one group per wavefront");
     (void)lane;
     (void)first;
@@ -479,10 +488,10 @@ __global__ void __launch_bounds__(1024) k_pw_resident(const ConvArgs a) {
     auto nth = [&](int k) { return k * nw + ((k & 1) ? nw - 1 - wave : wave); };
     const bool any = nth(0) < ng;
     Work w0 = no_work(), w1 = no_work();
-    Run2<V, MF, GS> run0, run1;
+    Runs<V, MF, GS> run0, run1;
     if (any) {
         w0 = load_work(a.work, g_begin + nth(0));
-        run0 = load_run2<V, MF, GS>(a, w0.start, lane);
+        run0 = load_runs<V, MF, GS>(a, w0.start, w0.cnt, lane);
         if (nth(1) < ng) w1 = load_work(a.work, g_begin + nth(1));
     }
 
@@ -500,7 +509,7 @@ __global__ void __launch_bounds__(1024) k_pw_resident(const ConvArgs a) {
         const bool more = nth(k + 1) < ng;
         Work w2 = no_work();
         if (more) {
-            run1 = load_run2<V, MF, GS>(a, w1.start, lane);
+            run1 = load_runs<V, MF, GS>(a, w1.start, w1.cnt, lane);
             if (nth(k + 2) < ng) w2 = load_work(a.work, g_begin + nth(k + 2));
         }
         Acc<V, PV, MF> acc;
@@ -547,13 +556,13 @@ __global__ void __launch_bounds__(512) k_pw_chunked(const ConvArgs a) {
         const int c0 = ch * a.KC, c1 = min(a.Cin, c0 + a.KC);
         // work records and first weight runs of this chunk: fetched ahead of the input rows
         Work wk[UG];
-        Run2<V, MF> rn[UG];
+        Runs<V, MF> rn[UG];
 #pragma unroll
         for (int u = 0; u < UG; ++u) {
             wk[u] = no_work();
             if (slot[u] >= 0) {
                 wk[u] = load_work(a.work, (size_t)slot[u] * a.nchunks + ch);
-                rn[u] = load_run2<V, MF>(a, wk[u].start, lane);
+                rn[u] = load_runs<V, MF>(a, wk[u].start, wk[u].cnt, lane);
             }
         }
         if (ch) __syncthreads();
@@ -657,12 +666,12 @@ __global__ void __launch_bounds__(512) k_pw_stream(const ConvArgs a) {
             const int base = lane * PV * 4;
             Work w0 = load_work(a.work, nth(0)), w1 = no_work();
             if (nth(1) < a.G) w1 = load_work(a.work, nth(1));
-            Run2<V, true> run0 = load_run2<V, true>(al, w0.start, lane), run1;
+            Runs<V, true> run0 = load_runs<V, true>(al, w0.start, w0.cnt, lane), run1;
             for (int k = 0;; ++k) {
                 const bool more = nth(k + 1) < a.G;
                 Work w2 = no_work();
                 if (more) {
-                    run1 = load_run2<V, true>(al, w1.start, lane);
+                    run1 = load_runs<V, true>(al, w1.start, w1.cnt, lane);
                     if (nth(k + 2) < a.G) w2 = load_work(a.work, nth(k + 2));
                 }
                 Acc<V, PV, true> acc;
@@ -738,13 +747,13 @@ __global__ void __launch_bounds__(512) k_conv3(const ConvArgs a) {
         // the chunk's work records and first weight runs: fetched before the input tile, so
         // that their latency is covered by the staging (vector memory returns in order)
         Work wk[UG];
-        Run2<V, MF> rn[UG];
+        Runs<V, MF> rn[UG];
 #pragma unroll
         for (int u = 0; u < UG; ++u) {
             wk[u] = no_work();
             if (slot[u] >= 0) {
                 wk[u] = load_work(a.work, (size_t)slot[u] * a.nchunks + ch);
-                rn[u] = load_run2<V, MF>(a, wk[u].start, lane);
+                rn[u] = load_runs<V, MF>(a, wk[u].start, wk[u].cnt, lane);
             }
         }
         if (ch) __syncthreads();
