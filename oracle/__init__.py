@@ -94,6 +94,26 @@ def conv(Wd, X, bias=None, stride=1, nthreads=0):
     return Y
 
 
+ACTIVATIONS = {None: 0, "none": 0, "relu": 1, "relu6": 2}
+
+
+def conv_fused(Wd, X, bias=None, residual=None, act=None, stride=1, nthreads=0):
+    """act(conv(X) + bias + residual) with act in {None, "relu", "relu6"}; residual has Y's shape."""
+    Wd, X, bias, residual = _f32(Wd), _f32(X), _f32(bias), _f32(residual)
+    Cout, Cin, k, _ = Wd.shape
+    N, Cin2, H, Wi = X.shape
+    assert Cin == Cin2
+    Ho, Wo = out_size(H, k, stride), out_size(Wi, k, stride)
+    if residual is not None:
+        assert residual.shape == (N, Cout, Ho, Wo)
+    Y = np.empty((N, Cout, Ho, Wo), dtype=np.float32)
+    _check(_load().oracle_conv_fused(_p(Wd, ctypes.c_float), _p(X, ctypes.c_float),
+                                     _p(bias, ctypes.c_float), _p(residual, ctypes.c_float),
+                                     _p(Y, ctypes.c_float), N, Cin, Cout, H, Wi, k, stride,
+                                     ACTIVATIONS[act], int(nthreads)), "oracle_conv_fused")
+    return Y
+
+
 def conv_at(Wd, X, flat_idx, bias=None, stride=1):
     """The same sum for selected flat indices of Y[N,Cout,Ho,Wo]."""
     Wd, X, bias = _f32(Wd), _f32(X), _f32(bias)
@@ -165,6 +185,10 @@ def conv_csr(row_ptr, col_idx, vals, X, Cout, k, V, bias=None, stride=1):
     return Y
 
 
-def sparse_conv(W, mask, X, V, bias=None, stride=1, nthreads=0):
-    """Definition of the hot path end to end: densify the pruned weights, then convolve."""
-    return conv(densify(W, mask, V), X, bias=bias, stride=stride, nthreads=nthreads)
+def sparse_conv(W, mask, X, V, bias=None, stride=1, nthreads=0, residual=None, act=None):
+    """Definition of the hot path end to end: densify the pruned weights, then convolve
+    (with the fused epilogue when a residual or an activation is given)."""
+    if residual is None and ACTIVATIONS[act] == 0:
+        return conv(densify(W, mask, V), X, bias=bias, stride=stride, nthreads=nthreads)
+    return conv_fused(densify(W, mask, V), X, bias=bias, residual=residual, act=act, stride=stride,
+                      nthreads=nthreads)

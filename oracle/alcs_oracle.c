@@ -17,6 +17,9 @@
  *   - the multiplication of the grouped-CSR matrix W* with the patch matrix I*
  *     (Section 3.2.2, "Overview" and "Efficient multiplication computation")
  *                                                       -> oracle_im2col, oracle_conv_csr
+ *   - the element-wise layers after a convolution (ReLU, ReLU6, shortcut addition),
+ *     the "other layers" behind the constant tau of Section 3.3, Eq. (2), folded into
+ *     the convolution                                   -> oracle_conv_fused
  *
  * Extensions beyond the paper's equation, taken from the library's problem
  * statement: a batch of N independent images, zero padding pad=(k-1)/2, a stride,
@@ -69,9 +72,9 @@ int oracle_densify(const float *W, const uint8_t *mask, int Cout, int Cin, int k
     return ORACLE_OK;
 }
 
-/* One output element by the defining sum, in the order c, r, s. */
-static float conv_point(const float *Wd, const float *X, const float *bias, int Cin, int H,
-                        int Wi, int k, int stride, int n, int o, int ho, int wo) {
+/* One output element by the defining sum, in the order c, r, s, in double. */
+static double conv_point_d(const float *Wd, const float *X, const float *bias, int Cin, int H,
+                           int Wi, int k, int stride, int n, int o, int ho, int wo) {
     int pad = (k - 1) / 2;
     double acc = 0.0;
     for (int c = 0; c < Cin; ++c)
@@ -85,7 +88,12 @@ static float conv_point(const float *Wd, const float *X, const float *bias, int 
                 acc += (double)w * (double)X[(((size_t)n * Cin + c) * H + hi) * Wi + wi];
             }
     if (bias) acc += (double)bias[o];
-    return (float)acc;
+    return acc;
+}
+
+static float conv_point(const float *Wd, const float *X, const float *bias, int Cin, int H,
+                        int Wi, int k, int stride, int n, int o, int ho, int wo) {
+    return (float)conv_point_d(Wd, X, bias, Cin, H, Wi, k, stride, n, o, ho, wo);
 }
 
 /* The convolution equation of Section 3.2.2 on the densified weights:
@@ -107,6 +115,41 @@ int oracle_conv(const float *Wd, const float *X, const float *bias, float *Y, in
             for (int wo = 0; wo < Wo; ++wo)
                 Y[(((size_t)n * Cout + o) * Ho + ho) * Wo + wo] =
                     conv_point(Wd, X, bias, Cin, H, Wi, k, stride, n, o, ho, wo);
+    }
+    (void)nthreads;
+    return ORACLE_OK;
+}
+
+/* The convolution with the element-wise layers that follow it folded in:
+ *   Y = act(conv(X) + bias + R),  act in {identity, max(.,0), min(max(.,0),6)},
+ * R an optional tensor of Y's shape (a shortcut connection).  These are the "other
+ * layers (e.g. ReLU layers ...)" whose latency Section 3.3, Eq. (2) of the paper books
+ * as the constant tau; folding them into the convolution's epilogue removes their pass
+ * over Y.  Sum, bias and R are added in double, the activation is applied in double,
+ * and the result is rounded to float once.  R may be Y itself (element-wise in place). */
+int oracle_conv_fused(const float *Wd, const float *X, const float *bias, const float *R, float *Y,
+                      int N, int Cin, int Cout, int H, int Wi, int k, int stride, int act,
+                      int nthreads) {
+    if (!Wd || !X || !Y || N < 0 || Cin <= 0 || Cout <= 0 || H <= 0 || Wi <= 0) return ORACLE_BAD_ARG;
+    if (k <= 0 || (k % 2) == 0 || stride <= 0 || act < 0 || act > 2) return ORACLE_BAD_ARG;
+    int Ho = out_size(H, k, stride), Wo = out_size(Wi, k, stride);
+    if (Ho <= 0 || Wo <= 0) return ORACLE_BAD_ARG;
+    long long pairs = (long long)N * Cout;
+#ifdef _OPENMP
+    if (nthreads <= 0) nthreads = omp_get_max_threads();
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads)
+#endif
+    for (long long no = 0; no < pairs; ++no) {
+        int n = (int)(no / Cout), o = (int)(no % Cout);
+        for (int ho = 0; ho < Ho; ++ho)
+            for (int wo = 0; wo < Wo; ++wo) {
+                size_t at = (((size_t)n * Cout + o) * Ho + ho) * Wo + wo;
+                double v = conv_point_d(Wd, X, bias, Cin, H, Wi, k, stride, n, o, ho, wo);
+                if (R) v += (double)R[at];
+                if (act >= 1 && v < 0.0) v = 0.0;
+                if (act == 2 && v > 6.0) v = 6.0;
+                Y[at] = (float)v;
+            }
     }
     (void)nthreads;
     return ORACLE_OK;
