@@ -186,6 +186,72 @@ def report(kind, alcs, workloads, torch, np):
                     r["bytes"] / r["us"] / 1e3, r["bound"], r["roof_us"], r["roof_us"] / r["us"], r["err"]))
             pr("13 layers: sparse %.0f us, dense %.0f us (%.2fx), sum of rooflines %.0f us (%.3f)" %
                (tot, tdense, tdense / tot, troof, troof / tot))
+    elif kind == "fused":
+        # the element-wise layers behind a convolution folded into its epilogue, against the plain
+        # convolution followed by PyTorch's in-place element-wise kernels on the same buffers
+        def one(L, seed, act, residual):
+            d = workloads.make_layer(L, seed, with_bias=True)
+            p = alcs.alcs_pack_weights(d.W, d.mask, L.V)
+            X = torch.from_numpy(d.X).cuda()
+            b = torch.from_numpy(d.bias).cuda()
+            R = max(2, min(8, int(600e6 // (L.x_bytes() + (2 if residual else 1) * L.y_bytes())) + 1))
+            Xr = [X] + [X.clone() for _ in range(R - 1)]
+            Yr = [torch.empty((L.N, L.Cout, L.Ho, L.Wo), dtype=torch.float32, device="cuda") for _ in range(R)]
+            Rr = [torch.randn_like(Yr[0]) for _ in range(R)] if residual else [None] * R
+
+            def fused(i):
+                alcs.alcs_sparse_conv_fused(p, Xr[i % R], b, Rr[i % R], Yr[i % R], stride=L.stride, activation=act)
+
+            def unfused(i):
+                alcs.alcs_sparse_conv(p, Xr[i % R], b, Yr[i % R], stride=L.stride)
+                if residual:
+                    Yr[i % R].add_(Rr[i % R])
+                if act == "relu":
+                    Yr[i % R].relu_()
+                elif act == "relu6":
+                    Yr[i % R].clamp_(0.0, 6.0)
+
+            res = []
+            for fn in (fused, unfused):
+                for i in range(3):
+                    fn(i)
+                torch.cuda.synchronize()
+                n = 3 * R
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for i in range(n):
+                    fn(i)
+                e1.record()
+                torch.cuda.synchronize()
+                res.append(e0.elapsed_time(e1) * 1e3 / n)
+            fused(0)
+            unf = Yr[0].clone()
+            unfused(0)
+            torch.cuda.synchronize()
+            diff = float((unf - Yr[0]).abs().max() / Yr[0].abs().max().clamp_min(1e-30))
+            by = layer_bytes(L, p.nnzb) + 4 * L.Cout + (L.y_bytes() if residual else 0)
+            p.free()
+            return res[0], res[1], by, diff
+
+        pr("| layer | epilogue | fused us | conv + element-wise kernels us | ratio | fused eff GB/s | max diff |")
+        pr("|---|---|---|---|---|---|---|")
+        tf = tu = 0.0
+        for i, L in enumerate(workloads.mobilenet_v1_pointwise(32, 0.9)):
+            f, u, by, diff = one(L, workloads.seed_for(2, i), "relu", False)
+            tf += f
+            tu += u
+            pr("| %s %d->%d @%d | bias + ReLU | %.1f | %.1f | %.2f | %.0f | %.1e |" %
+               (L.name, L.Cin, L.Cout, L.H, f, u, u / f, by / f / 1e3, diff))
+        pr("| 13 MobileNetV1-shaped layers, batch 32 | | %.0f | %.0f | %.2f | | |" % (tf, tu, tu / tf))
+        tf = tu = 0.0
+        for i, L in enumerate(workloads.mobilenet_v2_pointwise(128, 4)):
+            if not L.name.startswith("proj") or L.Cin != 6 * L.Cout:
+                continue   # shortcut connections exist where a block keeps its width
+            f, u, by, diff = one(L, workloads.seed_for(5, 400 + i), None, True)
+            tf += f
+            tu += u
+            pr("| %s | bias + shortcut | %.1f | %.1f | %.2f | %.0f | %.1e |" % (L.name, f, u, u / f, by / f / 1e3, diff))
+        pr("| MobileNetV2-shaped projections with a shortcut, batch 128 | | %.0f | %.0f | %.2f | | |" % (tf, tu, tu / tf))
     elif kind == "paths":
         pr("| layer | MFMA us | FMA us | FMA / MFMA |")
         pr("|---|---|---|---|")
@@ -213,13 +279,15 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-batch", type=int, default=32)
     ap.add_argument("--layers-json", default=None, help="also write the per-layer table to this file")
-    ap.add_argument("--report", choices=["sweep", "resnet", "mbv2", "paths", "mbv1"], default=None,
+    ap.add_argument("--report", choices=["sweep", "resnet", "mbv2", "paths", "mbv1", "fused"], default=None,
                     help="instead of the benchmark line, print a per-layer table for another configuration: "
                          "the sparsity sweep with the same-GPU dense conv (config 4), the ResNet-50-shaped "
                          "bottleneck convs (config 3), the MobileNetV2-shaped pointwise convs for V in "
                          "{1,4,8,16} (config 5), MFMA against plain-FMA inner loops (V=4), or the "
                          "MobileNetV1-shaped pointwise convs at batch 1 and 32 with fixed and drawn "
-                         "sparsities, beside the dense conv (config 2)")
+                         "sparsities, beside the dense conv (config 2), or the fused epilogue "
+                         "(alcs_sparse_conv_fused) against the convolution followed by separate "
+                         "element-wise kernels")
     ap.add_argument("--calib-copy", action="store_true",
                     help="for rocprofv3 --pmc runs only: put a plain 256 MiB device copy in front of every "
                          "step, so that the HBM byte counters can be scaled by a kernel of known traffic "

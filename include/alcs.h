@@ -153,6 +153,29 @@ int alcs_sparse_conv_timed(const alcs_packed_t *Wp, const float *X_dev, const fl
                            float *Y_dev, int N, int Cin, int Cout, int H, int W, int kernel,
                            int stride, void *stream, void *start_event, void *stop_event);
 
+/* Activations of alcs_sparse_conv_fused. */
+typedef enum alcs_activation {
+    ALCS_ACT_NONE = 0,  /* identity */
+    ALCS_ACT_RELU = 1,  /* max(v, 0) */
+    ALCS_ACT_RELU6 = 2  /* min(max(v, 0), 6) */
+} alcs_activation;
+
+/*
+ * alcs_sparse_conv with the element-wise layers that follow the convolution folded into
+ * its epilogue, so that they cost no pass of their own over Y (they are the "other layers
+ * (e.g. ReLU layers ...)" whose latency Section 3.3, Eq. (2) books as the constant tau):
+ *   Y = act(sparse_conv(X) + bias + residual)
+ *   residual_dev  [N, Cout, Ho, Wo] fp32 (a shortcut connection) or NULL; it may be Y_dev
+ *                 itself (every element is read and then written by the same thread),
+ *                 but must not overlap Y in any other way; 16-byte aligned like the others.
+ *   activation    an alcs_activation value (ALCS_E_INVALID_ARG otherwise).
+ * With residual_dev = NULL and ALCS_ACT_NONE this is alcs_sparse_conv.  Other arguments,
+ * results and errors as there.  NaN inputs to ReLU/ReLU6 give 0 (fmax semantics).
+ */
+int alcs_sparse_conv_fused(const alcs_packed_t *Wp, const float *X_dev, const float *bias_dev,
+                           const float *residual_dev, float *Y_dev, int N, int Cin, int Cout, int H,
+                           int W, int kernel, int stride, int activation, void *stream);
+
 /*
  * Dense convolution with the same conventions: the sparsity-0 case of the
  * operation above and the same-GPU baseline (the role the dense models play in the

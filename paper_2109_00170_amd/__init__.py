@@ -13,6 +13,7 @@ from ._binding import (  # noqa: F401
     alcs_pack_weights,
     alcs_set_tuning,
     alcs_sparse_conv,
+    alcs_sparse_conv_fused,
     alcs_strerror,
     alcs_version,
     library_path,

@@ -14,7 +14,8 @@ _lib = None
 EXPORTS = [
     "alcs_strerror", "alcs_last_hip_error", "alcs_version", "alcs_pack_weights", "alcs_packed_info",
     "alcs_packed_on_device", "alcs_packed_export", "alcs_packed_selfcheck", "alcs_packed_free",
-    "alcs_sparse_conv", "alcs_sparse_conv_timed", "alcs_dense_conv", "alcs_set_tuning", "alcs_last_launch",
+    "alcs_sparse_conv", "alcs_sparse_conv_timed", "alcs_sparse_conv_fused", "alcs_dense_conv", "alcs_set_tuning",
+    "alcs_last_launch",
 ]
 
 
@@ -53,6 +54,7 @@ def load_library():
     lib.alcs_packed_free.restype = None
     lib.alcs_sparse_conv.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp]
     lib.alcs_sparse_conv_timed.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp, vp, vp]
+    lib.alcs_sparse_conv_fused.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp]
     lib.alcs_dense_conv.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp]
     lib.alcs_set_tuning.argtypes = [ctypes.c_char_p, ci]
     lib.alcs_last_launch.argtypes = [cip, ci]
@@ -180,6 +182,28 @@ def alcs_sparse_conv(packed: Packed, X, bias, Y, stride: int = 1, stream=None, e
                                         ctypes.c_void_p(events[1]))
     if rc != 0:
         raise AlcsError(rc, "alcs_sparse_conv")
+
+
+ACTIVATIONS = {None: 0, "none": 0, "relu": 1, "relu6": 2}
+
+
+def alcs_sparse_conv_fused(packed: Packed, X, bias, residual, Y, stride: int = 1, activation=None,
+                           stream=None) -> None:
+    """Y = act(sparse_conv(packed, X) + bias + residual); residual has Y's shape (or is None, or is Y);
+    activation is None, "relu", "relu6" or an alcs_activation integer."""
+    N, Cin, H, W = X.shape
+    k = packed.kernel
+    exp = (N, packed.Cout, out_size(H, k, stride), out_size(W, k, stride))
+    if tuple(Y.shape) != exp:
+        raise ValueError("Y must have shape %r, got %r" % (exp, tuple(Y.shape)))
+    if residual is not None and tuple(residual.shape) != exp:
+        raise ValueError("residual must have shape %r, got %r" % (exp, tuple(residual.shape)))
+    act = activation if isinstance(activation, int) else ACTIVATIONS[activation]
+    rc = load_library().alcs_sparse_conv_fused(packed.handle, _dev_ptr(X, "X"), _dev_ptr(bias, "bias"),
+                                               _dev_ptr(residual, "residual"), _dev_ptr(Y, "Y"), N, Cin,
+                                               packed.Cout, H, W, k, int(stride), int(act), _stream_ptr(stream))
+    if rc != 0:
+        raise AlcsError(rc, "alcs_sparse_conv_fused")
 
 
 class HipEvents:

@@ -39,6 +39,7 @@ typedef int i4 __attribute__((ext_vector_type(4)));
 struct ConvArgs {
     const float *X;
     const float *bias;
+    const float *residual;  // fused epilogue: tensor of Y's shape added before the activation, or null
     float *Y;
     const Work *work;   // [G * nchunks] in hand-out order (longest group first)
     const float *w;
@@ -54,8 +55,16 @@ struct ConvArgs {
     int ppw;            // streaming kernel: flattened pixels per workgroup (multiple of 4)
     int wfloats;        // streaming kernel: floats in the weight planes, planes * nblk * 4
     int nblk;           // padded blocks (= number of row selectors)
+    int act;    // fused epilogue: 0 none, 1 max(., 0), 2 min(max(., 0), 6)
     int debug;  // measurement only: bit 0 skips staging, bit 1 the multiply, bit 2 the stores
 };
+
+// The element-wise tail of the fused epilogue (the plain convolution passes act = 0).
+__device__ __forceinline__ float activate(const ConvArgs &a, float v) {
+    if (a.act >= 1) v = fmaxf(v, 0.f);
+    if (a.act == 2) v = fminf(v, 6.f);
+    return v;
+}
 
 constexpr int kXcds = 8;
 
@@ -403,31 +412,97 @@ __device__ __forceinline__ void pix_out(const ConvArgs &a, int q0, int lane, Pix
     }
 }
 
+// The residual of one group for the lane's pixels, fetched before the group is multiplied
+// (a load issued in the epilogue would be waited for at once).
+template <int V, int PV>
+struct Resid {
+    float r[V][PV];
+};
+template <int V, int PV, bool VEC>
+__device__ __forceinline__ void load_residual(const ConvArgs &a, int g, const PixOut<PV> &px, Resid<V, PV> &rr) {
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        const int ch = g * V + v;
+#pragma unroll
+        for (int pv = 0; pv < PV; ++pv) rr.r[v][pv] = 0.f;
+        if (ch >= a.Cout) continue;
+        const float *res = a.residual + (size_t)ch * a.P;
+        if constexpr (VEC && PV == 4) {
+            if (px.valid[0]) {
+                const f4 t = *reinterpret_cast<const f4 *>(res + px.yoff[0]);
+                rr.r[v][0] = t[0]; rr.r[v][1] = t[1]; rr.r[v][2] = t[2]; rr.r[v][3] = t[3];
+            }
+        } else if constexpr (VEC && PV == 2) {
+            if (px.valid[0]) {
+                const f2 t = *reinterpret_cast<const f2 *>(res + px.yoff[0]);
+                rr.r[v][0] = t[0]; rr.r[v][1] = t[1];
+            }
+        } else {
+#pragma unroll
+            for (int pv = 0; pv < PV; ++pv)
+                if (px.valid[pv]) rr.r[v][pv] = res[px.yoff[pv]];
+        }
+    }
+}
+
 // Epilogue: Y = acc + bias for the V channels of group g (rows beyond Cout of a
 // ragged last group are not stored).
 template <int V, int PV, bool MF, bool VEC>
 __device__ __forceinline__ void store_group(const ConvArgs &a, const Acc<V, PV, MF> &acc, int g,
-                                            const PixOut<PV> &px) {
+                                            const PixOut<PV> &px, const Resid<V, PV> *pre = nullptr) {
 #pragma unroll
     for (int v = 0; v < V; ++v) {
         const int ch = g * V + v;
         if (ch >= a.Cout) break;
-        const float b = a.bias ? as_const(a.bias)[ch] : 0.f;
+        float b = a.bias ? as_const(a.bias)[ch] : 0.f;
         float *dst = a.Y + (size_t)ch * a.P;
+        // the residual: already in registers (pre), or read here
+        const float *res = (a.residual && !pre) ? a.residual + (size_t)ch * a.P : nullptr;  // wave-uniform
+        if (pre) {
+            if constexpr (VEC && PV == 4) {
+                if (px.valid[0]) {
+                    f4 o = f4{acc.get(v, 0) + b + pre->r[v][0], acc.get(v, 1) + b + pre->r[v][1],
+                              acc.get(v, 2) + b + pre->r[v][2], acc.get(v, 3) + b + pre->r[v][3]};
+                    if (a.act) o = f4{activate(a, o[0]), activate(a, o[1]), activate(a, o[2]), activate(a, o[3])};
+                    __builtin_nontemporal_store(o, reinterpret_cast<f4 *>(dst + px.yoff[0]));
+                }
+            } else if constexpr (VEC && PV == 2) {
+                if (px.valid[0]) {
+                    f2 o = f2{acc.get(v, 0) + b + pre->r[v][0], acc.get(v, 1) + b + pre->r[v][1]};
+                    if (a.act) o = f2{activate(a, o[0]), activate(a, o[1])};
+                    __builtin_nontemporal_store(o, reinterpret_cast<f2 *>(dst + px.yoff[0]));
+                }
+            } else {
+#pragma unroll
+                for (int pv = 0; pv < PV; ++pv)
+                    if (px.valid[pv])
+                        __builtin_nontemporal_store(activate(a, acc.get(v, pv) + b + pre->r[v][pv]), dst + px.yoff[pv]);
+            }
+            continue;
+        }
         // Y is written once and not read again by this kernel: streaming (non-temporal) stores
         if constexpr (VEC && PV == 4) {
-            if (px.valid[0])
-                __builtin_nontemporal_store(
-                    f4{acc.get(v, 0) + b, acc.get(v, 1) + b, acc.get(v, 2) + b, acc.get(v, 3) + b},
-                    reinterpret_cast<f4 *>(dst + px.yoff[0]));
+            if (px.valid[0]) {
+                f4 o = f4{acc.get(v, 0) + b, acc.get(v, 1) + b, acc.get(v, 2) + b, acc.get(v, 3) + b};
+                if (res) o += *reinterpret_cast<const f4 *>(res + px.yoff[0]);
+                if (a.act) o = f4{activate(a, o[0]), activate(a, o[1]), activate(a, o[2]), activate(a, o[3])};
+                __builtin_nontemporal_store(o, reinterpret_cast<f4 *>(dst + px.yoff[0]));
+            }
         } else if constexpr (VEC && PV == 2) {
-            if (px.valid[0])
-                __builtin_nontemporal_store(f2{acc.get(v, 0) + b, acc.get(v, 1) + b},
-                                            reinterpret_cast<f2 *>(dst + px.yoff[0]));
+            if (px.valid[0]) {
+                f2 o = f2{acc.get(v, 0) + b, acc.get(v, 1) + b};
+                if (res) o += *reinterpret_cast<const f2 *>(res + px.yoff[0]);
+                if (a.act) o = f2{activate(a, o[0]), activate(a, o[1])};
+                __builtin_nontemporal_store(o, reinterpret_cast<f2 *>(dst + px.yoff[0]));
+            }
         } else {
 #pragma unroll
             for (int pv = 0; pv < PV; ++pv)
-                if (px.valid[pv]) __builtin_nontemporal_store(acc.get(v, pv) + b, dst + px.yoff[pv]);
+                if (px.valid[pv]) {
+                    float o = acc.get(v, pv) + b;
+                    if (res) o += res[px.yoff[pv]];
+                    __builtin_nontemporal_store(activate(a, o), dst + px.yoff[pv]);
+                }
         }
     }
 }
@@ -457,7 +532,9 @@ __device__ __forceinline__ void store_slots(const ConvArgs &a, const Acc<V, 1, t
         const int ch = g * V + v;
         if (ch >= a.Cout) break;
         const float b = a.bias ? a.bias[ch] : 0.f;
-        __builtin_nontemporal_store(acc.get(v, 0) + b, a.Y + (size_t)ch * a.P + px.yoff[0]);
+        float o = acc.get(v, 0) + b;
+        if (a.residual) o += a.residual[(size_t)ch * a.P + px.yoff[0]];
+        __builtin_nontemporal_store(activate(a, o), a.Y + (size_t)ch * a.P + px.yoff[0]);
     }
 }
 
@@ -469,8 +546,9 @@ __device__ __forceinline__ void store_slots(const ConvArgs &a, const Acc<V, 1, t
 // first run of group k+1 are fetched while group k is multiplied, and always before
 // group k's output stores are issued (memory operations retire in order, so a load
 // queued behind stores would wait for them).
-template <int V, int PV, bool MF, bool VEC, int GS>
+template <int V, int PV, bool MF, bool VEC, int GS, bool RES = false>
 __global__ void __launch_bounds__(1024) k_pw_resident(const ConvArgs a) {
+    static_assert(!RES || GS == 1, "residual prefetch: one group per wavefront");
     static_assert(GS == 1 || (PV == 1 && MF), "several groups per wavefront: MFMA form, one pixel per lane");
     extern __shared__ float lds[];
     constexpr int TP = 64 * PV / GS;
@@ -514,9 +592,11 @@ __global__ void __launch_bounds__(1024) k_pw_resident(const ConvArgs a) {
         }
         Acc<V, PV, MF> acc;
         acc.zero();
+        Resid<V, PV> rr;
+        if constexpr (RES) load_residual<V, PV, VEC>(a, w0.group[0], px, rr);
         if (!(a.debug & 2)) mac_segment<V, PV, SH, GS>(a, w0.start, w0.cnt, ldsb, base, lane, run0, acc);
         if (!(a.debug & 4)) {
-            if constexpr (GS == 1) store_group<V, PV, MF, VEC>(a, acc, w0.group[0], px);
+            if constexpr (GS == 1) store_group<V, PV, MF, VEC>(a, acc, w0.group[0], px, RES ? &rr : nullptr);
             else store_slots<V, GS>(a, acc, lane_group<GS>(w0, lane), px);
         }
         if (!more) break;
@@ -824,7 +904,16 @@ static inline int ceil_div(long long a, long long b) { return (int)((a + b - 1) 
 typedef void (*kern_t)(const ConvArgs);
 
 template <int V, bool MF>
-static kern_t pick_resident(int pv, bool vec, int gs) {
+static kern_t pick_resident(int pv, bool vec, int gs, bool res = false) {
+    if constexpr (MF && V * 4 <= 32) {
+        // with a residual: the variants that fetch it ahead of the multiply (vector form, one
+        // group per wavefront, at most 32 values per lane)
+        if (res && vec && gs == 1) {
+            if (pv == 4) return k_pw_resident<V, 4, true, true, 1, true>;
+            if (pv == 2) return k_pw_resident<V, 2, true, true, 1, true>;
+            return k_pw_resident<V, 1, true, true, 1, true>;
+        }
+    }
     if constexpr (MF) {
         if (gs == 2) return vec ? k_pw_resident<V, 1, true, true, 2> : k_pw_resident<V, 1, true, false, 2>;
         if (gs == 4) return vec ? k_pw_resident<V, 1, true, true, 4> : k_pw_resident<V, 1, true, false, 4>;
@@ -907,13 +996,15 @@ using namespace alcs;
 
 static int launch_sparse(const alcs_packed_t *Wp, const float *X_dev, const float *bias_dev,
                          float *Y_dev, int N, int Cin, int Cout, int H, int W, int kernel,
-                         int stride, void *stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
+                         int stride, void *stream, hipEvent_t ev_start, hipEvent_t ev_stop,
+                         const float *residual_dev = nullptr, int activation = 0) {
     if (!Wp || N < 0 || H <= 0 || W <= 0) return ALCS_E_INVALID_ARG;
     if (Cin != Wp->Cin || Cout != Wp->Cout || kernel != Wp->k) return ALCS_E_INVALID_ARG;
     if (stride != 1 && stride != 2) return ALCS_E_UNSUPPORTED;
     if (N == 0) return ALCS_OK;
     if (!X_dev || !Y_dev) return ALCS_E_INVALID_ARG;
-    if (((uintptr_t)X_dev | (uintptr_t)Y_dev) & 15) return ALCS_E_INVALID_ARG;
+    if (((uintptr_t)X_dev | (uintptr_t)Y_dev | (uintptr_t)residual_dev) & 15) return ALCS_E_INVALID_ARG;
+    if (activation < 0 || activation > 2) return ALCS_E_INVALID_ARG;
     const int pad = (kernel - 1) / 2;
     const int Ho = (H + 2 * pad - kernel) / stride + 1, Wo = (W + 2 * pad - kernel) / stride + 1;
     if (Ho <= 0 || Wo <= 0) return ALCS_E_INVALID_ARG;
@@ -931,6 +1022,7 @@ static int launch_sparse(const alcs_packed_t *Wp, const float *X_dev, const floa
     const int V = Wp->V, G = Wp->G;
     ConvArgs a{};
     a.X = X_dev; a.bias = bias_dev; a.Y = Y_dev;
+    a.residual = residual_dev; a.act = activation;
     a.work = Wp->dev.work; a.w = Wp->dev.w;
     a.off = Wp->dev.off[0];
     a.wplane = (long long)L.wplane;
@@ -1027,9 +1119,9 @@ static int launch_sparse(const alcs_packed_t *Wp, const float *X_dev, const floa
             switch (V) {
                 case 1: kern = pick_resident<1, false>(pv, vec, GS); break;
                 case 2: kern = pick_resident<2, false>(pv, vec, GS); break;
-                case 4: kern = mfma ? pick_resident<4, true>(pv, vec, GS) : pick_resident<4, false>(pv, vec, GS); break;
-                case 8: kern = pick_resident<8, true>(pv, vec, GS); break;
-                case 16: kern = pick_resident<16, true>(pv, vec, GS); break;
+                case 4: kern = mfma ? pick_resident<4, true>(pv, vec, GS, a.residual != nullptr) : pick_resident<4, false>(pv, vec, GS); break;
+                case 8: kern = pick_resident<8, true>(pv, vec, GS, a.residual != nullptr); break;
+                case 16: kern = pick_resident<16, true>(pv, vec, GS, a.residual != nullptr); break;
             }
         } else {
             mode = 2;
@@ -1107,4 +1199,11 @@ extern "C" int alcs_sparse_conv_timed(const alcs_packed_t *Wp, const float *X_de
                                       int stride, void *stream, void *start_event, void *stop_event) {
     return launch_sparse(Wp, X_dev, bias_dev, Y_dev, N, Cin, Cout, H, W, kernel, stride, stream,
                          (hipEvent_t)start_event, (hipEvent_t)stop_event);
+}
+
+extern "C" int alcs_sparse_conv_fused(const alcs_packed_t *Wp, const float *X_dev, const float *bias_dev,
+                                      const float *residual_dev, float *Y_dev, int N, int Cin, int Cout,
+                                      int H, int W, int kernel, int stride, int activation, void *stream) {
+    return launch_sparse(Wp, X_dev, bias_dev, Y_dev, N, Cin, Cout, H, W, kernel, stride, stream, nullptr, nullptr,
+                         residual_dev, activation);
 }
