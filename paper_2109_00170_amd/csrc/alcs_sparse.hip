@@ -30,7 +30,22 @@
 
 #include "alcs_internal.h"
 
+// This file is compiled twice.  As it stands it gives alcs_sparse_conv and
+// alcs_sparse_conv_timed, whose kernels have no trace of the fused epilogue (a run-time
+// test for a residual or an activation in every store cost 3-4 % of the benchmark step).
+// alcs_sparse_fused.hip defines ALCS_FUSED_EPILOGUE and includes this file: the same
+// kernels with the epilogue compiled in, in namespace alcs::fused, behind
+// alcs_sparse_conv_fused.
+#ifndef ALCS_FUSED_EPILOGUE
+#define ALCS_FUSED_EPILOGUE 0
+#endif
+
 namespace alcs {
+#if ALCS_FUSED_EPILOGUE
+namespace fused {
+#endif
+
+constexpr bool kFused = ALCS_FUSED_EPILOGUE != 0;
 
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef float f2 __attribute__((ext_vector_type(2)));
@@ -61,9 +76,16 @@ struct ConvArgs {
 
 // The element-wise tail of the fused epilogue (the plain convolution passes act = 0).
 __device__ __forceinline__ float activate(const ConvArgs &a, float v) {
-    if (a.act >= 1) v = fmaxf(v, 0.f);
-    if (a.act == 2) v = fminf(v, 6.f);
+    if constexpr (kFused) {
+        if (a.act >= 1) v = fmaxf(v, 0.f);
+        if (a.act == 2) v = fminf(v, 6.f);
+    }
     return v;
+}
+// The residual tensor, or null where the epilogue is compiled out.
+__device__ __forceinline__ const float *residual_of(const ConvArgs &a) {
+    if constexpr (kFused) return a.residual;
+    else return nullptr;
 }
 
 constexpr int kXcds = 8;
@@ -457,19 +479,19 @@ __device__ __forceinline__ void store_group(const ConvArgs &a, const Acc<V, PV, 
         float b = a.bias ? as_const(a.bias)[ch] : 0.f;
         float *dst = a.Y + (size_t)ch * a.P;
         // the residual: already in registers (pre), or read here
-        const float *res = (a.residual && !pre) ? a.residual + (size_t)ch * a.P : nullptr;  // wave-uniform
-        if (pre) {
+        const float *res = (residual_of(a) && !pre) ? residual_of(a) + (size_t)ch * a.P : nullptr;  // wave-uniform
+        if (kFused && pre) {
             if constexpr (VEC && PV == 4) {
                 if (px.valid[0]) {
                     f4 o = f4{acc.get(v, 0) + b + pre->r[v][0], acc.get(v, 1) + b + pre->r[v][1],
                               acc.get(v, 2) + b + pre->r[v][2], acc.get(v, 3) + b + pre->r[v][3]};
-                    if (a.act) o = f4{activate(a, o[0]), activate(a, o[1]), activate(a, o[2]), activate(a, o[3])};
+                    if (kFused && a.act) o = f4{activate(a, o[0]), activate(a, o[1]), activate(a, o[2]), activate(a, o[3])};
                     __builtin_nontemporal_store(o, reinterpret_cast<f4 *>(dst + px.yoff[0]));
                 }
             } else if constexpr (VEC && PV == 2) {
                 if (px.valid[0]) {
                     f2 o = f2{acc.get(v, 0) + b + pre->r[v][0], acc.get(v, 1) + b + pre->r[v][1]};
-                    if (a.act) o = f2{activate(a, o[0]), activate(a, o[1])};
+                    if (kFused && a.act) o = f2{activate(a, o[0]), activate(a, o[1])};
                     __builtin_nontemporal_store(o, reinterpret_cast<f2 *>(dst + px.yoff[0]));
                 }
             } else {
@@ -485,14 +507,14 @@ __device__ __forceinline__ void store_group(const ConvArgs &a, const Acc<V, PV, 
             if (px.valid[0]) {
                 f4 o = f4{acc.get(v, 0) + b, acc.get(v, 1) + b, acc.get(v, 2) + b, acc.get(v, 3) + b};
                 if (res) o += *reinterpret_cast<const f4 *>(res + px.yoff[0]);
-                if (a.act) o = f4{activate(a, o[0]), activate(a, o[1]), activate(a, o[2]), activate(a, o[3])};
+                if (kFused && a.act) o = f4{activate(a, o[0]), activate(a, o[1]), activate(a, o[2]), activate(a, o[3])};
                 __builtin_nontemporal_store(o, reinterpret_cast<f4 *>(dst + px.yoff[0]));
             }
         } else if constexpr (VEC && PV == 2) {
             if (px.valid[0]) {
                 f2 o = f2{acc.get(v, 0) + b, acc.get(v, 1) + b};
                 if (res) o += *reinterpret_cast<const f2 *>(res + px.yoff[0]);
-                if (a.act) o = f2{activate(a, o[0]), activate(a, o[1])};
+                if (kFused && a.act) o = f2{activate(a, o[0]), activate(a, o[1])};
                 __builtin_nontemporal_store(o, reinterpret_cast<f2 *>(dst + px.yoff[0]));
             }
         } else {
@@ -533,7 +555,7 @@ __device__ __forceinline__ void store_slots(const ConvArgs &a, const Acc<V, 1, t
         if (ch >= a.Cout) break;
         const float b = a.bias ? a.bias[ch] : 0.f;
         float o = acc.get(v, 0) + b;
-        if (a.residual) o += a.residual[(size_t)ch * a.P + px.yoff[0]];
+        if (residual_of(a)) o += residual_of(a)[(size_t)ch * a.P + px.yoff[0]];
         __builtin_nontemporal_store(activate(a, o), a.Y + (size_t)ch * a.P + px.yoff[0]);
     }
 }
@@ -546,8 +568,8 @@ __device__ __forceinline__ void store_slots(const ConvArgs &a, const Acc<V, 1, t
 // first run of group k+1 are fetched while group k is multiplied, and always before
 // group k's output stores are issued (memory operations retire in order, so a load
 // queued behind stores would wait for them).
-template <int V, int PV, bool MF, bool VEC, int GS, bool RES = false>
-__global__ void __launch_bounds__(1024) k_pw_resident(const ConvArgs a) {
+template <int V, int PV, bool MF, bool VEC, int GS, bool RES>
+__device__ __forceinline__ void pw_resident_body(const ConvArgs &a) {
     static_assert(!RES || GS == 1, "residual prefetch: one group per wavefront");
     static_assert(GS == 1 || (PV == 1 && MF), "several groups per wavefront: MFMA form, one pixel per lane");
     extern __shared__ float lds[];
@@ -604,6 +626,17 @@ __global__ void __launch_bounds__(1024) k_pw_resident(const ConvArgs a) {
         w1 = w2;
         run0 = run1;
     }
+}
+
+template <int V, int PV, bool MF, bool VEC, int GS>
+__global__ void __launch_bounds__(1024) k_pw_resident(const ConvArgs a) {
+    pw_resident_body<V, PV, MF, VEC, GS, false>(a);
+}
+// The same walk with every group's residual fetched ahead of its multiply (fused epilogue,
+// MFMA and vector form, one group per wavefront).
+template <int V, int PV>
+__global__ void __launch_bounds__(1024) k_pw_resident_res(const ConvArgs a) {
+    pw_resident_body<V, PV, true, true, 1, true>(a);
 }
 
 // Mode 2: input channels streamed through LDS in chunks of KC; every wavefront owns
@@ -905,13 +938,15 @@ typedef void (*kern_t)(const ConvArgs);
 
 template <int V, bool MF>
 static kern_t pick_resident(int pv, bool vec, int gs, bool res = false) {
-    if constexpr (MF && V * 4 <= 32) {
+    if constexpr (kFused && MF && V <= 8) {
         // with a residual: the variants that fetch it ahead of the multiply (vector form, one
-        // group per wavefront, at most 32 values per lane)
+        // group per wavefront, at most 16 values per lane)
         if (res && vec && gs == 1) {
-            if (pv == 4) return k_pw_resident<V, 4, true, true, 1, true>;
-            if (pv == 2) return k_pw_resident<V, 2, true, true, 1, true>;
-            return k_pw_resident<V, 1, true, true, 1, true>;
+            if constexpr (V * 4 <= 16) {
+                if (pv == 4) return k_pw_resident_res<V, 4>;
+            }
+            if (pv == 2) return k_pw_resident_res<V, 2>;
+            if (pv == 1) return k_pw_resident_res<V, 1>;
         }
     }
     if constexpr (MF) {
@@ -990,9 +1025,15 @@ static int set_lds_limit(kern_t k, int lds) {
     return ALCS_OK;
 }
 
+#if ALCS_FUSED_EPILOGUE
+}  // namespace fused
+#endif
 }  // namespace alcs
 
 using namespace alcs;
+#if ALCS_FUSED_EPILOGUE
+using namespace alcs::fused;
+#endif
 
 static int launch_sparse(const alcs_packed_t *Wp, const float *X_dev, const float *bias_dev,
                          float *Y_dev, int N, int Cin, int Cout, int H, int W, int kernel,
@@ -1188,6 +1229,7 @@ static int launch_sparse(const alcs_packed_t *Wp, const float *X_dev, const floa
     return ALCS_OK;
 }
 
+#if !ALCS_FUSED_EPILOGUE
 extern "C" int alcs_sparse_conv(const alcs_packed_t *Wp, const float *X_dev, const float *bias_dev,
                                 float *Y_dev, int N, int Cin, int Cout, int H, int W, int kernel,
                                 int stride, void *stream) {
@@ -1201,9 +1243,11 @@ extern "C" int alcs_sparse_conv_timed(const alcs_packed_t *Wp, const float *X_de
                          (hipEvent_t)start_event, (hipEvent_t)stop_event);
 }
 
+#else
 extern "C" int alcs_sparse_conv_fused(const alcs_packed_t *Wp, const float *X_dev, const float *bias_dev,
                                       const float *residual_dev, float *Y_dev, int N, int Cin, int Cout,
                                       int H, int W, int kernel, int stride, int activation, void *stream) {
     return launch_sparse(Wp, X_dev, bias_dev, Y_dev, N, Cin, Cout, H, W, kernel, stride, stream, nullptr, nullptr,
                          residual_dev, activation);
 }
+#endif
