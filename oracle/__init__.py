@@ -37,6 +37,8 @@ def _load():
         build()
         lib = ctypes.CDLL(_LIB)
         lib.oracle_pack_count.restype = ctypes.c_int64
+        lib.oracle_latency_estimate.restype = ctypes.c_double
+        lib.oracle_network_latency.restype = ctypes.c_double
         _lib = lib
     return _lib
 
@@ -192,3 +194,36 @@ def sparse_conv(W, mask, X, V, bias=None, stride=1, nthreads=0, residual=None, a
         return conv(densify(W, mask, V), X, bias=bias, stride=stride, nthreads=nthreads)
     return conv_fused(densify(W, mask, V), X, bias=bias, residual=residual, act=act, stride=stride,
                       nthreads=nthreads)
+
+
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def latency_estimate(k, t, s) -> float:
+    """Section 3.3, Eqs. (4)-(6): run time of a layer with ``s`` non-zero weights, from the
+    run times ``t`` measured at ``k`` non-zero weights (``k`` strictly increasing)."""
+    k, t = _f64(k), _f64(t)
+    if k.ndim != 1 or k.shape != t.shape or k.size < 2 or not np.all(np.diff(k) > 0):
+        raise ValueError("latency_estimate: need two or more strictly increasing knots")
+    return float(_load().oracle_latency_estimate(_p(k, ctypes.c_double), _p(t, ctypes.c_double),
+                                                 int(k.size), ctypes.c_double(float(s))))
+
+
+def network_latency(tau, tables, nnz) -> float:
+    """Section 3.3, Eq. (2): ``tau`` plus the estimate of every layer; ``tables`` is a list of
+    (k, t) pairs, ``nnz`` the layers' numbers of non-zero weights."""
+    if len(tables) != len(nnz):
+        raise ValueError("network_latency: one table per layer")
+    ks = [_f64(k) for k, _ in tables]
+    ts = [_f64(t) for _, t in tables]
+    for k, t in zip(ks, ts):
+        if k.ndim != 1 or k.shape != t.shape or k.size < 2 or not np.all(np.diff(k) > 0):
+            raise ValueError("network_latency: need two or more strictly increasing knots per layer")
+    n = np.array([k.size for k in ks], dtype=np.int32)
+    kk = _f64(np.concatenate(ks)) if ks else np.zeros(0)
+    tt = _f64(np.concatenate(ts)) if ts else np.zeros(0)
+    s = _f64(nnz)
+    return float(_load().oracle_network_latency(ctypes.c_double(float(tau)), _p(kk, ctypes.c_double),
+                                                _p(tt, ctypes.c_double), _p(n, ctypes.c_int), int(len(ks)),
+                                                _p(s, ctypes.c_double)))

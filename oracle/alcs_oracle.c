@@ -20,6 +20,10 @@
  *   - the element-wise layers after a convolution (ReLU, ReLU6, shortcut addition),
  *     the "other layers" behind the constant tau of Section 3.3, Eq. (2), folded into
  *     the convolution                                   -> oracle_conv_fused
+ *   - the latency model of Section 3.3: a layer's run time as a piecewise-linear
+ *     function of its number of non-zero weights, Eqs. (4)-(6), and the network's
+ *     run time as tau plus the sum over layers, Eq. (2)
+ *                                 -> oracle_latency_estimate, oracle_network_latency
  *
  * Extensions beyond the paper's equation, taken from the library's problem
  * statement: a batch of N independent images, zero padding pad=(k-1)/2, a stride,
@@ -297,6 +301,36 @@ int oracle_conv_csr(const int32_t *row_ptr, const int32_t *col_idx, const float 
         }
     }
     return ORACLE_OK;
+}
+
+/* Section 3.3, Eqs. (4)-(6).  k[0] < k[1] < ... < k[n-1] are the numbers of non-zero
+ * weights at which the layer was timed and t[i] the run time measured at k[i].  The
+ * estimate for s non-zero weights starts from t[0] and adds, for every interval i whose
+ * left end s has reached (delta_i = 1), the slope alpha_i of that interval times the part
+ * of the interval that lies below s.  Written term by term as the equation states it. */
+double oracle_latency_estimate(const double *k, const double *t, int n, double s) {
+    double est = t[0];
+    for (int i = 0; i + 1 < n; ++i) {
+        const double delta = s >= k[i] ? 1.0 : 0.0;                      /* Eq. (5) */
+        const double alpha = (t[i + 1] - t[i]) / (k[i + 1] - k[i]);      /* Eq. (6) */
+        const double whole = k[i + 1] - k[i], part = s - k[i];
+        est += delta * alpha * (whole < part ? whole : part);            /* Eq. (4) */
+    }
+    return est;
+}
+
+/* Section 3.3, Eq. (2): tau plus the estimates of the L layers.  Layer l owns the n[l]
+ * knots that start at k[first[l]], t[first[l]] (first[l] = n[0] + ... + n[l-1]) and has
+ * s[l] non-zero weights. */
+double oracle_network_latency(double tau, const double *k, const double *t, const int *n, int L,
+                              const double *s) {
+    double total = tau;
+    int first = 0;
+    for (int l = 0; l < L; ++l) {
+        total += oracle_latency_estimate(k + first, t + first, n[l], s[l]);
+        first += n[l];
+    }
+    return total;
 }
 
 int oracle_max_threads(void) {
