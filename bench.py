@@ -252,6 +252,70 @@ def report(kind, alcs, workloads, torch, np):
             tu += u
             pr("| %s | bias + shortcut | %.1f | %.1f | %.2f | %.0f | %.1e |" % (L.name, f, u, u / f, by / f / 1e3, diff))
         pr("| MobileNetV2-shaped projections with a shortcut, batch 128 | | %.0f | %.0f | %.2f | | |" % (tf, tu, tu / tf))
+    elif kind == "latency":
+        # Section 3.3 of the paper on this GPU: time every layer at block densities 0, 0.1, ..., 1
+        # (eleven runs per layer), interpolate linearly in the number of non-zero weights
+        # (alcs_latency_estimate / alcs_network_latency), and compare estimate and measurement on
+        # randomly drawn sparse networks.
+        def layer_timer(L, seed):
+            rng = np.random.Generator(np.random.PCG64(seed))
+            W = rng.standard_normal(size=(L.Cout, L.Cin, L.k, L.k), dtype=np.float32) * np.float32(L.w_std)
+            X = torch.from_numpy(workloads.draw_x((L.N, L.Cin, L.H, L.W), L.x_dist, rng)).cuda()
+            R = max(2, min(8, int(600e6 // (L.x_bytes() + L.y_bytes())) + 1))
+            Xr = [X] + [X.clone() for _ in range(R - 1)]
+            Yr = [torch.empty((L.N, L.Cout, L.Ho, L.Wo), dtype=torch.float32, device="cuda") for _ in range(R)]
+            iters = max(7, R + 1)
+            ev = alcs.HipEvents(iters)
+
+            def timed(density):
+                mask = workloads.mask_exact(L.G, L.Cin, L.k, 1.0 - density, rng, tap_shared=L.tap_shared)
+                p = alcs.alcs_pack_weights(W, mask, L.V)
+                alcs.alcs_sparse_conv(p, Xr[0], None, Yr[0], stride=L.stride)
+                for i in range(iters):
+                    alcs.alcs_sparse_conv(p, Xr[(i + 1) % R], None, Yr[(i + 1) % R], stride=L.stride,
+                                          events=ev.pairs[i])
+                torch.cuda.synchronize()
+                t = float(np.median([ev.elapsed_us(i) for i in range(iters)]))
+                nnz = float(p.nnzb) * L.V
+                p.free()
+                return nnz, t
+            return timed, ev
+
+        nets = (("13 MobileNetV1-shaped pointwise convs, batch 32", workloads.mobilenet_v1_pointwise(32, 0.0), 2, 100),
+                ("ResNet-50-shaped bottleneck convs (1x1 and 3x3), batch 16", workloads.resnet50_bottlenecks(16, 0.0), 3, 40))
+        for title, layers, cfg, n_models in nets:
+            pr("\n## %s\n" % title)
+            pr("Run time in us at block density 0, 0.1, ..., 1.0 (kernel time stamps, median of 7 or more cold launches):\n")
+            pr("| layer | shape | " + " | ".join("%.1f" % (0.1 * j) for j in range(11)) + " |")
+            pr("|---|---|" + "---|" * 11)
+            draw = np.random.Generator(np.random.PCG64(workloads.seed_for(cfg, 900)))
+            dens = draw.random((n_models, len(layers)))          # every layer's density, per sampled network
+            real = np.zeros(n_models)
+            est = np.zeros(n_models)
+            layer_err = []
+            for li, L in enumerate(layers):
+                timed, ev = layer_timer(L, workloads.seed_for(cfg, 500 + li))
+                pts = [timed(0.1 * j) for j in range(11)]
+                k = [a for a, _ in pts]
+                t = [b for _, b in pts]
+                pr("| %s | %d->%d %dx%d/%d @%d | " % (L.name, L.Cin, L.Cout, L.k, L.k, L.stride, L.H) +
+                   " | ".join("%.1f" % v for v in t) + " |")
+                errs = []
+                for m in range(n_models):
+                    nnz, tm = timed(float(dens[m, li]))
+                    te = alcs.alcs_latency_estimate(k, t, nnz)
+                    real[m] += tm * L.repeats
+                    est[m] += te * L.repeats
+                    errs.append(abs(te - tm) / tm)
+                layer_err.append((L.name, float(np.mean(errs)), float(np.max(errs))))
+                ev.close()
+            rel = np.abs(est - real) / real
+            pr("\n%d sampled networks (every layer's block density drawn from U(0, 1), fresh random mask):"
+               " measured total %.0f-%.0f us; estimate off by %.2f %% on average, %.2f %% at most; "
+               "correlation %.5f." % (n_models, real.min(), real.max(), 100 * rel.mean(), 100 * rel.max(),
+                                      float(np.corrcoef(est, real)[0, 1])))
+            pr("Per layer, mean / largest relative error of the estimate: " +
+               ", ".join("%s %.1f / %.1f %%" % (n, 100 * a, 100 * b) for n, a, b in layer_err) + ".")
     elif kind == "paths":
         pr("| layer | MFMA us | FMA us | FMA / MFMA |")
         pr("|---|---|---|---|")
@@ -279,7 +343,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-batch", type=int, default=32)
     ap.add_argument("--layers-json", default=None, help="also write the per-layer table to this file")
-    ap.add_argument("--report", choices=["sweep", "resnet", "mbv2", "paths", "mbv1", "fused"], default=None,
+    ap.add_argument("--report", choices=["sweep", "resnet", "mbv2", "paths", "mbv1", "fused", "latency"], default=None,
                     help="instead of the benchmark line, print a per-layer table for another configuration: "
                          "the sparsity sweep with the same-GPU dense conv (config 4), the ResNet-50-shaped "
                          "bottleneck convs (config 3), the MobileNetV2-shaped pointwise convs for V in "

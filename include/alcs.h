@@ -207,6 +207,26 @@ int alcs_dense_conv(const float *W_dev, const float *X_dev, const float *bias_de
  */
 int alcs_set_tuning(const char *name, int value);
 
+/* Latency model (Section 3.3 of the paper).  A layer is timed at n numbers of non-zero weights
+ * k[0] < k[1] < ... < k[n-1] (the paper uses 0, 0.1 N, ..., N: eleven runs of
+ * alcs_sparse_conv_timed per layer), giving run times t[0..n-1] in any unit.
+ *
+ * alcs_latency_estimate: Eqs. (4)-(6) - the estimate for a layer with s non-zero weights,
+ *   t[0] plus, for every interval that s has reached, the interval's slope
+ *   (t[i+1]-t[i]) / (k[i+1]-k[i]) times the part of it below s: the piecewise-linear
+ *   interpolant of the measured points, t[0] for s <= k[0] and t[n-1] for s >= k[n-1].
+ * alcs_network_latency: Eq. (2) - tau (the run time of all layers that are not pruned, a
+ *   constant) plus the estimates of L layers.  Layer l owns the n_host[l] knots that start at
+ *   index n_host[0] + ... + n_host[l-1] of k_host / t_host and has s_host[l] non-zero weights.
+ *
+ * All pointers are host memory, read during the call only; results are written to
+ * *estimate_out / *latency_out.  ALCS_E_INVALID_ARG: null pointers, fewer than two knots,
+ * knots not strictly increasing, non-finite table entries or tau, NaN s.  No GPU is used. */
+int alcs_latency_estimate(const double *k_host, const double *t_host, int n, double s,
+                          double *estimate_out);
+int alcs_network_latency(double tau, const double *k_host, const double *t_host, const int *n_host,
+                         int L, const double *s_host, double *latency_out);
+
 /* What the last alcs_sparse_conv call of this thread launched: fills up to `cap`
  * ints {mode (1 = all input channels resident in LDS, 2 = chunked, 3 = 3x3,
  * 4 = persistent double-buffered), pv, waves, workgroups, lds_bytes, group_tiles,

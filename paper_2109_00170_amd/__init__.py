@@ -10,6 +10,8 @@ from ._binding import (  # noqa: F401
     Packed,
     alcs_dense_conv,
     alcs_last_launch,
+    alcs_latency_estimate,
+    alcs_network_latency,
     alcs_pack_weights,
     alcs_set_tuning,
     alcs_sparse_conv,

@@ -15,7 +15,7 @@ EXPORTS = [
     "alcs_strerror", "alcs_last_hip_error", "alcs_version", "alcs_pack_weights", "alcs_packed_info",
     "alcs_packed_on_device", "alcs_packed_export", "alcs_packed_selfcheck", "alcs_packed_free",
     "alcs_sparse_conv", "alcs_sparse_conv_timed", "alcs_sparse_conv_fused", "alcs_dense_conv", "alcs_set_tuning",
-    "alcs_last_launch",
+    "alcs_last_launch", "alcs_latency_estimate", "alcs_network_latency",
 ]
 
 
@@ -268,3 +268,44 @@ def alcs_last_launch() -> dict:
     keys = ["mode", "pv", "waves", "workgroups", "lds_bytes", "group_tiles", "chunk_channels", "path",
             "group_slots", "tile_width"]
     return {k: int(buf[i]) for i, k in enumerate(keys[:n])}
+
+
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def alcs_latency_estimate(k, t, s) -> float:
+    """Run time of a layer with ``s`` non-zero weights from times ``t`` measured at ``k``."""
+    k, t = _f64(k), _f64(t)
+    if k.ndim != 1 or k.shape != t.shape:
+        raise ValueError("k and t must be vectors of one length")
+    out = ctypes.c_double()
+    dp = ctypes.POINTER(ctypes.c_double)
+    rc = load_library().alcs_latency_estimate(k.ctypes.data_as(dp), t.ctypes.data_as(dp), int(k.size),
+                                              ctypes.c_double(float(s)), ctypes.byref(out))
+    if rc != 0:
+        raise AlcsError(rc, "alcs_latency_estimate")
+    return float(out.value)
+
+
+def alcs_network_latency(tau, tables, nnz) -> float:
+    """``tau`` plus the estimates of all layers; ``tables`` = [(k, t), ...], ``nnz`` per layer."""
+    if len(tables) != len(nnz):
+        raise ValueError("one table per layer")
+    ks = [_f64(k) for k, _ in tables]
+    ts = [_f64(t) for _, t in tables]
+    for k, t in zip(ks, ts):
+        if k.ndim != 1 or k.shape != t.shape:
+            raise ValueError("k and t must be vectors of one length")
+    n = np.array([k.size for k in ks], dtype=np.int32)
+    kk = _f64(np.concatenate(ks)) if ks else np.zeros(1)
+    tt = _f64(np.concatenate(ts)) if ts else np.zeros(1)
+    s = _f64(nnz) if len(nnz) else np.zeros(1)
+    out = ctypes.c_double()
+    dp = ctypes.POINTER(ctypes.c_double)
+    rc = load_library().alcs_network_latency(ctypes.c_double(float(tau)), kk.ctypes.data_as(dp),
+                                             tt.ctypes.data_as(dp), n.ctypes.data_as(ctypes.POINTER(ctypes.c_int)),
+                                             int(len(ks)), s.ctypes.data_as(dp), ctypes.byref(out))
+    if rc != 0:
+        raise AlcsError(rc, "alcs_network_latency")
+    return float(out.value)
