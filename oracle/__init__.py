@@ -116,6 +116,20 @@ def conv_fused(Wd, X, bias=None, residual=None, act=None, stride=1, nthreads=0):
     return Y
 
 
+def depthwise(D, X, bias=None, stride=1, act=None):
+    """Z = act(depthwise_conv(X; D) + bias): D is [C,k,k], one filter per channel."""
+    D, X, bias = _f32(D), _f32(X), _f32(bias)
+    C, k = D.shape[0], D.shape[1]
+    if D.shape != (C, k, k) or X.ndim != 4 or X.shape[1] != C:
+        raise ValueError("depthwise: D must be [C,k,k] and X [N,C,H,W]")
+    N, _, H, Wi = X.shape
+    Z = np.empty((N, C, out_size(H, k, stride), out_size(Wi, k, stride)), dtype=np.float32)
+    _check(_load().oracle_depthwise(_p(D, ctypes.c_float), _p(X, ctypes.c_float), _p(bias, ctypes.c_float),
+                                    _p(Z, ctypes.c_float), N, C, H, Wi, k, int(stride), ACTIVATIONS[act]),
+           "oracle_depthwise")
+    return Z
+
+
 def conv_at(Wd, X, flat_idx, bias=None, stride=1):
     """The same sum for selected flat indices of Y[N,Cout,Ho,Wo]."""
     Wd, X, bias = _f32(Wd), _f32(X), _f32(bias)

@@ -20,6 +20,10 @@
  *   - the element-wise layers after a convolution (ReLU, ReLU6, shortcut addition),
  *     the "other layers" behind the constant tau of Section 3.3, Eq. (2), folded into
  *     the convolution                                   -> oracle_conv_fused
+ *   - the depthwise 3x3 layer that precedes every pointwise convolution of the
+ *     MobileNet the paper prunes (Section 4; one filter per channel, the conv
+ *     equation of Section 3.2.2 with the sum over c reduced to the channel itself),
+ *     with its bias and activation                      -> oracle_depthwise
  *   - the latency model of Section 3.3: a layer's run time as a piecewise-linear
  *     function of its number of non-zero weights, Eqs. (4)-(6), and the network's
  *     run time as tau plus the sum over layers, Eq. (2)
@@ -156,6 +160,37 @@ int oracle_conv_fused(const float *Wd, const float *X, const float *bias, const 
             }
     }
     (void)nthreads;
+    return ORACLE_OK;
+}
+
+/* Depthwise convolution: channel c of the output sees only channel c of the input,
+ *   Z(c,h,w) = act(b(c) + sum_r sum_s D(c,r,s) I(c, h*stride + r - pad, w*stride + s - pad)),
+ * the convolution equation of Section 3.2.2 without the sum over input channels; zero
+ * padding pad = (k-1)/2, no kernel flip.  D is [C,k,k].  Sum in double, one rounding.
+ * It is the layer in front of each pointwise convolution of the MobileNet of Section 4. */
+int oracle_depthwise(const float *D, const float *X, const float *bias, float *Z, int N, int C,
+                     int H, int Wi, int k, int stride, int act) {
+    if (!D || !X || !Z || N < 0 || C <= 0 || H <= 0 || Wi <= 0) return ORACLE_BAD_ARG;
+    if (k <= 0 || (k % 2) == 0 || stride <= 0 || act < 0 || act > 2) return ORACLE_BAD_ARG;
+    int Ho = out_size(H, k, stride), Wo = out_size(Wi, k, stride);
+    if (Ho <= 0 || Wo <= 0) return ORACLE_BAD_ARG;
+    int pad = (k - 1) / 2;
+    for (int n = 0; n < N; ++n)
+        for (int c = 0; c < C; ++c)
+            for (int ho = 0; ho < Ho; ++ho)
+                for (int wo = 0; wo < Wo; ++wo) {
+                    double v = bias ? (double)bias[c] : 0.0;
+                    for (int r = 0; r < k; ++r)
+                        for (int q = 0; q < k; ++q) {
+                            int hi = ho * stride + r - pad, wi = wo * stride + q - pad;
+                            if (hi < 0 || hi >= H || wi < 0 || wi >= Wi) continue;
+                            v += (double)D[((size_t)c * k + r) * k + q] *
+                                 (double)X[(((size_t)n * C + c) * H + hi) * Wi + wi];
+                        }
+                    if (act >= 1 && v < 0.0) v = 0.0;
+                    if (act == 2 && v > 6.0) v = 6.0;
+                    Z[(((size_t)n * C + c) * Ho + ho) * Wo + wo] = (float)v;
+                }
     return ORACLE_OK;
 }
 
