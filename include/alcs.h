@@ -177,6 +177,39 @@ int alcs_sparse_conv_fused(const alcs_packed_t *Wp, const float *X_dev, const fl
                            int W, int kernel, int stride, int activation, void *stream);
 
 /*
+ * Depthwise 3x3 layer and the MobileNet block (the network pruned in Section 4 of the paper:
+ * every pointwise convolution is preceded by a depthwise 3x3 layer with its own bias and
+ * activation; they are among the layers behind the constant tau of Section 3.3, Eq. (2)).
+ *
+ * alcs_depthwise_conv:  Z[n,c,ho,wo] = act(bias[c] + sum_{r,s} D[c,r,s] *
+ *     X[n, c, ho*stride + r - 1, wo*stride + s - 1]),  zero outside the image, no kernel flip;
+ *     Ho = (H-1)/stride + 1, Wo = (W-1)/stride + 1.  dw_weights_dev is [C,3,3], X_dev [N,C,H,W],
+ *     Y_dev [N,C,Ho,Wo], bias_dev [C] or NULL: device memory, caller-owned, no aliasing.
+ *
+ * alcs_dw_sparse_conv_fused:  Y = act(conv1x1(Wp; Z) + bias + residual) with Z the depthwise
+ *     layer above applied to X_dev (dw_weights_dev, dw_bias_dev, dw_stride, dw_activation), in
+ *     one kernel: Z is produced tile by tile in on-chip memory and never written out.  Wp must
+ *     be a 1x1 handle with Cin inputs; X_dev is [N,Cin,H,W]; Y_dev and residual_dev (NULL or a
+ *     tensor of Y's shape, may be Y_dev itself) are [N,Cout,Ho,Wo].  workspace_dev is NULL or
+ *     [N,Cin,Ho,Wo] floats of scratch: handles whose input channels do not fit one on-chip
+ *     tile (more than 2559 input channels, or V < 4 with more than 639) are then run as the two
+ *     layers one after the other through the workspace; without one they return
+ *     ALCS_E_UNSUPPORTED.
+ *
+ * Both: stride in {1, 2} (else ALCS_E_UNSUPPORTED); activations are alcs_activation values
+ * (else ALCS_E_INVALID_ARG); X_dev / Y_dev / residual_dev 16-byte aligned for the fused call;
+ * asynchronous on `stream`, nothing allocated, N = 0 is a no-op.
+ */
+int alcs_depthwise_conv(const float *dw_weights_dev, const float *X_dev, const float *bias_dev,
+                        float *Y_dev, int N, int C, int H, int W, int stride, int activation,
+                        void *stream);
+int alcs_dw_sparse_conv_fused(const alcs_packed_t *Wp, const float *dw_weights_dev,
+                              const float *dw_bias_dev, int dw_stride, int dw_activation,
+                              const float *X_dev, const float *bias_dev, const float *residual_dev,
+                              float *Y_dev, float *workspace_dev, int N, int Cin, int Cout, int H,
+                              int W, int activation, void *stream);
+
+/*
  * Dense convolution with the same conventions: the sparsity-0 case of the
  * operation above and the same-GPU baseline (the role the dense models play in the
  * paper's Section 4.1 timing protocol).

@@ -9,6 +9,8 @@ from ._binding import (  # noqa: F401
     HipEvents,
     Packed,
     alcs_dense_conv,
+    alcs_depthwise_conv,
+    alcs_dw_sparse_conv_fused,
     alcs_last_launch,
     alcs_latency_estimate,
     alcs_network_latency,

@@ -15,6 +15,7 @@ EXPORTS = [
     "alcs_strerror", "alcs_last_hip_error", "alcs_version", "alcs_pack_weights", "alcs_packed_info",
     "alcs_packed_on_device", "alcs_packed_export", "alcs_packed_selfcheck", "alcs_packed_free",
     "alcs_sparse_conv", "alcs_sparse_conv_timed", "alcs_sparse_conv_fused", "alcs_dense_conv", "alcs_set_tuning",
+    "alcs_depthwise_conv", "alcs_dw_sparse_conv_fused",
     "alcs_last_launch", "alcs_latency_estimate", "alcs_network_latency",
 ]
 
@@ -254,6 +255,49 @@ def alcs_dense_conv(W_dev, X, bias, Y, stride: int = 1, stream=None) -> None:
                                         _stream_ptr(stream))
     if rc != 0:
         raise AlcsError(rc, "alcs_dense_conv")
+
+
+def _act(activation) -> int:
+    return int(activation if isinstance(activation, int) else ACTIVATIONS[activation])
+
+
+def alcs_depthwise_conv(D_dev, X, bias, Y, stride: int = 1, activation=None, stream=None) -> None:
+    """Y = act(depthwise3x3(X; D_dev) + bias): D_dev [C,3,3] on the device."""
+    N, C, H, W = X.shape
+    if tuple(D_dev.shape) != (C, 3, 3):
+        raise ValueError("depthwise weights must have shape %r" % ((C, 3, 3),))
+    exp = (N, C, out_size(H, 3, stride), out_size(W, 3, stride))
+    if tuple(Y.shape) != exp:
+        raise ValueError("Y must have shape %r, got %r" % (exp, tuple(Y.shape)))
+    rc = load_library().alcs_depthwise_conv(_dev_ptr(D_dev, "dw_weights"), _dev_ptr(X, "X"), _dev_ptr(bias, "bias"),
+                                            _dev_ptr(Y, "Y"), N, C, H, W, int(stride), _act(activation),
+                                            _stream_ptr(stream))
+    if rc != 0:
+        raise AlcsError(rc, "alcs_depthwise_conv")
+
+
+def alcs_dw_sparse_conv_fused(packed: Packed, D_dev, dw_bias, X, bias, residual, Y, dw_stride: int = 1,
+                              dw_activation=None, activation=None, workspace=None, stream=None) -> None:
+    """Y = act(conv1x1(packed; dw_act(depthwise3x3(X; D_dev) + dw_bias)) + bias + residual) in one kernel;
+    ``workspace`` ([N,Cin,Ho,Wo] or None) is used only by layouts the fused kernels do not cover."""
+    N, Cin, H, W = X.shape
+    if tuple(D_dev.shape) != (Cin, 3, 3):
+        raise ValueError("depthwise weights must have shape %r" % ((Cin, 3, 3),))
+    Ho, Wo = out_size(H, 3, dw_stride), out_size(W, 3, dw_stride)
+    exp = (N, packed.Cout, Ho, Wo)
+    if tuple(Y.shape) != exp:
+        raise ValueError("Y must have shape %r, got %r" % (exp, tuple(Y.shape)))
+    if residual is not None and tuple(residual.shape) != exp:
+        raise ValueError("residual must have shape %r, got %r" % (exp, tuple(residual.shape)))
+    if workspace is not None and tuple(workspace.shape) != (N, Cin, Ho, Wo):
+        raise ValueError("workspace must have shape %r" % ((N, Cin, Ho, Wo),))
+    rc = load_library().alcs_dw_sparse_conv_fused(
+        packed.handle, _dev_ptr(D_dev, "dw_weights"), _dev_ptr(dw_bias, "dw_bias"), int(dw_stride),
+        _act(dw_activation), _dev_ptr(X, "X"), _dev_ptr(bias, "bias"), _dev_ptr(residual, "residual"),
+        _dev_ptr(Y, "Y"), _dev_ptr(workspace, "workspace"), N, Cin, packed.Cout, H, W, _act(activation),
+        _stream_ptr(stream))
+    if rc != 0:
+        raise AlcsError(rc, "alcs_dw_sparse_conv_fused")
 
 
 def alcs_set_tuning(name: str, value: int) -> None:

@@ -36,16 +36,30 @@
 // alcs_sparse_fused.hip defines ALCS_FUSED_EPILOGUE and includes this file: the same
 // kernels with the epilogue compiled in, in namespace alcs::fused, behind
 // alcs_sparse_conv_fused.
+//
+// alcs_sparse_dw.hip defines ALCS_DW_STAGE as well: the resident 1x1 kernels once more, in
+// namespace alcs::dwpw, with the staging of the input tile replaced by the depthwise 3x3
+// layer that precedes the pointwise convolution (its output goes straight into LDS and
+// never to memory), behind alcs_dw_sparse_conv_fused.
 #ifndef ALCS_FUSED_EPILOGUE
 #define ALCS_FUSED_EPILOGUE 0
 #endif
+#ifndef ALCS_DW_STAGE
+#define ALCS_DW_STAGE 0
+#endif
+#if ALCS_DW_STAGE && !ALCS_FUSED_EPILOGUE
+#error "the depthwise stage comes with the fused epilogue"
+#endif
 
 namespace alcs {
-#if ALCS_FUSED_EPILOGUE
+#if ALCS_DW_STAGE
+namespace dwpw {
+#elif ALCS_FUSED_EPILOGUE
 namespace fused {
 #endif
 
 constexpr bool kFused = ALCS_FUSED_EPILOGUE != 0;
+constexpr bool kDw = ALCS_DW_STAGE != 0;
 
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef float f2 __attribute__((ext_vector_type(2)));
@@ -72,6 +86,13 @@ struct ConvArgs {
     int nblk;           // padded blocks (= number of row selectors)
     int act;    // fused epilogue: 0 none, 1 max(., 0), 2 min(max(., 0), 6)
     int debug;  // measurement only: bit 0 skips staging, bit 1 the multiply, bit 2 the stores
+#if ALCS_DW_STAGE
+    // Depthwise stage: X is the depthwise layer's input [N, Cin, H, W]; its output
+    // [N, Cin, Ho, Wo] is what the pointwise convolution (stride 1) multiplies.
+    const float *dw_w;     // [Cin, 3, 3]
+    const float *dw_bias;  // [Cin] or null
+    int dw_stride, dw_act;
+#endif
 };
 
 // The element-wise tail of the fused epilogue (the plain convolution passes act = 0).
@@ -411,6 +432,74 @@ __device__ __forceinline__ void stage_pw(const ConvArgs &a, float *lds, int q0, 
     }
 }
 
+#if ALCS_DW_STAGE
+// The depthwise 3x3 layer (zero padding 1, stride 1 or 2, bias, activation) evaluated for
+// the pixel tile [q0, q0 + TP) of its flattened (n, ho, wo) output axis, every channel c
+// into LDS row c: the tile the pointwise convolution multiplies is produced in place and
+// never visits memory.  A thread owns one pixel of the tile and every (blockDim / TP)-th
+// channel; the nine taps are nine loads that neighbouring lanes and the next rows share
+// through the vector cache.  With TP >= 64 a wavefront works on one channel at a time, so
+// the filter and the bias come through scalar loads.
+template <int TP>
+__device__ __forceinline__ void stage_dw(const ConvArgs &a, float *lds, int q0) {
+    const int tid = threadIdx.x, nt = blockDim.x;
+    // A pass covers `span` pixels of the tile with nt / span channels side by side; a
+    // workgroup with fewer threads than the tile has pixels takes several passes.
+    const int span = nt < TP ? nt : TP;
+    const int rpp = nt / span;
+    int r0 = tid / span;
+    if constexpr (TP >= 64) r0 = __builtin_amdgcn_readfirstlane(r0);  // span is a multiple of 64 then
+    if (r0 >= rpp) return;  // threads beyond the last full set of channels
+    const auto wts = as_const(a.dw_w);
+    const auto bs = as_const(a.dw_bias);
+    for (int e = tid - r0 * span; e < TP; e += span) {
+        const int q = q0 + e;
+        const bool valid = q < a.NP;
+        const int n = valid ? q / a.P : 0;
+        const int po = valid ? q - n * a.P : 0;
+        const int ho = po / a.Wo, wo = po - ho * a.Wo;
+        const int hi0 = ho * a.dw_stride - 1, wi0 = wo * a.dw_stride - 1;
+        bool ok[9];
+        int off[9];
+#pragma unroll
+        for (int r = 0; r < 3; ++r)
+#pragma unroll
+            for (int t = 0; t < 3; ++t) {
+                const int hi = hi0 + r, wi = wi0 + t;
+                ok[r * 3 + t] = valid && hi >= 0 && hi < a.H && wi >= 0 && wi < a.W;
+                off[r * 3 + t] = ok[r * 3 + t] ? hi * a.W + wi : 0;
+            }
+        const float *src = a.X + (size_t)n * a.Cin * a.Pin;
+        auto one = [&](int c, float (&x)[9]) {
+            const float *xc = src + (size_t)c * a.Pin;
+#pragma unroll
+            for (int t = 0; t < 9; ++t) x[t] = ok[t] ? xc[off[t]] : 0.f;
+        };
+        auto finish = [&](int c, const float (&x)[9]) {
+            float acc = a.dw_bias ? bs[c] : 0.f;
+#pragma unroll
+            for (int t = 0; t < 9; ++t) acc = fmaf(wts[c * 9 + t], x[t], acc);
+            if (a.dw_act >= 1) acc = fmaxf(acc, 0.f);
+            if (a.dw_act == 2) acc = fminf(acc, 6.f);
+            lds[c * TP + e] = valid ? acc : 0.f;
+        };
+        int c = r0;
+        for (; c + rpp < a.Cin; c += 2 * rpp) {  // two channels' loads in flight
+            float x0[9], x1[9];
+            one(c, x0);
+            one(c + rpp, x1);
+            finish(c, x0);
+            finish(c + rpp, x1);
+        }
+        if (c < a.Cin) {
+            float x0[9];
+            one(c, x0);
+            finish(c, x0);
+        }
+    }
+}
+#endif
+
 // Where a lane's PV pixels go in Y (offset of channel 0; add ch * P).
 template <int PV>
 struct PixOut {
@@ -595,7 +684,11 @@ __device__ __forceinline__ void pw_resident_body(const ConvArgs &a) {
         if (nth(1) < ng) w1 = load_work(a.work, g_begin + nth(1));
     }
 
+#if ALCS_DW_STAGE
+    if (!(a.debug & 1)) stage_dw<TP>(a, lds, q0);
+#else
     if (!(a.debug & 1)) stage_pw<TP, VEC>(a, lds, q0, 0, a.Cin);
+#endif
     for (int t = tid; t < TP; t += blockDim.x) lds[a.KC * TP + t] = 0.f;  // the all-zero row
     __syncthreads();
     if (!any) return;
@@ -938,7 +1031,7 @@ typedef void (*kern_t)(const ConvArgs);
 
 template <int V, bool MF>
 static kern_t pick_resident(int pv, bool vec, int gs, bool res = false) {
-    if constexpr (kFused && MF && V <= 8) {
+    if constexpr (kFused && !kDw && MF && V <= 8) {
         // with a residual: the variants that fetch it ahead of the multiply (vector form, one
         // group per wavefront, at most 16 values per lane)
         if (res && vec && gs == 1) {
@@ -1025,30 +1118,48 @@ static int set_lds_limit(kern_t k, int lds) {
     return ALCS_OK;
 }
 
-#if ALCS_FUSED_EPILOGUE
+#if ALCS_DW_STAGE
+}  // namespace dwpw
+#elif ALCS_FUSED_EPILOGUE
 }  // namespace fused
 #endif
 }  // namespace alcs
 
 using namespace alcs;
-#if ALCS_FUSED_EPILOGUE
+#if ALCS_DW_STAGE
+using namespace alcs::dwpw;
+#elif ALCS_FUSED_EPILOGUE
 using namespace alcs::fused;
 #endif
 
+namespace {
+// The depthwise layer in front of the pointwise convolution (depthwise build only).
+struct DwStage {
+    const float *w, *bias;
+    int stride, act;
+};
+}  // namespace
+
+// With a depthwise stage, H x W is the depthwise layer's input, `stride` its stride, and the
+// 1x1 convolution runs at stride 1 over the depthwise layer's output.
 static int launch_sparse(const alcs_packed_t *Wp, const float *X_dev, const float *bias_dev,
                          float *Y_dev, int N, int Cin, int Cout, int H, int W, int kernel,
                          int stride, void *stream, hipEvent_t ev_start, hipEvent_t ev_stop,
-                         const float *residual_dev = nullptr, int activation = 0) {
+                         const float *residual_dev = nullptr, int activation = 0,
+                         const DwStage *dw = nullptr) {
     if (!Wp || N < 0 || H <= 0 || W <= 0) return ALCS_E_INVALID_ARG;
     if (Cin != Wp->Cin || Cout != Wp->Cout || kernel != Wp->k) return ALCS_E_INVALID_ARG;
     if (stride != 1 && stride != 2) return ALCS_E_UNSUPPORTED;
+    if (kDw != (dw != nullptr)) return ALCS_E_INVALID_ARG;
+    if (dw && (kernel != 1 || !dw->w || dw->act < 0 || dw->act > 2)) return ALCS_E_INVALID_ARG;
     if (N == 0) return ALCS_OK;
     if (!X_dev || !Y_dev) return ALCS_E_INVALID_ARG;
     if (((uintptr_t)X_dev | (uintptr_t)Y_dev | (uintptr_t)residual_dev) & 15) return ALCS_E_INVALID_ARG;
     if (activation < 0 || activation > 2) return ALCS_E_INVALID_ARG;
-    const int pad = (kernel - 1) / 2;
-    const int Ho = (H + 2 * pad - kernel) / stride + 1, Wo = (W + 2 * pad - kernel) / stride + 1;
+    const int pad = dw ? 1 : (kernel - 1) / 2, kin = dw ? 3 : kernel;
+    const int Ho = (H + 2 * pad - kin) / stride + 1, Wo = (W + 2 * pad - kin) / stride + 1;
     if (Ho <= 0 || Wo <= 0) return ALCS_E_INVALID_ARG;
+    if (dw) stride = 1;  // of the pointwise convolution; the depthwise stride stays in dw->stride
     const long long P = (long long)Ho * Wo, Pin = (long long)H * W;
     if (P > INT32_MAX || Pin > INT32_MAX) return ALCS_E_UNSUPPORTED;
     if ((long double)N * Cin * Pin >= 9e18L || (long double)N * Cout * P >= 9e18L) return ALCS_E_UNSUPPORTED;
@@ -1073,6 +1184,9 @@ static int launch_sparse(const alcs_packed_t *Wp, const float *X_dev, const floa
     a.NP = (int)((long long)N * P);
     a.G = L.nbundles; a.nchunks = L.nchunks; a.KC = L.KC;  // kernels count bundles of GS groups
     a.debug = T.debug;
+#if ALCS_DW_STAGE
+    a.dw_w = dw->w; a.dw_bias = dw->bias; a.dw_stride = dw->stride; a.dw_act = dw->act;
+#endif
 
     bool mfma = V >= 4;
     if (V == 4 && T.path == 1) mfma = false;
@@ -1085,6 +1199,7 @@ static int launch_sparse(const alcs_packed_t *Wp, const float *X_dev, const floa
         // there are enough pixels to give every compute unit several tiles
         bool stream_ok = false;
         int s_pv = 1, s_lds = 0, s_nw = 8, s_nwg = 0;
+#if !ALCS_DW_STAGE
         if (L.nchunks == 1 && L.GS == 1 && vec && mfma && T.path == 4) {
             const long long wbytes = (long long)L.planes * L.ncol * 16 + (long long)L.ncol * 4;
             for (int cand = 4; cand >= 1 && !stream_ok; cand >>= 1) {
@@ -1119,7 +1234,11 @@ static int launch_sparse(const alcs_packed_t *Wp, const float *X_dev, const floa
                 case 8: kern = pv == 4 ? k_pw_stream<8, 4, 8> : pv == 2 ? k_pw_stream<8, 2, 8> : k_pw_stream<8, 1, 8>; break;
                 case 16: kern = pv == 4 ? k_pw_stream<16, 4, 8> : pv == 2 ? k_pw_stream<16, 2, 8> : k_pw_stream<16, 1, 8>; break;
             }
-        } else if (L.nchunks == 1) {
+        } else
+#else
+        (void)s_pv; (void)s_lds; (void)s_nw; (void)s_nwg; (void)stream_ok;
+#endif
+        if (L.nchunks == 1) {
             mode = 1;
             // Launch shape, from sweeps over the MobileNet/ResNet-shaped layers on MI355X:
             // pixels per lane - the widest tile whose Cin+1 rows stay below ~68 KB (two
@@ -1176,6 +1295,9 @@ static int launch_sparse(const alcs_packed_t *Wp, const float *X_dev, const floa
                 case 16: kern = pick_resident<16, true>(pv, vec, GS, a.residual != nullptr); break;
             }
         } else {
+#if ALCS_DW_STAGE
+            return ALCS_E_UNSUPPORTED;  // the depthwise stage fills a resident tile only
+#else
             mode = 2;
             pv = 1;
             if (vec && (T.pv == 2 || T.pv == 4)) pv = T.pv;
@@ -1195,8 +1317,12 @@ static int launch_sparse(const alcs_packed_t *Wp, const float *X_dev, const floa
                 case 8: kern = pick_chunked<8, true>(pv, vec, ug); break;
                 case 16: kern = pick_chunked<16, true>(pv, vec, ug); break;
             }
+#endif
         }
     } else {
+#if ALCS_DW_STAGE
+        return ALCS_E_UNSUPPORTED;
+#else
         mode = 3;
         ti = pick_tile3(Ho, Wo, T.tile_w);
         a.off = Wp->dev.off[off_table3(stride, ti)];
@@ -1216,7 +1342,9 @@ static int launch_sparse(const alcs_packed_t *Wp, const float *X_dev, const floa
             case 8: kern = pick_conv3<8, true>(stride, ti, ug); break;
             case 16: kern = pick_conv3<16, true>(stride, ti, ug); break;
         }
+#endif
     }
+    (void)ug; (void)ti; (void)G;
     if (!kern || lds > kMaxLds) return ALCS_E_UNSUPPORTED;
     const long long total = (long long)a.npt * a.ngt;
     if (total > (1LL << 30)) return ALCS_E_UNSUPPORTED;
@@ -1240,7 +1368,29 @@ static int launch_sparse(const alcs_packed_t *Wp, const float *X_dev, const floa
     return ALCS_OK;
 }
 
-#if !ALCS_FUSED_EPILOGUE
+#if ALCS_DW_STAGE
+extern "C" int alcs_dw_sparse_conv_fused(const alcs_packed_t *Wp, const float *dw_weights_dev,
+                                         const float *dw_bias_dev, int dw_stride, int dw_activation,
+                                         const float *X_dev, const float *bias_dev, const float *residual_dev,
+                                         float *Y_dev, float *workspace_dev, int N, int Cin, int Cout, int H,
+                                         int W, int activation, void *stream) {
+    if (!dw_weights_dev || (dw_stride != 1 && dw_stride != 2)) return ALCS_E_INVALID_ARG;
+    if (dw_activation < 0 || dw_activation > 2 || activation < 0 || activation > 2) return ALCS_E_INVALID_ARG;
+    const DwStage dw{dw_weights_dev, dw_bias_dev, dw_stride, dw_activation};
+    const int rc = launch_sparse(Wp, X_dev, bias_dev, Y_dev, N, Cin, Cout, H, W, 1, dw_stride, stream, nullptr,
+                                 nullptr, residual_dev, activation, &dw);
+    if (rc != ALCS_E_UNSUPPORTED || !workspace_dev) return rc;
+    // Layouts the resident kernels do not cover (input channels streamed in chunks): the two
+    // layers one after the other, the intermediate tensor in the caller's workspace.
+    const int rc1 = alcs_depthwise_conv(dw_weights_dev, X_dev, dw_bias_dev, workspace_dev, N, Cin, H, W,
+                                        dw_stride, dw_activation, stream);
+    if (rc1 != ALCS_OK) return rc1;
+    const int Hd = (H - 1) / dw_stride + 1, Wd = (W - 1) / dw_stride + 1;
+    return alcs_sparse_conv_fused(Wp, workspace_dev, bias_dev, residual_dev, Y_dev, N, Cin, Cout, Hd, Wd, 1, 1,
+                                  activation, stream);
+}
+
+#elif !ALCS_FUSED_EPILOGUE
 extern "C" int alcs_sparse_conv(const alcs_packed_t *Wp, const float *X_dev, const float *bias_dev,
                                 float *Y_dev, int N, int Cin, int Cout, int H, int W, int kernel,
                                 int stride, void *stream) {
