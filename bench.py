@@ -252,6 +252,75 @@ def report(kind, alcs, workloads, torch, np):
             tu += u
             pr("| %s | bias + shortcut | %.1f | %.1f | %.2f | %.0f | %.1e |" % (L.name, f, u, u / f, by / f / 1e3, diff))
         pr("| MobileNetV2-shaped projections with a shortcut, batch 128 | | %.0f | %.0f | %.2f | | |" % (tf, tu, tu / tf))
+    elif kind == "block":
+        # depthwise 3x3 + bias + ReLU -> sparse pointwise + bias + ReLU: one kernel against two
+        def one(L, dws, seed):
+            d = workloads.make_layer(L, seed, with_bias=True)
+            p = alcs.alcs_pack_weights(d.W, d.mask, L.V)
+            rng = np.random.Generator(np.random.PCG64(seed + 17))
+            Hin, Win = L.H * dws, L.W * dws
+            D = torch.from_numpy((rng.standard_normal((L.Cin, 3, 3)) * 0.3).astype(np.float32)).cuda()
+            b1 = torch.from_numpy(rng.standard_normal(L.Cin).astype(np.float32)).cuda()
+            b2 = torch.from_numpy(d.bias).cuda()
+            xin = 4 * L.N * L.Cin * Hin * Win
+            R = max(2, min(8, int(600e6 // (xin + L.x_bytes() + L.y_bytes())) + 1))
+            X0 = torch.from_numpy(workloads.draw_x((L.N, L.Cin, Hin, Win), "relu", rng)).cuda()
+            Xr = [X0] + [X0.clone() for _ in range(R - 1)]
+            Zr = [torch.empty((L.N, L.Cin, L.H, L.W), dtype=torch.float32, device="cuda") for _ in range(R)]
+            Yr = [torch.empty((L.N, L.Cout, L.H, L.W), dtype=torch.float32, device="cuda") for _ in range(R)]
+
+            def fused(i):
+                alcs.alcs_dw_sparse_conv_fused(p, D, b1, Xr[i % R], b2, None, Yr[i % R], dw_stride=dws,
+                                               dw_activation="relu", activation="relu")
+
+            def two(i):
+                alcs.alcs_depthwise_conv(D, Xr[i % R], b1, Zr[i % R], stride=dws, activation="relu")
+                alcs.alcs_sparse_conv_fused(p, Zr[i % R], b2, None, Yr[i % R], activation="relu")
+
+            def dw_only(i):
+                alcs.alcs_depthwise_conv(D, Xr[i % R], b1, Zr[i % R], stride=dws, activation="relu")
+
+            def pw_only(i):
+                alcs.alcs_sparse_conv_fused(p, Zr[i % R], b2, None, Yr[i % R], activation="relu")
+
+            res = []
+            for fn in (fused, two, dw_only, pw_only):
+                for i in range(3):
+                    fn(i)
+                torch.cuda.synchronize()
+                n = 3 * R
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for i in range(n):
+                    fn(i)
+                e1.record()
+                torch.cuda.synchronize()
+                res.append(e0.elapsed_time(e1) * 1e3 / n)
+            fused(0)
+            info = alcs.alcs_last_launch()
+            yf = Yr[0].clone()
+            two(0)
+            torch.cuda.synchronize()
+            diff = float((yf - Yr[0]).abs().max() / Yr[0].abs().max().clamp_min(1e-30))
+            by_f = xin + L.y_bytes()
+            by_u = xin + 2 * L.x_bytes() + L.y_bytes()
+            p.free()
+            return res, by_f, by_u, diff, info
+
+        for N in (32, 1):
+            pr("\nbatch %d\n" % N)
+            pr("| block | depthwise | pointwise | one kernel us | two kernels us | ratio | depthwise alone us | pointwise alone us | "
+               "one kernel eff GB/s | bytes saved | max diff | launch |")
+            pr("|---|---|---|---|---|---|---|---|---|---|---|---|")
+            tf = tu = 0.0
+            for i, (L, dws) in enumerate(workloads.mobilenet_v1_blocks(N, 0.9)):
+                (f, u, t_dw, t_pw), by_f, by_u, diff, info = one(L, dws, workloads.seed_for(2, 300 + i))
+                tf += f
+                tu += u
+                pr("| %d | %d ch 3x3/%d @%d | %d->%d @%d | %.1f | %.1f | %.2f | %.1f | %.1f | %.0f | %.0f %% | %.1e | pv%d w%d wg%d |" %
+                   (i + 1, L.Cin, dws, L.H * dws, L.Cin, L.Cout, L.H, f, u, u / f, t_dw, t_pw, by_f / f / 1e3,
+                    100.0 * (by_u - by_f) / by_u, diff, info["pv"], info["waves"], info["workgroups"]))
+            pr("| 13 MobileNetV1-shaped blocks, 90 %% block sparsity | | | %.0f | %.0f | %.2f | | | | | | |" % (tf, tu, tu / tf))
     elif kind == "latency":
         # Section 3.3 of the paper on this GPU: time every layer at block densities 0, 0.1, ..., 1
         # (eleven runs per layer), interpolate linearly in the number of non-zero weights
@@ -343,7 +412,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-batch", type=int, default=32)
     ap.add_argument("--layers-json", default=None, help="also write the per-layer table to this file")
-    ap.add_argument("--report", choices=["sweep", "resnet", "mbv2", "paths", "mbv1", "fused", "latency"], default=None,
+    ap.add_argument("--report", choices=["sweep", "resnet", "mbv2", "paths", "mbv1", "fused", "latency", "block"], default=None,
                     help="instead of the benchmark line, print a per-layer table for another configuration: "
                          "the sparsity sweep with the same-GPU dense conv (config 4), the ResNet-50-shaped "
                          "bottleneck convs (config 3), the MobileNetV2-shaped pointwise convs for V in "

@@ -192,9 +192,9 @@ int alcs_sparse_conv_fused(const alcs_packed_t *Wp, const float *X_dev, const fl
  *     be a 1x1 handle with Cin inputs; X_dev is [N,Cin,H,W]; Y_dev and residual_dev (NULL or a
  *     tensor of Y's shape, may be Y_dev itself) are [N,Cout,Ho,Wo].  workspace_dev is NULL or
  *     [N,Cin,Ho,Wo] floats of scratch: handles whose input channels do not fit one on-chip
- *     tile (more than 2559 input channels, or V < 4 with more than 639) are then run as the two
- *     layers one after the other through the workspace; without one they return
- *     ALCS_E_UNSUPPORTED.
+ *     tile (more than 2559 input channels, or V < 4 with more than 639), and inputs of more than
+ *     about 10^9 elements per image, are then run as the two layers one after the other through
+ *     the workspace; without one they return ALCS_E_UNSUPPORTED.
  *
  * Both: stride in {1, 2} (else ALCS_E_UNSUPPORTED); activations are alcs_activation values
  * (else ALCS_E_INVALID_ARG); X_dev / Y_dev / residual_dev 16-byte aligned for the fused call;
@@ -230,7 +230,9 @@ int alcs_dense_conv(const float *W_dev, const float *X_dev, const float *bias_de
  *     "tile_width"      output-tile width of the 3x3 kernel: 8, 16 or 32 (tile height 64/width)
  *     "debug"           measurement only, results become meaningless: bit 0 skips input
  *                       staging, bit 1 the multiply, bit 2 the output stores, bit 3
- *                       makes the kernel return at once
+ *                       makes the kernel return at once; bit 4 (results unchanged) makes
+ *                       the depthwise stage of alcs_dw_sparse_conv_fused load all nine
+ *                       taps of a pixel itself instead of sharing them between lanes
  *   read by alcs_pack_weights (they shape the device layout of handles packed later):
  *     "chunk_channels"  input channels per LDS chunk (forces the chunked kernels)
  *     "group_slots"     output-channel groups multiplied per wavefront: 1, 2 or 4

@@ -3,13 +3,14 @@
 // the MobileNet pruned in Section 4 of arXiv 2109.00170.  Stand-alone form: the unfused
 // reference for alcs_dw_sparse_conv_fused and its fallback for layouts the fused kernels do
 // not cover.  The layer moves each element once (one read, one write) and does 9 multiply-adds
-// per output: a streaming kernel, one thread per output element of the flattened
-// [N*C, Ho*Wo] tensor, the nine taps served by the vector cache.
+// per output: a streaming kernel; a wavefront takes 64 consecutive pixels of a few planes and
+// neighbouring lanes share taps (alcs_dw_taps.h).
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
 
 #include "alcs_internal.h"
+#include "alcs_dw_taps.h"
 
 namespace alcs {
 
@@ -18,35 +19,52 @@ struct DwArgs {
     const float *X;     // [N, C, H, W]
     const float *bias;  // [C] or null
     float *Z;           // [N, C, Ho, Wo]
-    long long total;    // N * C * Ho * Wo
+    long long planes;   // N * C
+    int nchunks;        // 64-pixel chunks per plane
     int C, H, W, Ho, Wo, P, Pin, stride, act;
 };
 
+constexpr int kPlanesPerWave = 8;
+
+// A wavefront owns 64 consecutive output pixels of kPlanesPerWave (n, c) planes: the pixel
+// geometry (row / column, border flags, tap offsets) is worked out once and reused for every
+// plane, the filter and the bias are wave-uniform.  All lanes stay in the loop (neighbours take
+// taps from them); lanes beyond the plane's last pixel re-read its first element and store nothing.
+template <int MODE>
 __global__ void __launch_bounds__(256) k_depthwise(const DwArgs a) {
-    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= a.total) return;
-    const long long plane = idx / a.P;           // n * C + c
-    const int po = (int)(idx - plane * a.P);
-    const int c = (int)(plane % a.C);
-    const int ho = po / a.Wo, wo = po - ho * a.Wo;
-    const int hi0 = ho * a.stride - 1, wi0 = wo * a.stride - 1;
-    const float *xc = a.X + (size_t)plane * a.Pin;
-    const float *d = a.D + (size_t)c * 9;
-    float x[9];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const unsigned chunk = blockIdx.x % (unsigned)a.nchunks;
+    const long long pg = (long long)(blockIdx.x / (unsigned)a.nchunks) * 4 + wave;  // plane group
+    const int po = (int)chunk * 64 + lane;
+    const bool valid = po < a.P;
+    const int ho = valid ? po / a.Wo : 0, wo = valid ? po - ho * a.Wo : 0;
+    DwTaps<MODE, 64> taps;
+    taps.init(valid, 0, ho, wo, a.H, a.W, a.stride, lane);
+    const long long p0 = pg * kPlanesPerWave;
+    if (p0 >= a.planes) return;  // the whole wavefront
+    const auto wts = reinterpret_cast<const float __attribute__((address_space(4))) *>((uintptr_t)a.D);
+    const auto bs = reinterpret_cast<const float __attribute__((address_space(4))) *>((uintptr_t)a.bias);
+    int c0 = __builtin_amdgcn_readfirstlane((int)(p0 % a.C));  // channel of plane p0; the next planes count up
+    auto finish = [&](long long plane, int c, const typename DwTaps<MODE, 64>::Raw &x) {
+        float acc = taps.apply(x, wts + c * 9, a.bias ? bs[c] : 0.f);   // wave-uniform: scalar loads
+        if (a.act >= 1) acc = fmaxf(acc, 0.f);
+        if (a.act == 2) acc = fminf(acc, 6.f);
+        if (valid) __builtin_nontemporal_store(acc, a.Z + (size_t)plane * a.P + po);
+    };
 #pragma unroll
-    for (int r = 0; r < 3; ++r)
-#pragma unroll
-        for (int t = 0; t < 3; ++t) {
-            const int hi = hi0 + r, wi = wi0 + t;
-            const bool ok = hi >= 0 && hi < a.H && wi >= 0 && wi < a.W;
-            x[r * 3 + t] = ok ? xc[hi * a.W + wi] : 0.f;
-        }
-    float acc = a.bias ? a.bias[c] : 0.f;
-#pragma unroll
-    for (int t = 0; t < 9; ++t) acc = fmaf(d[t], x[t], acc);
-    if (a.act >= 1) acc = fmaxf(acc, 0.f);
-    if (a.act == 2) acc = fminf(acc, 6.f);
-    __builtin_nontemporal_store(acc, a.Z + idx);
+    for (int i = 0; i < kPlanesPerWave; i += 2) {
+        const long long pa = p0 + i, pb = p0 + i + 1;
+        if (pa >= a.planes) break;  // wave-uniform
+        const int ca = c0, cb = c0 + 1 == a.C ? 0 : c0 + 1;
+        c0 = cb + 1 == a.C ? 0 : cb + 1;
+        typename DwTaps<MODE, 64>::Raw x0, x1;
+        taps.load(a.X + (size_t)pa * a.Pin, x0);
+        const bool two = pb < a.planes;
+        if (two) taps.load(a.X + (size_t)pb * a.Pin, x1);
+        finish(pa, ca, x0);
+        if (two) finish(pb, cb, x1);
+    }
 }
 
 }  // namespace alcs
@@ -63,16 +81,20 @@ extern "C" int alcs_depthwise_conv(const float *dw_weights_dev, const float *X_d
     if (!dw_weights_dev || !X_dev || !Y_dev) return ALCS_E_INVALID_ARG;
     const int Ho = (H - 1) / stride + 1, Wo = (W - 1) / stride + 1;  // (H + 2 - 3) / stride + 1
     const long long P = (long long)Ho * Wo, Pin = (long long)H * W;
-    if (P > INT32_MAX || Pin > INT32_MAX) return ALCS_E_UNSUPPORTED;
+    if (P > INT32_MAX || Pin >= (1LL << 30)) return ALCS_E_UNSUPPORTED;  // 32-bit byte offsets inside a plane
     if ((long double)N * C * Pin >= 9e18L) return ALCS_E_UNSUPPORTED;
     DwArgs a{};
     a.D = dw_weights_dev; a.X = X_dev; a.bias = bias_dev; a.Z = Y_dev;
-    a.total = (long long)N * C * P;
+    a.planes = (long long)N * C;
+    a.nchunks = (int)((P + 63) / 64);
     a.C = C; a.H = H; a.W = W; a.Ho = Ho; a.Wo = Wo; a.P = (int)P; a.Pin = (int)Pin;
     a.stride = stride; a.act = activation;
-    const long long blocks = (a.total + 255) / 256;
+    const long long groups = (a.planes + 4 * kPlanesPerWave - 1) / (4 * kPlanesPerWave);
+    const long long blocks = groups * a.nchunks;
     if (blocks > INT32_MAX) return ALCS_E_UNSUPPORTED;
-    hipLaunchKernelGGL(k_depthwise, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, a);
+    const int mode = dw_mode_for(stride, W, X_dev);
+    void (*kern)(const DwArgs) = mode == kDwPair ? k_depthwise<kDwPair> : k_depthwise<kDwNine>;
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, a);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_hip_error((int)e); return ALCS_E_HIP; }
     return ALCS_OK;

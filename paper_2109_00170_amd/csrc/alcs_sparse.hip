@@ -29,6 +29,9 @@
 #include <utility>
 
 #include "alcs_internal.h"
+#if ALCS_DW_STAGE
+#include "alcs_dw_taps.h"
+#endif
 
 // This file is compiled twice.  As it stands it gives alcs_sparse_conv and
 // alcs_sparse_conv_timed, whose kernels have no trace of the fused epilogue (a run-time
@@ -92,6 +95,7 @@ struct ConvArgs {
     const float *dw_w;     // [Cin, 3, 3]
     const float *dw_bias;  // [Cin] or null
     int dw_stride, dw_act;
+    int dw_mode;           // DwMode: how lanes share taps
 #endif
 };
 
@@ -436,20 +440,21 @@ __device__ __forceinline__ void stage_pw(const ConvArgs &a, float *lds, int q0, 
 // The depthwise 3x3 layer (zero padding 1, stride 1 or 2, bias, activation) evaluated for
 // the pixel tile [q0, q0 + TP) of its flattened (n, ho, wo) output axis, every channel c
 // into LDS row c: the tile the pointwise convolution multiplies is produced in place and
-// never visits memory.  A thread owns one pixel of the tile and every (blockDim / TP)-th
-// channel; the nine taps are nine loads that neighbouring lanes and the next rows share
-// through the vector cache.  With TP >= 64 a wavefront works on one channel at a time, so
-// the filter and the bias come through scalar loads.
-template <int TP>
-__device__ __forceinline__ void stage_dw(const ConvArgs &a, float *lds, int q0) {
-    const int tid = threadIdx.x, nt = blockDim.x;
+// never visits memory.  Lanes hold consecutive pixels and share taps (alcs_dw_taps.h); a
+// thread owns one pixel of the tile and every (blockDim / TP)-th channel.  With TP >= 64 a
+// wavefront works on one channel at a time, so the filter and the bias come through scalar
+// loads.
+template <int TP, int MODE>
+__device__ __forceinline__ void stage_dw_mode(const ConvArgs &a, float *lds, int q0) {
+    constexpr int SPAN = TP < 64 ? TP : 64;
+    const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63;
     // A pass covers `span` pixels of the tile with nt / span channels side by side; a
     // workgroup with fewer threads than the tile has pixels takes several passes.
     const int span = nt < TP ? nt : TP;
     const int rpp = nt / span;
     int r0 = tid / span;
     if constexpr (TP >= 64) r0 = __builtin_amdgcn_readfirstlane(r0);  // span is a multiple of 64 then
-    if (r0 >= rpp) return;  // threads beyond the last full set of channels
+    if (r0 >= rpp) return;  // threads beyond the last full set of channels (whole spans)
     const auto wts = as_const(a.dw_w);
     const auto bs = as_const(a.dw_bias);
     for (int e = tid - r0 * span; e < TP; e += span) {
@@ -458,45 +463,42 @@ __device__ __forceinline__ void stage_dw(const ConvArgs &a, float *lds, int q0) 
         const int n = valid ? q / a.P : 0;
         const int po = valid ? q - n * a.P : 0;
         const int ho = po / a.Wo, wo = po - ho * a.Wo;
-        const int hi0 = ho * a.dw_stride - 1, wi0 = wo * a.dw_stride - 1;
-        bool ok[9];
-        int off[9];
-#pragma unroll
-        for (int r = 0; r < 3; ++r)
-#pragma unroll
-            for (int t = 0; t < 3; ++t) {
-                const int hi = hi0 + r, wi = wi0 + t;
-                ok[r * 3 + t] = valid && hi >= 0 && hi < a.H && wi >= 0 && wi < a.W;
-                off[r * 3 + t] = ok[r * 3 + t] ? hi * a.W + wi : 0;
-            }
-        const float *src = a.X + (size_t)n * a.Cin * a.Pin;
-        auto one = [&](int c, float (&x)[9]) {
-            const float *xc = src + (size_t)c * a.Pin;
-#pragma unroll
-            for (int t = 0; t < 9; ++t) x[t] = ok[t] ? xc[off[t]] : 0.f;
-        };
-        auto finish = [&](int c, const float (&x)[9]) {
-            float acc = a.dw_bias ? bs[c] : 0.f;
-#pragma unroll
-            for (int t = 0; t < 9; ++t) acc = fmaf(wts[c * 9 + t], x[t], acc);
+        // The wavefront's first lane holds its lowest pixel; taps are addressed from that
+        // lane's image (wave-uniform) plus what the lane's own image and channel add.
+        const int n0 = __builtin_amdgcn_readfirstlane(n);
+        const int rl = TP >= 64 ? 0 : r0;  // channel offset inside the wavefront (narrow tiles)
+        const long long delta = valid ? ((long long)(n - n0) * a.Cin + rl) * a.Pin : (long long)rl * a.Pin;
+        DwTaps<MODE, SPAN> taps;
+        taps.init(valid, delta, ho, wo, a.H, a.W, a.dw_stride, lane);
+        const float *src = a.X + (size_t)n0 * a.Cin * a.Pin;
+        auto finish = [&](int c, const typename DwTaps<MODE, SPAN>::Raw &x) {
+            float acc = taps.apply(x, wts + c * 9, a.dw_bias ? bs[c] : 0.f);
             if (a.dw_act >= 1) acc = fmaxf(acc, 0.f);
             if (a.dw_act == 2) acc = fminf(acc, 6.f);
             lds[c * TP + e] = valid ? acc : 0.f;
         };
-        int c = r0;
-        for (; c + rpp < a.Cin; c += 2 * rpp) {  // two channels' loads in flight
-            float x0[9], x1[9];
-            one(c, x0);
-            one(c + rpp, x1);
+        int c = r0;  // the lane's channel; c - rl is wave-uniform
+        // two channels' loads in flight (one on the narrow tiles, whose kernels hold the
+        // weights of several groups in registers meanwhile)
+        for (; TP >= 64 && c + rpp < a.Cin; c += 2 * rpp) {
+            typename DwTaps<MODE, SPAN>::Raw x0, x1;
+            taps.load(src + (size_t)(c - rl) * a.Pin, x0);
+            taps.load(src + (size_t)(c - rl + rpp) * a.Pin, x1);
             finish(c, x0);
             finish(c + rpp, x1);
         }
-        if (c < a.Cin) {
-            float x0[9];
-            one(c, x0);
+        for (; c < a.Cin; c += rpp) {
+            typename DwTaps<MODE, SPAN>::Raw x0;
+            taps.load(src + (size_t)(c - rl) * a.Pin, x0);
             finish(c, x0);
         }
     }
+}
+
+template <int TP>
+__device__ __forceinline__ void stage_dw(const ConvArgs &a, float *lds, int q0) {
+    if (a.dw_mode == kDwPair) stage_dw_mode<TP, kDwPair>(a, lds, q0);
+    else stage_dw_mode<TP, kDwNine>(a, lds, q0);
 }
 #endif
 
@@ -1186,6 +1188,8 @@ static int launch_sparse(const alcs_packed_t *Wp, const float *X_dev, const floa
     a.debug = T.debug;
 #if ALCS_DW_STAGE
     a.dw_w = dw->w; a.dw_bias = dw->bias; a.dw_stride = dw->stride; a.dw_act = dw->act;
+    a.dw_mode = dw_mode_for(dw->stride, W, X_dev, (T.debug & 16) != 0);
+    if (!dw_offsets_fit(Cin, Pin, P)) return ALCS_E_UNSUPPORTED;  // tap offsets are 32-bit
 #endif
 
     bool mfma = V >= 4;

@@ -114,6 +114,16 @@ def test_block_workgroups_smaller_than_the_tile(pv, waves):
     assert info["pv"] == pv and info["waves"] == waves
 
 
+@pytest.mark.parametrize("dw_stride", [1, 2])
+@pytest.mark.parametrize("slots", [1, 2])
+def test_block_taps_loaded_one_by_one(dw_stride, slots):
+    # debug bit 4: the stage that shares no taps between lanes must give the same block
+    Cin = 64 if slots == 1 else 700
+    L = workloads.Layer("blk_generic", Cin, 24, 14, 14, N=3, V=4, sparsity=0.8, w_std=0.2)
+    run_block(L, 14 * dw_stride, 14 * dw_stride, dw_stride, 2080 + slots, debug=16,
+              pack_tuning={"group_slots": slots} if slots > 1 else None)
+
+
 @pytest.mark.parametrize("dw_act,act,with_res", [(None, None, False), ("relu6", "relu6", False),
                                                  ("relu", None, True), ("relu6", "relu", True)])
 def test_block_epilogues(dw_act, act, with_res):

@@ -202,6 +202,16 @@ def mobilenet_v1_pointwise(N: int, sparsity: Optional[float] = None) -> List[Lay
     return out
 
 
+_MBV1_DW_STRIDE = [1, 2, 1, 2, 1, 2, 1, 1, 1, 1, 1, 2, 1]
+
+
+def mobilenet_v1_blocks(N: int, sparsity: Optional[float] = None):
+    """The 13 depthwise-separable blocks of MobileNetV1 at 224x224: (pointwise layer, stride of the
+    depthwise 3x3 layer in front of it); the depthwise layer's input is stride times larger than
+    the pointwise layer's."""
+    return list(zip(mobilenet_v1_pointwise(N, sparsity), _MBV1_DW_STRIDE))
+
+
 def resnet50_bottlenecks(N: int, sparsity: float = 0.8, distinct: bool = True) -> List[Layer]:
     """1x1 reduce / 3x3 / 1x1 expand convs of the 16 ResNet-50 bottleneck blocks at
     224x224 (stride on the 3x3 of each stage's first block).  ``distinct`` merges
