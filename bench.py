@@ -273,6 +273,10 @@ def report(kind, alcs, workloads, torch, np):
                 alcs.alcs_dw_sparse_conv_fused(p, D, b1, Xr[i % R], b2, None, Yr[i % R], dw_stride=dws,
                                                dw_activation="relu", activation="relu")
 
+            def auto(i):
+                alcs.alcs_dw_sparse_conv_fused(p, D, b1, Xr[i % R], b2, None, Yr[i % R], dw_stride=dws,
+                                               dw_activation="relu", activation="relu", workspace=Zr[i % R])
+
             def two(i):
                 alcs.alcs_depthwise_conv(D, Xr[i % R], b1, Zr[i % R], stride=dws, activation="relu")
                 alcs.alcs_sparse_conv_fused(p, Zr[i % R], b2, None, Yr[i % R], activation="relu")
@@ -284,7 +288,7 @@ def report(kind, alcs, workloads, torch, np):
                 alcs.alcs_sparse_conv_fused(p, Zr[i % R], b2, None, Yr[i % R], activation="relu")
 
             res = []
-            for fn in (fused, two, dw_only, pw_only):
+            for fn in (fused, two, dw_only, pw_only, auto):
                 for i in range(3):
                     fn(i)
                 torch.cuda.synchronize()
@@ -309,18 +313,19 @@ def report(kind, alcs, workloads, torch, np):
 
         for N in (32, 1):
             pr("\nbatch %d\n" % N)
-            pr("| block | depthwise | pointwise | one kernel us | two kernels us | ratio | depthwise alone us | pointwise alone us | "
-               "one kernel eff GB/s | bytes saved | max diff | launch |")
-            pr("|---|---|---|---|---|---|---|---|---|---|---|---|")
-            tf = tu = 0.0
+            pr("| block | depthwise | pointwise | one kernel us | two kernels us | ratio | with workspace us | depthwise alone us | "
+               "pointwise alone us | one kernel eff GB/s | bytes saved | max diff | launch |")
+            pr("|---|---|---|---|---|---|---|---|---|---|---|---|---|")
+            tf = tu = ta = 0.0
             for i, (L, dws) in enumerate(workloads.mobilenet_v1_blocks(N, 0.9)):
-                (f, u, t_dw, t_pw), by_f, by_u, diff, info = one(L, dws, workloads.seed_for(2, 300 + i))
+                (f, u, t_dw, t_pw, t_auto), by_f, by_u, diff, info = one(L, dws, workloads.seed_for(2, 300 + i))
                 tf += f
                 tu += u
-                pr("| %d | %d ch 3x3/%d @%d | %d->%d @%d | %.1f | %.1f | %.2f | %.1f | %.1f | %.0f | %.0f %% | %.1e | pv%d w%d wg%d |" %
-                   (i + 1, L.Cin, dws, L.H * dws, L.Cin, L.Cout, L.H, f, u, u / f, t_dw, t_pw, by_f / f / 1e3,
+                ta += t_auto
+                pr("| %d | %d ch 3x3/%d @%d | %d->%d @%d | %.1f | %.1f | %.2f | %.1f | %.1f | %.1f | %.0f | %.0f %% | %.1e | pv%d w%d wg%d |" %
+                   (i + 1, L.Cin, dws, L.H * dws, L.Cin, L.Cout, L.H, f, u, u / f, t_auto, t_dw, t_pw, by_f / f / 1e3,
                     100.0 * (by_u - by_f) / by_u, diff, info["pv"], info["waves"], info["workgroups"]))
-            pr("| 13 MobileNetV1-shaped blocks, 90 %% block sparsity | | | %.0f | %.0f | %.2f | | | | | | |" % (tf, tu, tu / tf))
+            pr("| 13 MobileNetV1-shaped blocks, 90 %% block sparsity | | | %.0f | %.0f | %.2f | %.0f | | | | | | |" % (tf, tu, tu / tf, ta))
     elif kind == "latency":
         # Section 3.3 of the paper on this GPU: time every layer at block densities 0, 0.1, ..., 1
         # (eleven runs per layer), interpolate linearly in the number of non-zero weights

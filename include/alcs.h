@@ -191,10 +191,14 @@ int alcs_sparse_conv_fused(const alcs_packed_t *Wp, const float *X_dev, const fl
  *     one kernel: Z is produced tile by tile in on-chip memory and never written out.  Wp must
  *     be a 1x1 handle with Cin inputs; X_dev is [N,Cin,H,W]; Y_dev and residual_dev (NULL or a
  *     tensor of Y's shape, may be Y_dev itself) are [N,Cout,Ho,Wo].  workspace_dev is NULL or
- *     [N,Cin,Ho,Wo] floats of scratch: handles whose input channels do not fit one on-chip
- *     tile (more than 2559 input channels, or V < 4 with more than 639), and inputs of more than
- *     about 10^9 elements per image, are then run as the two layers one after the other through
- *     the workspace; without one they return ALCS_E_UNSUPPORTED.
+ *     [N,Cin,Ho,Wo] floats of scratch.  With a workspace the library runs the two layers one
+ *     after the other through it (same result to rounding; the workspace's contents afterwards
+ *     are unspecified) where that is the faster or the only way: small layers whose output
+ *     groups are split over several workgroups per pixel tile (each would evaluate the
+ *     depthwise layer again), handles whose input channels do not fit one on-chip tile (more
+ *     than 2559 input channels, or V < 4 with more than 639), inputs of more than about 10^9
+ *     elements per image.  Without a workspace the first kind still runs as one kernel and
+ *     the other two return ALCS_E_UNSUPPORTED.
  *
  * Both: stride in {1, 2} (else ALCS_E_UNSUPPORTED); activations are alcs_activation values
  * (else ALCS_E_INVALID_ARG); X_dev / Y_dev / residual_dev 16-byte aligned for the fused call;
@@ -232,7 +236,9 @@ int alcs_dense_conv(const float *W_dev, const float *X_dev, const float *bias_de
  *                       staging, bit 1 the multiply, bit 2 the output stores, bit 3
  *                       makes the kernel return at once; bit 4 (results unchanged) makes
  *                       the depthwise stage of alcs_dw_sparse_conv_fused load all nine
- *                       taps of a pixel itself instead of sharing them between lanes
+ *                       taps of a pixel itself instead of sharing them between lanes;
+ *                       bit 5 (results unchanged) keeps alcs_dw_sparse_conv_fused in one
+ *                       kernel even where it would use its workspace for speed
  *   read by alcs_pack_weights (they shape the device layout of handles packed later):
  *     "chunk_channels"  input channels per LDS chunk (forces the chunked kernels)
  *     "group_slots"     output-channel groups multiplied per wavefront: 1, 2 or 4

@@ -1148,7 +1148,7 @@ static int launch_sparse(const alcs_packed_t *Wp, const float *X_dev, const floa
                          float *Y_dev, int N, int Cin, int Cout, int H, int W, int kernel,
                          int stride, void *stream, hipEvent_t ev_start, hipEvent_t ev_stop,
                          const float *residual_dev = nullptr, int activation = 0,
-                         const DwStage *dw = nullptr) {
+                         const DwStage *dw = nullptr, bool decline_restaged = false) {
     if (!Wp || N < 0 || H <= 0 || W <= 0) return ALCS_E_INVALID_ARG;
     if (Cin != Wp->Cin || Cout != Wp->Cout || kernel != Wp->k) return ALCS_E_INVALID_ARG;
     if (stride != 1 && stride != 2) return ALCS_E_UNSUPPORTED;
@@ -1350,6 +1350,10 @@ static int launch_sparse(const alcs_packed_t *Wp, const float *X_dev, const floa
     }
     (void)ug; (void)ti; (void)G;
     if (!kern || lds > kMaxLds) return ALCS_E_UNSUPPORTED;
+    // Depthwise stage: every group tile of a pixel tile evaluates the depthwise layer again, so
+    // a launch that splits the groups is slower than the two layers run one after the other;
+    // the caller that can do that (it has a workspace) is told to.
+    if (kDw && decline_restaged && a.ngt > 1 && !(T.debug & 32)) return ALCS_E_UNSUPPORTED;
     const long long total = (long long)a.npt * a.ngt;
     if (total > (1LL << 30)) return ALCS_E_UNSUPPORTED;
     a.total_wgs = (int)total;
@@ -1382,9 +1386,10 @@ extern "C" int alcs_dw_sparse_conv_fused(const alcs_packed_t *Wp, const float *d
     if (dw_activation < 0 || dw_activation > 2 || activation < 0 || activation > 2) return ALCS_E_INVALID_ARG;
     const DwStage dw{dw_weights_dev, dw_bias_dev, dw_stride, dw_activation};
     const int rc = launch_sparse(Wp, X_dev, bias_dev, Y_dev, N, Cin, Cout, H, W, 1, dw_stride, stream, nullptr,
-                                 nullptr, residual_dev, activation, &dw);
+                                 nullptr, residual_dev, activation, &dw, workspace_dev != nullptr);
     if (rc != ALCS_E_UNSUPPORTED || !workspace_dev) return rc;
-    // Layouts the resident kernels do not cover (input channels streamed in chunks): the two
+    // Layouts the resident kernels do not cover (input channels streamed in chunks) and layers
+    // small enough that the groups are split over several workgroups per pixel tile: the two
     // layers one after the other, the intermediate tensor in the caller's workspace.
     const int rc1 = alcs_depthwise_conv(dw_weights_dev, X_dev, dw_bias_dev, workspace_dev, N, Cin, H, W,
                                         dw_stride, dw_activation, stream);

@@ -92,6 +92,8 @@ def run_block(L, Hin, Win, dw_stride, seed, dw_act="relu", act=None, with_res=Fa
         assert info["mode"] == expect_mode, info
     if workspace and expect_mode == 1:
         assert bool(torch.isnan(ws).all()), "the fused kernel must not touch the workspace"
+    if workspace and expect_mode is None:
+        assert not bool(torch.isnan(ws).any()), "the two-layer path fills the workspace"
     return info
 
 
@@ -165,7 +167,16 @@ def test_block_through_the_workspace_when_channels_are_chunked():
     with pytest.raises(alcs.AlcsError) as ei:
         run_block(L, 11, 11, 2, 2500, workspace=False, expect_mode=None)
     assert ei.value.status == -2 or "unsupported" in str(ei.value).lower()
-    # a resident layout leaves the workspace alone
+    # a small layer whose groups are split over several workgroups per pixel tile goes through the
+    # workspace for speed (two launches: the last one is the plain pointwise kernel, whose group
+    # tiles show), unless told to stay in one kernel; without a workspace it is one kernel anyway
+    L1 = workloads.Layer("blk_split", 64, 256, 7, 7, N=4, V=4, sparsity=0.8, w_std=0.2)
+    info = run_block(L1, 7, 7, 1, 2502, workspace=True, expect_mode=None)
+    assert info["group_tiles"] > 1
+    info = run_block(L1, 7, 7, 1, 2502, workspace=True, expect_mode=1, debug=32)
+    assert info["group_tiles"] > 1
+    run_block(L1, 7, 7, 1, 2502, workspace=False, expect_mode=1)
+    # a resident layout with one group tile leaves the workspace alone
     L2 = workloads.Layer("blk_ws_unused", 32, 16, 8, 8, N=2, V=4, sparsity=0.5, w_std=0.3)
     run_block(L2, 8, 8, 1, 2501, workspace=True, expect_mode=1)
     torch.cuda.synchronize()
