@@ -241,3 +241,82 @@ def network_latency(tau, tables, nnz) -> float:
     return float(_load().oracle_network_latency(ctypes.c_double(float(tau)), _p(kk, ctypes.c_double),
                                                 _p(tt, ctypes.c_double), _p(n, ctypes.c_int), int(len(ks)),
                                                 _p(s, ctypes.c_double)))
+
+
+# ---------------------------------------------------------------------------------------------
+# Projection onto the latency constraint (Section 3.4, Algorithm 1 of the paper): plain numpy.
+# Test infrastructure like the rest of this package.
+
+def block_scores(W, V) -> np.ndarray:
+    """Algorithm 1, steps 1-2: the squared L2 norm of every block (the V weights of one group at
+    one filter position; Section 3.2.1), the quantity the blocks are sorted by.  Returned as
+    [G, Cin, k, k] float32.  Floating point decides the order, so the precision is part of the
+    definition: float32, sum = 0, then for v = 0 .. V-1: sum = sum + w_v * w_v with the product
+    and the sum each rounded to float32 (no fused multiply-add); rows beyond Cout in a ragged last
+    group count as zero."""
+    W = _f32(W)
+    Cout, Cin, k, _ = W.shape
+    G = n_groups(Cout, V)
+    s = np.zeros((G, Cin, k, k), dtype=np.float32)
+    for v in range(V):
+        rows = np.arange(G) * V + v
+        ok = rows < Cout
+        w = np.zeros((G, Cin, k, k), dtype=np.float32)
+        w[ok] = W[rows[ok]]
+        s = (s + (w * w).astype(np.float32)).astype(np.float32)   # numpy float32 ops round once each
+    return s
+
+
+def topn_mask(scores, N) -> np.ndarray:
+    """Algorithm 1, step 7: keep the N blocks with the largest score.  ``scores`` is the
+    concatenation of all layers' block scores (1-D float32, non-negative).  Order: larger score
+    first; among equal scores the block with the lower index first (the paper does not say; a
+    total order makes the selection unique).  Scores are compared through their bit patterns,
+    which orders non-negative floats (and puts NaN above infinity)."""
+    s = np.ascontiguousarray(scores, dtype=np.float32).reshape(-1)
+    n = s.size
+    if not 0 <= N <= n:
+        raise ValueError("N out of range")
+    bits = s.view(np.uint32).astype(np.uint64)
+    order = np.lexsort((np.arange(n, dtype=np.uint64), np.uint64(0xFFFFFFFF) - bits))  # primary: bits descending
+    mask = np.zeros(n, dtype=np.uint8)
+    mask[order[:N]] = 1
+    return mask
+
+
+def project_latency(scores_per_layer, V_per_layer, tables, tau, budget, eps):
+    """Algorithm 1 (projection with bisection).  ``scores_per_layer``: one block-score array per
+    layer (any shape); ``V_per_layer``: the layers' group sizes (a kept block is V non-zero
+    weights); ``tables``: the layers' (k, t) latency tables; ``tau``, ``budget``, ``eps`` as in the
+    algorithm.  Returns (N, masks_per_layer, t0, t1): the number of kept blocks, the keep / drop
+    flag of every block (shaped like the scores) and the final latency bracket.
+
+    Steps as printed: N0 = 0, N1 = number of blocks; t0 / t1 = latency with nothing / everything
+    kept; while t1 - t0 > eps: N = (N0 + N1) / 2, t = T(top-N); t < budget moves (t0, N0) up,
+    otherwise (t1, N1) down; the result keeps the (N0 + N1) / 2 largest blocks.  Halves are integer
+    divisions, and the loop also ends when N1 - N0 <= 1 (the paper's loop would not end when one
+    block changes the latency by more than eps)."""
+    flat = [np.ascontiguousarray(s, dtype=np.float32).reshape(-1) for s in scores_per_layer]
+    sizes = [f.size for f in flat]
+    allscores = np.concatenate(flat) if flat else np.zeros(0, np.float32)
+    starts = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+
+    def latency(N):
+        m = topn_mask(allscores, N)
+        nnz = [float(int(m[starts[l]:starts[l + 1]].sum()) * int(V_per_layer[l])) for l in range(len(flat))]
+        return network_latency(tau, tables, nnz), m
+
+    N0, N1 = 0, int(allscores.size)
+    t0, _ = latency(N0)
+    t1, _ = latency(N1)
+    while t1 - t0 > eps and N1 - N0 > 1:
+        N = (N0 + N1) // 2
+        t, _ = latency(N)
+        if t < budget:
+            t0, N0 = t, N
+        else:
+            t1, N1 = t, N
+    N = (N0 + N1) // 2
+    _, m = latency(N)
+    masks = [m[starts[l]:starts[l + 1]].reshape(np.shape(scores_per_layer[l])) for l in range(len(flat))]
+    return N, masks, t0, t1
