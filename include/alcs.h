@@ -268,6 +268,50 @@ int alcs_latency_estimate(const double *k_host, const double *t_host, int n, dou
 int alcs_network_latency(double tau, const double *k_host, const double *t_host, const int *n_host,
                          int L, const double *s_host, double *latency_out);
 
+/*
+ * Projection onto the latency constraint (Section 3.4, Algorithm 1 of the paper) on the GPU.
+ *
+ * alcs_block_scores (steps 1-2): scores_dev[g*K + col] = squared L2 norm of the block of V weights
+ *   W[g*V .. g*V+V-1][col] (K = Cin*kernel*kernel columns of the stretched filter, G = ceil(Cout/V)
+ *   groups; rows beyond Cout count as zero).  The score decides an order, so its arithmetic is
+ *   fixed: float32, sum = 0, then sum = sum + w_v*w_v for v = 0 .. V-1 with product and sum
+ *   rounded separately.  W_dev [Cout,Cin,kernel,kernel] and scores_dev [G*K] are device memory.
+ *
+ * alcs_topn_mask (step 7): mask_dev[i] = 1 for the N blocks with the largest score among
+ *   scores_dev[0 .. n_blocks), 0 for the others; larger score first (compared through the bit
+ *   pattern: scores are non-negative, NaN ranks above infinity), lower index first among equal
+ *   scores.  seg_starts_host [n_segments + 1] (ascending, first 0, last n_blocks; NULL = one
+ *   segment) splits the array into layers; seg_counts_host [n_segments] (or NULL) receives the
+ *   number of kept blocks per segment.  mask_dev may be NULL (counts only).  n_blocks < 2^32.
+ *   The call returns after the stream has finished when counts are asked for.
+ *
+ * alcs_project_latency: the whole of Algorithm 1.  scores_dev holds the scores of n_layers layers
+ *   back to back (layer l = [seg_starts_host[l], seg_starts_host[l+1])), V_host[l] is the layer's
+ *   group size (a kept block is V non-zero weights), (tau, k_host, t_host, n_host) are the latency
+ *   tables in the layout of alcs_network_latency.  N0 = 0, N1 = n_blocks, t0 / t1 = latency with
+ *   nothing / everything kept; while t1 - t0 > eps: N = (N0+N1)/2, t = latency of the network
+ *   that keeps the N largest blocks; t < budget moves (t0, N0) up, else (t1, N1) down; the
+ *   result keeps the (N0+N1)/2 largest blocks.  Halves are integer divisions and the loop also
+ *   ends when N1 - N0 <= 1.  Outputs: mask_dev [n_blocks] (device, may be NULL), *N_out,
+ *   *t0_out, *t1_out (host, may be NULL).  Synchronises `stream` once per bisection step.
+ *
+ * workspace_dev: device memory of at least alcs_select_workspace_bytes(n_segments) bytes, 8-byte
+ * aligned, owned by the caller, overwritten by the call; calls that share a workspace must not
+ * overlap.  Errors: ALCS_E_INVALID_ARG (null pointers, N outside [0, n_blocks], bad segment
+ * table, negative eps), ALCS_E_UNSUPPORTED (V, kernel, 2^32 blocks or more), ALCS_E_HIP.
+ */
+int alcs_block_scores(const float *W_dev, int Cout, int Cin, int kernel, int V, float *scores_dev,
+                      void *stream);
+size_t alcs_select_workspace_bytes(int n_segments);
+int alcs_topn_mask(const float *scores_dev, long long n_blocks, long long N,
+                   const long long *seg_starts_host, int n_segments, uint8_t *mask_dev,
+                   long long *seg_counts_host, void *workspace_dev, void *stream);
+int alcs_project_latency(const float *scores_dev, const long long *seg_starts_host, const int *V_host,
+                         int n_layers, double tau, const double *k_host, const double *t_host,
+                         const int *n_host, double budget, double eps, uint8_t *mask_dev,
+                         long long *N_out, double *t0_out, double *t1_out, void *workspace_dev,
+                         void *stream);
+
 /* What the last alcs_sparse_conv call of this thread launched: fills up to `cap`
  * ints {mode (1 = all input channels resident in LDS, 2 = chunked, 3 = 3x3,
  * 4 = persistent double-buffered), pv, waves, workgroups, lds_bytes, group_tiles,

@@ -8,6 +8,7 @@ from ._binding import (  # noqa: F401
     AlcsError,
     HipEvents,
     Packed,
+    alcs_block_scores,
     alcs_dense_conv,
     alcs_depthwise_conv,
     alcs_dw_sparse_conv_fused,
@@ -15,10 +16,12 @@ from ._binding import (  # noqa: F401
     alcs_latency_estimate,
     alcs_network_latency,
     alcs_pack_weights,
+    alcs_project_latency,
     alcs_set_tuning,
     alcs_sparse_conv,
     alcs_sparse_conv_fused,
     alcs_strerror,
+    alcs_topn_mask,
     alcs_version,
     library_path,
     load_library,

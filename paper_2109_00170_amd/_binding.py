@@ -15,7 +15,8 @@ EXPORTS = [
     "alcs_strerror", "alcs_last_hip_error", "alcs_version", "alcs_pack_weights", "alcs_packed_info",
     "alcs_packed_on_device", "alcs_packed_export", "alcs_packed_selfcheck", "alcs_packed_free",
     "alcs_sparse_conv", "alcs_sparse_conv_timed", "alcs_sparse_conv_fused", "alcs_dense_conv", "alcs_set_tuning",
-    "alcs_depthwise_conv", "alcs_dw_sparse_conv_fused",
+    "alcs_depthwise_conv", "alcs_dw_sparse_conv_fused", "alcs_block_scores", "alcs_select_workspace_bytes",
+    "alcs_topn_mask", "alcs_project_latency",
     "alcs_last_launch", "alcs_latency_estimate", "alcs_network_latency",
 ]
 
@@ -353,3 +354,79 @@ def alcs_network_latency(tau, tables, nnz) -> float:
     if rc != 0:
         raise AlcsError(rc, "alcs_network_latency")
     return float(out.value)
+
+
+def alcs_block_scores(W_dev, V: int, scores=None, stream=None):
+    """Squared L2 norm of every block of V weights: W_dev [Cout,Cin,k,k] on the device ->
+    float32 tensor [ceil(Cout/V), Cin, k, k] (allocated here unless ``scores`` is given)."""
+    import torch
+    Cout, Cin, k, _ = W_dev.shape
+    G = (Cout + V - 1) // V
+    if scores is None:
+        scores = torch.empty((G, Cin, k, k), dtype=torch.float32, device=W_dev.device)
+    if tuple(scores.shape) != (G, Cin, k, k):
+        raise ValueError("scores must have shape %r" % ((G, Cin, k, k),))
+    rc = load_library().alcs_block_scores(_dev_ptr(W_dev, "W"), Cout, Cin, k, int(V), _dev_ptr(scores, "scores"),
+                                          _stream_ptr(stream))
+    if rc != 0:
+        raise AlcsError(rc, "alcs_block_scores")
+    return scores
+
+
+def _select_workspace(n_seg, device):
+    import torch
+    lib = load_library()
+    lib.alcs_select_workspace_bytes.restype = ctypes.c_size_t
+    nbytes = int(lib.alcs_select_workspace_bytes(int(n_seg)))
+    return torch.empty(((nbytes + 7) // 8,), dtype=torch.int64, device=device)
+
+
+def alcs_topn_mask(scores, N: int, seg_starts=None, want_mask: bool = True, stream=None):
+    """Keep flags (uint8 tensor, or None) of the N largest entries of the 1-D float32 device tensor
+    ``scores`` and the kept count per segment (numpy int64)."""
+    import torch
+    n = int(scores.numel())
+    starts = np.ascontiguousarray([0, n] if seg_starts is None else seg_starts, dtype=np.int64)
+    n_seg = int(starts.size) - 1
+    ws = _select_workspace(n_seg, scores.device)
+    mask = torch.empty((n,), dtype=torch.uint8, device=scores.device) if want_mask else None
+    counts = np.zeros(n_seg, dtype=np.int64)
+    llp = ctypes.POINTER(ctypes.c_longlong)
+    rc = load_library().alcs_topn_mask(
+        _dev_ptr(scores, "scores"), ctypes.c_longlong(n), ctypes.c_longlong(int(N)), starts.ctypes.data_as(llp), n_seg,
+        None if mask is None else ctypes.c_void_p(mask.data_ptr()), counts.ctypes.data_as(llp),
+        ctypes.c_void_p(ws.data_ptr()), _stream_ptr(stream))
+    if rc != 0:
+        raise AlcsError(rc, "alcs_topn_mask")
+    return mask, counts
+
+
+def alcs_project_latency(scores, seg_starts, V_per_layer, tables, tau, budget, eps, want_mask: bool = True,
+                         stream=None):
+    """Algorithm 1 on the device tensor ``scores`` (all layers back to back): returns
+    (N, mask uint8 tensor or None, t0, t1)."""
+    import torch
+    starts = np.ascontiguousarray(seg_starts, dtype=np.int64)
+    L = int(starts.size) - 1
+    if len(V_per_layer) != L or len(tables) != L:
+        raise ValueError("one group size and one table per layer")
+    Vs = np.ascontiguousarray(V_per_layer, dtype=np.int32)
+    ks = [_f64(k) for k, _ in tables]
+    ts = [_f64(t) for _, t in tables]
+    nn = np.array([k.size for k in ks], dtype=np.int32)
+    kk, tt = _f64(np.concatenate(ks)), _f64(np.concatenate(ts))
+    n = int(scores.numel())
+    ws = _select_workspace(L, scores.device)
+    mask = torch.empty((n,), dtype=torch.uint8, device=scores.device) if want_mask else None
+    N_out = ctypes.c_longlong()
+    t0, t1 = ctypes.c_double(), ctypes.c_double()
+    dp, ip = ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)
+    rc = load_library().alcs_project_latency(
+        _dev_ptr(scores, "scores"), starts.ctypes.data_as(ctypes.POINTER(ctypes.c_longlong)), Vs.ctypes.data_as(ip), L,
+        ctypes.c_double(float(tau)), kk.ctypes.data_as(dp), tt.ctypes.data_as(dp), nn.ctypes.data_as(ip),
+        ctypes.c_double(float(budget)), ctypes.c_double(float(eps)),
+        None if mask is None else ctypes.c_void_p(mask.data_ptr()), ctypes.byref(N_out), ctypes.byref(t0),
+        ctypes.byref(t1), ctypes.c_void_p(ws.data_ptr()), _stream_ptr(stream))
+    if rc != 0:
+        raise AlcsError(rc, "alcs_project_latency")
+    return int(N_out.value), mask, float(t0.value), float(t1.value)
