@@ -326,6 +326,69 @@ def report(kind, alcs, workloads, torch, np):
                    (i + 1, L.Cin, dws, L.H * dws, L.Cin, L.Cout, L.H, f, u, u / f, t_auto, t_dw, t_pw, by_f / f / 1e3,
                     100.0 * (by_u - by_f) / by_u, diff, info["pv"], info["waves"], info["workgroups"]))
             pr("| 13 MobileNetV1-shaped blocks, 90 %% block sparsity | | | %.0f | %.0f | %.2f | %.0f | | | | | | |" % (tf, tu, tu / tf, ta))
+    elif kind == "project":
+        # Algorithm 1 on the GPU: block scores, top-N selection, the bisection; times are wall-clock
+        # around synchronised calls (the bisection synchronises once per step by design)
+        import time
+
+        def net(name):
+            if name == "mbv1":
+                return [(L.Cout, L.Cin, 1) for L in workloads.mobilenet_v1_pointwise(1, 0.0)]
+            return [(L.Cout, L.Cin, L.k) for L in workloads.resnet50_bottlenecks(1, 0.0, distinct=False)]
+
+        pr("| network | weights | blocks (V=4) | scores us | scores eff GB/s | select N = half us | select eff GB/s | "
+           "projection ms | bisection steps | kept blocks | estimate vs budget |")
+        pr("|---|---|---|---|---|---|---|---|---|---|---|")
+        for name, title in (("mbv1", "13 MobileNetV1-shaped pointwise layers"), ("resnet", "48 ResNet-50-shaped convs")):
+            rng = np.random.Generator(np.random.PCG64(workloads.seed_for(2, 700)))
+            shapes = net(name)
+            Ws = [torch.from_numpy((rng.standard_normal((co, ci, k, k), dtype=np.float32) *
+                                    np.float32(0.05 + 0.2 * rng.random()))).cuda() for co, ci, k in shapes]
+            V = 4
+            sizes = [((co + V - 1) // V) * ci * k * k for co, ci, k in shapes]
+            starts = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+            allsc = torch.empty((int(starts[-1]),), dtype=torch.float32, device="cuda")
+            views = [allsc[int(a):int(b)].view((co + V - 1) // V, ci, k, k) for (co, ci, k), a, b in zip(shapes, starts, starts[1:])]
+
+            def scores():
+                for W, v in zip(Ws, views):
+                    alcs.alcs_block_scores(W, V, scores=v)
+            for _ in range(2):
+                scores()
+            torch.cuda.synchronize()
+            reps = 10
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                scores()
+            e1.record()
+            torch.cuda.synchronize()
+            t_sc = e0.elapsed_time(e1) * 1e3 / reps
+            nw = sum(co * ci * k * k for co, ci, k in shapes)
+            by_sc = 4 * nw + 4 * int(starts[-1])
+            n = int(starts[-1])
+            alcs.alcs_topn_mask(allsc, n // 2, seg_starts=starts)
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                alcs.alcs_topn_mask(allsc, n // 2, seg_starts=starts)
+            t_sel = (time.perf_counter() - t0) * 1e6 / reps
+            by_sel = 9 * 4 * n + n
+            # latency tables of the shape measured on this GPU: a floor plus a slope per kept weight
+            tables = []
+            for co, ci, k in shapes:
+                kk = np.arange(11) * 0.1 * (co * ci * k * k)
+                tables.append((kk, 9.0 + 60.0 * np.arange(11) / 10.0 * (k * k) ** 0.5))
+            t_none = sum(t[0] for _, t in tables)
+            t_all = sum(t[-1] for _, t in tables)
+            budget = t_none + 0.3 * (t_all - t_none)
+            alcs.alcs_project_latency(allsc, starts, [V] * len(shapes), tables, 0.0, budget, 1e-3)
+            t0 = time.perf_counter()
+            N, mask, lo, hi = alcs.alcs_project_latency(allsc, starts, [V] * len(shapes), tables, 0.0, budget, 1e-3)
+            t_proj = (time.perf_counter() - t0) * 1e3
+            steps = int(np.ceil(np.log2(max(n, 2))))
+            pr("| %s | %.2f M | %.2f M | %.1f | %.0f | %.0f | %.0f | %.2f | <= %d | %d (%.1f %%) | %.1f <= %.1f <= %.1f |" %
+               (title, nw / 1e6, n / 1e6, t_sc, by_sc / t_sc / 1e3, t_sel, by_sel / t_sel / 1e3, t_proj, steps, N,
+                100.0 * N / n, lo, budget, hi))
     elif kind == "latency":
         # Section 3.3 of the paper on this GPU: time every layer at block densities 0, 0.1, ..., 1
         # (eleven runs per layer), interpolate linearly in the number of non-zero weights
@@ -417,7 +480,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-batch", type=int, default=32)
     ap.add_argument("--layers-json", default=None, help="also write the per-layer table to this file")
-    ap.add_argument("--report", choices=["sweep", "resnet", "mbv2", "paths", "mbv1", "fused", "latency", "block"], default=None,
+    ap.add_argument("--report", choices=["sweep", "resnet", "mbv2", "paths", "mbv1", "fused", "latency", "block", "project"], default=None,
                     help="instead of the benchmark line, print a per-layer table for another configuration: "
                          "the sparsity sweep with the same-GPU dense conv (config 4), the ResNet-50-shaped "
                          "bottleneck convs (config 3), the MobileNetV2-shaped pointwise convs for V in "
