@@ -212,15 +212,18 @@ int upload(alcs_packed *p) {
 }
 
 // Tile policy for kernel 1.  One group per wavefront and all input channels in one
-// LDS tile while a 64-pixel tile of Cin+1 rows fits (Cin <= 639 in 160 KB); wider
-// inputs shrink the tile to 32 or 16 pixels and multiply 2 or 4 groups per wavefront
-// (V >= 4 only); beyond that, or for V < 4, chunks of 256 channels.
+// LDS tile while a 64-pixel tile of Cin+1 rows fits (Cin <= 639 in 160 KB); from 512
+// input channels on (V >= 4 only) the tile shrinks to 32 or 16 pixels and a wavefront
+// multiplies 2 or 4 groups: two workgroups then share a compute unit and one fills its
+// tile while the other multiplies (512 channels measured both ways: 512->1024 @7x7
+// 16.9 -> 11.0 us, 512->512 @14x14 17.2 -> 16.6 us, 512->256 @28x28 86 -> 82 us).
+// Beyond 2559 channels, or beyond 639 for V < 4, chunks of 256 channels.
 // Kernel 3: 32 channels per chunk (the haloed tile plane is 240 to 476 floats per channel).
 static void default_tiles(int Cin, int k, int V, int *KC, int *GS) {
     *GS = 1;
     if (k == 3) { *KC = std::min(Cin, 32); return; }
+    if (V >= 4 && Cin >= 512 && Cin <= 2559) { *KC = Cin; *GS = Cin <= 1279 ? 2 : 4; return; }
     if (Cin <= 639) { *KC = Cin; return; }
-    if (V >= 4 && Cin <= 2559) { *KC = Cin; *GS = Cin <= 1279 ? 2 : 4; return; }
     *KC = 256;
 }
 

@@ -1281,8 +1281,9 @@ static int launch_sparse(const alcs_packed_t *Wp, const float *X_dev, const floa
             // one resident workgroup per compute unit aim at one round (<= 256 workgroups),
             // else at about 1.5 workgroups per compute unit.
             int ngt = 1;
-            const int want = lds > 80 * 1024 ? kCUs : kMinWgs;
-            if (a.npt < want) ngt = std::min(std::max(1, NB / 4), std::max(1, lds > 80 * 1024 ? want / a.npt : ceil_div(want, a.npt)));
+            const bool one_round = lds > 80 * 1024 || GS > 1;  // narrow tiles: measured best at <= 256 workgroups too
+            const int want = one_round ? kCUs : kMinWgs;
+            if (a.npt < want) ngt = std::min(std::max(1, NB / 4), std::max(1, one_round ? want / a.npt : ceil_div(want, a.npt)));
             if (T.group_tiles > 0) ngt = std::min(T.group_tiles, NB);
             a.gpt = ceil_div(NB, ngt);
             a.ngt = ceil_div(NB, a.gpt);
