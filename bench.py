@@ -458,14 +458,15 @@ def report(kind, alcs, workloads, torch, np):
         pr("|---|---|---|---|")
         for i, L in enumerate(workloads.mobilenet_v1_pointwise(32, 0.9)):
             if L.Cin > 639:
-                continue    # wider inputs pair groups per wavefront, which only the MFMA form does
-            a = time_layer(alcs, torch, np, workloads, L, workloads.seed_for(2, i), tuning={"path": 2})
-            b = time_layer(alcs, torch, np, workloads, L, workloads.seed_for(2, i), tuning={"path": 1})
+                continue    # wider inputs need several groups per wavefront, which only the MFMA form does
+            # one group per wavefront for both forms (the default layout pairs groups from 512 channels on)
+            a = time_layer(alcs, torch, np, workloads, L, workloads.seed_for(2, i), tuning={"path": 2, "group_slots": 1})
+            b = time_layer(alcs, torch, np, workloads, L, workloads.seed_for(2, i), tuning={"path": 1, "group_slots": 1})
             pr("| %s | %.1f | %.1f | %.2f |" % (L.name, a["us"], b["us"], b["us"] / a["us"]))
         for s in (0.5, 0.9):
             L = workloads.sweep_layer(s)
-            a = time_layer(alcs, torch, np, workloads, L, workloads.seed_for(4, int(s * 100)), tuning={"path": 2})
-            b = time_layer(alcs, torch, np, workloads, L, workloads.seed_for(4, int(s * 100)), tuning={"path": 1})
+            a = time_layer(alcs, torch, np, workloads, L, workloads.seed_for(4, int(s * 100)), tuning={"path": 2, "group_slots": 1})
+            b = time_layer(alcs, torch, np, workloads, L, workloads.seed_for(4, int(s * 100)), tuning={"path": 1, "group_slots": 1})
             pr("| sweep s=%.2f | %.1f | %.1f | %.2f |" % (s, a["us"], b["us"], b["us"] / a["us"]))
 
 
