@@ -177,6 +177,19 @@ int alcs_sparse_conv_fused(const alcs_packed_t *Wp, const float *X_dev, const fl
                            int W, int kernel, int stride, int activation, void *stream);
 
 /*
+ * alcs_sparse_conv_fused (Section 3.2.2, "Efficient multiplication computation") on tensors stored
+ * as bfloat16: X_dev, residual_dev and Y_dev hold the upper 16 bits of a float per element (NCHW,
+ * same shapes); the packed weights, the bias and every sum stay float32, and Y is rounded to
+ * nearest even once, after bias, residual and activation.  The layers this library runs at the
+ * HBM roofline move half the bytes.  1x1 handles whose input channels fit one on-chip tile only
+ * (at most 2559 input channels, 639 for V < 4; ALCS_E_UNSUPPORTED otherwise); X_dev, Y_dev and
+ * residual_dev 8-byte aligned; everything else as alcs_sparse_conv_fused.
+ */
+int alcs_sparse_conv_bf16(const alcs_packed_t *Wp, const uint16_t *X_dev, const float *bias_dev,
+                          const uint16_t *residual_dev, uint16_t *Y_dev, int N, int Cin, int Cout,
+                          int H, int W, int kernel, int stride, int activation, void *stream);
+
+/*
  * Depthwise 3x3 layer and the MobileNet block (the network pruned in Section 4 of the paper:
  * every pointwise convolution is preceded by a depthwise 3x3 layer with its own bias and
  * activation; they are among the layers behind the constant tau of Section 3.3, Eq. (2)).

@@ -320,3 +320,14 @@ def project_latency(scores_per_layer, V_per_layer, tables, tau, budget, eps):
     _, m = latency(N)
     masks = [m[starts[l]:starts[l + 1]].reshape(np.shape(scores_per_layer[l])) for l in range(len(flat))]
     return N, masks, t0, t1
+
+
+def round_bf16(x) -> np.ndarray:
+    """Round float32 values to bfloat16 (8 significant bits, round to nearest, ties to even) and
+    return them as float32; NaN stays NaN.  For the tensors of the bfloat16 entry point."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    bits = x.view(np.uint32).astype(np.uint64)
+    rounded = ((bits + 0x7FFF + ((bits >> 16) & 1)) >> 16) << 16
+    out = (rounded & 0xFFFFFFFF).astype(np.uint32).view(np.float32).reshape(x.shape).copy()
+    out[np.isnan(x)] = np.nan
+    return out

@@ -15,7 +15,7 @@ EXPORTS = [
     "alcs_strerror", "alcs_last_hip_error", "alcs_version", "alcs_pack_weights", "alcs_packed_info",
     "alcs_packed_on_device", "alcs_packed_export", "alcs_packed_selfcheck", "alcs_packed_free",
     "alcs_sparse_conv", "alcs_sparse_conv_timed", "alcs_sparse_conv_fused", "alcs_dense_conv", "alcs_set_tuning",
-    "alcs_depthwise_conv", "alcs_dw_sparse_conv_fused", "alcs_block_scores", "alcs_select_workspace_bytes",
+    "alcs_depthwise_conv", "alcs_dw_sparse_conv_fused", "alcs_sparse_conv_bf16", "alcs_block_scores", "alcs_select_workspace_bytes",
     "alcs_topn_mask", "alcs_project_latency",
     "alcs_last_launch", "alcs_latency_estimate", "alcs_network_latency",
 ]
@@ -161,7 +161,7 @@ def _dev_ptr(t, name, dtype_name="torch.float32"):
     if t is None:
         return None
     if not t.is_cuda or not t.is_contiguous() or str(t.dtype) != dtype_name:
-        raise ValueError("%s must be a contiguous fp32 tensor on the GPU" % name)
+        raise ValueError("%s must be a contiguous %s tensor on the GPU" % (name, dtype_name))
     return ctypes.c_void_p(t.data_ptr())
 
 
@@ -206,6 +206,24 @@ def alcs_sparse_conv_fused(packed: Packed, X, bias, residual, Y, stride: int = 1
                                                packed.Cout, H, W, k, int(stride), int(act), _stream_ptr(stream))
     if rc != 0:
         raise AlcsError(rc, "alcs_sparse_conv_fused")
+
+
+def alcs_sparse_conv_bf16(packed: Packed, X, bias, residual, Y, stride: int = 1, activation=None, stream=None) -> None:
+    """alcs_sparse_conv_fused on torch.bfloat16 tensors X, residual (or None) and Y; bias stays float32."""
+    N, Cin, H, W = X.shape
+    k = packed.kernel
+    exp = (N, packed.Cout, out_size(H, k, stride), out_size(W, k, stride))
+    if tuple(Y.shape) != exp:
+        raise ValueError("Y must have shape %r, got %r" % (exp, tuple(Y.shape)))
+    if residual is not None and tuple(residual.shape) != exp:
+        raise ValueError("residual must have shape %r, got %r" % (exp, tuple(residual.shape)))
+    act = activation if isinstance(activation, int) else ACTIVATIONS[activation]
+    bf = "torch.bfloat16"
+    rc = load_library().alcs_sparse_conv_bf16(packed.handle, _dev_ptr(X, "X", bf), _dev_ptr(bias, "bias"),
+                                              _dev_ptr(residual, "residual", bf), _dev_ptr(Y, "Y", bf), N, Cin,
+                                              packed.Cout, H, W, k, int(stride), int(act), _stream_ptr(stream))
+    if rc != 0:
+        raise AlcsError(rc, "alcs_sparse_conv_bf16")
 
 
 class HipEvents:

@@ -50,13 +50,27 @@
 #ifndef ALCS_DW_STAGE
 #define ALCS_DW_STAGE 0
 #endif
-#if ALCS_DW_STAGE && !ALCS_FUSED_EPILOGUE
-#error "the depthwise stage comes with the fused epilogue"
+//
+// alcs_sparse_bf16.hip defines ALCS_IO_BF16: the resident 1x1 kernels with X, the residual and Y
+// stored as bfloat16 (namespace alcs::bf16io), behind alcs_sparse_conv_bf16.  Weights, bias,
+// LDS tile and accumulation stay float32; only the tensors that cross HBM are narrower.
+#ifndef ALCS_IO_BF16
+#define ALCS_IO_BF16 0
 #endif
+#if (ALCS_DW_STAGE || ALCS_IO_BF16) && !ALCS_FUSED_EPILOGUE
+#error "the depthwise stage and the bfloat16 tensors come with the fused epilogue"
+#endif
+#if ALCS_DW_STAGE && ALCS_IO_BF16
+#error "one variant per compilation"
+#endif
+// builds that hold only the resident 1x1 kernels
+#define ALCS_RESIDENT_ONLY (ALCS_DW_STAGE || ALCS_IO_BF16)
 
 namespace alcs {
 #if ALCS_DW_STAGE
 namespace dwpw {
+#elif ALCS_IO_BF16
+namespace bf16io {
 #elif ALCS_FUSED_EPILOGUE
 namespace fused {
 #endif
@@ -68,11 +82,50 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 typedef float f2 __attribute__((ext_vector_type(2)));
 typedef int i4 __attribute__((ext_vector_type(4)));
 
+// Element type of X, the residual and Y in memory, and 1 / 2 / 4 consecutive elements of it
+// as floats.  bfloat16 is the upper half of a float: widening is a shift, narrowing rounds to
+// nearest even (v_cvt_pk_bf16_f32).  Stores are non-temporal: Y is not read again.
+#if ALCS_IO_BF16
+typedef unsigned short io_t;
+typedef unsigned int u2v __attribute__((ext_vector_type(2)));
+typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float io_load1(const io_t *p) { return __builtin_bit_cast(float, (unsigned int)*p << 16); }
+__device__ __forceinline__ f2 io_load2(const io_t *p) {
+    const unsigned int u = *reinterpret_cast<const unsigned int *>(p);
+    return f2{__builtin_bit_cast(float, u << 16), __builtin_bit_cast(float, u & 0xffff0000u)};
+}
+__device__ __forceinline__ f4 io_load4(const io_t *p) {
+    const u2v u = *reinterpret_cast<const u2v *>(p);
+    return f4{__builtin_bit_cast(float, u.x << 16), __builtin_bit_cast(float, u.x & 0xffff0000u),
+              __builtin_bit_cast(float, u.y << 16), __builtin_bit_cast(float, u.y & 0xffff0000u)};
+}
+__device__ __forceinline__ unsigned int pack_bf2(float a, float b) {
+    return __builtin_bit_cast(unsigned int, __builtin_convertvector(f2{a, b}, bf2));
+}
+__device__ __forceinline__ void io_store1(io_t *p, float v) {
+    __builtin_nontemporal_store((io_t)(pack_bf2(v, 0.f) & 0xffffu), p);
+}
+__device__ __forceinline__ void io_store2(io_t *p, f2 v) {
+    __builtin_nontemporal_store(pack_bf2(v[0], v[1]), reinterpret_cast<unsigned int *>(p));
+}
+__device__ __forceinline__ void io_store4(io_t *p, f4 v) {
+    __builtin_nontemporal_store(u2v{pack_bf2(v[0], v[1]), pack_bf2(v[2], v[3])}, reinterpret_cast<u2v *>(p));
+}
+#else
+typedef float io_t;
+__device__ __forceinline__ float io_load1(const io_t *p) { return *p; }
+__device__ __forceinline__ f2 io_load2(const io_t *p) { return *reinterpret_cast<const f2 *>(p); }
+__device__ __forceinline__ f4 io_load4(const io_t *p) { return *reinterpret_cast<const f4 *>(p); }
+__device__ __forceinline__ void io_store1(io_t *p, float v) { __builtin_nontemporal_store(v, p); }
+__device__ __forceinline__ void io_store2(io_t *p, f2 v) { __builtin_nontemporal_store(v, reinterpret_cast<f2 *>(p)); }
+__device__ __forceinline__ void io_store4(io_t *p, f4 v) { __builtin_nontemporal_store(v, reinterpret_cast<f4 *>(p)); }
+#endif
+
 struct ConvArgs {
-    const float *X;
+    const io_t *X;
     const float *bias;
-    const float *residual;  // fused epilogue: tensor of Y's shape added before the activation, or null
-    float *Y;
+    const io_t *residual;  // fused epilogue: tensor of Y's shape added before the activation, or null
+    io_t *Y;
     const Work *work;   // [G * nchunks] in hand-out order (longest group first)
     const float *w;
     const int32_t *off;
@@ -108,7 +161,7 @@ __device__ __forceinline__ float activate(const ConvArgs &a, float v) {
     return v;
 }
 // The residual tensor, or null where the epilogue is compiled out.
-__device__ __forceinline__ const float *residual_of(const ConvArgs &a) {
+__device__ __forceinline__ const io_t *residual_of(const ConvArgs &a) {
     if constexpr (kFused) return a.residual;
     else return nullptr;
 }
@@ -391,7 +444,7 @@ __device__ __forceinline__ void stage_pw(const ConvArgs &a, float *lds, int q0, 
         const bool valid = q < a.NP;
         const int n = valid ? q / a.P : 0;
         const int p = valid ? q - n * a.P : 0;
-        const float *src = a.X + ((size_t)n * a.Cin + c0) * a.P + p;
+        const io_t *src = a.X + ((size_t)n * a.Cin + c0) * a.P + p;
         float *dst = lds + quad * 4;
         const int rows = c1 - c0;
         constexpr int U = 8;  // independent 16-byte loads in flight per thread
@@ -401,17 +454,14 @@ __device__ __forceinline__ void stage_pw(const ConvArgs &a, float *lds, int q0, 
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 v[u] = f4{0, 0, 0, 0};
-                if (valid) {
-                    const f4 *ptr = reinterpret_cast<const f4 *>(src + (size_t)(r + u * rpp) * a.P);
-                    v[u] = *ptr;
-                }
+                if (valid) v[u] = io_load4(src + (size_t)(r + u * rpp) * a.P);
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) *reinterpret_cast<f4 *>(dst + (r + u * rpp) * TP) = v[u];
         }
         for (; r < rows; r += rpp) {
             f4 v0 = f4{0, 0, 0, 0};
-            if (valid) v0 = *reinterpret_cast<const f4 *>(src + (size_t)r * a.P);
+            if (valid) v0 = io_load4(src + (size_t)r * a.P);
             *reinterpret_cast<f4 *>(dst + r * TP) = v0;
         }
     } else {
@@ -421,18 +471,18 @@ __device__ __forceinline__ void stage_pw(const ConvArgs &a, float *lds, int q0, 
         const int n = valid ? q / a.P : 0;
         const int po = valid ? q - n * a.P : 0;
         const int ho = po / a.Wo, wo = po - ho * a.Wo;
-        const float *src = a.X + ((size_t)n * a.Cin + c0) * a.Pin + (size_t)(ho * a.stride) * a.W + wo * a.stride;
+        const io_t *src = a.X + ((size_t)n * a.Cin + c0) * a.Pin + (size_t)(ho * a.stride) * a.W + wo * a.stride;
         const int rows = c1 - c0;
         constexpr int U = 16;  // independent 4-byte loads in flight per thread
         int r = r0;
         for (; r + (U - 1) * rpp < rows; r += U * rpp) {
             float v[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) v[u] = valid ? src[(size_t)(r + u * rpp) * a.Pin] : 0.f;
+            for (int u = 0; u < U; ++u) v[u] = valid ? io_load1(src + (size_t)(r + u * rpp) * a.Pin) : 0.f;
 #pragma unroll
             for (int u = 0; u < U; ++u) lds[(r + u * rpp) * TP + e] = v[u];
         }
-        for (; r < rows; r += rpp) lds[r * TP + e] = valid ? src[(size_t)r * a.Pin] : 0.f;
+        for (; r < rows; r += rpp) lds[r * TP + e] = valid ? io_load1(src + (size_t)r * a.Pin) : 0.f;
     }
 }
 
@@ -539,21 +589,21 @@ __device__ __forceinline__ void load_residual(const ConvArgs &a, int g, const Pi
 #pragma unroll
         for (int pv = 0; pv < PV; ++pv) rr.r[v][pv] = 0.f;
         if (ch >= a.Cout) continue;
-        const float *res = a.residual + (size_t)ch * a.P;
+        const io_t *res = a.residual + (size_t)ch * a.P;
         if constexpr (VEC && PV == 4) {
             if (px.valid[0]) {
-                const f4 t = *reinterpret_cast<const f4 *>(res + px.yoff[0]);
+                const f4 t = io_load4(res + px.yoff[0]);
                 rr.r[v][0] = t[0]; rr.r[v][1] = t[1]; rr.r[v][2] = t[2]; rr.r[v][3] = t[3];
             }
         } else if constexpr (VEC && PV == 2) {
             if (px.valid[0]) {
-                const f2 t = *reinterpret_cast<const f2 *>(res + px.yoff[0]);
+                const f2 t = io_load2(res + px.yoff[0]);
                 rr.r[v][0] = t[0]; rr.r[v][1] = t[1];
             }
         } else {
 #pragma unroll
             for (int pv = 0; pv < PV; ++pv)
-                if (px.valid[pv]) rr.r[v][pv] = res[px.yoff[pv]];
+                if (px.valid[pv]) rr.r[v][pv] = io_load1(res + px.yoff[pv]);
         }
     }
 }
@@ -568,28 +618,28 @@ __device__ __forceinline__ void store_group(const ConvArgs &a, const Acc<V, PV, 
         const int ch = g * V + v;
         if (ch >= a.Cout) break;
         float b = a.bias ? as_const(a.bias)[ch] : 0.f;
-        float *dst = a.Y + (size_t)ch * a.P;
+        io_t *dst = a.Y + (size_t)ch * a.P;
         // the residual: already in registers (pre), or read here
-        const float *res = (residual_of(a) && !pre) ? residual_of(a) + (size_t)ch * a.P : nullptr;  // wave-uniform
+        const io_t *res = (residual_of(a) && !pre) ? residual_of(a) + (size_t)ch * a.P : nullptr;  // wave-uniform
         if (kFused && pre) {
             if constexpr (VEC && PV == 4) {
                 if (px.valid[0]) {
                     f4 o = f4{acc.get(v, 0) + b + pre->r[v][0], acc.get(v, 1) + b + pre->r[v][1],
                               acc.get(v, 2) + b + pre->r[v][2], acc.get(v, 3) + b + pre->r[v][3]};
                     if (kFused && a.act) o = f4{activate(a, o[0]), activate(a, o[1]), activate(a, o[2]), activate(a, o[3])};
-                    __builtin_nontemporal_store(o, reinterpret_cast<f4 *>(dst + px.yoff[0]));
+                    io_store4(dst + px.yoff[0], o);
                 }
             } else if constexpr (VEC && PV == 2) {
                 if (px.valid[0]) {
                     f2 o = f2{acc.get(v, 0) + b + pre->r[v][0], acc.get(v, 1) + b + pre->r[v][1]};
                     if (kFused && a.act) o = f2{activate(a, o[0]), activate(a, o[1])};
-                    __builtin_nontemporal_store(o, reinterpret_cast<f2 *>(dst + px.yoff[0]));
+                    io_store2(dst + px.yoff[0], o);
                 }
             } else {
 #pragma unroll
                 for (int pv = 0; pv < PV; ++pv)
                     if (px.valid[pv])
-                        __builtin_nontemporal_store(activate(a, acc.get(v, pv) + b + pre->r[v][pv]), dst + px.yoff[pv]);
+                        io_store1(dst + px.yoff[pv], activate(a, acc.get(v, pv) + b + pre->r[v][pv]));
             }
             continue;
         }
@@ -597,24 +647,24 @@ __device__ __forceinline__ void store_group(const ConvArgs &a, const Acc<V, PV, 
         if constexpr (VEC && PV == 4) {
             if (px.valid[0]) {
                 f4 o = f4{acc.get(v, 0) + b, acc.get(v, 1) + b, acc.get(v, 2) + b, acc.get(v, 3) + b};
-                if (res) o += *reinterpret_cast<const f4 *>(res + px.yoff[0]);
+                if (res) o += io_load4(res + px.yoff[0]);
                 if (kFused && a.act) o = f4{activate(a, o[0]), activate(a, o[1]), activate(a, o[2]), activate(a, o[3])};
-                __builtin_nontemporal_store(o, reinterpret_cast<f4 *>(dst + px.yoff[0]));
+                io_store4(dst + px.yoff[0], o);
             }
         } else if constexpr (VEC && PV == 2) {
             if (px.valid[0]) {
                 f2 o = f2{acc.get(v, 0) + b, acc.get(v, 1) + b};
-                if (res) o += *reinterpret_cast<const f2 *>(res + px.yoff[0]);
+                if (res) o += io_load2(res + px.yoff[0]);
                 if (kFused && a.act) o = f2{activate(a, o[0]), activate(a, o[1])};
-                __builtin_nontemporal_store(o, reinterpret_cast<f2 *>(dst + px.yoff[0]));
+                io_store2(dst + px.yoff[0], o);
             }
         } else {
 #pragma unroll
             for (int pv = 0; pv < PV; ++pv)
                 if (px.valid[pv]) {
                     float o = acc.get(v, pv) + b;
-                    if (res) o += res[px.yoff[pv]];
-                    __builtin_nontemporal_store(activate(a, o), dst + px.yoff[pv]);
+                    if (res) o += io_load1(res + px.yoff[pv]);
+                    io_store1(dst + px.yoff[pv], activate(a, o));
                 }
         }
     }
@@ -646,8 +696,8 @@ __device__ __forceinline__ void store_slots(const ConvArgs &a, const Acc<V, 1, t
         if (ch >= a.Cout) break;
         const float b = a.bias ? a.bias[ch] : 0.f;
         float o = acc.get(v, 0) + b;
-        if (residual_of(a)) o += residual_of(a)[(size_t)ch * a.P + px.yoff[0]];
-        __builtin_nontemporal_store(activate(a, o), a.Y + (size_t)ch * a.P + px.yoff[0]);
+        if (residual_of(a)) o += io_load1(residual_of(a) + (size_t)ch * a.P + px.yoff[0]);
+        io_store1(a.Y + (size_t)ch * a.P + px.yoff[0], activate(a, o));
     }
 }
 
@@ -734,6 +784,7 @@ __global__ void __launch_bounds__(1024) k_pw_resident_res(const ConvArgs a) {
     pw_resident_body<V, PV, true, true, 1, true>(a);
 }
 
+#if !ALCS_RESIDENT_ONLY
 // Mode 2: input channels streamed through LDS in chunks of KC; every wavefront owns
 // UG groups for the whole kernel and keeps their accumulators in registers.
 template <int V, int PV, int UG, bool MF, bool VEC>
@@ -1022,6 +1073,8 @@ __global__ void __launch_bounds__(512) k_conv3(const ConvArgs a) {
             store_group<V, 1, MF, false>(a, acc[u], load_work(a.work, (size_t)slot[u] * a.nchunks).group[0], px);
 }
 
+#endif  // !ALCS_RESIDENT_ONLY
+
 // ------------------------------------------------------------------ launcher
 
 constexpr int kMaxLds = 160 * 1024;
@@ -1056,6 +1109,7 @@ static kern_t pick_resident(int pv, bool vec, int gs, bool res = false) {
     return k_pw_resident<V, 1, MF, false, 1>;
 }
 
+#if !ALCS_RESIDENT_ONLY
 template <int V, bool MF>
 static kern_t pick_chunked(int pv, bool vec, int ug) {
     if (vec) {
@@ -1081,6 +1135,8 @@ static kern_t pick_conv3(int stride, int ti, int ug) {
     if (ti == 1) return pick_conv3_shape<V, 1, MF>(stride, ug);
     return pick_conv3_shape<V, 0, MF>(stride, ug);
 }
+
+#endif  // !ALCS_RESIDENT_ONLY
 
 // Tile shape of the 3x3 kernel: the share of lanes that fall on real output pixels decides,
 // with a preference for wide tiles (longer contiguous loads and stores).
@@ -1122,6 +1178,8 @@ static int set_lds_limit(kern_t k, int lds) {
 
 #if ALCS_DW_STAGE
 }  // namespace dwpw
+#elif ALCS_IO_BF16
+}  // namespace bf16io
 #elif ALCS_FUSED_EPILOGUE
 }  // namespace fused
 #endif
@@ -1130,6 +1188,8 @@ static int set_lds_limit(kern_t k, int lds) {
 using namespace alcs;
 #if ALCS_DW_STAGE
 using namespace alcs::dwpw;
+#elif ALCS_IO_BF16
+using namespace alcs::bf16io;
 #elif ALCS_FUSED_EPILOGUE
 using namespace alcs::fused;
 #endif
@@ -1144,10 +1204,10 @@ struct DwStage {
 
 // With a depthwise stage, H x W is the depthwise layer's input, `stride` its stride, and the
 // 1x1 convolution runs at stride 1 over the depthwise layer's output.
-static int launch_sparse(const alcs_packed_t *Wp, const float *X_dev, const float *bias_dev,
-                         float *Y_dev, int N, int Cin, int Cout, int H, int W, int kernel,
+static int launch_sparse(const alcs_packed_t *Wp, const io_t *X_dev, const float *bias_dev,
+                         io_t *Y_dev, int N, int Cin, int Cout, int H, int W, int kernel,
                          int stride, void *stream, hipEvent_t ev_start, hipEvent_t ev_stop,
-                         const float *residual_dev = nullptr, int activation = 0,
+                         const io_t *residual_dev = nullptr, int activation = 0,
                          const DwStage *dw = nullptr, bool decline_restaged = false) {
     if (!Wp || N < 0 || H <= 0 || W <= 0) return ALCS_E_INVALID_ARG;
     if (Cin != Wp->Cin || Cout != Wp->Cout || kernel != Wp->k) return ALCS_E_INVALID_ARG;
@@ -1156,7 +1216,8 @@ static int launch_sparse(const alcs_packed_t *Wp, const float *X_dev, const floa
     if (dw && (kernel != 1 || !dw->w || dw->act < 0 || dw->act > 2)) return ALCS_E_INVALID_ARG;
     if (N == 0) return ALCS_OK;
     if (!X_dev || !Y_dev) return ALCS_E_INVALID_ARG;
-    if (((uintptr_t)X_dev | (uintptr_t)Y_dev | (uintptr_t)residual_dev) & 15) return ALCS_E_INVALID_ARG;
+    // four consecutive elements are moved at once: 16-byte (bfloat16: 8-byte) alignment
+    if (((uintptr_t)X_dev | (uintptr_t)Y_dev | (uintptr_t)residual_dev) & (4 * sizeof(io_t) - 1)) return ALCS_E_INVALID_ARG;
     if (activation < 0 || activation > 2) return ALCS_E_INVALID_ARG;
     const int pad = dw ? 1 : (kernel - 1) / 2, kin = dw ? 3 : kernel;
     const int Ho = (H + 2 * pad - kin) / stride + 1, Wo = (W + 2 * pad - kin) / stride + 1;
@@ -1203,7 +1264,7 @@ static int launch_sparse(const alcs_packed_t *Wp, const float *X_dev, const floa
         // there are enough pixels to give every compute unit several tiles
         bool stream_ok = false;
         int s_pv = 1, s_lds = 0, s_nw = 8, s_nwg = 0;
-#if !ALCS_DW_STAGE
+#if !ALCS_RESIDENT_ONLY
         if (L.nchunks == 1 && L.GS == 1 && vec && mfma && T.path == 4) {
             const long long wbytes = (long long)L.planes * L.ncol * 16 + (long long)L.ncol * 4;
             for (int cand = 4; cand >= 1 && !stream_ok; cand >>= 1) {
@@ -1300,8 +1361,8 @@ static int launch_sparse(const alcs_packed_t *Wp, const float *X_dev, const floa
                 case 16: kern = pick_resident<16, true>(pv, vec, GS, a.residual != nullptr); break;
             }
         } else {
-#if ALCS_DW_STAGE
-            return ALCS_E_UNSUPPORTED;  // the depthwise stage fills a resident tile only
+#if ALCS_RESIDENT_ONLY
+            return ALCS_E_UNSUPPORTED;  // this build holds the resident kernels only
 #else
             mode = 2;
             pv = 1;
@@ -1325,7 +1386,7 @@ static int launch_sparse(const alcs_packed_t *Wp, const float *X_dev, const floa
 #endif
         }
     } else {
-#if ALCS_DW_STAGE
+#if ALCS_RESIDENT_ONLY
         return ALCS_E_UNSUPPORTED;
 #else
         mode = 3;
@@ -1398,6 +1459,14 @@ extern "C" int alcs_dw_sparse_conv_fused(const alcs_packed_t *Wp, const float *d
     const int Hd = (H - 1) / dw_stride + 1, Wd = (W - 1) / dw_stride + 1;
     return alcs_sparse_conv_fused(Wp, workspace_dev, bias_dev, residual_dev, Y_dev, N, Cin, Cout, Hd, Wd, 1, 1,
                                   activation, stream);
+}
+
+#elif ALCS_IO_BF16
+extern "C" int alcs_sparse_conv_bf16(const alcs_packed_t *Wp, const uint16_t *X_dev, const float *bias_dev,
+                                     const uint16_t *residual_dev, uint16_t *Y_dev, int N, int Cin, int Cout,
+                                     int H, int W, int kernel, int stride, int activation, void *stream) {
+    return launch_sparse(Wp, X_dev, bias_dev, Y_dev, N, Cin, Cout, H, W, kernel, stride, stream, nullptr, nullptr,
+                         residual_dev, activation);
 }
 
 #elif !ALCS_FUSED_EPILOGUE

@@ -17,7 +17,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "alcs.h")).read()
-    declared = set(re.findall(r"\b(alcs_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(alcs_[a-z0-9_]+)\s*\(", header))
     declared -= {"alcs_status"}
     assert declared == set(_binding.EXPORTS), declared ^ set(_binding.EXPORTS)
     lib = alcs.load_library()

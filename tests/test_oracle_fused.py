@@ -120,3 +120,16 @@ def test_sparse_conv_routes_the_epilogue():
     assert np.max(np.abs(a - b)) <= 1e-6
     with pytest.raises(KeyError):
         oracle.sparse_conv(W, mask, X, 4, act="gelu")
+
+
+def test_round_bf16_against_the_library_conversion():
+    rng = np.random.default_rng(12)
+    x = np.concatenate([rng.standard_normal(5000).astype(np.float32) * np.float32(10.0) ** rng.integers(-20, 20, 5000),
+                        np.array([0.0, -0.0, 1.0, 1.00390625, 1.01171875, np.inf, -np.inf, 3.3895314e38], np.float32)])
+    want = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    got = oracle.round_bf16(x)
+    assert got.tobytes() == want.tobytes()
+    # ties go to the even neighbour: 1 + 2^-8 is halfway between 1 and 1 + 2^-7
+    assert oracle.round_bf16(np.float32(1.00390625)) == np.float32(1.0)
+    assert oracle.round_bf16(np.float32(1.01171875)) == np.float32(1.015625)
+    assert np.isnan(oracle.round_bf16(np.float32(np.nan)))
