@@ -326,6 +326,61 @@ def report(kind, alcs, workloads, torch, np):
                    (i + 1, L.Cin, dws, L.H * dws, L.Cin, L.Cout, L.H, f, u, u / f, t_auto, t_dw, t_pw, by_f / f / 1e3,
                     100.0 * (by_u - by_f) / by_u, diff, info["pv"], info["waves"], info["workgroups"]))
             pr("| 13 MobileNetV1-shaped blocks, 90 %% block sparsity | | | %.0f | %.0f | %.2f | %.0f | | | | | | |" % (tf, tu, tu / tf, ta))
+    elif kind == "bf16":
+        # the same layers with X and Y stored as bfloat16 against float32 tensors (both through the
+        # fused-epilogue entry points with bias + ReLU; stream events over rotated buffers)
+        def one(L, seed):
+            d = workloads.make_layer(L, seed, with_bias=True)
+            p = alcs.alcs_pack_weights(d.W, d.mask, L.V)
+            b = torch.from_numpy(d.bias).cuda()
+            X = torch.from_numpy(d.X).cuda()
+            R = max(2, min(8, int(600e6 // (L.x_bytes() + L.y_bytes())) + 1))
+            X32 = [X] + [X.clone() for _ in range(R - 1)]
+            Y32 = [torch.empty((L.N, L.Cout, L.Ho, L.Wo), dtype=torch.float32, device="cuda") for _ in range(R)]
+            X16 = [x.to(torch.bfloat16) for x in X32] + [X.to(torch.bfloat16) for _ in range(R)]   # same bytes in rotation
+            Y16 = [torch.empty((L.N, L.Cout, L.Ho, L.Wo), dtype=torch.bfloat16, device="cuda") for _ in range(2 * R)]
+
+            def f32(i):
+                alcs.alcs_sparse_conv_fused(p, X32[i % R], b, None, Y32[i % R], stride=L.stride, activation="relu")
+
+            def f16(i):
+                alcs.alcs_sparse_conv_bf16(p, X16[i % (2 * R)], b, None, Y16[i % (2 * R)], stride=L.stride, activation="relu")
+
+            res = []
+            for fn in (f32, f16):
+                for i in range(3):
+                    fn(i)
+                torch.cuda.synchronize()
+                n = 6 * R
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for i in range(n):
+                    fn(i)
+                e1.record()
+                torch.cuda.synchronize()
+                res.append(e0.elapsed_time(e1) * 1e3 / n)
+            f32(0)
+            f16(0)
+            torch.cuda.synchronize()
+            diff = float((Y32[0] - Y16[0].float()).abs().max() / Y32[0].abs().max().clamp_min(1e-30))
+            wb = layer_bytes(L, p.nnzb) - L.x_bytes() - L.y_bytes()
+            by32 = layer_bytes(L, p.nnzb) + 4 * L.Cout
+            by16 = (L.x_bytes() + L.y_bytes()) // 2 + wb + 4 * L.Cout
+            p.free()
+            return res[0], res[1], by32, by16, diff
+
+        pr("| layer | float32 us | bfloat16 us | ratio | bfloat16 bytes MB | bfloat16 eff GB/s | bfloat16 HBM roofline frac | max diff (of max) |")
+        pr("|---|---|---|---|---|---|---|---|")
+        t32 = t16 = roof = 0.0
+        for i, L in enumerate(workloads.mobilenet_v1_pointwise(32, 0.9)):
+            a, b_, by32, by16, diff = one(L, workloads.seed_for(2, i))
+            t32 += a
+            t16 += b_
+            roof += by16 / (HBM_PEAK_GBS * 1e3)
+            pr("| %s %d->%d @%d | %.1f | %.1f | %.2f | %.1f | %.0f | %.3f | %.1e |" %
+               (L.name, L.Cin, L.Cout, L.H, a, b_, a / b_, by16 / 1e6, by16 / b_ / 1e3, by16 / (HBM_PEAK_GBS * 1e3) / b_, diff))
+        pr("| 13 MobileNetV1-shaped layers, batch 32, 90 %% block sparsity | %.0f | %.0f | %.2f | | | %.3f | |" %
+           (t32, t16, t32 / t16, roof / t16))
     elif kind == "project":
         # Algorithm 1 on the GPU: block scores, top-N selection, the bisection; times are wall-clock
         # around synchronised calls (the bisection synchronises once per step by design)
@@ -481,7 +536,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-batch", type=int, default=32)
     ap.add_argument("--layers-json", default=None, help="also write the per-layer table to this file")
-    ap.add_argument("--report", choices=["sweep", "resnet", "mbv2", "paths", "mbv1", "fused", "latency", "block", "project"], default=None,
+    ap.add_argument("--report", choices=["sweep", "resnet", "mbv2", "paths", "mbv1", "fused", "latency", "block", "project", "bf16"], default=None,
                     help="instead of the benchmark line, print a per-layer table for another configuration: "
                          "the sparsity sweep with the same-GPU dense conv (config 4), the ResNet-50-shaped "
                          "bottleneck convs (config 3), the MobileNetV2-shaped pointwise convs for V in "
