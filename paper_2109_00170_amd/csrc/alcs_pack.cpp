@@ -218,10 +218,14 @@ int upload(alcs_packed *p) {
 // tile while the other multiplies (512 channels measured both ways: 512->1024 @7x7
 // 16.9 -> 11.0 us, 512->512 @14x14 17.2 -> 16.6 us, 512->256 @28x28 86 -> 82 us).
 // Beyond 2559 channels, or beyond 639 for V < 4, chunks of 256 channels.
-// Kernel 3: 32 channels per chunk (the haloed tile plane is 240 to 476 floats per channel).
+// Kernel 3: 32 channels per chunk (the haloed tile plane is 240 to 476 floats per channel);
+// 64 from 512 input channels on - such layers sit on 14x14 and 7x7 images, where a workgroup's
+// time is the chain of its chunks' round trips (512->512 @7x7, N=64: 131 -> 100 us; stride 2
+// from 14x14: 141 -> 131 us), while on large images the smaller chunk's higher occupancy wins
+// (128->128 stride 2 @56x56: 104 us with 32 channels, 148 us with 64).
 static void default_tiles(int Cin, int k, int V, int *KC, int *GS) {
     *GS = 1;
-    if (k == 3) { *KC = std::min(Cin, 32); return; }
+    if (k == 3) { *KC = Cin >= 512 ? 64 : std::min(Cin, 32); return; }
     if (V >= 4 && Cin >= 512 && Cin <= 2559) { *KC = Cin; *GS = Cin <= 1279 ? 2 : 4; return; }
     if (Cin <= 639) { *KC = Cin; return; }
     *KC = 256;
