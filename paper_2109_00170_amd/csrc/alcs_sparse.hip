@@ -1399,6 +1399,10 @@ static int launch_sparse(const alcs_packed_t *Wp, const io_t *X_dev, const float
         nw = 8;
         if (T.waves > 0) nw = std::min(T.waves, 8);
         ug = pick_ug(G, nw, T.ug);
+        // At most one workgroup per compute unit and room for a second one: halve the groups
+        // per wavefront, so that two workgroups share a compute unit and one stages a chunk
+        // while the other multiplies (512->512 @7x7, N=64: 102 -> 89 us).
+        if (T.ug == 0 && ug == 4 && (long long)a.npt * ceil_div(G, nw * 4) <= kCUs && 2 * lds <= kMaxLds) ug = 2;
         a.gpt = nw * ug;
         a.ngt = ceil_div(G, a.gpt);
         switch (V) {
