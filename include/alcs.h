@@ -325,6 +325,30 @@ int alcs_project_latency(const float *scores_dev, const long long *seg_starts_ho
                          long long *N_out, double *t0_out, double *t1_out, void *workspace_dev,
                          void *stream);
 
+/*
+ * The storage format of Section 3.2.2 ("Storage format") built on the device, and a handle made
+ * from the format's arrays.
+ *
+ * alcs_pack_csr_device: the canonical arrays of alcs_packed_export - row_ptr_dev [G+1],
+ *   col_idx_dev [nnzb], vals_dev [nnzb*V] - from W_dev [Cout,Cin,kernel,kernel] and mask_dev
+ *   [G,Cin,kernel,kernel] (NULL keeps every block), all device memory owned by the caller; bit for
+ *   bit what alcs_pack_weights builds on the host.  The call synchronises `stream` once to learn
+ *   nnzb, which it stores in *nnzb_out (host, may be NULL).  With col_idx_dev = vals_dev = NULL
+ *   only row_ptr_dev is filled (a counting pass to size the other two); otherwise
+ *   capacity_blocks (the number of blocks col_idx_dev / vals_dev have room for) must be at least
+ *   nnzb, else ALCS_E_INVALID_ARG and nothing but row_ptr_dev is written.
+ *
+ * alcs_pack_from_csr: a handle like alcs_pack_weights' from canonical arrays in host memory
+ *   (copied; columns must ascend inside every group and lie below K, counts must add up:
+ *   ALCS_E_INVALID_ARG otherwise).  Together: device flags -> device arrays -> one copy of the
+ *   kept values to the host -> handle, without the dense weights leaving the device.
+ */
+int alcs_pack_csr_device(const float *W_dev, const uint8_t *mask_dev, int Cout, int Cin, int kernel,
+                         int V, int32_t *row_ptr_dev, int32_t *col_idx_dev, float *vals_dev,
+                         long long capacity_blocks, long long *nnzb_out, void *stream);
+int alcs_pack_from_csr(const int32_t *row_ptr_host, const int32_t *col_idx_host, const float *vals_host,
+                       int Cout, int Cin, int kernel, int V, alcs_packed_t **out);
+
 /* What the last alcs_sparse_conv call of this thread launched: fills up to `cap`
  * ints {mode (1 = all input channels resident in LDS, 2 = chunked, 3 = 3x3,
  * 4 = persistent double-buffered), pv, waves, workgroups, lds_bytes, group_tiles,

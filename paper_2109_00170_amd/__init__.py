@@ -15,6 +15,9 @@ from ._binding import (  # noqa: F401
     alcs_last_launch,
     alcs_latency_estimate,
     alcs_network_latency,
+    alcs_pack_csr_device,
+    alcs_pack_from_csr,
+    alcs_pack_on_device,
     alcs_pack_weights,
     alcs_project_latency,
     alcs_set_tuning,

@@ -16,7 +16,7 @@ EXPORTS = [
     "alcs_packed_on_device", "alcs_packed_export", "alcs_packed_selfcheck", "alcs_packed_free",
     "alcs_sparse_conv", "alcs_sparse_conv_timed", "alcs_sparse_conv_fused", "alcs_dense_conv", "alcs_set_tuning",
     "alcs_depthwise_conv", "alcs_dw_sparse_conv_fused", "alcs_sparse_conv_bf16", "alcs_block_scores", "alcs_select_workspace_bytes",
-    "alcs_topn_mask", "alcs_project_latency",
+    "alcs_topn_mask", "alcs_project_latency", "alcs_pack_csr_device", "alcs_pack_from_csr",
     "alcs_last_launch", "alcs_latency_estimate", "alcs_network_latency",
 ]
 
@@ -448,3 +448,56 @@ def alcs_project_latency(scores, seg_starts, V_per_layer, tables, tau, budget, e
     if rc != 0:
         raise AlcsError(rc, "alcs_project_latency")
     return int(N_out.value), mask, float(t0.value), float(t1.value)
+
+
+def alcs_pack_csr_device(W_dev, mask_dev, V: int, stream=None):
+    """The grouped CSR of Section 3.2.2 built on the device: returns (row_ptr int32 [G+1],
+    col_idx int32 [nnzb], vals float32 [nnzb*V]) as device tensors.  mask_dev: uint8 device tensor
+    [G,Cin,k,k] (or flat) or None."""
+    import torch
+    Cout, Cin, k, _ = W_dev.shape
+    G = (Cout + V - 1) // V
+    if mask_dev is not None and mask_dev.numel() != G * Cin * k * k:
+        raise ValueError("mask must have %d entries" % (G * Cin * k * k))
+    lib = load_library()
+    row_ptr = torch.empty((G + 1,), dtype=torch.int32, device=W_dev.device)
+    nnzb = ctypes.c_longlong()
+    mp = _dev_ptr(mask_dev, "mask", "torch.uint8")
+    args = (_dev_ptr(W_dev, "W"), mp, Cout, Cin, k, int(V), _dev_ptr(row_ptr, "row_ptr", "torch.int32"))
+    rc = lib.alcs_pack_csr_device(*args, None, None, ctypes.c_longlong(0), ctypes.byref(nnzb), _stream_ptr(stream))
+    if rc != 0:
+        raise AlcsError(rc, "alcs_pack_csr_device")
+    n = int(nnzb.value)
+    col_idx = torch.empty((n,), dtype=torch.int32, device=W_dev.device)
+    vals = torch.empty((n * V,), dtype=torch.float32, device=W_dev.device)
+    if n:
+        rc = lib.alcs_pack_csr_device(*args, _dev_ptr(col_idx, "col_idx", "torch.int32"), _dev_ptr(vals, "vals"),
+                                      ctypes.c_longlong(n), ctypes.byref(nnzb), _stream_ptr(stream))
+        if rc != 0:
+            raise AlcsError(rc, "alcs_pack_csr_device")
+    return row_ptr, col_idx, vals
+
+
+def alcs_pack_from_csr(row_ptr, col_idx, vals, Cout: int, Cin: int, kernel: int, V: int) -> Packed:
+    """A handle from the canonical arrays (numpy, host)."""
+    row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int32)
+    col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
+    vals = np.ascontiguousarray(vals, dtype=np.float32)
+    G = (Cout + V - 1) // V
+    if row_ptr.size != G + 1 or col_idx.size != int(row_ptr[-1]) or vals.size != col_idx.size * V:
+        raise ValueError("array sizes do not fit the layer")
+    out = ctypes.c_void_p()
+    vp = ctypes.c_void_p
+    rc = load_library().alcs_pack_from_csr(vp(row_ptr.ctypes.data), vp(col_idx.ctypes.data) if col_idx.size else None,
+                                           vp(vals.ctypes.data) if vals.size else None, int(Cout), int(Cin), int(kernel),
+                                           int(V), ctypes.byref(out))
+    if rc != 0:
+        raise AlcsError(rc, "alcs_pack_from_csr")
+    return Packed(out, Cout, Cin, kernel, int(V))
+
+
+def alcs_pack_on_device(W_dev, mask_dev, V: int) -> Packed:
+    """Device weights and flags -> device CSR -> one copy of the kept values to the host -> handle."""
+    Cout, Cin, k, _ = W_dev.shape
+    row_ptr, col_idx, vals = alcs_pack_csr_device(W_dev, mask_dev, V)
+    return alcs_pack_from_csr(row_ptr.cpu().numpy(), col_idx.cpu().numpy(), vals.cpu().numpy(), Cout, Cin, k, V)

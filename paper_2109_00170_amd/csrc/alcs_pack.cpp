@@ -235,6 +235,31 @@ static void default_tiles(int Cin, int k, int V, int *KC, int *GS) {
 
 using namespace alcs;
 
+extern "C" void alcs_packed_free(alcs_packed_t *p);
+
+// The tuned device layout and its upload, once the canonical arrays of the handle are in place.
+static int finish_pack(alcs_packed *p, int rc, alcs_packed_t **out) {
+    if (rc == ALCS_OK) {
+        int KC = 0, GS = 1;
+        default_tiles(p->Cin, p->k, p->V, &KC, &GS);
+        if (tuning().kc > 0) { KC = std::min(tuning().kc, p->Cin); GS = 1; }
+        if (tuning().gs > 0 && p->k == 1 && p->V >= 4 && KC == p->Cin &&
+            (long long)(p->Cin + 1) * (kRowBytes1 / tuning().gs) <= 160 * 1024)
+            GS = tuning().gs;
+        rc = build_layout(p, KC, GS);
+    }
+    if (rc == ALCS_OK) {
+        rc = upload(p);
+        if (rc == ALCS_E_NO_DEVICE) rc = ALCS_OK;  // host-only handle
+    }
+    if (rc != ALCS_OK) {
+        alcs_packed_free(p);
+        return rc;
+    }
+    *out = p;
+    return ALCS_OK;
+}
+
 extern "C" {
 
 const char *alcs_strerror(int status) {
@@ -305,25 +330,47 @@ int alcs_pack_weights(const float *W_host, const uint8_t *mask_host, int Cout, i
     } catch (const std::bad_alloc &) {
         rc = ALCS_E_ALLOC;
     }
-    if (rc == ALCS_OK) {
-        int KC = 0, GS = 1;
-        default_tiles(Cin, kernel, V, &KC, &GS);
-        if (tuning().kc > 0) { KC = std::min(tuning().kc, Cin); GS = 1; }
-        if (tuning().gs > 0 && kernel == 1 && V >= 4 && KC == Cin &&
-            (long long)(Cin + 1) * (kRowBytes1 / tuning().gs) <= 160 * 1024)
-            GS = tuning().gs;
-        rc = build_layout(p, KC, GS);
+    return finish_pack(p, rc, out);
+}
+
+int alcs_pack_from_csr(const int32_t *row_ptr_host, const int32_t *col_idx_host, const float *vals_host,
+                       int Cout, int Cin, int kernel, int V, alcs_packed_t **out) {
+    if (out) *out = nullptr;
+    if (!row_ptr_host || !out || Cout <= 0 || Cin <= 0) return ALCS_E_INVALID_ARG;
+    if (kernel != 1 && kernel != 3) return ALCS_E_UNSUPPORTED;
+    if (V != 1 && V != 2 && V != 4 && V != 8 && V != 16) return ALCS_E_UNSUPPORTED;
+    const int64_t K64 = (int64_t)Cin * kernel * kernel;
+    if (K64 > (1 << 24) || Cout > (1 << 24)) return ALCS_E_UNSUPPORTED;
+    const int K = (int)K64, G = (Cout + V - 1) / V;
+    if ((int64_t)G * K > (int64_t)INT32_MAX - 1024) return ALCS_E_UNSUPPORTED;
+    // the arrays must be the canonical form: counts add up, columns ascend inside a group
+    if (row_ptr_host[0] != 0) return ALCS_E_INVALID_ARG;
+    for (int g = 0; g < G; ++g) {
+        const int64_t lo = row_ptr_host[g], hi = row_ptr_host[g + 1];
+        if (hi < lo || hi - lo > K) return ALCS_E_INVALID_ARG;
     }
-    if (rc == ALCS_OK) {
-        rc = upload(p);
-        if (rc == ALCS_E_NO_DEVICE) rc = ALCS_OK;  // host-only handle
+    const int64_t nnzb = row_ptr_host[G];
+    if (nnzb > 0 && (!col_idx_host || !vals_host)) return ALCS_E_INVALID_ARG;
+    for (int g = 0; g < G; ++g)
+        for (int64_t t = row_ptr_host[g]; t < row_ptr_host[g + 1]; ++t) {
+            const int32_t col = col_idx_host[t];
+            if (col < 0 || col >= K || (t > row_ptr_host[g] && col <= col_idx_host[t - 1])) return ALCS_E_INVALID_ARG;
+        }
+    alcs_packed *p = new (std::nothrow) alcs_packed();
+    if (!p) return ALCS_E_ALLOC;
+    p->Cout = Cout; p->Cin = Cin; p->k = kernel; p->V = V; p->G = G; p->K = K;
+    int rc = ALCS_OK;
+    try {
+        p->row_ptr.assign(row_ptr_host, row_ptr_host + G + 1);
+        p->nnzb = nnzb;
+        p->col_idx.assign(col_idx_host, col_idx_host + nnzb);
+        p->vals.resize((size_t)nnzb * V);
+        if (nnzb) std::memcpy(p->vals.data(), vals_host, (size_t)nnzb * V * sizeof(float));
+        for (int g = 0; g < G; ++g) p->max_count = std::max(p->max_count, p->row_ptr[g + 1] - p->row_ptr[g]);
+    } catch (const std::bad_alloc &) {
+        rc = ALCS_E_ALLOC;
     }
-    if (rc != ALCS_OK) {
-        alcs_packed_free(p);
-        return rc;
-    }
-    *out = p;
-    return ALCS_OK;
+    return finish_pack(p, rc, out);
 }
 
 int alcs_packed_info(const alcs_packed_t *p, int *G, int *K, int64_t *nnzb) {

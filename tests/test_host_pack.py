@@ -154,3 +154,30 @@ def test_python_binding_rejects_bad_mask_shape():
         alcs.alcs_pack_weights(W, np.ones((3, 4, 1, 1), np.uint8), 4)
     with pytest.raises(alcs.AlcsError):
         alcs.alcs_pack_weights(W, None, 5)
+
+
+def test_handle_from_canonical_arrays_equals_handle_from_weights():
+    import workloads
+    rng = np.random.default_rng(77)
+    for (Cout, Cin, k, V, sp) in [(10, 6, 3, 4, 0.6), (8, 700, 1, 2, 0.9), (33, 5, 1, 16, 0.3), (4, 4, 1, 4, 1.0)]:
+        W = rng.standard_normal((Cout, Cin, k, k)).astype(np.float32)
+        mask = workloads.mask_exact((Cout + V - 1) // V, Cin, k, sp, rng)
+        rp, ci, va = oracle.pack(W, mask, V)
+        a = alcs.alcs_pack_from_csr(rp, ci, va, Cout, Cin, k, V)
+        b = alcs.alcs_pack_weights(W, mask, V)
+        assert a.nnzb == b.nnzb and a.selfcheck() == 0
+        for x, y in zip(a.export(), b.export()):
+            assert x.tobytes() == y.tobytes()
+        a.free()
+        b.free()
+    # arrays that are not the canonical form are refused
+    W = rng.standard_normal((8, 8, 1, 1)).astype(np.float32)
+    rp, ci, va = oracle.pack(W, np.ones((2, 8, 1, 1), np.uint8), 4)
+    bad = ci.copy()
+    bad[0], bad[1] = bad[1], bad[0]
+    with pytest.raises(alcs.AlcsError):
+        alcs.alcs_pack_from_csr(rp, bad, va, 8, 8, 1, 4)
+    bad = ci.copy()
+    bad[3] = 8
+    with pytest.raises(alcs.AlcsError):
+        alcs.alcs_pack_from_csr(rp, bad, va, 8, 8, 1, 4)
