@@ -391,6 +391,7 @@ def report(kind, alcs, workloads, torch, np):
                 return [(L.Cout, L.Cin, 1) for L in workloads.mobilenet_v1_pointwise(1, 0.0)]
             return [(L.Cout, L.Cin, L.k) for L in workloads.resnet50_bottlenecks(1, 0.0, distinct=False)]
 
+        notes = []
         pr("| network | weights | blocks (V=4) | scores us | scores eff GB/s | select N = half us | select eff GB/s | "
            "projection ms | bisection steps | kept blocks | estimate vs budget |")
         pr("|---|---|---|---|---|---|---|---|---|---|---|")
@@ -444,6 +445,35 @@ def report(kind, alcs, workloads, torch, np):
             pr("| %s | %.2f M | %.2f M | %.1f | %.0f | %.0f | %.0f | %.2f | <= %d | %d (%.1f %%) | %.1f <= %.1f <= %.1f |" %
                (title, nw / 1e6, n / 1e6, t_sc, by_sc / t_sc / 1e3, t_sel, by_sel / t_sel / 1e3, t_proj, steps, N,
                 100.0 * N / n, lo, budget, hi))
+            # from the projection's flags to handles: storage format built on the device against the
+            # host packer (which needs the dense weights and the flags in host memory)
+            masks = [mask[int(a):int(b)] for a, b in zip(starts, starts[1:])]
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            csr = [alcs.alcs_pack_csr_device(W, m, V) for W, m in zip(Ws, masks)]
+            torch.cuda.synchronize()
+            t_csr = (time.perf_counter() - t0) * 1e3
+            t0 = time.perf_counter()
+            hs = [alcs.alcs_pack_from_csr(r.cpu().numpy(), c.cpu().numpy(), v.cpu().numpy(), co, ci, k, V)
+                  for (r, c, v), (co, ci, k) in zip(csr, shapes)]
+            t_from = (time.perf_counter() - t0) * 1e3
+            for h in hs:
+                h.free()
+            t0 = time.perf_counter()
+            Wh = [W.cpu().numpy() for W in Ws]
+            mh = [m.cpu().numpy().reshape((co + V - 1) // V, ci, k, k) for m, (co, ci, k) in zip(masks, shapes)]
+            t_down = (time.perf_counter() - t0) * 1e3
+            t0 = time.perf_counter()
+            hs = [alcs.alcs_pack_weights(W, m, V) for W, m in zip(Wh, mh)]
+            t_host = (time.perf_counter() - t0) * 1e3
+            for h in hs:
+                h.free()
+            notes.append("%s: storage format on the device %.2f ms (%d layers, 2 calls each), arrays to the host + "
+                         "layout + upload %.2f ms; host path: weights and flags to the host %.2f ms, alcs_pack_weights "
+                         "%.2f ms." % (title, t_csr, len(shapes), t_from, t_down, t_host))
+        pr("")
+        for line in notes:
+            pr(line)
     elif kind == "latency":
         # Section 3.3 of the paper on this GPU: time every layer at block densities 0, 0.1, ..., 1
         # (eleven runs per layer), interpolate linearly in the number of non-zero weights
