@@ -8,11 +8,12 @@
 // index first among equal scores" is plain integer order.  The N-th largest key is found by a
 // radix select: eight passes, most significant byte first, each a histogram of the byte over
 // the keys that match the bytes chosen so far (per-workgroup histograms in LDS, merged with
-// atomics), after which one small kernel walks the 256 bins from the top and fixes the next
-// byte.  A last pass writes the keep / drop flags and counts the kept blocks per layer; the
-// host loop of the bisection reads only those counts.  All state lives in a caller-provided
-// workspace; every pass streams the 4-byte scores once, so a selection moves 9 x 4 bytes per
-// block.
+// atomics); the next launch starts by walking the 256 bins from the top and fixing that byte
+// (every workgroup for itself: a kernel boundary is the only synchronisation).  A last pass
+// writes the keep / drop flags and counts the kept blocks per layer; the host loop of the
+// bisection reads only those counts.  All state lives in a caller-provided workspace; a
+// selection is ten launches (one to set up, eight passes, one to emit) that stream the 4-byte
+// scores nine times.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -24,10 +25,14 @@
 
 namespace alcs {
 
+constexpr int kPasses = 8;  // bytes of a key
+
+// hist[p] = histogram of pass p; prefix[p], remaining[p] = the bytes of the N-th largest key fixed
+// before pass p and its rank (1 = largest) among the keys that share them.
 struct SelectState {
-    unsigned long long hist[256];
-    unsigned long long prefix;     // the bytes of the N-th largest key fixed so far
-    unsigned long long remaining;  // its rank among the keys that match the prefix (1 = largest)
+    unsigned long long hist[kPasses][256];
+    unsigned long long prefix[kPasses + 1];
+    unsigned long long remaining[kPasses + 1];
 };
 
 __device__ __forceinline__ unsigned long long key_of(const float *scores, unsigned long long i) {
@@ -58,54 +63,69 @@ __global__ void __launch_bounds__(256) k_block_scores(const float *W, float *sco
 
 __global__ void k_select_init(SelectState *st, unsigned long long N, unsigned long long *counts, int n_seg) {
     const int t = threadIdx.x;
-    if (t < 256) st->hist[t] = 0;
-    if (t == 0) { st->prefix = 0; st->remaining = N; }
+    for (int p = 0; p < kPasses; ++p)
+        if (t < 256) st->hist[p][t] = 0;
+    if (t == 0) { st->prefix[0] = 0; st->remaining[0] = N; }
     for (int s = t; s < n_seg; s += blockDim.x) counts[s] = 0;
 }
 
-// One pass: byte `shift / 8` of the keys whose higher bytes equal the prefix.
+// What pass p - 1 decided, worked out by every workgroup of the next launch for itself from the
+// finished histogram (a kernel boundary is the only synchronisation): walk the 256 bins from
+// the largest byte down until `remaining` keys are covered and fix that byte.  Workgroup 0
+// also records the result for the launch after this one.  Called by all threads; p >= 1.
+__device__ __forceinline__ void decide(SelectState *st, int p, unsigned long long &prefix, unsigned long long &remaining) {
+    __shared__ unsigned long long bins[256];
+    __shared__ unsigned long long out[2];
+    bins[threadIdx.x] = st->hist[p - 1][threadIdx.x];
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned long long rem = st->remaining[p - 1];
+        unsigned long long above = 0;
+        int b = 255;
+        for (; b > 0; --b) {
+            if (above + bins[b] >= rem) break;
+            above += bins[b];
+        }
+        out[0] = st->prefix[p - 1] | ((unsigned long long)b << (56 - 8 * (p - 1)));
+        out[1] = rem - above;
+        if (blockIdx.x == 0 && blockIdx.y == 0) { st->prefix[p] = out[0]; st->remaining[p] = out[1]; }
+    }
+    __syncthreads();
+    prefix = out[0];
+    remaining = out[1];
+}
+
+// Pass p: byte 7 - p of the keys whose higher bytes equal the prefix.
 __global__ void __launch_bounds__(256) k_select_hist(const float *scores, unsigned long long n, SelectState *st,
-                                                     int shift) {
+                                                     int p) {
     __shared__ unsigned int h[256];
     h[threadIdx.x] = 0;
-    __syncthreads();
-    const unsigned long long prefix = st->prefix;
+    unsigned long long prefix = 0, remaining = 0;
+    if (p > 0) decide(st, p, prefix, remaining);
+    else __syncthreads();
+    const int shift = 56 - 8 * p;
     const unsigned long long stride = (unsigned long long)gridDim.x * 256;
     for (unsigned long long i = (unsigned long long)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
         const unsigned long long key = key_of(scores, i);
-        const bool match = shift == 56 || ((key ^ prefix) >> (shift + 8)) == 0;
+        const bool match = p == 0 || ((key ^ prefix) >> (shift + 8)) == 0;
         if (match) atomicAdd(&h[(key >> shift) & 255], 1u);
     }
     __syncthreads();
     const unsigned int c = h[threadIdx.x];
-    if (c) atomicAdd(&st->hist[threadIdx.x], (unsigned long long)c);
-}
-
-// Walk the bins from the largest byte down until `remaining` keys are covered; fix that byte.
-__global__ void k_select_pick(SelectState *st, int shift) {
-    if (threadIdx.x != 0) return;
-    unsigned long long rem = st->remaining, above = 0;
-    int b = 255;
-    for (; b > 0; --b) {
-        const unsigned long long c = st->hist[b];
-        if (above + c >= rem) break;
-        above += c;
-    }
-    st->prefix |= (unsigned long long)b << shift;
-    st->remaining = rem - above;
-    for (int i = 0; i < 256; ++i) st->hist[i] = 0;
+    if (c) atomicAdd(&st->hist[p][threadIdx.x], (unsigned long long)c);
 }
 
 // Keep flags and kept blocks per segment (layer).  mode 0: keep keys >= the selected key,
 // 1: keep nothing, 2: keep everything.  blockIdx.y = segment.
 __global__ void __launch_bounds__(256) k_select_emit(const float *scores, const long long *seg_starts,
-                                                     const SelectState *st, int mode, uint8_t *mask,
+                                                     SelectState *st, int mode, uint8_t *mask,
                                                      unsigned long long *counts) {
     __shared__ unsigned int total;
     if (threadIdx.x == 0) total = 0;
-    __syncthreads();
+    unsigned long long kth = 0, rank = 0;
+    if (mode == 0) decide(st, kPasses, kth, rank);  // the last byte
+    else __syncthreads();
     const unsigned long long lo = (unsigned long long)seg_starts[blockIdx.y], hi = (unsigned long long)seg_starts[blockIdx.y + 1];
-    const unsigned long long kth = st->prefix;
     const unsigned long long stride = (unsigned long long)gridDim.x * 256;
     unsigned int mine = 0;
     for (unsigned long long i = lo + (unsigned long long)blockIdx.x * 256 + threadIdx.x; i < hi; i += stride) {
@@ -153,10 +173,8 @@ static int select_async(const float *scores, long long n, long long N, const Wor
     const int blocks = (int)std::min<long long>(kSelectBlocks, (n + 255) / 256);
     int mode = N <= 0 ? 1 : N >= n ? 2 : 0;
     if (mode == 0) {
-        for (int shift = 56; shift >= 0; shift -= 8) {
-            hipLaunchKernelGGL(k_select_hist, dim3(blocks), dim3(256), 0, stream, scores, (unsigned long long)n, w.st, shift);
-            hipLaunchKernelGGL(k_select_pick, dim3(1), dim3(64), 0, stream, w.st, shift);
-        }
+        for (int p = 0; p < kPasses; ++p)
+            hipLaunchKernelGGL(k_select_hist, dim3(blocks), dim3(256), 0, stream, scores, (unsigned long long)n, w.st, p);
     }
     hipLaunchKernelGGL(k_select_emit, dim3(std::max(1, std::min(blocks, 256)), n_seg), dim3(256), 0, stream, scores,
                        w.seg_starts, w.st, mode, mask, w.counts);
