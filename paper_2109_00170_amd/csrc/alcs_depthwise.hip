@@ -21,6 +21,7 @@ struct DwArgs {
     float *Z;           // [N, C, Ho, Wo]
     long long planes;   // N * C
     int nchunks;        // 64-pixel chunks per plane
+    unsigned wg_per_xcd, total_wgs;
     int C, H, W, Ho, Wo, P, Pin, stride, act;
 };
 
@@ -34,8 +35,14 @@ template <int MODE>
 __global__ void __launch_bounds__(256) k_depthwise(const DwArgs a) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const unsigned chunk = blockIdx.x % (unsigned)a.nchunks;
-    const long long pg = (long long)(blockIdx.x / (unsigned)a.nchunks) * 4 + wave;  // plane group
+    // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Renumber them so that
+    // neighbouring 64-pixel chunks of the same planes - which share two of their three input rows -
+    // run on one XCD and find those rows in its L2 (without this every row came from HBM about
+    // three times: 42 us instead of 25 us for 32 channels at 112x112, batch 32).
+    const unsigned logical = (blockIdx.x % 8u) * a.wg_per_xcd + blockIdx.x / 8u;
+    if (logical >= a.total_wgs) return;
+    const unsigned chunk = logical % (unsigned)a.nchunks;
+    const long long pg = (long long)(logical / (unsigned)a.nchunks) * 4 + wave;  // plane group
     const int po = (int)chunk * 64 + lane;
     const bool valid = po < a.P;
     const int ho = valid ? po / a.Wo : 0, wo = valid ? po - ho * a.Wo : 0;
@@ -52,18 +59,26 @@ __global__ void __launch_bounds__(256) k_depthwise(const DwArgs a) {
         if (a.act == 2) acc = fminf(acc, 6.f);
         if (valid) __builtin_nontemporal_store(acc, a.Z + (size_t)plane * a.P + po);
     };
+    // Software pipeline over pairs of planes: the loads of the next pair are issued before the
+    // current pair is finished, so up to four planes' taps are in flight per wavefront (the
+    // kernel is bound by the latency of these round trips, not by bytes or arithmetic).
+    typedef typename DwTaps<MODE, 64>::Raw Raw;
+    const float *xb = a.X + (size_t)p0 * a.Pin;
+    const long long left = a.planes - p0;            // planes this wavefront owns (>= 1)
+    const int np = left < kPlanesPerWave ? (int)left : kPlanesPerWave;
+    auto chan = [&](int i) { return __builtin_amdgcn_readfirstlane((c0 + i) % a.C); };  // wave-uniform
+    Raw x0 = {}, x1 = {}, y0 = {}, y1 = {};
+    taps.load(xb, x0);
+    if (np > 1) taps.load(xb + (size_t)a.Pin, x1);
 #pragma unroll
     for (int i = 0; i < kPlanesPerWave; i += 2) {
-        const long long pa = p0 + i, pb = p0 + i + 1;
-        if (pa >= a.planes) break;  // wave-uniform
-        const int ca = c0, cb = c0 + 1 == a.C ? 0 : c0 + 1;
-        c0 = cb + 1 == a.C ? 0 : cb + 1;
-        typename DwTaps<MODE, 64>::Raw x0, x1;
-        taps.load(a.X + (size_t)pa * a.Pin, x0);
-        const bool two = pb < a.planes;
-        if (two) taps.load(a.X + (size_t)pb * a.Pin, x1);
-        finish(pa, ca, x0);
-        if (two) finish(pb, cb, x1);
+        if (i >= np) break;  // wave-uniform
+        if (i + 2 < np) taps.load(xb + (size_t)(i + 2) * a.Pin, y0);
+        if (i + 3 < np) taps.load(xb + (size_t)(i + 3) * a.Pin, y1);
+        finish(p0 + i, chan(i), x0);
+        if (i + 1 < np) finish(p0 + i + 1, chan(i + 1), x1);
+        x0 = y0;
+        x1 = y1;
     }
 }
 
@@ -91,10 +106,12 @@ extern "C" int alcs_depthwise_conv(const float *dw_weights_dev, const float *X_d
     a.stride = stride; a.act = activation;
     const long long groups = (a.planes + 4 * kPlanesPerWave - 1) / (4 * kPlanesPerWave);
     const long long blocks = groups * a.nchunks;
-    if (blocks > INT32_MAX) return ALCS_E_UNSUPPORTED;
+    if (blocks > INT32_MAX - 8) return ALCS_E_UNSUPPORTED;
+    a.total_wgs = (unsigned)blocks;
+    a.wg_per_xcd = (unsigned)((blocks + 7) / 8);
     const int mode = dw_mode_for(stride, W, X_dev);
     void (*kern)(const DwArgs) = mode == kDwPair ? k_depthwise<kDwPair> : k_depthwise<kDwNine>;
-    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, a);
+    hipLaunchKernelGGL(kern, dim3(a.wg_per_xcd * 8), dim3(256), 0, (hipStream_t)stream, a);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_hip_error((int)e); return ALCS_E_HIP; }
     return ALCS_OK;
