@@ -82,6 +82,78 @@ __global__ void __launch_bounds__(256) k_depthwise(const DwArgs a) {
     }
 }
 
+// Stride 1 and a width that is a multiple of 4: a lane owns four consecutive pixels of a row, so
+// every tap row is one aligned 16-byte load plus its left and right neighbour, and the outputs
+// leave as one 16-byte store - a quarter of the memory instructions of the kernel above.  The
+// neighbours beyond the image are read from the row's own end (in bounds) and zeroed.
+typedef float dw_f4 __attribute__((ext_vector_type(4)));
+
+constexpr int kPlanesPerWaveQuad = 2;  // few planes per wavefront: four pixels per lane leave few wavefronts
+
+__global__ void __launch_bounds__(256) k_depthwise_quad(const DwArgs a) {
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const unsigned logical = (blockIdx.x % 8u) * a.wg_per_xcd + blockIdx.x / 8u;
+    if (logical >= a.total_wgs) return;
+    const unsigned chunk = logical % (unsigned)a.nchunks;
+    const long long pg = (long long)(logical / (unsigned)a.nchunks) * 4 + wave;
+    const long long p0 = pg * kPlanesPerWaveQuad;
+    if (p0 >= a.planes) return;  // the whole wavefront
+    const int po = ((int)chunk * 64 + lane) * 4;
+    const bool valid = po < a.P;
+    const int ho = valid ? po / a.W : 0, wo = valid ? po - ho * a.W : 0;   // stride 1: Wo == W
+    bool rok[3];
+    uint32_t roff[3], loff[3], qoff[3];
+#pragma unroll
+    for (int r = 0; r < 3; ++r) {
+        const int hi = ho - 1 + r;
+        rok[r] = valid && hi >= 0 && hi < a.H;
+        const uint32_t at = (uint32_t)(min(max(hi, 0), a.H - 1) * a.W + wo);
+        roff[r] = at * 4u;
+        loff[r] = (wo > 0 ? at - 1u : at) * 4u;
+        qoff[r] = (wo + 4 < a.W ? at + 4u : at + 3u) * 4u;
+    }
+    const bool hasl = wo > 0, hasr = wo + 4 < a.W;
+    const auto wts = reinterpret_cast<const float __attribute__((address_space(4))) *>((uintptr_t)a.D);
+    const auto bs = reinterpret_cast<const float __attribute__((address_space(4))) *>((uintptr_t)a.bias);
+    const int c0 = __builtin_amdgcn_readfirstlane((int)(p0 % a.C));
+    const long long left = a.planes - p0;
+    const int np = left < kPlanesPerWaveQuad ? (int)left : kPlanesPerWaveQuad;
+#pragma unroll
+    for (int i = 0; i < kPlanesPerWaveQuad; ++i) {
+        if (i >= np) break;  // wave-uniform
+        const int c = __builtin_amdgcn_readfirstlane((c0 + i) % a.C);
+        const char *b = reinterpret_cast<const char *>(a.X + (size_t)(p0 + i) * a.Pin);
+        float x[3][6];
+#pragma unroll
+        for (int r = 0; r < 3; ++r) {
+            const dw_f4 m = *reinterpret_cast<const dw_f4 *>(b + roff[r]);
+            const float l = *reinterpret_cast<const float *>(b + loff[r]);
+            const float q = *reinterpret_cast<const float *>(b + qoff[r]);
+            x[r][0] = (rok[r] && hasl) ? l : 0.f;
+            x[r][1] = rok[r] ? m[0] : 0.f;
+            x[r][2] = rok[r] ? m[1] : 0.f;
+            x[r][3] = rok[r] ? m[2] : 0.f;
+            x[r][4] = rok[r] ? m[3] : 0.f;
+            x[r][5] = (rok[r] && hasr) ? q : 0.f;
+        }
+        const float bias = a.bias ? bs[c] : 0.f;
+        dw_f4 o;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float acc = bias;   // taps in the order (r, t) ascending, as in the other forms
+#pragma unroll
+            for (int r = 0; r < 3; ++r)
+#pragma unroll
+                for (int t = 0; t < 3; ++t) acc = fmaf(wts[c * 9 + r * 3 + t], x[r][j + t], acc);
+            if (a.act >= 1) acc = fmaxf(acc, 0.f);
+            if (a.act == 2) acc = fminf(acc, 6.f);
+            o[j] = acc;
+        }
+        if (valid) __builtin_nontemporal_store(o, reinterpret_cast<dw_f4 *>(a.Z + (size_t)(p0 + i) * a.P + po));
+    }
+}
+
 }  // namespace alcs
 
 using namespace alcs;
@@ -101,16 +173,18 @@ extern "C" int alcs_depthwise_conv(const float *dw_weights_dev, const float *X_d
     DwArgs a{};
     a.D = dw_weights_dev; a.X = X_dev; a.bias = bias_dev; a.Z = Y_dev;
     a.planes = (long long)N * C;
-    a.nchunks = (int)((P + 63) / 64);
+    const bool quad = stride == 1 && (W % 4) == 0 && ((((uintptr_t)X_dev) | ((uintptr_t)Y_dev)) & 15) == 0;
+    a.nchunks = (int)((P + (quad ? 255 : 63)) / (quad ? 256 : 64));
     a.C = C; a.H = H; a.W = W; a.Ho = Ho; a.Wo = Wo; a.P = (int)P; a.Pin = (int)Pin;
     a.stride = stride; a.act = activation;
-    const long long groups = (a.planes + 4 * kPlanesPerWave - 1) / (4 * kPlanesPerWave);
+    const int ppw = quad ? kPlanesPerWaveQuad : kPlanesPerWave;
+    const long long groups = (a.planes + 4 * ppw - 1) / (4 * ppw);
     const long long blocks = groups * a.nchunks;
     if (blocks > INT32_MAX - 8) return ALCS_E_UNSUPPORTED;
     a.total_wgs = (unsigned)blocks;
     a.wg_per_xcd = (unsigned)((blocks + 7) / 8);
     const int mode = dw_mode_for(stride, W, X_dev);
-    void (*kern)(const DwArgs) = mode == kDwPair ? k_depthwise<kDwPair> : k_depthwise<kDwNine>;
+    void (*kern)(const DwArgs) = quad ? k_depthwise_quad : mode == kDwPair ? k_depthwise<kDwPair> : k_depthwise<kDwNine>;
     hipLaunchKernelGGL(kern, dim3(a.wg_per_xcd * 8), dim3(256), 0, (hipStream_t)stream, a);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_hip_error((int)e); return ALCS_E_HIP; }

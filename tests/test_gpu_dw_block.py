@@ -34,7 +34,7 @@ def dw_inputs(C, N, H, W, seed, x_scale=1.5):
 @pytest.mark.parametrize("act", [None, "relu", "relu6"])
 @pytest.mark.parametrize("stride", [1, 2])
 @pytest.mark.parametrize("C,N,H,W", [(5, 3, 17, 16), (64, 2, 7, 7), (3, 1, 1, 1), (2, 2, 1, 9), (130, 1, 33, 2),
-                                     (16, 2, 56, 56)])
+                                     (16, 2, 56, 56), (3, 2, 1, 4), (7, 1, 5, 8), (33, 3, 9, 20), (2, 1, 70, 4)])
 def test_depthwise_layer(C, N, H, W, stride, act):
     import torch
     D, X, b = dw_inputs(C, N, H, W, 11 * C + H + stride)
