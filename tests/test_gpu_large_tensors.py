@@ -70,3 +70,115 @@ def test_conv3x3_input_beyond_2_31_elements(entry):
     # 9 x 64 x 2048 x 2048 = 2.42e9 input elements; stride 2 output 1024 x 1024
     L = workloads.Layer("big_c3", 64, 8, 2048, 2048, k=3, stride=2, N=9, V=4, sparsity=0.9, w_std=0.1)
     big_check(L, 8102, entry)
+
+
+def test_depthwise_input_beyond_2_31_elements():
+    """9 x 64 x 2048 x 2048 = 2.42e9 input elements (9.7 GB), stride 2: plane offsets need 64 bits.
+    Four whole planes, among them the very last one, are recomputed by the oracle."""
+    import torch
+    N, C, H, W, stride = 9, 64, 2048, 2048, 2
+    free_b, _ = torch.cuda.mem_get_info()
+    need = 4 * N * C * (H * W + (H // 2) * (W // 2)) + (1 << 30)
+    if free_b < need:
+        pytest.skip("needs %.1f GB of device memory" % (need / 1e9))
+    rng = np.random.default_rng(8103)
+    D = (rng.standard_normal((C, 3, 3)) * 0.4).astype(np.float32)
+    b = rng.standard_normal(C).astype(np.float32)
+    X = torch.empty((N, C, H, W), dtype=torch.float32, device="cuda")
+    planes = [(0, 0), (3, 17), (8, 0), (8, 63)]
+    host = {}
+    for n in range(N):                                 # filled image by image: no 9.7 GB host array
+        X[n].normal_(0.0, 1.5)
+    for (n, c) in planes:
+        host[(n, c)] = X[n, c].cpu().numpy()
+    Y = torch.full((N, C, H // 2, W // 2), float("nan"), dtype=torch.float32, device="cuda")
+    alcs.alcs_depthwise_conv(torch.from_numpy(D).cuda(), X, torch.from_numpy(b).cuda(), Y, stride=stride,
+                             activation="relu")
+    torch.cuda.synchronize()
+    assert not bool(torch.isnan(Y[8]).any()) and not bool(torch.isnan(Y[0]).any())
+    for (n, c) in planes:
+        ref = oracle.depthwise(D[c:c + 1], host[(n, c)][None, None], bias=b[c:c + 1], stride=stride, act="relu")[0, 0]
+        pre = oracle.depthwise(D[c:c + 1], host[(n, c)][None, None], bias=b[c:c + 1], stride=stride)[0, 0]
+        got = Y[n, c].cpu().numpy()
+        err = float(np.max(np.abs(got.astype(np.float64) - ref)) / np.max(np.abs(pre)))
+        assert err <= TOL, "plane (%d, %d): %.3g" % (n, c, err)
+
+
+def test_block_with_an_image_too_large_for_32_bit_tap_offsets():
+    """1 x 64 x 4096 x 4096 (1.07e9 elements per image): the one-kernel block declines (its tap offsets
+    are 32-bit) and the call runs the two layers through the workspace; without one it is refused.
+    A band of output rows at the top, in the middle and at the bottom is recomputed by the oracle."""
+    import torch
+    N, Cin, Cout, H, W, s = 1, 64, 8, 4096, 4096, 2
+    Ho, Wo = H // s, W // s
+    free_b, _ = torch.cuda.mem_get_info()
+    need = 4 * (Cin * H * W + Cin * Ho * Wo + Cout * Ho * Wo) + (1 << 30)
+    if free_b < need:
+        pytest.skip("needs %.1f GB of device memory" % (need / 1e9))
+    L = workloads.Layer("big_blk", Cin, Cout, Ho, Wo, N=1, V=4, sparsity=0.75, w_std=0.1)
+    d = workloads.make_layer(workloads.Layer("big_blk_w", Cin, Cout, 2, 2, N=1, V=4, sparsity=0.75, w_std=0.1), 8104,
+                             with_bias=True)                       # weights, mask and bias only
+    packed = alcs.alcs_pack_weights(d.W, d.mask, 4)
+    rng = np.random.default_rng(8105)
+    D = (rng.standard_normal((Cin, 3, 3)) * 0.4).astype(np.float32)
+    b1 = rng.standard_normal(Cin).astype(np.float32)
+    X = torch.empty((N, Cin, H, W), dtype=torch.float32, device="cuda").normal_(0.0, 1.5)
+    Y = torch.full((N, Cout, Ho, Wo), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty((N, Cin, Ho, Wo), dtype=torch.float32, device="cuda")
+    Dd, b1d, b2d = torch.from_numpy(D).cuda(), torch.from_numpy(b1).cuda(), torch.from_numpy(d.bias).cuda()
+    with pytest.raises(alcs.AlcsError) as ei:
+        alcs.alcs_dw_sparse_conv_fused(packed, Dd, b1d, X, b2d, None, Y, dw_stride=s, dw_activation="relu")
+    assert ei.value.status == -2
+    alcs.alcs_dw_sparse_conv_fused(packed, Dd, b1d, X, b2d, None, Y, dw_stride=s, dw_activation="relu",
+                                   activation="relu", workspace=ws)
+    torch.cuda.synchronize()
+    assert not bool(torch.isnan(Y).any())
+    for h0, h1 in ((0, 3), (1000, 1003), (Ho - 3, Ho)):
+        # input rows 2*(h0-1) .. 2*h1 give output rows h0-1 .. h1 of which h0 .. h1-1 have their true
+        # neighbours (the crop's own first and last output row see the crop's edge, except at the image's edge)
+        r0, r1 = max(2 * (h0 - 1), 0), min(2 * h1 + 1, H)
+        crop = X[:, :, r0:r1].cpu().numpy()
+        Z = oracle.depthwise(D, crop, bias=b1, stride=s, act="relu")
+        ref = oracle.sparse_conv(d.W, d.mask, Z, 4, bias=d.bias, act="relu")
+        pre = oracle.sparse_conv(d.W, d.mask, Z, 4, bias=d.bias)
+        first = h0 - r0 // 2                                 # crop-local index of output row h0
+        got = Y[:, :, h0:h1].cpu().numpy()
+        want = ref[:, :, first:first + (h1 - h0)]
+        err = float(np.max(np.abs(got.astype(np.float64) - want)) / np.max(np.abs(pre)))
+        assert err <= TOL, "rows %d-%d: %.3g" % (h0, h1, err)
+    packed.free()
+
+
+def test_bf16_pointwise_input_beyond_2_31_elements():
+    """33 x 64 x 1024 x 1024 bfloat16 elements (4.4 GB): element offsets beyond 2^31 in the bfloat16
+    build.  Sampled outputs (the last image among them) against the 1x1 definition written out in
+    double on the gathered input columns."""
+    import torch
+    N, Cin, Cout, H, W, V = 33, 64, 8, 1024, 1024, 4
+    free_b, _ = torch.cuda.mem_get_info()
+    need = 2 * N * (Cin + Cout) * H * W + (1 << 30)
+    if free_b < need:
+        pytest.skip("needs %.1f GB of device memory" % (need / 1e9))
+    assert N * Cin * H * W > 2 ** 31
+    d = workloads.make_layer(workloads.Layer("big_bf_w", Cin, Cout, 2, 2, N=1, V=V, sparsity=0.75, w_std=0.1), 8106,
+                             with_bias=True)
+    packed = alcs.alcs_pack_weights(d.W, d.mask, V)
+    X = torch.empty((N, Cin, H, W), dtype=torch.bfloat16, device="cuda")
+    for n in range(N):
+        X[n].normal_(0.0, 1.0)
+    Y = torch.full((N, Cout, H, W), float("nan"), dtype=torch.bfloat16, device="cuda")
+    alcs.alcs_sparse_conv_bf16(packed, X, torch.from_numpy(d.bias).cuda(), None, Y, activation="relu")
+    torch.cuda.synchronize()
+    assert not bool(torch.isnan(Y[N - 1]).any()) and not bool(torch.isnan(Y[0]).any())
+    rng = np.random.default_rng(8107)
+    ns = np.concatenate([rng.integers(0, N, 1500), np.full(500, N - 1), [0, N - 1]])
+    ps = np.concatenate([rng.integers(0, H * W, 2000), [0, H * W - 1]])
+    nt, pt = torch.from_numpy(ns).cuda(), torch.from_numpy(ps).cuda()
+    cols = X.reshape(N, Cin, H * W)[nt, :, pt].float().cpu().numpy().astype(np.float64)        # [samples, Cin]
+    got = Y.reshape(N, Cout, H * W)[nt, :, pt].float().cpu().numpy().astype(np.float64)       # [samples, Cout]
+    Wd = oracle.densify(d.W, d.mask, V).reshape(Cout, Cin).astype(np.float64)
+    pre = cols @ Wd.T + d.bias
+    ref = np.maximum(pre, 0.0)
+    bound = 2.0 ** -8 * np.abs(ref) + TOL * np.max(np.abs(pre))
+    assert float(np.max(np.abs(got - ref) - bound)) <= 0.0
+    packed.free()
