@@ -54,6 +54,16 @@ def test_topn_mask_bit_exact(n):
         assert list(c2) == [N]
 
 
+def test_topn_with_nan_scores_ranks_them_above_infinity():
+    import torch
+    s = np.array([1.0, np.nan, np.inf, 0.5, np.nan, 3.0], dtype=np.float32)
+    for N in range(7):
+        mask, _ = alcs.alcs_topn_mask(torch.from_numpy(s).cuda(), N)
+        assert mask.cpu().numpy().tobytes() == oracle.topn_mask(s, N).tobytes()
+    mask, _ = alcs.alcs_topn_mask(torch.from_numpy(s).cuda(), 2)
+    assert list(mask.cpu().numpy()) == [0, 1, 0, 0, 1, 0]
+
+
 def test_topn_all_scores_equal_keeps_the_lowest_indices():
     import torch
     s = np.full(1000, 2.5, dtype=np.float32)
