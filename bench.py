@@ -96,7 +96,7 @@ def time_layer(alcs, torch, np, workloads, L, seed, dense=False, iters=10, tunin
     torch.cuda.synchronize()
     t = float(np.median([ev.elapsed_us(i) for i in range(iters)]))
     ev.close()
-    td = None
+    td = tl = None
     err = float("nan")
     if dense:
         # dense weights of the pruned layer: kept blocks as they are, dropped blocks zero
@@ -115,6 +115,21 @@ def time_layer(alcs, torch, np, workloads, L, seed, dense=False, iters=10, tunin
             b.record()
         torch.cuda.synchronize()
         td = float(np.median([a.elapsed_time(b) * 1e3 for a, b in e]))
+        # the vendor library's dense convolution (PyTorch -> MIOpen, float32) on the same tensors: context
+        # for the speed-up columns, which would otherwise rest on this repository's own dense kernel alone
+        import torch.nn.functional as F
+        pad = (L.k - 1) // 2
+        for _ in range(3):
+            Yl = F.conv2d(X, Wd, stride=L.stride, padding=pad)
+        torch.cuda.synchronize()
+        e = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(5)]
+        for a, b in e:
+            a.record()
+            Yl = F.conv2d(X, Wd, stride=L.stride, padding=pad)
+            b.record()
+        torch.cuda.synchronize()
+        tl = float(np.median([a.elapsed_time(b) * 1e3 for a, b in e]))
+        del Yl
     nn = p.nnzb
     by, fl = layer_bytes(L, nn), layer_flops(L, nn)
     p.free()
@@ -122,7 +137,7 @@ def time_layer(alcs, torch, np, workloads, L, seed, dense=False, iters=10, tunin
         alcs.alcs_set_tuning(k, 0)
     roof = max(by / (HBM_PEAK_GBS * 1e9), fl / (MFMA_FP32_PEAK_TFLOPS * 1e12)) * 1e6
     bound = "hbm" if by / (HBM_PEAK_GBS * 1e9) >= fl / (MFMA_FP32_PEAK_TFLOPS * 1e12) else "mfma"
-    return {"us": t, "dense_us": td, "roof_us": roof, "bound": bound, "bytes": by, "flops": fl, "err": err,
+    return {"us": t, "dense_us": td, "lib_us": tl, "roof_us": roof, "bound": bound, "bytes": by, "flops": fl, "err": err,
             "info": info}
 
 
@@ -130,29 +145,30 @@ def report(kind, alcs, workloads, torch, np):
     """Per-layer tables for configurations 3, 4, 5 and the MFMA / FMA comparison (markdown on stdout)."""
     pr = lambda *a: print(*a, flush=True)
     if kind == "sweep":
-        pr("| sparsity | sparse us | dense us | speed-up | dense-equiv TFLOP/s | actual TFLOP/s | bound | roofline frac | max diff vs dense |")
-        pr("|---|---|---|---|---|---|---|---|---|")
+        pr("| sparsity | sparse us | dense us | speed-up | PyTorch dense us | vs PyTorch | dense-equiv TFLOP/s | actual TFLOP/s | bound | roofline frac | max diff vs dense |")
+        pr("|---|---|---|---|---|---|---|---|---|---|---|")
         for s in workloads.SWEEP_SPARSITIES:
             L = workloads.sweep_layer(s)
             r = time_layer(alcs, torch, np, workloads, L, workloads.seed_for(4, int(round(s * 100))), dense=True)
-            pr("| %.2f | %.1f | %.1f | %.2f | %.1f | %.1f | %s | %.3f | %.1e |" %
-               (s, r["us"], r["dense_us"], r["dense_us"] / r["us"], L.dense_flops() / r["us"] / 1e6,
+            pr("| %.2f | %.1f | %.1f | %.2f | %.1f | %.2f | %.1f | %.1f | %s | %.3f | %.1e |" %
+               (s, r["us"], r["dense_us"], r["dense_us"] / r["us"], r["lib_us"], r["lib_us"] / r["us"], L.dense_flops() / r["us"] / 1e6,
                 r["flops"] / r["us"] / 1e6, r["bound"], r["roof_us"] / r["us"], r["err"]))
     elif kind == "resnet":
-        pr("| layer | Cin->Cout | k/s | HxW | x | sparse us | dense us | speed-up | actual TFLOP/s | eff GB/s | bound | roofline frac | max diff vs dense |")
-        pr("|---|---|---|---|---|---|---|---|---|---|---|---|---|")
-        tot = troof = tdense = 0.0
+        pr("| layer | Cin->Cout | k/s | HxW | x | sparse us | dense us | speed-up | PyTorch dense us | vs PyTorch | actual TFLOP/s | eff GB/s | bound | roofline frac | max diff vs dense |")
+        pr("|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|")
+        tot = troof = tdense = tlib = 0.0
         for i, L in enumerate(workloads.resnet50_bottlenecks(64)):
             r = time_layer(alcs, torch, np, workloads, L, workloads.seed_for(3, i), dense=True)
             tot += r["us"] * L.repeats
             troof += r["roof_us"] * L.repeats
             tdense += r["dense_us"] * L.repeats
-            pr("| %s | %d->%d | %d/%d | %d | %d | %.1f | %.1f | %.2f | %.1f | %.0f | %s | %.3f | %.1e |" %
+            tlib += r["lib_us"] * L.repeats
+            pr("| %s | %d->%d | %d/%d | %d | %d | %.1f | %.1f | %.2f | %.1f | %.2f | %.1f | %.0f | %s | %.3f | %.1e |" %
                (L.name, L.Cin, L.Cout, L.k, L.stride, L.H, L.repeats, r["us"], r["dense_us"],
-                r["dense_us"] / r["us"], r["flops"] / r["us"] / 1e6, r["bytes"] / r["us"] / 1e3, r["bound"],
-                r["roof_us"] / r["us"], r["err"]))
-        pr("\nall 48 convs, batch 64: sparse %.0f us, dense %.0f us (%.2fx), sum of rooflines %.0f us (%.3f)" %
-           (tot, tdense, tdense / tot, troof, troof / tot))
+                r["dense_us"] / r["us"], r["lib_us"], r["lib_us"] / r["us"], r["flops"] / r["us"] / 1e6,
+                r["bytes"] / r["us"] / 1e3, r["bound"], r["roof_us"] / r["us"], r["err"]))
+        pr("\nall 48 convs, batch 64: sparse %.0f us, dense %.0f us (%.2fx), PyTorch dense %.0f us (%.2fx), sum of rooflines %.0f us (%.3f)" %
+           (tot, tdense, tdense / tot, tlib, tlib / tot, troof, troof / tot))
     elif kind == "mbv2":
         for V in (1, 4, 8, 16):
             pr("\nV = %d" % V)
@@ -173,19 +189,21 @@ def report(kind, alcs, workloads, torch, np):
                              (32, None, "batch 32, per-layer block sparsity drawn from U(0.7, 0.9)"),
                              (1, None, "batch 1, per-layer block sparsity drawn from U(0.7, 0.9)")):
             pr("\n%s" % label)
-            pr("| layer | Cin->Cout | HxW | sparsity | sparse us | dense us | speed-up | eff GB/s | bound | roofline us | roofline frac | max diff vs dense |")
-            pr("|---|---|---|---|---|---|---|---|---|---|---|---|")
-            tot = troof = tdense = 0.0
+            pr("| layer | Cin->Cout | HxW | sparsity | sparse us | dense us | speed-up | PyTorch dense us | vs PyTorch | eff GB/s | bound | roofline us | roofline frac | max diff vs dense |")
+            pr("|---|---|---|---|---|---|---|---|---|---|---|---|---|---|")
+            tot = troof = tdense = tlib = 0.0
             for i, L in enumerate(workloads.mobilenet_v1_pointwise(N, sp)):
                 r = time_layer(alcs, torch, np, workloads, L, workloads.seed_for(2, i), dense=True)
                 tot += r["us"]
                 troof += r["roof_us"]
                 tdense += r["dense_us"]
-                pr("| %s | %d->%d | %d | %.3f | %.1f | %.1f | %.2f | %.0f | %s | %.2f | %.3f | %.1e |" %
+                tlib += r["lib_us"]
+                pr("| %s | %d->%d | %d | %.3f | %.1f | %.1f | %.2f | %.1f | %.2f | %.0f | %s | %.2f | %.3f | %.1e |" %
                    (L.name, L.Cin, L.Cout, L.H, L.sparsity, r["us"], r["dense_us"], r["dense_us"] / r["us"],
-                    r["bytes"] / r["us"] / 1e3, r["bound"], r["roof_us"], r["roof_us"] / r["us"], r["err"]))
-            pr("13 layers: sparse %.0f us, dense %.0f us (%.2fx), sum of rooflines %.0f us (%.3f)" %
-               (tot, tdense, tdense / tot, troof, troof / tot))
+                    r["lib_us"], r["lib_us"] / r["us"], r["bytes"] / r["us"] / 1e3, r["bound"], r["roof_us"],
+                    r["roof_us"] / r["us"], r["err"]))
+            pr("13 layers: sparse %.0f us, dense %.0f us (%.2fx), PyTorch dense %.0f us (%.2fx), sum of rooflines %.0f us (%.3f)" %
+               (tot, tdense, tdense / tot, tlib, tlib / tot, troof, troof / tot))
     elif kind == "fused":
         # the element-wise layers behind a convolution folded into its epilogue, against the plain
         # convolution followed by PyTorch's in-place element-wise kernels on the same buffers
