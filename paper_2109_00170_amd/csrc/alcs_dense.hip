@@ -222,9 +222,10 @@ extern "C" int alcs_dense_conv(const float *W_dev, const float *X_dev, const flo
     a.stride = stride; a.k = kernel; a.P = (int)P; a.Pin = (int)Pin; a.K = (int)K;
     a.NP = (long long)N * P;
     const bool vec = kernel == 1 && stride == 1 && (P % 4 == 0);
-    const int BM = Cout > 64 ? 128 : 64;
-    a.mt = (Cout + BM - 1) / BM;
     const long long ntile = (a.NP + BN - 1) / BN;
+    // 128 output channels per workgroup, or 64 when that leaves fewer workgroups than compute units
+    const int BM = (Cout > 64 && ntile * ((Cout + 127) / 128) >= 256) ? 128 : 64;
+    a.mt = (Cout + BM - 1) / BM;
     const long long total = ntile * a.mt;
     if (total > (1LL << 30)) return ALCS_E_UNSUPPORTED;
     a.nt = (int)ntile;
