@@ -88,11 +88,20 @@ struct DwTaps {
         const char *b = reinterpret_cast<const char *>(base);
         if constexpr (MODE == kDwNine) {
 #pragma unroll
-            for (int t = 0; t < 9; ++t) v.x[t] = *reinterpret_cast<const float *>(b + boff[t]);
+            for (int t = 0; t < 9; ++t) {
+                // The empty statement keeps the 32-bit offset a 32-bit register here (otherwise its
+                // zero extension is hoisted out of the channel loop and every load needs a 64-bit
+                // vector add): the load then takes the scalar base + vector offset form.
+                uint32_t o = boff[t];
+                asm volatile("" : "+v"(o));
+                v.x[t] = *reinterpret_cast<const float *>(b + o);
+            }
         } else {
 #pragma unroll
             for (int r = 0; r < 3; ++r) {
-                const dw_f2 p = *reinterpret_cast<const dw_f2 *>(b + boff[r]);
+                uint32_t o = boff[r];
+                asm volatile("" : "+v"(o));  // as above: scalar base + 32-bit vector offset
+                const dw_f2 p = *reinterpret_cast<const dw_f2 *>(b + o);
                 v.x[r * 3 + 1] = p.x;
                 v.x[r * 3 + 2] = p.y;
             }
