@@ -215,18 +215,30 @@ int upload(alcs_packed *p) {
 // LDS tile while a 64-pixel tile of Cin+1 rows fits (Cin <= 639 in 160 KB); from 512
 // input channels on (V >= 4 only) the tile shrinks to 32 or 16 pixels and a wavefront
 // multiplies 2 or 4 groups: two workgroups then share a compute unit and one fills its
-// tile while the other multiplies (512 channels measured both ways: 512->1024 @7x7
-// 16.9 -> 11.0 us, 512->512 @14x14 17.2 -> 16.6 us, 512->256 @28x28 86 -> 82 us).
+// tile while the other multiplies (512 channels: 512->1024 @7x7 16.9 -> 11.0 us).
+// Up to 1279 channels, V = 4 and groups of similar length (the longest at most twice the
+// mean) take 4 groups per wavefront, each on 16 lanes that hold two pixels of the 32-pixel
+// tile, which halves the LDS row reads per kept weight (512->512 @14x14: 17.2 us with one
+// group per wavefront, 17.1 with two, 15.6 with four; 512->128 @28x28, N=64: 58 -> 43 us).
+// With groups of very different lengths a workgroup's time is the walk through its longest
+// bundle, which two pixels per lane make 1.5x longer (576->96 @14x14, longest group 6x the
+// mean: 39 us with two groups per wavefront, 45 with four); V = 8 and 16 gain nothing from
+// four (their accumulators already alternate).  With 256 input channels one group per
+// wavefront stays ahead.
 // Beyond 2559 channels, or beyond 639 for V < 4, chunks of 256 channels.
 // Kernel 3: 32 channels per chunk (the haloed tile plane is 240 to 476 floats per channel);
 // 64 from 512 input channels on - such layers sit on 14x14 and 7x7 images, where a workgroup's
 // time is the chain of its chunks' round trips (512->512 @7x7, N=64: 131 -> 100 us; stride 2
 // from 14x14: 141 -> 131 us), while on large images the smaller chunk's higher occupancy wins
 // (128->128 stride 2 @56x56: 104 us with 32 channels, 148 us with 64).
-static void default_tiles(int Cin, int k, int V, int *KC, int *GS) {
+static void default_tiles(int Cin, int k, int V, bool even_groups, int *KC, int *GS) {
     *GS = 1;
     if (k == 3) { *KC = Cin >= 512 ? 64 : std::min(Cin, 32); return; }
-    if (V >= 4 && Cin >= 512 && Cin <= 2559) { *KC = Cin; *GS = Cin <= 1279 ? 2 : 4; return; }
+    if (V >= 4 && Cin >= 512 && Cin <= 2559) {
+        *KC = Cin;
+        *GS = (Cin > 1279 || (V == 4 && even_groups)) ? 4 : 2;
+        return;
+    }
     if (Cin <= 639) { *KC = Cin; return; }
     *KC = 256;
 }
@@ -241,7 +253,8 @@ extern "C" void alcs_packed_free(alcs_packed_t *p);
 static int finish_pack(alcs_packed *p, int rc, alcs_packed_t **out) {
     if (rc == ALCS_OK) {
         int KC = 0, GS = 1;
-        default_tiles(p->Cin, p->k, p->V, &KC, &GS);
+        const bool even_groups = (int64_t)p->max_count * p->G <= 2 * p->nnzb;
+        default_tiles(p->Cin, p->k, p->V, even_groups, &KC, &GS);
         if (tuning().kc > 0) { KC = std::min(tuning().kc, p->Cin); GS = 1; }
         if (tuning().gs > 0 && p->k == 1 && p->V >= 4 && KC == p->Cin &&
             (long long)(p->Cin + 1) * (kRowBytes1 / tuning().gs) <= 160 * 1024)

@@ -277,11 +277,11 @@ struct Run {
 // (before the previous group's output stores: vector memory operations complete in
 // order, so a load issued behind stores waits for them).  N = 4 covers segments of up
 // to 64 columns without any load inside the multiply loop; with many weight registers
-// per run (V/4 * GS > 2) N = 2.  The walk over a longer segment re-fills register set i
+// per run (V/4 * GS > 2, except four groups of V = 4) N = 2.  The walk over a longer segment re-fills register set i
 // right after its use with the run N places further on: no register is ever copied, so
 // nothing waits for a load before the run that needs it.
 template <int V, bool MF, int GS>
-constexpr int runs_ahead() { return !MF ? 1 : (V / 4) * GS <= 2 ? 4 : 2; }
+constexpr int runs_ahead() { return !MF ? 1 : ((V / 4) * GS <= 2 || (V == 4 && GS == 4)) ? 4 : 2; }
 
 template <int V, bool MF, int GS = 1>
 struct Runs {
@@ -434,8 +434,19 @@ __device__ __forceinline__ void mac_segment(const ConvArgs &a, int start, int cn
 // Rows [c0, c1) of the pixel tile [q0, q0 + TP) of the flattened (n, pixel) axis into
 // LDS rows 0.. (row length TP).  VEC: stride 1 and P % 4 == 0, so four consecutive
 // pixels never straddle an image and are 16-byte aligned.
-template <int TP, bool VEC>
+// Place of the tile's e-th pixel in an LDS row.  SPLIT (two pixels per lane without the
+// vector form, where a pair of neighbours may straddle two images): a lane owns pixels
+// e and e + TP/2, stored side by side so that one 8-byte read fetches both, and a store
+// instruction still writes a contiguous run of pixels.
+template <int TP, bool SPLIT>
+__device__ __forceinline__ int tile_pos(int e) {
+    if constexpr (SPLIT) return (e % (TP / 2)) * 2 + e / (TP / 2);
+    return e;
+}
+
+template <int TP, bool VEC, bool SPLIT = false>
 __device__ __forceinline__ void stage_pw(const ConvArgs &a, float *lds, int q0, int c0, int c1) {
+    static_assert(!(VEC && SPLIT), "the vector form keeps neighbouring pixels together");
     const int tid = threadIdx.x, nt = blockDim.x;
     if constexpr (VEC) {
         constexpr int NQ = TP / 4;
@@ -480,9 +491,9 @@ __device__ __forceinline__ void stage_pw(const ConvArgs &a, float *lds, int q0, 
 #pragma unroll
             for (int u = 0; u < U; ++u) v[u] = valid ? io_load1(src + (size_t)(r + u * rpp) * a.Pin) : 0.f;
 #pragma unroll
-            for (int u = 0; u < U; ++u) lds[(r + u * rpp) * TP + e] = v[u];
+            for (int u = 0; u < U; ++u) lds[(r + u * rpp) * TP + tile_pos<TP, SPLIT>(e)] = v[u];
         }
-        for (; r < rows; r += rpp) lds[r * TP + e] = valid ? io_load1(src + (size_t)r * a.Pin) : 0.f;
+        for (; r < rows; r += rpp) lds[r * TP + tile_pos<TP, SPLIT>(e)] = valid ? io_load1(src + (size_t)r * a.Pin) : 0.f;
     }
 }
 
@@ -494,7 +505,7 @@ __device__ __forceinline__ void stage_pw(const ConvArgs &a, float *lds, int q0, 
 // thread owns one pixel of the tile and every (blockDim / TP)-th channel.  With TP >= 64 a
 // wavefront works on one channel at a time, so the filter and the bias come through scalar
 // loads.
-template <int TP, int MODE>
+template <int TP, int MODE, bool SPLIT>
 __device__ __forceinline__ void stage_dw_mode(const ConvArgs &a, float *lds, int q0) {
     constexpr int SPAN = TP < 64 ? TP : 64;
     const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63;
@@ -525,7 +536,7 @@ __device__ __forceinline__ void stage_dw_mode(const ConvArgs &a, float *lds, int
             float acc = taps.apply(x, wts + c * 9, a.dw_bias ? bs[c] : 0.f);
             if (a.dw_act >= 1) acc = fmaxf(acc, 0.f);
             if (a.dw_act == 2) acc = fminf(acc, 6.f);
-            lds[c * TP + e] = valid ? acc : 0.f;
+            lds[c * TP + tile_pos<TP, SPLIT>(e)] = valid ? acc : 0.f;
         };
         int c = r0;  // the lane's channel; c - rl is wave-uniform
         // two channels' loads in flight (one on the narrow tiles, whose kernels hold the
@@ -545,10 +556,10 @@ __device__ __forceinline__ void stage_dw_mode(const ConvArgs &a, float *lds, int
     }
 }
 
-template <int TP>
+template <int TP, bool SPLIT>
 __device__ __forceinline__ void stage_dw(const ConvArgs &a, float *lds, int q0) {
-    if (a.dw_mode == kDwPair) stage_dw_mode<TP, kDwPair>(a, lds, q0);
-    else stage_dw_mode<TP, kDwNine>(a, lds, q0);
+    if (a.dw_mode == kDwPair) stage_dw_mode<TP, kDwPair, SPLIT>(a, lds, q0);
+    else stage_dw_mode<TP, kDwNine, SPLIT>(a, lds, q0);
 }
 #endif
 
@@ -559,11 +570,12 @@ struct PixOut {
     bool valid[PV];
 };
 
-template <int PV, bool VEC>
+// PSTRIDE > 0: the lane's pixels are PSTRIDE apart (see tile_pos), else neighbours.
+template <int PV, bool VEC, int PSTRIDE = 0>
 __device__ __forceinline__ void pix_out(const ConvArgs &a, int q0, int lane, PixOut<PV> &px) {
 #pragma unroll
     for (int pv = 0; pv < PV; ++pv) {
-        const int q = q0 + lane * PV + pv;
+        const int q = PSTRIDE > 0 ? q0 + lane + pv * PSTRIDE : q0 + lane * PV + pv;
         px.valid[pv] = q < a.NP;
         if (VEC && pv > 0) {
             px.yoff[pv] = px.yoff[0] + pv;
@@ -686,18 +698,34 @@ __device__ __forceinline__ int lane_group(const Work &w, int lane) {
 }
 
 // Epilogue with GS groups per wavefront: g is the group of the lane's slot (-1: none).
-template <int V, int GS>
-__device__ __forceinline__ void store_slots(const ConvArgs &a, const Acc<V, 1, true> &acc, int g,
-                                            const PixOut<1> &px) {
-    if (g < 0 || !px.valid[0]) return;
+// In vector form the two pixels of a lane are an 8-byte aligned pair inside one image and
+// go out as one store.
+template <int V, int PV, int GS, bool VEC>
+__device__ __forceinline__ void store_slots(const ConvArgs &a, const Acc<V, PV, true> &acc, int g,
+                                            const PixOut<PV> &px) {
+    static_assert(PV == 1 || PV == 2, "several groups per wavefront: one or two pixels per lane");
+    if (g < 0) return;
 #pragma unroll
     for (int v = 0; v < V; ++v) {
         const int ch = g * V + v;
         if (ch >= a.Cout) break;
         const float b = a.bias ? a.bias[ch] : 0.f;
-        float o = acc.get(v, 0) + b;
-        if (residual_of(a)) o += io_load1(residual_of(a) + (size_t)ch * a.P + px.yoff[0]);
-        io_store1(a.Y + (size_t)ch * a.P + px.yoff[0], activate(a, o));
+        if constexpr (PV == 2 && VEC) {
+            if (px.valid[0]) {
+                f2 o = f2{acc.get(v, 0) + b, acc.get(v, 1) + b};
+                if (residual_of(a)) o += io_load2(residual_of(a) + (size_t)ch * a.P + px.yoff[0]);
+                if (kFused && a.act) o = f2{activate(a, o[0]), activate(a, o[1])};
+                io_store2(a.Y + (size_t)ch * a.P + px.yoff[0], o);
+            }
+        } else {
+#pragma unroll
+            for (int pv = 0; pv < PV; ++pv)
+                if (px.valid[pv]) {
+                    float o = acc.get(v, pv) + b;
+                    if (residual_of(a)) o += io_load1(residual_of(a) + (size_t)ch * a.P + px.yoff[pv]);
+                    io_store1(a.Y + (size_t)ch * a.P + px.yoff[pv], activate(a, o));
+                }
+        }
     }
 }
 
@@ -712,10 +740,11 @@ __device__ __forceinline__ void store_slots(const ConvArgs &a, const Acc<V, 1, t
 template <int V, int PV, bool MF, bool VEC, int GS, bool RES>
 __device__ __forceinline__ void pw_resident_body(const ConvArgs &a) {
     static_assert(!RES || GS == 1, "residual prefetch: one group per wavefront");
-    static_assert(GS == 1 || (PV == 1 && MF), "several groups per wavefront: MFMA form, one pixel per lane");
+    static_assert(GS == 1 || (MF && PV <= 2), "several groups per wavefront: MFMA form, one or two pixels per lane");
     extern __shared__ float lds[];
     constexpr int TP = 64 * PV / GS;
     constexpr int SH = PV == 4 ? 2 : PV == 2 ? 1 : 0;
+    constexpr bool SPLIT = GS > 1 && PV == 2 && !VEC;  // the lane's two pixels are TP/2 apart
     const int logical = logical_wg(a);
     if (logical >= a.total_wgs || (a.debug & 8)) return;
     const int pt = logical / a.ngt, gt = logical - pt * a.ngt;
@@ -737,17 +766,17 @@ __device__ __forceinline__ void pw_resident_body(const ConvArgs &a) {
     }
 
 #if ALCS_DW_STAGE
-    if (!(a.debug & 1)) stage_dw<TP>(a, lds, q0);
+    if (!(a.debug & 1)) stage_dw<TP, SPLIT>(a, lds, q0);
 #else
-    if (!(a.debug & 1)) stage_pw<TP, VEC>(a, lds, q0, 0, a.Cin);
+    if (!(a.debug & 1)) stage_pw<TP, VEC, SPLIT>(a, lds, q0, 0, a.Cin);
 #endif
     for (int t = tid; t < TP; t += blockDim.x) lds[a.KC * TP + t] = 0.f;  // the all-zero row
     __syncthreads();
     if (!any) return;
 
-    const int plane = GS == 1 ? lane : (lane & (TP - 1));  // the lane's pixel position in the tile
+    const int plane = lane & (64 / GS - 1);  // the lane's place among the pixels (pairs, quads) of the tile
     PixOut<PV> px;
-    pix_out<PV, VEC>(a, q0, plane, px);
+    pix_out<PV, VEC, SPLIT ? TP / 2 : 0>(a, q0, plane, px);
     const char *ldsb = reinterpret_cast<const char *>(lds);
     const int base = plane * PV * 4;
     for (int k = 0;; ++k) {
@@ -764,7 +793,7 @@ __device__ __forceinline__ void pw_resident_body(const ConvArgs &a) {
         if (!(a.debug & 2)) mac_segment<V, PV, SH, GS>(a, w0.start, w0.cnt, ldsb, base, lane, run0, acc);
         if (!(a.debug & 4)) {
             if constexpr (GS == 1) store_group<V, PV, MF, VEC>(a, acc, w0.group[0], px, RES ? &rr : nullptr);
-            else store_slots<V, GS>(a, acc, lane_group<GS>(w0, lane), px);
+            else store_slots<V, PV, GS, VEC>(a, acc, lane_group<GS>(w0, lane), px);
         }
         if (!more) break;
         w0 = w1;
@@ -1098,6 +1127,8 @@ static kern_t pick_resident(int pv, bool vec, int gs, bool res = false) {
         }
     }
     if constexpr (MF) {
+        if (gs == 2 && pv == 2) return vec ? k_pw_resident<V, 2, true, true, 2> : k_pw_resident<V, 2, true, false, 2>;
+        if (gs == 4 && pv == 2) return vec ? k_pw_resident<V, 2, true, true, 4> : k_pw_resident<V, 2, true, false, 4>;
         if (gs == 2) return vec ? k_pw_resident<V, 1, true, true, 2> : k_pw_resident<V, 1, true, false, 2>;
         if (gs == 4) return vec ? k_pw_resident<V, 1, true, true, 4> : k_pw_resident<V, 1, true, false, 4>;
     }
@@ -1333,6 +1364,13 @@ static int launch_sparse(const alcs_packed_t *Wp, const io_t *X_dev, const float
                 }
                 if (T.pv == 1 || T.pv == 2 || T.pv == 4) pv = T.pv;
             }
+            // Several groups per wavefront: four groups of 16 lanes with a pixel pair each read
+            // half as many LDS rows per kept weight as two groups of 32 lanes with one pixel
+            // (same 32-pixel tile; 512->512 @14x14: 17.4 -> 15.7 us).
+            if (GS > 1) {
+                pv = (GS == 4 && (long long)(Cin + 1) * 32 * 4 <= kMaxLds) ? 2 : 1;
+                if (T.pv == 1 || T.pv == 2) pv = T.pv;
+            }
             const int TP = 64 * pv / GS;
             lds = (Cin + 1) * TP * 4;
             if (lds > kMaxLds) return ALCS_E_UNSUPPORTED;
@@ -1350,8 +1388,9 @@ static int launch_sparse(const alcs_packed_t *Wp, const io_t *X_dev, const float
             a.ngt = ceil_div(NB, a.gpt);
             nw = lds > 40 * 1024 ? 16 : 8;
             // fewer wavefronts when the group tile has fewer bundles, but at least one per 8 KB
-            // of tile: wavefronts without a bundle still help to stage it
-            nw = std::min(nw, std::max(std::max(1, a.gpt), lds / 8192));
+            // of tile (4 KB with several groups per wavefront, whose group tiles hold few
+            // bundles): wavefronts without a bundle still help to stage it
+            nw = std::min(nw, std::max(std::max(1, a.gpt), lds / (GS > 1 ? 4096 : 8192)));
             if (T.waves > 0) nw = std::min(T.waves, 16);
             switch (V) {
                 case 1: kern = pick_resident<1, false>(pv, vec, GS); break;

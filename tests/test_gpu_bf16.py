@@ -84,7 +84,15 @@ def test_odd_images_and_strides_bf16(H, W, stride):
 def test_several_groups_per_wavefront_bf16(Cin, slots):
     L = workloads.Layer("bf_gs", Cin, 72, 7, 7, N=9, V=4, sparsity=0.9, w_std=0.1)
     info = run_bf16(L, 3540 + Cin, act=None, with_res=True, pack_tuning={"group_slots": slots} if slots else None)
-    assert info["group_slots"] == (slots or 2)
+    assert info["group_slots"] == (slots or 4)
+
+
+@pytest.mark.parametrize("slots", [2, 4])
+@pytest.mark.parametrize("pv", [1, 2])
+def test_several_groups_per_wavefront_pixel_pairs_bf16(slots, pv):
+    L = workloads.Layer("bf_gs_pv", 520, 72, 12, 12, N=5, V=4, sparsity=0.9, w_std=0.1)
+    info = run_bf16(L, 3550 + slots + pv, act="relu", with_res=True, pack_tuning={"group_slots": slots}, pv=pv)
+    assert info["group_slots"] == slots and info["pv"] == pv
 
 
 def test_in_place_residual_and_no_bias_bf16():

@@ -150,6 +150,17 @@ def test_block_several_groups_per_wavefront(Cin, slots):
     assert info["group_slots"] == slots
 
 
+@pytest.mark.parametrize("slots", [2, 4])
+@pytest.mark.parametrize("hw,dw_stride", [(8, 1), (8, 2), (7, 1)])
+@pytest.mark.parametrize("pv", [1, 2])
+def test_block_several_groups_per_wavefront_pixels_per_lane(slots, hw, dw_stride, pv):
+    # one or two pixels per lane: neighbouring pairs at 8x8, pixels half a tile apart at 7x7
+    L = workloads.Layer("blk_gs%d_pv%d" % (slots, pv), 520, 40, hw, hw, N=7, V=4, sparsity=0.9, w_std=0.1)
+    info = run_block(L, hw * dw_stride, hw * dw_stride, dw_stride, 2350 + slots + hw, pv=pv,
+                     pack_tuning={"group_slots": slots})
+    assert info["group_slots"] == slots and info["pv"] == pv
+
+
 def test_block_mobilenet_shapes_small_batch():
     for (cin, cout, hw, s) in ((32, 64, 112, 1), (64, 128, 56, 2), (256, 512, 14, 2), (512, 512, 14, 1),
                                (1024, 1024, 7, 1)):

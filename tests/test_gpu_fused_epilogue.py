@@ -83,10 +83,10 @@ def test_activation_only_and_residual_only():
     run_fused(L, 1021, None, with_res=True)
 
 
-@pytest.mark.parametrize("Cin,gs", [(700, 2), (1400, 4)])
+@pytest.mark.parametrize("Cin,gs", [(700, 2), (700, 4), (1400, 4)])
 def test_several_groups_per_wavefront(Cin, gs):
     L = workloads.Layer("fr_gs%d" % gs, Cin, 72, 7, 7, k=1, stride=1, N=5, V=8, sparsity=0.9, w_std=0.1)
-    info = run_fused(L, 1030 + gs, "relu6")
+    info = run_fused(L, 1030 + gs, "relu6", pack_tuning={"group_slots": gs})
     assert info["group_slots"] == gs
 
 

@@ -95,7 +95,18 @@ def test_pointwise_several_groups_per_wavefront(V, gs, hw):
     assert info["mode"] == 1 and info["group_slots"] == gs
 
 
-@pytest.mark.parametrize("Cin,gs", [(1100, 2), (2048, 4)])
+@pytest.mark.parametrize("V,gs", [(4, 2), (4, 4), (8, 2), (8, 4), (16, 2), (16, 4)])
+@pytest.mark.parametrize("hw", [12, 7])
+def test_pointwise_several_groups_per_wavefront_two_pixels_per_lane(V, gs, hw):
+    """The same with two pixels per lane (64 or 32 pixels per tile): an aligned pair at 12x12,
+    two pixels half a tile apart at 7x7, where neighbours may lie in different images.  5
+    images leave a ragged last tile, Cout=44 a partly empty last bundle."""
+    L = workloads.Layer("pw_gs%d_v%d_pv2" % (gs, V), 60, 44, hw, hw, N=5, V=V, sparsity=0.6)
+    info = check(L, 440 + V + gs + hw, group_slots=gs, pv=2)
+    assert info["mode"] == 1 and info["group_slots"] == gs and info["pv"] == 2
+
+
+@pytest.mark.parametrize("Cin,gs", [(512, 4), (1100, 4), (2048, 4)])
 def test_pointwise_wide_inputs_pair_groups_by_default(Cin, gs):
     L = workloads.Layer("pw_wide%d" % Cin, Cin, 40, 7, 7, N=3, V=4, sparsity=0.9)
     info = check(L, 450 + gs)
