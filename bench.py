@@ -668,9 +668,11 @@ def main():
         if calib is not None:
             calib[1].copy_(calib[0])
         run_step()
+    t_submitted = time.perf_counter()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    host_submit_ms_per_step = (t_submitted - t0) * 1e3 / args.steps  # the host's share: all launches queued
 
     # ---- the same `steps` steps once more, every launch carrying a pair of HIP events that
     # take the kernel's own begin/end time stamps (alcs_sparse_conv_timed): per-launch
@@ -773,6 +775,8 @@ def main():
         "effective_gbs": round(alg_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "actual_gflops": round(alg_flops / (ms_per_step * 1e-3) / 1e9, 1),
         "roofline_frac_step": round(roof_sum * 1e3 / ms_per_step, 4),
+        "host_submit_ms_per_step": round(host_submit_ms_per_step, 5),
+        "sum_of_kernel_us": round(sum(layer_us), 1),
         "roofline": roofline,
         "cache_warm": {"sum_of_kernel_us": round(sum(warm_us), 1),
                        "roofline_frac": round(roof_sum * 1e6 / sum(warm_us), 4),

@@ -1388,9 +1388,9 @@ static int launch_sparse(const alcs_packed_t *Wp, const io_t *X_dev, const float
             a.ngt = ceil_div(NB, a.gpt);
             nw = lds > 40 * 1024 ? 16 : 8;
             // fewer wavefronts when the group tile has fewer bundles, but at least one per 8 KB
-            // of tile (4 KB with several groups per wavefront, whose group tiles hold few
+            // of tile (4 KB with four groups per wavefront, whose group tiles hold few
             // bundles): wavefronts without a bundle still help to stage it
-            nw = std::min(nw, std::max(std::max(1, a.gpt), lds / (GS > 1 ? 4096 : 8192)));
+            nw = std::min(nw, std::max(std::max(1, a.gpt), lds / (GS == 4 ? 4096 : 8192)));
             if (T.waves > 0) nw = std::min(T.waves, 16);
             switch (V) {
                 case 1: kern = pick_resident<1, false>(pv, vec, GS); break;
