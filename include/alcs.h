@@ -239,7 +239,8 @@ int alcs_dense_conv(const float *W_dev, const float *X_dev, const float *bias_de
  * Tuning knobs for measurements and tests (process-wide, not thread-safe against
  * concurrent calls).  A value of 0 restores the automatic choice.
  *   read by alcs_sparse_conv:
- *     "pv"              pixels per lane of the 1x1 kernels: 1, 2 or 4
+ *     "pv"              pixels per lane of the 1x1 kernels: 1, 2 or 4 (1 or 2 with several
+ *                       groups per wavefront)
  *     "waves"           wavefronts per workgroup
  *     "group_tiles"     number of workgroups that share one pixel tile
  *     "path"            1 = plain-FMA inner loop where it exists (V = 4), 2 = MFMA inner
@@ -254,7 +255,10 @@ int alcs_dense_conv(const float *W_dev, const float *X_dev, const float *bias_de
  *                       kernel even where it would use its workspace for speed
  *   read by alcs_pack_weights (they shape the device layout of handles packed later):
  *     "chunk_channels"  input channels per LDS chunk (forces the chunked kernels)
- *     "group_slots"     output-channel groups multiplied per wavefront: 1, 2 or 4
+ *     "group_slots"     output-channel groups multiplied per wavefront: 1, 2 or 4 (automatic
+ *                       choice: 1 below 512 input channels or for V < 4; from 512 channels on 4
+ *                       for V = 4 when no group keeps more than twice the mean number of
+ *                       columns, else 2; 4 from 1280 channels on)
  *     "groups_per_wave" reserved
  * Unknown names return ALCS_E_INVALID_ARG.  Results never depend on the knobs beyond
  * floating-point summation order (except "debug").
