@@ -252,7 +252,9 @@ int alcs_dense_conv(const float *W_dev, const float *X_dev, const float *bias_de
  *                       the depthwise stage of alcs_dw_sparse_conv_fused load all nine
  *                       taps of a pixel itself instead of sharing them between lanes;
  *                       bit 5 (results unchanged) keeps alcs_dw_sparse_conv_fused in one
- *                       kernel even where it would use its workspace for speed
+ *                       kernel even where it would use its workspace for speed; bit 6 (results
+ *                       unchanged) keeps full pixel tiles where the 1x1 kernels would give
+ *                       every workgroup fewer pixels to occupy all compute units
  *   read by alcs_pack_weights (they shape the device layout of handles packed later):
  *     "chunk_channels"  input channels per LDS chunk (forces the chunked kernels)
  *     "group_slots"     output-channel groups multiplied per wavefront: 1, 2 or 4 (automatic

@@ -133,6 +133,7 @@ struct ConvArgs {
     int N, Cin, Cout, H, W, Ho, Wo, stride;
     int P, Pin;         // Ho*Wo, H*W
     int NP;             // N * P, flattened output pixels (< 2^31)
+    int tile_px;        // resident 1x1 kernels: pixels of the flattened axis per workgroup (<= tile width)
     int G, nchunks, KC;
     int npt, ngt, gpt;  // pixel tiles, group tiles, groups per group tile
     int tiles_x, tiles_y;  // 3x3: output tiles per image
@@ -348,9 +349,11 @@ __device__ __forceinline__ int bcast_sel(int ov) {
 // multiply them with the lane's pixel value(s).  Segment lengths are padded to a
 // multiple of B (zero weights, selector of the all-zero row), so a batch never
 // branches: the compiler keeps all B reads in flight ahead of the MFMAs.
-// base is the lane's byte offset inside an LDS row (minus the chunk's first row);
-// selectors are byte offsets for 64-pixel rows, scaled by 1 << SH for wider rows.
-template <int B0, int B, int V, int PV, int SH, int GS>
+// base is the lane's byte offset inside an LDS row (minus the chunk's first row); ov holds
+// the run's selectors already scaled to the row length (the caller shifts the register once
+// per run: a shift behind the broadcast would cost a move, a broadcast and a shift-add per
+// column where one add with the broadcast folded in does).
+template <int B0, int B, int V, int PV, int GS>
 __device__ __forceinline__ void mfma_batch(const float (&aw)[(V / 4) * GS], int ov, const char *lds,
                                            int base, Acc<V, PV, true> &acc) {
     constexpr int CPA = 16 / GS;           // columns per weight register
@@ -358,7 +361,7 @@ __device__ __forceinline__ void mfma_batch(const float (&aw)[(V / 4) * GS], int 
     float x[B][PV];
     static_for<B>([&](auto c) {
         constexpr int C = decltype(c)::value;
-        lds_read<PV>(reinterpret_cast<const float *>(lds + base + (bcast_sel<B0 + C>(ov) << SH)), x[C]);
+        lds_read<PV>(reinterpret_cast<const float *>(lds + base + bcast_sel<B0 + C>(ov)), x[C]);
     });
     // With two pixels per lane the scheduler would trade reads in flight for registers and
     // interleave two reads at a time with the MFMAs; keep all B reads ahead of them.  (With
@@ -394,8 +397,10 @@ __device__ __forceinline__ void mac_segment(const ConvArgs &a, int start, int cn
             constexpr int I = decltype(ii)::value;
             const int j = j0 + 16 * I;
             if (j < cnt) {
-                mfma_batch<0, B, V, PV, SH, GS>(rs.r[I].a, rs.r[I].o, lds, base, acc);
-                if (j + 8 < cnt) mfma_batch<8, B, V, PV, SH, GS>(rs.r[I].a, rs.r[I].o, lds, base, acc);
+                // selectors are byte offsets for 64-pixel rows: scale them to this tile's rows
+                const int ov = rs.r[I].o << SH;
+                mfma_batch<0, B, V, PV, GS>(rs.r[I].a, ov, lds, base, acc);
+                if (j + 8 < cnt) mfma_batch<8, B, V, PV, GS>(rs.r[I].a, ov, lds, base, acc);
                 if (j + 16 * N < cnt) rs.r[I] = load_run<V, true, GS>(a, start + j + 16 * N, lane);
             }
         });
@@ -445,14 +450,14 @@ __device__ __forceinline__ int tile_pos(int e) {
 }
 
 template <int TP, bool VEC, bool SPLIT = false>
-__device__ __forceinline__ void stage_pw(const ConvArgs &a, float *lds, int q0, int c0, int c1) {
+__device__ __forceinline__ void stage_pw(const ConvArgs &a, float *lds, int q0, int c0, int c1, int q_end) {
     static_assert(!(VEC && SPLIT), "the vector form keeps neighbouring pixels together");
     const int tid = threadIdx.x, nt = blockDim.x;
     if constexpr (VEC) {
         constexpr int NQ = TP / 4;
         const int quad = tid % NQ, r0 = tid / NQ, rpp = nt / NQ;
         const int q = q0 + quad * 4;
-        const bool valid = q < a.NP;
+        const bool valid = q < q_end;
         const int n = valid ? q / a.P : 0;
         const int p = valid ? q - n * a.P : 0;
         const io_t *src = a.X + ((size_t)n * a.Cin + c0) * a.P + p;
@@ -478,7 +483,7 @@ __device__ __forceinline__ void stage_pw(const ConvArgs &a, float *lds, int q0, 
     } else {
         const int e = tid % TP, r0 = tid / TP, rpp = nt / TP;
         const int q = q0 + e;
-        const bool valid = q < a.NP;
+        const bool valid = q < q_end;
         const int n = valid ? q / a.P : 0;
         const int po = valid ? q - n * a.P : 0;
         const int ho = po / a.Wo, wo = po - ho * a.Wo;
@@ -506,7 +511,7 @@ __device__ __forceinline__ void stage_pw(const ConvArgs &a, float *lds, int q0, 
 // wavefront works on one channel at a time, so the filter and the bias come through scalar
 // loads.
 template <int TP, int MODE, bool SPLIT>
-__device__ __forceinline__ void stage_dw_mode(const ConvArgs &a, float *lds, int q0) {
+__device__ __forceinline__ void stage_dw_mode(const ConvArgs &a, float *lds, int q0, int q_end) {
     constexpr int SPAN = TP < 64 ? TP : 64;
     const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63;
     // A pass covers `span` pixels of the tile with nt / span channels side by side; a
@@ -520,7 +525,7 @@ __device__ __forceinline__ void stage_dw_mode(const ConvArgs &a, float *lds, int
     const auto bs = as_const(a.dw_bias);
     for (int e = tid - r0 * span; e < TP; e += span) {
         const int q = q0 + e;
-        const bool valid = q < a.NP;
+        const bool valid = q < q_end;
         const int n = valid ? q / a.P : 0;
         const int po = valid ? q - n * a.P : 0;
         const int ho = po / a.Wo, wo = po - ho * a.Wo;
@@ -557,9 +562,9 @@ __device__ __forceinline__ void stage_dw_mode(const ConvArgs &a, float *lds, int
 }
 
 template <int TP, bool SPLIT>
-__device__ __forceinline__ void stage_dw(const ConvArgs &a, float *lds, int q0) {
-    if (a.dw_mode == kDwPair) stage_dw_mode<TP, kDwPair, SPLIT>(a, lds, q0);
-    else stage_dw_mode<TP, kDwNine, SPLIT>(a, lds, q0);
+__device__ __forceinline__ void stage_dw(const ConvArgs &a, float *lds, int q0, int q_end) {
+    if (a.dw_mode == kDwPair) stage_dw_mode<TP, kDwPair, SPLIT>(a, lds, q0, q_end);
+    else stage_dw_mode<TP, kDwNine, SPLIT>(a, lds, q0, q_end);
 }
 #endif
 
@@ -572,11 +577,11 @@ struct PixOut {
 
 // PSTRIDE > 0: the lane's pixels are PSTRIDE apart (see tile_pos), else neighbours.
 template <int PV, bool VEC, int PSTRIDE = 0>
-__device__ __forceinline__ void pix_out(const ConvArgs &a, int q0, int lane, PixOut<PV> &px) {
+__device__ __forceinline__ void pix_out(const ConvArgs &a, int q0, int lane, PixOut<PV> &px, int q_end) {
 #pragma unroll
     for (int pv = 0; pv < PV; ++pv) {
         const int q = PSTRIDE > 0 ? q0 + lane + pv * PSTRIDE : q0 + lane * PV + pv;
-        px.valid[pv] = q < a.NP;
+        px.valid[pv] = q < q_end;
         if (VEC && pv > 0) {
             px.yoff[pv] = px.yoff[0] + pv;
         } else {
@@ -748,7 +753,11 @@ __device__ __forceinline__ void pw_resident_body(const ConvArgs &a) {
     const int logical = logical_wg(a);
     if (logical >= a.total_wgs || (a.debug & 8)) return;
     const int pt = logical / a.ngt, gt = logical - pt * a.ngt;
-    const int q0 = pt * TP;
+    // the workgroup's pixels [q0, q_end): all TP of the tile, or fewer when the launcher
+    // spreads the pixels over more workgroups than full tiles would give (the rest of the
+    // tile is staged as zeros and not stored)
+    const int q0 = pt * a.tile_px;
+    const int q_end = min(a.NP, q0 + a.tile_px);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), nw = blockDim.x >> 6;
     const int g_begin = gt * a.gpt;
@@ -766,9 +775,9 @@ __device__ __forceinline__ void pw_resident_body(const ConvArgs &a) {
     }
 
 #if ALCS_DW_STAGE
-    if (!(a.debug & 1)) stage_dw<TP, SPLIT>(a, lds, q0);
+    if (!(a.debug & 1)) stage_dw<TP, SPLIT>(a, lds, q0, q_end);
 #else
-    if (!(a.debug & 1)) stage_pw<TP, VEC, SPLIT>(a, lds, q0, 0, a.Cin);
+    if (!(a.debug & 1)) stage_pw<TP, VEC, SPLIT>(a, lds, q0, 0, a.Cin, q_end);
 #endif
     for (int t = tid; t < TP; t += blockDim.x) lds[a.KC * TP + t] = 0.f;  // the all-zero row
     __syncthreads();
@@ -776,7 +785,7 @@ __device__ __forceinline__ void pw_resident_body(const ConvArgs &a) {
 
     const int plane = lane & (64 / GS - 1);  // the lane's place among the pixels (pairs, quads) of the tile
     PixOut<PV> px;
-    pix_out<PV, VEC, SPLIT ? TP / 2 : 0>(a, q0, plane, px);
+    pix_out<PV, VEC, SPLIT ? TP / 2 : 0>(a, q0, plane, px, q_end);
     const char *ldsb = reinterpret_cast<const char *>(lds);
     const int base = plane * PV * 4;
     for (int k = 0;; ++k) {
@@ -854,7 +863,7 @@ __global__ void __launch_bounds__(512) k_pw_chunked(const ConvArgs a) {
             }
         }
         if (ch) __syncthreads();
-        if (!(a.debug & 1)) stage_pw<TP, VEC>(a, lds, q0, c0, c1);
+        if (!(a.debug & 1)) stage_pw<TP, VEC>(a, lds, q0, c0, c1, a.NP);
         __syncthreads();
         const int base = lane * PV * 4 - c0 * (kRowBytes1 << SH);
 #pragma unroll
@@ -863,7 +872,7 @@ __global__ void __launch_bounds__(512) k_pw_chunked(const ConvArgs a) {
                 mac_segment<V, PV, SH>(a, wk[u].start, wk[u].cnt, ldsb, base, lane, rn[u], acc[u]);
     }
     PixOut<PV> px;
-    pix_out<PV, VEC>(a, q0, lane, px);
+    pix_out<PV, VEC>(a, q0, lane, px, a.NP);
 #pragma unroll
     for (int u = 0; u < UG; ++u)
         if (slot[u] >= 0 && !(a.debug & 4))
@@ -1375,6 +1384,7 @@ static int launch_sparse(const alcs_packed_t *Wp, const io_t *X_dev, const float
             lds = (Cin + 1) * TP * 4;
             if (lds > kMaxLds) return ALCS_E_UNSUPPORTED;
             a.npt = ceil_div(a.NP, TP);
+            a.tile_px = TP;
             // Group tiles: split the bundles over several workgroups only when there are too
             // few pixel tiles (every extra group tile re-stages the pixel tile's rows).  With
             // one resident workgroup per compute unit aim at one round (<= 256 workgroups),
@@ -1386,6 +1396,21 @@ static int launch_sparse(const alcs_packed_t *Wp, const io_t *X_dev, const float
             if (T.group_tiles > 0) ngt = std::min(T.group_tiles, NB);
             a.gpt = ceil_div(NB, ngt);
             a.ngt = ceil_div(NB, a.gpt);
+            // A single round that would leave compute units idle (196 tiles of 32 pixels for
+            // 32 images of 14x14): give every workgroup fewer pixels of its tile instead (a
+            // multiple of 4, at least half the tile), so that all compute units share the work
+            // (512->512 @14x14: 15.4 -> 14.9 us).  Only with several groups per wavefront, i.e.
+            // from 512 input channels on, where the multiply weighs most: on the layers with
+            // fewer channels the shorter, less aligned load and store runs cost as much as the
+            // idle compute units (256->256 @28x28: 17.0 -> 17.5 us).
+            if (GS > 1 && (long long)a.npt * a.ngt < kCUs && !(T.debug & 64)) {
+                const int tiles_wanted = kCUs / a.ngt;
+                const int tp = (ceil_div(a.NP, tiles_wanted) + 3) & ~3;
+                if (tp < TP && 2 * tp >= TP) {
+                    a.tile_px = tp;
+                    a.npt = ceil_div(a.NP, tp);
+                }
+            }
             nw = lds > 40 * 1024 ? 16 : 8;
             // fewer wavefronts when the group tile has fewer bundles, but at least one per 8 KB
             // of tile (4 KB with four groups per wavefront, whose group tiles hold few

@@ -95,6 +95,13 @@ def test_several_groups_per_wavefront_pixel_pairs_bf16(slots, pv):
     assert info["group_slots"] == slots and info["pv"] == pv
 
 
+def test_single_round_spreads_pixels_over_all_compute_units_bf16():
+    L = workloads.Layer("bf_narrow", 512, 64, 14, 14, N=32, V=4, sparsity=0.9, w_std=0.1)
+    full = run_bf16(L, 3570, act="relu", with_res=True, debug=64)
+    spread = run_bf16(L, 3570, act="relu", with_res=True, debug=0)
+    assert spread["workgroups"] > full["workgroups"], (full, spread)
+
+
 def test_in_place_residual_and_no_bias_bf16():
     L = workloads.Layer("bf_inplace", 64, 64, 14, 14, N=4, V=4, sparsity=0.8, w_std=0.3)
     run_bf16(L, 3560, act="relu", with_res=True, in_place=True, with_bias=False)

@@ -150,6 +150,15 @@ def test_block_several_groups_per_wavefront(Cin, slots):
     assert info["group_slots"] == slots
 
 
+@pytest.mark.parametrize("Cin,hw,dw_stride,N", [(512, 14, 1, 32), (512, 7, 2, 120)])
+def test_block_single_round_spreads_pixels_over_all_compute_units(Cin, hw, dw_stride, N):
+    # workgroups that take fewer pixels than their tile holds (see the pointwise test of the same name)
+    L = workloads.Layer("blk_narrow", Cin, 64, hw, hw, N=N, V=4, sparsity=0.9, w_std=0.1)
+    full = run_block(L, hw * dw_stride, hw * dw_stride, dw_stride, 2400 + hw, debug=64)
+    spread = run_block(L, hw * dw_stride, hw * dw_stride, dw_stride, 2400 + hw, debug=0)
+    assert spread["workgroups"] > full["workgroups"], (full, spread)
+
+
 @pytest.mark.parametrize("slots", [2, 4])
 @pytest.mark.parametrize("hw,dw_stride", [(8, 1), (8, 2), (7, 1)])
 @pytest.mark.parametrize("pv", [1, 2])

@@ -106,6 +106,21 @@ def test_pointwise_several_groups_per_wavefront_two_pixels_per_lane(V, gs, hw):
     assert info["mode"] == 1 and info["group_slots"] == gs and info["pv"] == 2
 
 
+@pytest.mark.parametrize("Cin,Cout,hw,N", [(512, 64, 14, 32),    # four groups per wavefront, pixel pairs: 28 of 32 pixels
+                                           (512, 64, 7, 120),    # the same where pairs are half a tile apart: 24 of 32
+                                           (1300, 64, 14, 15)])  # one pixel per lane: 16-pixel tiles, 12 of 16
+def test_pointwise_single_round_spreads_pixels_over_all_compute_units(Cin, Cout, hw, N):
+    """A launch of one round with fewer workgroups than compute units gives every workgroup
+    fewer pixels than its tile holds; debug bit 6 keeps full tiles.  Both must match the oracle."""
+    L = workloads.Layer("pw_narrow", Cin, Cout, hw, hw, N=N, V=4, sparsity=0.9)
+    full = check(L, 480 + Cin + hw, debug=64)
+    alcs.alcs_set_tuning("debug", 0)
+    spread = check(L, 480 + Cin + hw)
+    assert full["mode"] == 1 and spread["mode"] == 1
+    assert spread["workgroups"] > full["workgroups"], (full, spread)
+    assert spread["workgroups"] <= 256
+
+
 @pytest.mark.parametrize("Cin,gs", [(512, 4), (1100, 4), (2048, 4)])
 def test_pointwise_wide_inputs_pair_groups_by_default(Cin, gs):
     L = workloads.Layer("pw_wide%d" % Cin, Cin, 40, 7, 7, N=3, V=4, sparsity=0.9)
