@@ -702,33 +702,52 @@ __device__ __forceinline__ int lane_group(const Work &w, int lane) {
     return (slot & 2) ? hi : lo;
 }
 
-// Epilogue with GS groups per wavefront: g is the group of the lane's slot (-1: none).
-// In vector form the two pixels of a lane are an 8-byte aligned pair inside one image and
-// go out as one store.
-template <int V, int PV, int GS, bool VEC>
-__device__ __forceinline__ void store_slots(const ConvArgs &a, const Acc<V, PV, true> &acc, int g,
-                                            const PixOut<PV> &px) {
-    static_assert(PV == 1 || PV == 2, "several groups per wavefront: one or two pixels per lane");
-    if (g < 0) return;
+// The bias of the V channels of the lane's group (several groups per wavefront: the group
+// differs between lanes, so these are vector loads), fetched before the group is multiplied:
+// a load issued in the epilogue would be waited for at once, channel after channel, each
+// behind the previous channel's store.
+template <int V>
+struct SlotBias {
+    float b[V];
+};
+template <int V>
+__device__ __forceinline__ void load_slot_bias(const ConvArgs &a, int g, SlotBias<V> &sb) {
 #pragma unroll
     for (int v = 0; v < V; ++v) {
-        const int ch = g * V + v;
-        if (ch >= a.Cout) break;
-        const float b = a.bias ? a.bias[ch] : 0.f;
+        sb.b[v] = 0.f;
+        if (a.bias && g >= 0 && g * V + v < a.Cout) sb.b[v] = a.bias[g * V + v];
+    }
+}
+
+// Epilogue with GS groups per wavefront: g is the group of the lane's slot (-1: none).
+// In vector form the two pixels of a lane are an 8-byte aligned pair inside one image and
+// go out as one store.  The output address is formed once per group and advanced by one
+// image plane per channel.
+template <int V, int PV, int GS, bool VEC>
+__device__ __forceinline__ void store_slots(const ConvArgs &a, const Acc<V, PV, true> &acc, int g,
+                                            const PixOut<PV> &px, const SlotBias<V> &sb) {
+    static_assert(PV == 1 || PV == 2, "several groups per wavefront: one or two pixels per lane");
+    if (g < 0) return;
+    const size_t ch0 = (size_t)g * V * a.P;
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        if (g * V + v >= a.Cout) break;
+        const size_t plane = ch0 + (size_t)v * a.P;
+        const float b = sb.b[v];
         if constexpr (PV == 2 && VEC) {
             if (px.valid[0]) {
                 f2 o = f2{acc.get(v, 0) + b, acc.get(v, 1) + b};
-                if (residual_of(a)) o += io_load2(residual_of(a) + (size_t)ch * a.P + px.yoff[0]);
+                if (residual_of(a)) o += io_load2(residual_of(a) + plane + px.yoff[0]);
                 if (kFused && a.act) o = f2{activate(a, o[0]), activate(a, o[1])};
-                io_store2(a.Y + (size_t)ch * a.P + px.yoff[0], o);
+                io_store2(a.Y + plane + px.yoff[0], o);
             }
         } else {
 #pragma unroll
             for (int pv = 0; pv < PV; ++pv)
                 if (px.valid[pv]) {
                     float o = acc.get(v, pv) + b;
-                    if (residual_of(a)) o += io_load1(residual_of(a) + (size_t)ch * a.P + px.yoff[pv]);
-                    io_store1(a.Y + (size_t)ch * a.P + px.yoff[pv], activate(a, o));
+                    if (residual_of(a)) o += io_load1(residual_of(a) + plane + px.yoff[pv]);
+                    io_store1(a.Y + plane + px.yoff[pv], activate(a, o));
                 }
         }
     }
@@ -799,10 +818,16 @@ __device__ __forceinline__ void pw_resident_body(const ConvArgs &a) {
         acc.zero();
         Resid<V, PV> rr;
         if constexpr (RES) load_residual<V, PV, VEC>(a, w0.group[0], px, rr);
+        SlotBias<GS == 1 ? 1 : V> sb;
+        int g_lane = w0.group[0];
+        if constexpr (GS > 1) {
+            g_lane = lane_group<GS>(w0, lane);
+            load_slot_bias<V>(a, g_lane, sb);
+        }
         if (!(a.debug & 2)) mac_segment<V, PV, SH, GS>(a, w0.start, w0.cnt, ldsb, base, lane, run0, acc);
         if (!(a.debug & 4)) {
             if constexpr (GS == 1) store_group<V, PV, MF, VEC>(a, acc, w0.group[0], px, RES ? &rr : nullptr);
-            else store_slots<V, PV, GS, VEC>(a, acc, lane_group<GS>(w0, lane), px);
+            else store_slots<V, PV, GS, VEC>(a, acc, g_lane, px, sb);
         }
         if (!more) break;
         w0 = w1;
