@@ -25,6 +25,7 @@
 #include <algorithm>
 #include <cstdint>
 #include <mutex>
+#include <map>
 #include <set>
 #include <utility>
 
@@ -1241,6 +1242,21 @@ static int set_lds_limit(kern_t k, int lds) {
     return ALCS_OK;
 }
 
+// Vector registers per lane of a kernel (0 if the runtime cannot tell), looked up once.
+static int kernel_registers(kern_t k) {
+    static std::mutex mu;
+    static std::map<const void *, int> known;
+    std::lock_guard<std::mutex> lock(mu);
+    auto it = known.find((const void *)k);
+    if (it != known.end()) return it->second;
+    hipFuncAttributes attr;
+    int regs = 0;
+    if (hipFuncGetAttributes(&attr, (const void *)k) == hipSuccess) regs = attr.numRegs;
+    else (void)hipGetLastError();
+    known[(const void *)k] = regs;
+    return regs;
+}
+
 #if ALCS_DW_STAGE
 }  // namespace dwpw
 #elif ALCS_IO_BF16
@@ -1441,7 +1457,6 @@ static int launch_sparse(const alcs_packed_t *Wp, const io_t *X_dev, const float
             // of tile (4 KB with four groups per wavefront, whose group tiles hold few
             // bundles): wavefronts without a bundle still help to stage it
             nw = std::min(nw, std::max(std::max(1, a.gpt), lds / (GS == 4 ? 4096 : 8192)));
-            if (T.waves > 0) nw = std::min(T.waves, 16);
             switch (V) {
                 case 1: kern = pick_resident<1, false>(pv, vec, GS); break;
                 case 2: kern = pick_resident<2, false>(pv, vec, GS); break;
@@ -1449,6 +1464,14 @@ static int launch_sparse(const alcs_packed_t *Wp, const io_t *X_dev, const float
                 case 8: kern = pick_resident<8, true>(pv, vec, GS, a.residual != nullptr); break;
                 case 16: kern = pick_resident<16, true>(pv, vec, GS, a.residual != nullptr); break;
             }
+            // A kernel that holds more than 64 registers per lane fits fewer than 32 wavefronts
+            // on a compute unit, so two of its 16-wavefront workgroups cannot share one.  With
+            // more workgroups than compute units and tiles of which two fit, 8 wavefronts per
+            // workgroup let two workgroups overlap their phases (four groups per wavefront, 86
+            // registers: 512->128 @28x28, N=64: 55 -> 43 us; 512->512 @14x14, N=256: 97 -> 89 us;
+            // 10 or 12 wavefronts measured no better than 16); a single round is faster with 16.
+            if (nw > 8 && (long long)a.npt * a.ngt > kCUs && 2 * lds <= kMaxLds && kernel_registers(kern) > 64) nw = 8;
+            if (T.waves > 0) nw = std::min(T.waves, 16);
         } else {
 #if ALCS_RESIDENT_ONLY
             return ALCS_E_UNSUPPORTED;  // this build holds the resident kernels only
