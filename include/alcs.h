@@ -240,7 +240,8 @@ int alcs_dense_conv(const float *W_dev, const float *X_dev, const float *bias_de
  * concurrent calls).  A value of 0 restores the automatic choice.
  *   read by alcs_sparse_conv:
  *     "pv"              pixels per lane of the 1x1 kernels: 1, 2 or 4 (1 or 2 with several
- *                       groups per wavefront)
+ *                       groups per wavefront); of the 3x3 kernel: 1 or 2 (2: tiles of twice the
+ *                       height, stride 1 and V = 4 or 8 only)
  *     "waves"           wavefronts per workgroup
  *     "group_tiles"     number of workgroups that share one pixel tile
  *     "path"            1 = plain-FMA inner loop where it exists (V = 4), 2 = MFMA inner

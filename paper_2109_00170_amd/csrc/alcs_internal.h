@@ -29,21 +29,26 @@ constexpr int kCntAlign = 8;   // and its padded length is a multiple of 8 colum
 constexpr int kTileShapes3 = 3;
 inline constexpr int tile_w3(int ti) { return 8 << ti; }
 inline constexpr int tile_h3(int ti) { return 8 >> ti; }
-inline constexpr int halo_rows3(int stride, int ti) { return (tile_h3(ti) - 1) * stride + 3; }
+// "Tall" tiles (stride 1, MFMA kernels): twice the rows, and a lane owns the pixels (ly, lx) and
+// (ly + TH, lx); their LDS words are TH * pitch apart, which one ds_read2_b32 fetches together.
+inline constexpr int tile_rows3(int ti, bool tall) { return tall ? 2 * tile_h3(ti) : tile_h3(ti); }
+inline constexpr int halo_rows3(int stride, int ti, bool tall = false) { return (tile_rows3(ti, tall) - 1) * stride + 3; }
 inline constexpr int halo_cols3(int stride, int ti) { return (tile_w3(ti) - 1) * stride + 3; }
 inline constexpr int pitch3(int stride, int ti) {
     return stride == 1 ? (ti == 0 ? 24 : ti == 1 ? 48 : 96) : (ti == 0 ? 28 : ti == 1 ? 40 : 80);
 }
 inline constexpr int odd3(int ti) { return ti == 0 ? 12 : ti == 1 ? 20 : 40; }
-inline constexpr int halo_area3(int stride, int ti) { return halo_rows3(stride, ti) * pitch3(stride, ti); }
+inline constexpr int halo_area3(int stride, int ti, bool tall = false) { return halo_rows3(stride, ti, tall) * pitch3(stride, ti); }
+inline constexpr int tall_step3(int ti) { return tile_h3(ti) * pitch3(1, ti); }  // words between a lane's two pixels
 inline constexpr int halo_col3(int stride, int ti, int hx) {
     return stride == 1 ? hx : ((hx & 1) ? odd3(ti) + (hx >> 1) : (hx >> 1));
 }
 // Compile-time proof of the two properties the kernels rely on: the 64 lane offsets of a
 // read are distinct modulo 64 (hence also no more than 2 lanes per bank of 32), and the
 // farthest read (last lane, last tap) stays inside the plane.
-inline constexpr bool layout3_ok(int stride, int ti) {
+inline constexpr bool layout3_ok(int stride, int ti, bool tall = false) {
     const int tw = tile_w3(ti), pitch = pitch3(stride, ti);
+    if (tall && (stride != 1 || tall_step3(ti) > 255)) return false;  // offset field of ds_read2_b32
     bool used[64] = {};
     for (int lane = 0; lane < 64; ++lane) {
         const int o = (lane / tw) * stride * pitch + lane % tw;
@@ -52,7 +57,7 @@ inline constexpr bool layout3_ok(int stride, int ti) {
     }
     int far = 0;
     for (int s = 0; s < 3; ++s) {
-        const int o = (tile_h3(ti) - 1) * stride * pitch + tw - 1 + 2 * pitch + halo_col3(stride, ti, s);
+        const int o = (tile_rows3(ti, tall) - 1) * stride * pitch + tw - 1 + 2 * pitch + halo_col3(stride, ti, s);
         far = o > far ? o : far;
     }
     // the staged columns of a row must fit the pitch as well
@@ -61,14 +66,20 @@ inline constexpr bool layout3_ok(int stride, int ti) {
         const int o = halo_col3(stride, ti, hx);
         widest = o > widest ? o : widest;
     }
-    return far < halo_area3(stride, ti) && widest < pitch;
+    return far < halo_area3(stride, ti, tall) && widest < pitch;
 }
 static_assert(layout3_ok(1, 0) && layout3_ok(1, 1) && layout3_ok(1, 2) && layout3_ok(2, 0) &&
-                  layout3_ok(2, 1) && layout3_ok(2, 2),
+                  layout3_ok(2, 1) && layout3_ok(2, 2) && layout3_ok(1, 0, true) && layout3_ok(1, 1, true) &&
+                  layout3_ok(1, 2, true),
               "3x3 LDS plane layout");
-// index of the selector table of a (stride, tile shape) pair
-inline constexpr int off_table3(int stride, int ti) { return (stride - 1) * kTileShapes3 + ti; }
-constexpr int kMaxOff = 2 * kTileShapes3;
+// index of the selector table of a (stride, tile shape, tall) triple, and back
+inline constexpr int off_table3(int stride, int ti, bool tall = false) {
+    return tall ? 2 * kTileShapes3 + ti : (stride - 1) * kTileShapes3 + ti;
+}
+constexpr int kMaxOff = 3 * kTileShapes3;
+inline constexpr int table_stride3(int table) { return table / kTileShapes3 == 1 ? 2 : 1; }
+inline constexpr int table_ti3(int table) { return table % kTileShapes3; }
+inline constexpr bool table_tall3(int table) { return table / kTileShapes3 == 2; }
 
 // Bytes per LDS row that the stored 1x1 row selectors assume with one group per
 // wavefront (a 64-pixel fp32 tile); with GS groups per wavefront the tile has 64/GS

@@ -37,13 +37,13 @@ static inline int col_channel(int col, int kk) { return col / kk; }
 static inline int32_t off_of(int col, int k, int table, int GS) {
     if (k == 1) return col * (kRowBytes1 / GS);
     const int c = col / 9, tap = col % 9, r = tap / 3, s = tap % 3;
-    const int stride = table / kTileShapes3 + 1, ti = table % kTileShapes3;
-    return (c * halo_area3(stride, ti) + r * pitch3(stride, ti) + halo_col3(stride, ti, s)) * 4;
+    const int stride = table_stride3(table), ti = table_ti3(table);
+    return (c * halo_area3(stride, ti, table_tall3(table)) + r * pitch3(stride, ti) + halo_col3(stride, ti, s)) * 4;
 }
 
 static inline int32_t pad_off(int c0, int KC, int k, int table, int GS) {
     if (k == 1) return (c0 + KC) * (kRowBytes1 / GS);
-    return (c0 + KC) * halo_area3(table / kTileShapes3 + 1, table % kTileShapes3) * 4;
+    return (c0 + KC) * halo_area3(table_stride3(table), table_ti3(table), table_tall3(table)) * 4;
 }
 
 // Index of (bundle column `col` counted from the start of the arrays, slot s) in a

@@ -249,9 +249,15 @@ struct Acc<V, PV, false> {
     __device__ __forceinline__ float get(int v, int pv) const { return a[v][pv]; }
 };
 
-template <int PV>
+// The lane's PV pixels of one LDS row: neighbours (PD = 1), or two words PD apart, which the
+// compiler fetches with one ds_read2_b32 (PD <= 255, no alignment beyond 4 bytes needed).
+template <int PV, int PD = 1>
 __device__ __forceinline__ void lds_read(const float *p, float (&x)[PV]) {
-    if constexpr (PV == 4) {
+    if constexpr (PD != 1) {
+        static_assert(PV == 2 && PD <= 255, "two pixels a fixed distance apart");
+        x[0] = p[0];
+        x[1] = p[PD];
+    } else if constexpr (PV == 4) {
         f4 t = *reinterpret_cast<const f4 *>(p);
         x[0] = t[0]; x[1] = t[1]; x[2] = t[2]; x[3] = t[3];
     } else if constexpr (PV == 2) {
@@ -354,7 +360,7 @@ __device__ __forceinline__ int bcast_sel(int ov) {
 // the run's selectors already scaled to the row length (the caller shifts the register once
 // per run: a shift behind the broadcast would cost a move, a broadcast and a shift-add per
 // column where one add with the broadcast folded in does).
-template <int B0, int B, int V, int PV, int GS>
+template <int B0, int B, int V, int PV, int GS, int PD = 1>
 __device__ __forceinline__ void mfma_batch(const float (&aw)[(V / 4) * GS], int ov, const char *lds,
                                            int base, Acc<V, PV, true> &acc) {
     constexpr int CPA = 16 / GS;           // columns per weight register
@@ -362,7 +368,7 @@ __device__ __forceinline__ void mfma_batch(const float (&aw)[(V / 4) * GS], int 
     float x[B][PV];
     static_for<B>([&](auto c) {
         constexpr int C = decltype(c)::value;
-        lds_read<PV>(reinterpret_cast<const float *>(lds + base + bcast_sel<B0 + C>(ov)), x[C]);
+        lds_read<PV, PD>(reinterpret_cast<const float *>(lds + base + bcast_sel<B0 + C>(ov)), x[C]);
     });
     // With two pixels per lane the scheduler would trade reads in flight for registers and
     // interleave two reads at a time with the MFMAs; keep all B reads ahead of them.  (With
@@ -386,7 +392,7 @@ __device__ __forceinline__ void mfma_batch(const float (&aw)[(V / 4) * GS], int 
 // MFMA form.  start/cnt are wave-uniform; base is the lane's byte offset inside an LDS
 // row (minus the chunk's first row); SH = log2(pixels per lane) for 1x1, 0 for 3x3.
 // `rs` holds the segment's first runs, loaded by the caller (see Runs).
-template <int V, int PV, int SH, int GS = 1>
+template <int V, int PV, int SH, int GS = 1, int PD = 1>
 __device__ __forceinline__ void mac_segment(const ConvArgs &a, int start, int cnt,
                                             const char *lds, int base, int lane,
                                             Runs<V, true, GS> rs, Acc<V, PV, true> &acc) {
@@ -400,8 +406,8 @@ __device__ __forceinline__ void mac_segment(const ConvArgs &a, int start, int cn
             if (j < cnt) {
                 // selectors are byte offsets for 64-pixel rows: scale them to this tile's rows
                 const int ov = rs.r[I].o << SH;
-                mfma_batch<0, B, V, PV, GS>(rs.r[I].a, ov, lds, base, acc);
-                if (j + 8 < cnt) mfma_batch<8, B, V, PV, GS>(rs.r[I].a, ov, lds, base, acc);
+                mfma_batch<0, B, V, PV, GS, PD>(rs.r[I].a, ov, lds, base, acc);
+                if (j + 8 < cnt) mfma_batch<8, B, V, PV, GS, PD>(rs.r[I].a, ov, lds, base, acc);
                 if (j + 16 * N < cnt) rs.r[I] = load_run<V, true, GS>(a, start + j + 16 * N, lane);
             }
         });
@@ -410,11 +416,11 @@ __device__ __forceinline__ void mac_segment(const ConvArgs &a, int start, int cn
 
 // Same segment with plain FMAs; selectors and the V weights of a column come from
 // scalar loads.
-template <int V, int PV, int SH, int GS = 1>
+template <int V, int PV, int SH, int GS = 1, int PD = 1>
 __device__ __forceinline__ void mac_segment(const ConvArgs &a, int start, int cnt,
                                             const char *lds, int base, int lane,
                                             Runs<V, false, GS> first, Acc<V, PV, false> &acc) {
-    static_assert(V <= 4 && GS == 1, "FMA path is built for V <= 4, one group per wavefront");
+    static_assert(V <= 4 && GS == 1 && PD == 1, "FMA path is built for V <= 4, one group per wavefront");
     (void)lane;
     (void)first;
     cptr<float> wp = as_const(a.w) + (size_t)start * V;
@@ -1022,13 +1028,19 @@ __global__ void __launch_bounds__(512) k_pw_stream(const ConvArgs a) {
 // chunks of KC, each channel as a haloed plane in the bank-conflict-free layout described
 // with halo_col3.  The selector stored with every kept column is
 // 4*(c*HA + r*pitch + col(s)), so the tap shift costs nothing at run time.
-template <int V, int STRIDE, int TI, int UG, bool MF>
+// TALL (stride 1, MFMA form): the tile has 2*TH rows and a lane owns the pixels (ly, lx) and
+// (ly + TH, lx), whose LDS words one ds_read2_b32 fetches together: two MFMAs per LDS
+// instruction instead of one, in a kernel whose multiply is bound by its LDS reads.
+template <int V, int STRIDE, int TI, int UG, bool MF, bool TALL = false>
 __global__ void __launch_bounds__(512) k_conv3(const ConvArgs a) {
+    static_assert(!TALL || (STRIDE == 1 && MF), "tall tiles: stride 1, MFMA form");
     extern __shared__ float lds[];
-    constexpr int TW = tile_w3(TI), TH = tile_h3(TI);
-    constexpr int ROWS = halo_rows3(STRIDE, TI), COLS = halo_cols3(STRIDE, TI);
+    constexpr int PV = TALL ? 2 : 1;
+    constexpr int PD = TALL ? tall_step3(TI) : 1;
+    constexpr int TW = tile_w3(TI), TH = tile_h3(TI), TROWS = tile_rows3(TI, TALL);
+    constexpr int ROWS = halo_rows3(STRIDE, TI, TALL), COLS = halo_cols3(STRIDE, TI);
     constexpr int PITCH = pitch3(STRIDE, TI);
-    constexpr int HA = halo_area3(STRIDE, TI);
+    constexpr int HA = halo_area3(STRIDE, TI, TALL);
     constexpr int HPOS = ROWS * COLS;          // halo positions that are actually loaded
     const int logical = logical_wg(a);
     if (logical >= a.total_wgs || (a.debug & 8)) return;
@@ -1036,7 +1048,7 @@ __global__ void __launch_bounds__(512) k_conv3(const ConvArgs a) {
     const int tiles_per_img = a.tiles_x * a.tiles_y;
     const int n = pt / tiles_per_img, trem = pt - n * tiles_per_img;
     const int tyi = trem / a.tiles_x, txi = trem - tyi * a.tiles_x;
-    const int oy0 = tyi * TH, ox0 = txi * TW;
+    const int oy0 = tyi * TROWS, ox0 = txi * TW;
     const int iy0 = oy0 * STRIDE - 1, ix0 = ox0 * STRIDE - 1;
     const int tid = threadIdx.x, lane = tid & 63, nt = blockDim.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -1045,7 +1057,7 @@ __global__ void __launch_bounds__(512) k_conv3(const ConvArgs a) {
 
     const char *ldsb = reinterpret_cast<const char *>(lds);
     int slot[UG];
-    Acc<V, 1, MF> acc[UG];
+    Acc<V, PV, MF> acc[UG];
 #pragma unroll
     for (int u = 0; u < UG; ++u) {
         const int idx = wave * UG + u;
@@ -1125,16 +1137,19 @@ __global__ void __launch_bounds__(512) k_conv3(const ConvArgs a) {
         const int base = (lane_base - c0 * HA) * 4;
 #pragma unroll
         for (int u = 0; u < UG; ++u)
-            if (slot[u] >= 0 && !(a.debug & 2)) mac_segment<V, 1, 0>(a, wk[u].start, wk[u].cnt, ldsb, base, lane, rn[u], acc[u]);
+            if (slot[u] >= 0 && !(a.debug & 2)) mac_segment<V, PV, 0, 1, PD>(a, wk[u].start, wk[u].cnt, ldsb, base, lane, rn[u], acc[u]);
     }
     const int oy = oy0 + ly, ox = ox0 + lx;
-    PixOut<1> px;
-    px.valid[0] = oy < a.Ho && ox < a.Wo;
-    px.yoff[0] = (long long)n * a.Cout * a.P + (long long)oy * a.Wo + ox;
+    PixOut<PV> px;
+#pragma unroll
+    for (int pv = 0; pv < PV; ++pv) {
+        px.valid[pv] = oy + pv * TH < a.Ho && ox < a.Wo;
+        px.yoff[pv] = (long long)n * a.Cout * a.P + (long long)(oy + pv * TH) * a.Wo + ox;
+    }
 #pragma unroll
     for (int u = 0; u < UG; ++u)
         if (slot[u] >= 0 && !(a.debug & 4))
-            store_group<V, 1, MF, false>(a, acc[u], load_work(a.work, (size_t)slot[u] * a.nchunks).group[0], px);
+            store_group<V, PV, MF, false>(a, acc[u], load_work(a.work, (size_t)slot[u] * a.nchunks).group[0], px);
 }
 
 #endif  // !ALCS_RESIDENT_ONLY
@@ -1191,22 +1206,26 @@ static kern_t pick_chunked(int pv, bool vec, int ug) {
 }
 
 template <int V, int TI, bool MF>
-static kern_t pick_conv3_shape(int stride, int ug) {
+static kern_t pick_conv3_shape(int stride, int ug, bool tall) {
+    if constexpr (MF && V <= 8) {
+        if (tall && stride == 1) return ug == 2 ? k_conv3<V, 1, TI, 2, true, true> : k_conv3<V, 1, TI, 4, true, true>;
+    }
+    if (tall) return nullptr;
     if (ug == 2) return stride == 1 ? k_conv3<V, 1, TI, 2, MF> : k_conv3<V, 2, TI, 2, MF>;
     return stride == 1 ? k_conv3<V, 1, TI, 4, MF> : k_conv3<V, 2, TI, 4, MF>;
 }
 template <int V, bool MF>
-static kern_t pick_conv3(int stride, int ti, int ug) {
-    if (ti == 2) return pick_conv3_shape<V, 2, MF>(stride, ug);
-    if (ti == 1) return pick_conv3_shape<V, 1, MF>(stride, ug);
-    return pick_conv3_shape<V, 0, MF>(stride, ug);
+static kern_t pick_conv3(int stride, int ti, int ug, bool tall) {
+    if (ti == 2) return pick_conv3_shape<V, 2, MF>(stride, ug, tall);
+    if (ti == 1) return pick_conv3_shape<V, 1, MF>(stride, ug, tall);
+    return pick_conv3_shape<V, 0, MF>(stride, ug, tall);
 }
 
 #endif  // !ALCS_RESIDENT_ONLY
 
 // Tile shape of the 3x3 kernel: the share of lanes that fall on real output pixels decides,
 // with a preference for wide tiles (longer contiguous loads and stores).
-static int pick_tile3(int Ho, int Wo, int forced_w) {
+static int pick_tile3(int Ho, int Wo, int forced_w, bool tall) {
     if (forced_w == 8) return 0;
     if (forced_w == 16) return 1;
     if (forced_w == 32) return 2;
@@ -1214,7 +1233,8 @@ static int pick_tile3(int Ho, int Wo, int forced_w) {
     int best = 0;
     double best_score = 0;
     for (int ti = 0; ti < kTileShapes3; ++ti) {
-        const double covered = (double)ceil_div(Ho, tile_h3(ti)) * tile_h3(ti) * ceil_div(Wo, tile_w3(ti)) * tile_w3(ti);
+        const int th = tile_rows3(ti, tall);
+        const double covered = (double)ceil_div(Ho, th) * th * ceil_div(Wo, tile_w3(ti)) * tile_w3(ti);
         const double score = (double)Ho * Wo / covered * bonus[ti];
         if (score > best_score) { best_score = score; best = ti; }
     }
@@ -1502,11 +1522,23 @@ static int launch_sparse(const alcs_packed_t *Wp, const io_t *X_dev, const float
         return ALCS_E_UNSUPPORTED;
 #else
         mode = 3;
-        ti = pick_tile3(Ho, Wo, T.tile_w);
-        a.off = Wp->dev.off[off_table3(stride, ti)];
-        lds = (L.KC + 1) * halo_area3(stride, ti) * 4;
+        // Tall tiles (two pixels per lane): stride 1, MFMA form, accumulators of at most 8
+        // channels.  By default for V = 4 on images of at least 12x12, which 16- or 8-row tiles
+        // still cover well (128->128 @28x28, N=64: 85 -> 71 us; 64->64 @56x56: 85 -> 80 us;
+        // 256->256 @14x14: 87 -> 81 us; a 7x7 image would leave most of a tall tile empty:
+        // 90 -> 158 us); "pv" = 1 or 2 forces the choice.
+        bool tall = stride == 1 && mfma && V <= 8 &&
+                    (T.pv == 2 || (T.pv == 0 && V == 4 && Ho >= 12 && Wo >= 12));
+        ti = pick_tile3(Ho, Wo, T.tile_w, tall);
+        if (tall && (L.KC + 1) * halo_area3(stride, ti, true) * 4 > kMaxLds) {
+            tall = false;
+            ti = pick_tile3(Ho, Wo, T.tile_w, false);
+        }
+        pv = tall ? 2 : 1;
+        a.off = Wp->dev.off[off_table3(stride, ti, tall)];
+        lds = (L.KC + 1) * halo_area3(stride, ti, tall) * 4;
         a.tiles_x = ceil_div(Wo, tile_w3(ti));
-        a.tiles_y = ceil_div(Ho, tile_h3(ti));
+        a.tiles_y = ceil_div(Ho, tile_rows3(ti, tall));
         a.npt = a.tiles_x * a.tiles_y * N;
         nw = 8;
         if (T.waves > 0) nw = std::min(T.waves, 8);
@@ -1518,11 +1550,11 @@ static int launch_sparse(const alcs_packed_t *Wp, const io_t *X_dev, const float
         a.gpt = nw * ug;
         a.ngt = ceil_div(G, a.gpt);
         switch (V) {
-            case 1: kern = pick_conv3<1, false>(stride, ti, ug); break;
-            case 2: kern = pick_conv3<2, false>(stride, ti, ug); break;
-            case 4: kern = mfma ? pick_conv3<4, true>(stride, ti, ug) : pick_conv3<4, false>(stride, ti, ug); break;
-            case 8: kern = pick_conv3<8, true>(stride, ti, ug); break;
-            case 16: kern = pick_conv3<16, true>(stride, ti, ug); break;
+            case 1: kern = pick_conv3<1, false>(stride, ti, ug, tall); break;
+            case 2: kern = pick_conv3<2, false>(stride, ti, ug, tall); break;
+            case 4: kern = mfma ? pick_conv3<4, true>(stride, ti, ug, tall) : pick_conv3<4, false>(stride, ti, ug, tall); break;
+            case 8: kern = pick_conv3<8, true>(stride, ti, ug, tall); break;
+            case 16: kern = pick_conv3<16, true>(stride, ti, ug, tall); break;
         }
 #endif
     }

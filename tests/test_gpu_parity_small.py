@@ -172,6 +172,31 @@ def test_conv3x3_tile_shapes(V, stride, tile_width):
     assert info["mode"] == 3 and info["tile_width"] == tile_width
 
 
+@pytest.mark.parametrize("V", [4, 8])
+@pytest.mark.parametrize("tile_width", [8, 16, 32])
+@pytest.mark.parametrize("ug", [2, 4])
+def test_conv3x3_two_pixels_per_lane(V, tile_width, ug):
+    """Stride 1, tiles of twice the height, a lane owns two pixels a fixed number of rows apart:
+    21 rows are ragged for 16-, 8- and 4-row tiles, 37 columns for every width; 70 channels =
+    3 chunks, the last one short."""
+    L = workloads.Layer("c3_tall_tw%d_v%d" % (tile_width, V), 70, 40, 21, 37, k=3, stride=1, N=2, V=V,
+                        sparsity=0.75, w_std=0.05)
+    info = check(L, 545 + V + tile_width + ug, tile_width=tile_width, pv=2, groups_per_wave=ug)
+    assert info["mode"] == 3 and info["tile_width"] == tile_width and info["pv"] == 2
+
+
+def test_conv3x3_two_pixels_per_lane_small_and_odd_images():
+    for hw, seed in ((7, 1), (5, 2), (1, 3), (14, 4)):
+        L = workloads.Layer("c3_tall_%d" % hw, 24, 16, hw, hw, k=3, stride=1, N=3, V=4, sparsity=0.5)
+        info = check(L, 548 + seed, pv=2)
+        assert info["pv"] == 2
+    # stride 2 and V = 16 keep one pixel per lane
+    L = workloads.Layer("c3_tall_s2", 24, 16, 9, 9, k=3, stride=2, N=2, V=4, sparsity=0.5)
+    assert check(L, 553, pv=2)["pv"] == 1
+    L = workloads.Layer("c3_tall_v16", 24, 32, 9, 9, k=3, stride=1, N=2, V=16, sparsity=0.5)
+    assert check(L, 554, pv=2)["pv"] == 1
+
+
 @pytest.mark.parametrize("tile_width", [8, 16, 32])
 def test_conv3x3_tile_shapes_few_waves_use_position_loop(tile_width):
     L = workloads.Layer("c3_tw%d_small_wg" % tile_width, 16, 16, 11, 35, k=3, stride=2, N=1, V=4, sparsity=0.5)
