@@ -1523,12 +1523,12 @@ static int launch_sparse(const alcs_packed_t *Wp, const io_t *X_dev, const float
 #else
         mode = 3;
         // Tall tiles (two pixels per lane): stride 1, MFMA form, accumulators of at most 8
-        // channels.  By default for V = 4 on images of at least 12x12, which 16- or 8-row tiles
+        // channels.  By default on images of at least 12x12, which 16- or 8-row tiles
         // still cover well (128->128 @28x28, N=64: 85 -> 71 us; 64->64 @56x56: 85 -> 80 us;
         // 256->256 @14x14: 87 -> 81 us; a 7x7 image would leave most of a tall tile empty:
         // 90 -> 158 us); "pv" = 1 or 2 forces the choice.
         bool tall = stride == 1 && mfma && V <= 8 &&
-                    (T.pv == 2 || (T.pv == 0 && V == 4 && Ho >= 12 && Wo >= 12));
+                    (T.pv == 2 || (T.pv == 0 && Ho >= 12 && Wo >= 12));
         ti = pick_tile3(Ho, Wo, T.tile_w, tall);
         if (tall && (L.KC + 1) * halo_area3(stride, ti, true) * 4 > kMaxLds) {
             tall = false;
@@ -1543,6 +1543,9 @@ static int launch_sparse(const alcs_packed_t *Wp, const io_t *X_dev, const float
         nw = 8;
         if (T.waves > 0) nw = std::min(T.waves, 8);
         ug = pick_ug(G, nw, T.ug);
+        // Groups of 8 or 16 channels: two per wavefront (their accumulators fill the register
+        // file otherwise; V = 8, 256->256 @14x14, N=64: 103 us with four, 71 with two).
+        if (T.ug == 0 && V >= 8) ug = 2;
         // At most one workgroup per compute unit and room for a second one: halve the groups
         // per wavefront, so that two workgroups share a compute unit and one stages a chunk
         // while the other multiplies (512->512 @7x7, N=64: 102 -> 89 us).
