@@ -121,6 +121,18 @@ def test_pointwise_single_round_spreads_pixels_over_all_compute_units(Cin, Cout,
     assert spread["workgroups"] <= 256
 
 
+def test_pointwise_many_tiles_of_a_register_heavy_kernel_take_8_wavefronts():
+    """More workgroups than compute units, tiles of which two fit a compute unit, and a kernel
+    that holds more than 64 registers per lane (four groups per wavefront): 8 wavefronts per
+    workgroup, so that two workgroups share a compute unit; a single round keeps 16."""
+    many = workloads.Layer("pw_many_tiles", 512, 64, 28, 28, N=12, V=4, sparsity=0.9)
+    info = check(many, 490)
+    assert info["group_slots"] == 4 and info["workgroups"] > 256 and info["waves"] == 8, info
+    few = workloads.Layer("pw_few_tiles", 512, 256, 14, 14, N=8, V=4, sparsity=0.9)
+    info = check(few, 491)
+    assert info["group_slots"] == 4 and info["workgroups"] <= 256 and info["waves"] == 16, info
+
+
 @pytest.mark.parametrize("Cin,gs", [(512, 4), (1100, 4), (2048, 4)])
 def test_pointwise_wide_inputs_pair_groups_by_default(Cin, gs):
     L = workloads.Layer("pw_wide%d" % Cin, Cin, 40, 7, 7, N=3, V=4, sparsity=0.9)
