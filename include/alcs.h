@@ -333,6 +333,25 @@ int alcs_project_latency(const float *scores_dev, const long long *seg_starts_ho
                          void *stream);
 
 /*
+ * alcs_topn_mask for callers that cannot allocate device memory or bring a workspace (code that
+ * runs where hipMalloc is forbidden: tight serving loops, harnesses that rule it out): the same
+ * selection, same arguments minus workspace_dev, same results bit for bit, with the selection
+ * state in a device array that is part of the library image.  The call allocates nothing, on the
+ * host or on the device.
+ *   - At most ALCS_TOPN_STATIC_MAX_SEGMENTS segments (ALCS_E_UNSUPPORTED beyond; n_blocks is
+ *     limited only as in alcs_topn_mask: the state's size depends on the segments alone).
+ *   - Every GPU the library is used on holds one copy of the array (about 33 KB) until the
+ *     process ends; its address is looked up on the first call on that device.
+ *   - All calls on one GPU share that array, whatever their stream: calls that overlap on one GPU
+ *     race, the caller serialises them.  The array keeps the previous call's contents; each call
+ *     clears what it needs itself.
+ */
+#define ALCS_TOPN_STATIC_MAX_SEGMENTS 1024
+int alcs_topn_mask_static(const float *scores_dev, long long n_blocks, long long N,
+                          const long long *seg_starts_host, int n_segments, uint8_t *mask_dev,
+                          long long *seg_counts_host, void *stream);
+
+/*
  * The storage format of Section 3.2.2 ("Storage format") built on the device, and a handle made
  * from the format's arrays.
  *

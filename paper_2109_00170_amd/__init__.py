@@ -26,6 +26,7 @@ from ._binding import (  # noqa: F401
     alcs_sparse_conv_fused,
     alcs_strerror,
     alcs_topn_mask,
+    alcs_topn_mask_static,
     alcs_version,
     library_path,
     load_library,

@@ -16,7 +16,7 @@ EXPORTS = [
     "alcs_packed_on_device", "alcs_packed_export", "alcs_packed_selfcheck", "alcs_packed_free",
     "alcs_sparse_conv", "alcs_sparse_conv_timed", "alcs_sparse_conv_fused", "alcs_dense_conv", "alcs_set_tuning",
     "alcs_depthwise_conv", "alcs_dw_sparse_conv_fused", "alcs_sparse_conv_bf16", "alcs_block_scores", "alcs_select_workspace_bytes",
-    "alcs_topn_mask", "alcs_project_latency", "alcs_pack_csr_device", "alcs_pack_from_csr",
+    "alcs_topn_mask", "alcs_topn_mask_static", "alcs_project_latency", "alcs_pack_csr_device", "alcs_pack_from_csr",
     "alcs_last_launch", "alcs_latency_estimate", "alcs_network_latency",
 ]
 
@@ -417,6 +417,25 @@ def alcs_topn_mask(scores, N: int, seg_starts=None, want_mask: bool = True, stre
     if rc != 0:
         raise AlcsError(rc, "alcs_topn_mask")
     return mask, counts
+
+
+def alcs_topn_mask_static(scores, N: int, seg_starts=None, mask=None, stream=None):
+    """alcs_topn_mask through the entry point that allocates nothing: ``mask`` is a caller-made uint8
+    device tensor of scores.numel() entries (or None for counts only); returns the kept count per
+    segment (numpy int64)."""
+    n = int(scores.numel())
+    starts = np.ascontiguousarray([0, n] if seg_starts is None else seg_starts, dtype=np.int64)
+    n_seg = int(starts.size) - 1
+    if mask is not None and int(mask.numel()) != n:
+        raise ValueError("mask must have %d entries" % n)
+    counts = np.zeros(n_seg, dtype=np.int64)
+    llp = ctypes.POINTER(ctypes.c_longlong)
+    rc = load_library().alcs_topn_mask_static(
+        _dev_ptr(scores, "scores"), ctypes.c_longlong(n), ctypes.c_longlong(int(N)), starts.ctypes.data_as(llp), n_seg,
+        _dev_ptr(mask, "mask", "torch.uint8"), counts.ctypes.data_as(llp), _stream_ptr(stream))
+    if rc != 0:
+        raise AlcsError(rc, "alcs_topn_mask_static")
+    return counts
 
 
 def alcs_project_latency(scores, seg_starts, V_per_layer, tables, tau, budget, eps, want_mask: bool = True,

@@ -19,6 +19,7 @@
 #include <algorithm>
 #include <cstdint>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "alcs_internal.h"
@@ -209,14 +210,16 @@ extern "C" size_t alcs_select_workspace_bytes(int n_segments) {
     return n_segments < 0 ? 0 : workspace_bytes(n_segments);
 }
 
-extern "C" int alcs_topn_mask(const float *scores_dev, long long n_blocks, long long N,
-                              const long long *seg_starts_host, int n_segments, uint8_t *mask_dev,
-                              long long *seg_counts_host, void *workspace_dev, void *stream) {
+// alcs_topn_mask with its selection state at `workspace_dev` (device memory of at least
+// workspace_bytes(n_segments) bytes, 8-byte aligned).  Allocates nothing, on the host or the device.
+static int topn_mask_in(const float *scores_dev, long long n_blocks, long long N, const long long *seg_starts_host,
+                        int n_segments, uint8_t *mask_dev, long long *seg_counts_host, void *workspace_dev,
+                        void *stream) {
     if (!scores_dev || !workspace_dev || n_blocks <= 0 || N < 0 || N > n_blocks) return ALCS_E_INVALID_ARG;
     if (n_blocks > 0xFFFFFFFFLL) return ALCS_E_UNSUPPORTED;  // the index half of a key is 32 bits
     if ((uintptr_t)workspace_dev & 7) return ALCS_E_INVALID_ARG;
-    std::vector<long long> whole = {0, n_blocks};
-    if (!seg_starts_host) { seg_starts_host = whole.data(); n_segments = 1; }
+    const long long whole[2] = {0, n_blocks};
+    if (!seg_starts_host) { seg_starts_host = whole; n_segments = 1; }
     if (n_segments <= 0 || n_segments > 65535) return ALCS_E_INVALID_ARG;
     if (seg_starts_host[0] != 0 || seg_starts_host[n_segments] != n_blocks) return ALCS_E_INVALID_ARG;
     for (int s = 0; s < n_segments; ++s)
@@ -237,6 +240,62 @@ extern "C" int alcs_topn_mask(const float *scores_dev, long long n_blocks, long 
         rc = check(hipStreamSynchronize(st));
     }
     return rc;
+}
+
+extern "C" int alcs_topn_mask(const float *scores_dev, long long n_blocks, long long N,
+                              const long long *seg_starts_host, int n_segments, uint8_t *mask_dev,
+                              long long *seg_counts_host, void *workspace_dev, void *stream) {
+    return topn_mask_in(scores_dev, n_blocks, N, seg_starts_host, n_segments, mask_dev, seg_counts_host,
+                        workspace_dev, stream);
+}
+
+// ---------------------------------------------------------------- selection without any allocation
+//
+// The selection state of alcs_topn_mask_static lives in a file-scope device array instead of a
+// caller-provided workspace: every GPU the library runs on holds one copy of it (kStaticBytes,
+// about 33 KB) until the process ends.  In host code the array's name is only a stand-in for the
+// symbol, not a device address; the address on the current device comes from
+// hipGetSymbolAddress, once per device, and is what the kernels and copies are given.
+namespace {
+constexpr int kStaticMaxSegments = ALCS_TOPN_STATIC_MAX_SEGMENTS;
+constexpr size_t kStaticBytes =
+    (sizeof(SelectState) + sizeof(long long) * (kStaticMaxSegments + 1) + sizeof(unsigned long long) * kStaticMaxSegments + 255) &
+    ~(size_t)255;
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (looked up on the first call there).
+int static_scratch(void **out) {
+    int dev = -1;
+    int rc = check(hipGetDevice(&dev));
+    if (rc != ALCS_OK) return rc;
+    if (dev < 0 || dev >= kMaxDevices) return ALCS_E_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        rc = check(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (rc != ALCS_OK) return rc;
+        if (!ptr) return ALCS_E_HIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return ALCS_OK;
+}
+}  // namespace
+
+extern "C" int alcs_topn_mask_static(const float *scores_dev, long long n_blocks, long long N,
+                                     const long long *seg_starts_host, int n_segments, uint8_t *mask_dev,
+                                     long long *seg_counts_host, void *stream) {
+    // the size limit first: it does not depend on a device
+    if (seg_starts_host && n_segments > kStaticMaxSegments) return ALCS_E_UNSUPPORTED;
+    static_assert(kStaticBytes >= sizeof(SelectState) + 8 * (size_t)(2 * kStaticMaxSegments + 1), "scratch size");
+    void *ws = nullptr;
+    const int rc = static_scratch(&ws);
+    if (rc != ALCS_OK) return rc;
+    return topn_mask_in(scores_dev, n_blocks, N, seg_starts_host, n_segments, mask_dev, seg_counts_host, ws, stream);
 }
 
 extern "C" int alcs_project_latency(const float *scores_dev, const long long *seg_starts_host, const int *V_host,
