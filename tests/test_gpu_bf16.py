@@ -55,7 +55,8 @@ def run_bf16(L, seed, act=None, with_res=False, with_bias=True, in_place=False, 
     Wd = oracle.densify(d.W, d.mask, L.V)
     ref = oracle.conv_fused(Wd, Xb, bias=d.bias, residual=Rb, act=act, stride=L.stride).astype(np.float64)
     pre = oracle.conv_fused(Wd, Xb, bias=d.bias, residual=Rb, act=None, stride=L.stride)
-    scale = float(np.max(np.abs(pre)))
+    # the float32 bound is taken relative to max |ref| (the stated bound) and max |pre|, whichever is smaller
+    scale = min(float(np.max(np.abs(pre))), float(np.max(np.abs(ref))))
     # half a bfloat16 unit of the element itself plus the float32 bound on the sum
     bound = 2.0 ** -8 * np.abs(ref) + TOL * scale
     worst = float(np.max(np.abs(got - ref) - bound))

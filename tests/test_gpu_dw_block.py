@@ -8,7 +8,7 @@ import pytest
 import oracle
 import paper_2109_00170_amd as alcs
 import workloads
-from gpu_util import TOL
+from gpu_util import TOL, assert_close_after_activation
 
 pytestmark = pytest.mark.gpu
 
@@ -49,8 +49,7 @@ def test_depthwise_layer(C, N, H, W, stride, act):
         assert not np.isnan(got).any()
         ref = oracle.depthwise(D, X, bias=bias, stride=stride, act=act)
         pre = oracle.depthwise(D, X, bias=bias, stride=stride)
-        err = float(np.max(np.abs(got.astype(np.float64) - ref)) / max(float(np.max(np.abs(pre))), 1e-30))
-        assert err <= TOL, "C=%d %dx%d s%d act=%s: %.3g" % (C, H, W, stride, act, err)
+        assert_close_after_activation(got, ref, pre, "C=%d %dx%d s%d act=%s" % (C, H, W, stride, act))
 
 
 def run_block(L, Hin, Win, dw_stride, seed, dw_act="relu", act=None, with_res=False, with_bias=True,
@@ -86,8 +85,7 @@ def run_block(L, Hin, Win, dw_stride, seed, dw_act="relu", act=None, with_res=Fa
     Z = oracle.depthwise(D, X, bias=b1, stride=dw_stride, act=dw_act)
     ref = oracle.sparse_conv(d.W, d.mask, Z, L.V, bias=d.bias, residual=R, act=act)
     pre = oracle.sparse_conv(d.W, d.mask, Z, L.V, bias=d.bias, residual=R, act=None)
-    err = float(np.max(np.abs(got.astype(np.float64) - ref)) / max(float(np.max(np.abs(pre))), 1e-30))
-    assert err <= TOL, "%s %s: rel err %.3g" % (L.name, info, err)
+    assert_close_after_activation(got, ref, pre, "%s %s" % (L.name, info))
     if expect_mode is not None:
         assert info["mode"] == expect_mode, info
     if workspace and expect_mode == 1:

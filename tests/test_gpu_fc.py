@@ -7,7 +7,7 @@ import pytest
 import oracle
 import paper_2109_00170_amd as alcs
 import workloads
-from gpu_util import TOL
+from gpu_util import TOL, assert_close_after_activation, rel_err
 
 pytestmark = pytest.mark.gpu
 
@@ -24,14 +24,17 @@ def test_fully_connected_layer(N, Cin, Cout, V):
     Y = torch.full((N, Cout, 1, 1), float("nan"), dtype=torch.float32, device="cuda")
     alcs.alcs_sparse_conv_fused(packed, X, b, None, Y, activation="relu")
     torch.cuda.synchronize()
-    got = Y.cpu().numpy().reshape(N, Cout)
+    got = Y.cpu().numpy()
     packed.free()
     assert not np.isnan(got).any()
-    # the definition of an FC layer, written out: relu(X Wd^T + b) in double
+    # the oracle's convolution on the same 1x1 layer (an FC layer is that layer on a 1x1 image)
+    ref = oracle.sparse_conv(d.W, d.mask, d.X, V, bias=d.bias, act="relu")
+    pre = oracle.sparse_conv(d.W, d.mask, d.X, V, bias=d.bias)
+    assert_close_after_activation(got, ref, pre, "fc %d->%d N=%d" % (Cin, Cout, N))
+    # and the matrix product written out, as a second opinion on the layer's meaning
     Wd = oracle.densify(d.W, d.mask, V).reshape(Cout, Cin).astype(np.float64)
-    pre = d.X.reshape(N, Cin).astype(np.float64) @ Wd.T + d.bias
-    err = float(np.max(np.abs(got - np.maximum(pre, 0.0))) / np.max(np.abs(pre)))
-    assert err <= TOL, err
+    mm = np.maximum(d.X.reshape(N, Cin).astype(np.float64) @ Wd.T + d.bias, 0.0)
+    assert float(np.max(np.abs(ref.reshape(N, Cout) - mm))) <= 1e-6 * float(np.max(np.abs(mm)))
 
 
 def test_batched_matrix_product():
@@ -43,8 +46,10 @@ def test_batched_matrix_product():
     Y = torch.full((B, Cout, 1, P), float("nan"), dtype=torch.float32, device="cuda")
     alcs.alcs_sparse_conv(packed, torch.from_numpy(d.X).cuda(), None, Y)
     torch.cuda.synchronize()
-    got = Y.cpu().numpy().reshape(B, Cout, P)
+    got = Y.cpu().numpy()
     packed.free()
+    ref = oracle.sparse_conv(d.W, d.mask, d.X, V)
+    assert rel_err(got, ref) <= TOL
     Wd = oracle.densify(d.W, d.mask, V).reshape(Cout, Cin).astype(np.float64)
-    ref = np.einsum("oc,bcp->bop", Wd, d.X.reshape(B, Cin, P).astype(np.float64))
-    assert float(np.max(np.abs(got - ref)) / np.max(np.abs(ref))) <= TOL
+    mm = np.einsum("oc,bcp->bop", Wd, d.X.reshape(B, Cin, P).astype(np.float64))
+    assert float(np.max(np.abs(ref.reshape(B, Cout, P) - mm))) <= 1e-6 * float(np.max(np.abs(mm)))

@@ -8,7 +8,7 @@ import pytest
 import oracle
 import paper_2109_00170_amd as alcs
 import workloads
-from gpu_util import TOL
+from gpu_util import TOL, assert_close_after_activation
 
 pytestmark = pytest.mark.gpu
 
@@ -44,13 +44,13 @@ def big_check(L, seed, entry):
         rng.integers(total - per_image, total, size=1000),      # last image: inputs beyond 2^31 elements
         [0, total - 1, per_image - 1, per_image]]))
     got = Y.reshape(-1)[torch.from_numpy(idx).cuda()].cpu().numpy()
-    ymax = float(Y.abs().max())
     blk = Y[:, :L.V].cpu().numpy()
     del Y, X
     torch.cuda.empty_cache()
     Wd_host = oracle.densify(d.W, d.mask, L.V)
     ref = oracle.conv_at(Wd_host, d.X, idx, bias=d.bias, stride=L.stride)
-    err = float(np.max(np.abs(got.astype(np.float64) - ref)) / max(ymax, 1e-30))
+    # the scale comes from the oracle's values alone (the largest sampled reference output)
+    err = float(np.max(np.abs(got.astype(np.float64) - ref)) / max(float(np.max(np.abs(ref))), 1e-30))
     assert err <= TOL, "%s %s: sampled rel err %.3g" % (L.name, entry, err)
     if entry != "dense":
         want = np.broadcast_to(d.bias[:L.V][None, :, None, None], blk.shape)
@@ -100,8 +100,7 @@ def test_depthwise_input_beyond_2_31_elements():
         ref = oracle.depthwise(D[c:c + 1], host[(n, c)][None, None], bias=b[c:c + 1], stride=stride, act="relu")[0, 0]
         pre = oracle.depthwise(D[c:c + 1], host[(n, c)][None, None], bias=b[c:c + 1], stride=stride)[0, 0]
         got = Y[n, c].cpu().numpy()
-        err = float(np.max(np.abs(got.astype(np.float64) - ref)) / np.max(np.abs(pre)))
-        assert err <= TOL, "plane (%d, %d): %.3g" % (n, c, err)
+        assert_close_after_activation(got, ref, pre, "plane (%d, %d)" % (n, c))
 
 
 def test_block_with_an_image_too_large_for_32_bit_tap_offsets():
@@ -144,8 +143,7 @@ def test_block_with_an_image_too_large_for_32_bit_tap_offsets():
         first = h0 - r0 // 2                                 # crop-local index of output row h0
         got = Y[:, :, h0:h1].cpu().numpy()
         want = ref[:, :, first:first + (h1 - h0)]
-        err = float(np.max(np.abs(got.astype(np.float64) - want)) / np.max(np.abs(pre)))
-        assert err <= TOL, "rows %d-%d: %.3g" % (h0, h1, err)
+        assert_close_after_activation(got, want, pre, "rows %d-%d" % (h0, h1))
     packed.free()
 
 
@@ -179,6 +177,6 @@ def test_bf16_pointwise_input_beyond_2_31_elements():
     Wd = oracle.densify(d.W, d.mask, V).reshape(Cout, Cin).astype(np.float64)
     pre = cols @ Wd.T + d.bias
     ref = np.maximum(pre, 0.0)
-    bound = 2.0 ** -8 * np.abs(ref) + TOL * np.max(np.abs(pre))
+    bound = 2.0 ** -8 * np.abs(ref) + TOL * min(np.max(np.abs(pre)), np.max(np.abs(ref)))
     assert float(np.max(np.abs(got - ref) - bound)) <= 0.0
     packed.free()

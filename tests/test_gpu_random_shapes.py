@@ -8,7 +8,7 @@ import pytest
 import oracle
 import paper_2109_00170_amd as alcs
 import workloads
-from gpu_util import TOL
+from gpu_util import TOL, assert_close_after_activation
 
 pytestmark = pytest.mark.gpu
 
@@ -62,6 +62,4 @@ def test_random_layer(seed):
     assert not np.isnan(got).any(), "%s %s: some outputs were never written" % (L, info)
     ref = oracle.sparse_conv(d.W, d.mask, d.X, L.V, bias=d.bias, stride=L.stride, residual=R, act=act)
     pre = oracle.sparse_conv(d.W, d.mask, d.X, L.V, bias=d.bias, stride=L.stride, residual=R, act=None)
-    scale = float(np.max(np.abs(pre)))
-    err = float(np.max(np.abs(got.astype(np.float64) - ref)))
-    assert err <= TOL * scale or (scale == 0.0 and err == 0.0), "%s %s %s: err %.3g scale %.3g" % (L, info, epi, err, scale)
+    assert_close_after_activation(got, ref, pre, "%s %s %s" % (L, info, epi))
