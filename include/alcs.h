@@ -182,7 +182,7 @@ int alcs_sparse_conv_fused(const alcs_packed_t *Wp, const float *X_dev, const fl
  * same shapes); the packed weights, the bias and every sum stay float32, and Y is rounded to
  * nearest even once, after bias, residual and activation.  The layers this library runs at the
  * HBM roofline move half the bytes.  1x1 handles whose input channels fit one on-chip tile only
- * (at most 2559 input channels, 639 for V < 4; ALCS_E_UNSUPPORTED otherwise); X_dev, Y_dev and
+ * (at most 2558 input channels, 639 for V < 4; ALCS_E_UNSUPPORTED otherwise); X_dev, Y_dev and
  * residual_dev 8-byte aligned; everything else as alcs_sparse_conv_fused.
  */
 int alcs_sparse_conv_bf16(const alcs_packed_t *Wp, const uint16_t *X_dev, const float *bias_dev,
@@ -209,7 +209,7 @@ int alcs_sparse_conv_bf16(const alcs_packed_t *Wp, const uint16_t *X_dev, const 
  *     are unspecified) where that is the faster or the only way: small layers whose output
  *     groups are split over several workgroups per pixel tile (each would evaluate the
  *     depthwise layer again), handles whose input channels do not fit one on-chip tile (more
- *     than 2559 input channels, or V < 4 with more than 639), inputs of more than about 10^9
+ *     than 2558 input channels, or V < 4 with more than 639), inputs of more than about 10^9
  *     elements per image.  Without a workspace the first kind still runs as one kernel and
  *     the other two return ALCS_E_UNSUPPORTED.
  *

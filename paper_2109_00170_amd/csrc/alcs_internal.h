@@ -119,6 +119,7 @@ struct Layout {
     int nbundles = 0; // ceil(G / GS)
     int planes = 0;   // ceil(V / 4): weight rows 4q..4q+3 of every block live in plane q
     int VV = 0;       // min(V, 4) floats per block and plane
+    int max_cnt = 0;  // longest segment, in padded columns
     int64_t ncol = 0; // padded columns in total (multiple of kSegAlign)
     int64_t wplane = 0;  // floats per weight plane: ncol * VV * GS
     int noff = 0;     // 1 for kernel 1; kMaxOff for kernel 3 (one table per stride and tile shape)

@@ -41,9 +41,32 @@ static inline int32_t off_of(int col, int k, int table, int GS) {
     return (c * halo_area3(stride, ti, table_tall3(table)) + r * pitch3(stride, ti) + halo_col3(stride, ti, s)) * 4;
 }
 
-static inline int32_t pad_off(int c0, int KC, int k, int table, int GS) {
-    if (k == 1) return (c0 + KC) * (kRowBytes1 / GS);
+// Selector of a padded column: an all-zero row behind the chunk's rows.  Layouts with several
+// groups per wavefront have two of them (rows KC and KC + 1, one of each channel parity, see
+// arrange_slot); `which` picks one.
+static inline int32_t pad_off(int c0, int KC, int k, int table, int GS, int which = 0) {
+    if (k == 1) return (c0 + KC + which) * (kRowBytes1 / GS);
     return (c0 + KC) * halo_area3(table_stride3(table), table_ti3(table), table_tall3(table)) * 4;
+}
+
+// Order of one slot's columns inside a bundle segment of L columns (several groups per wavefront).
+// The 16- or 32-lane slots of a wavefront read different LDS rows in the same instruction; with
+// rows of 128 bytes, rows of equal channel parity lie on the same half of the 64 LDS banks, so two
+// slots that are served together (slots 0/1 and 2/3) conflict whenever their rows' parities agree.
+// The accumulation order inside a group is free, so the even slot of a pair takes its
+// even-channel columns from the front and its odd-channel ones right-aligned at the back, the odd
+// slot the other way round, and padding sits in between; the pair then disagrees in parity at
+// every step unless their like-parity columns together outnumber L.  place[j] is the index of the
+// column (counted inside the group's chunk range) at step j, or -1 for padding.
+static void arrange_slot(const int32_t *cols, int n, int kk, int L, bool evens_first, std::vector<int32_t> &place) {
+    place.assign((size_t)L, -1);
+    int front = 0, nback = 0;
+    for (int i = 0; i < n; ++i) nback += ((col_channel(cols[i], kk) & 1) == (evens_first ? 1 : 0));
+    int back = L - nback;
+    for (int i = 0; i < n; ++i) {
+        const bool to_back = (col_channel(cols[i], kk) & 1) == (evens_first ? 1 : 0);
+        place[(size_t)(to_back ? back++ : front++)] = i;
+    }
 }
 
 // Index of (bundle column `col` counted from the start of the arrays, slot s) in a
@@ -108,13 +131,15 @@ int build_layout(alcs_packed *p, int KC, int GS) {
                 if (cur > INT32_MAX / (4 * GS) - 64) return ALCS_E_UNSUPPORTED;
                 wk.start = (int32_t)cur;
                 wk.cnt = (int32_t)round_up(longest, kCntAlign);
+                L.max_cnt = std::max(L.max_cnt, (int)wk.cnt);
                 cur += round_up(wk.cnt, kSegAlign);
             }
         L.ncol = cur + kSegAlign;  // one spare run so that a read-ahead stays inside the arrays
         L.wplane = L.ncol * L.VV * GS;
         L.w.assign((size_t)L.planes * L.wplane, 0.0f);
         for (int tb = 0; tb < L.noff; ++tb) L.off[tb].assign((size_t)L.ncol * GS, 0);
-        // pass 2: fill (padding: zero weights, selector of the chunk's all-zero row)
+        // pass 2: fill (padding: zero weights, selector of an all-zero row of the chunk)
+        std::vector<int32_t> place[kMaxSlots];
         for (int b = 0; b < L.nbundles; ++b)
             for (int ch = 0; ch < L.nchunks; ++ch) {
                 const Work wk = L.work[(size_t)b * L.nchunks + ch];
@@ -124,14 +149,40 @@ int build_layout(alcs_packed *p, int KC, int GS) {
                     const int g = wk.group[s];
                     const size_t gi = g >= 0 ? (size_t)g * L.nchunks + ch : 0;
                     const int32_t nreal = g >= 0 ? hi[gi] - lo[gi] : 0;
+                    if (GS > 1) {
+                        arrange_slot(nreal ? &p->col_idx[lo[gi]] : nullptr, nreal, kk, wk.cnt, (s & 1) == 0, place[s]);
+                    } else {
+                        place[s].assign((size_t)wk.cnt, -1);
+                        for (int32_t j = 0; j < nreal; ++j) place[s][(size_t)j] = j;
+                    }
+                }
+                for (int s = 0; s < GS; ++s) {
+                    const int g = wk.group[s];
+                    const size_t gi = g >= 0 ? (size_t)g * L.nchunks + ch : 0;
                     for (int64_t j = 0; j < span; ++j) {
                         const int64_t col = wk.start + j;
-                        const bool real = j < nreal;
+                        const int32_t at = j < wk.cnt ? place[s][(size_t)j] : -1;
+                        if (at < 0) {
+                            // padding: the zero row whose parity differs from the partner slot's row
+                            // at this step (the partner's own padding takes the other zero row)
+                            int which = 0;
+                            if (GS > 1 && j < wk.cnt) {
+                                const int m = s ^ 1;
+                                const int32_t mate = m < GS && wk.group[m] >= 0 ? place[m][(size_t)j] : -1;
+                                if (mate >= 0) {
+                                    const size_t mi = (size_t)wk.group[m] * L.nchunks + ch;
+                                    const int parity = col_channel(p->col_idx[lo[mi] + mate], kk) & 1;
+                                    which = ((c0 + KC) & 1) == parity ? 1 : 0;
+                                } else {
+                                    which = s & 1;
+                                }
+                            }
+                            for (int tb = 0; tb < L.noff; ++tb) L.off[tb][off_index(L, col, s)] = pad_off(c0, KC, k, tb, GS, which);
+                            continue;
+                        }
                         for (int tb = 0; tb < L.noff; ++tb)
-                            L.off[tb][off_index(L, col, s)] =
-                                real ? off_of(p->col_idx[lo[gi] + j], k, tb, GS) : pad_off(c0, KC, k, tb, GS);
-                        if (!real) continue;
-                        const float *src = &p->vals[(size_t)(lo[gi] + j) * V];
+                            L.off[tb][off_index(L, col, s)] = off_of(p->col_idx[lo[gi] + at], k, tb, GS);
+                        const float *src = &p->vals[(size_t)(lo[gi] + at) * V];
                         for (int v = 0; v < V; ++v) {
                             const int q = V < 4 ? 0 : v / 4, i = V < 4 ? v : v % 4;
                             L.w[(size_t)q * L.wplane + w_index(L, col, s, i)] = src[v];
@@ -225,7 +276,7 @@ int upload(alcs_packed *p) {
 // mean: 39 us with two groups per wavefront, 45 with four); V = 8 and 16 gain nothing from
 // four (their accumulators already alternate).  With 256 input channels one group per
 // wavefront stays ahead.
-// Beyond 2559 channels, or beyond 639 for V < 4, chunks of 256 channels.
+// Beyond 2558 channels, or beyond 639 for V < 4, chunks of 256 channels.
 // Kernel 3: 32 channels per chunk (the haloed tile plane is 240 to 476 floats per channel);
 // 64 from 512 input channels on - such layers sit on 14x14 and 7x7 images, where a workgroup's
 // time is the chain of its chunks' round trips (512->512 @7x7, N=64: 131 -> 100 us; stride 2
@@ -234,7 +285,7 @@ int upload(alcs_packed *p) {
 static void default_tiles(int Cin, int k, int V, bool even_groups, int *KC, int *GS) {
     *GS = 1;
     if (k == 3) { *KC = Cin >= 512 ? 64 : std::min(Cin, 32); return; }
-    if (V >= 4 && Cin >= 512 && Cin <= 2559) {
+    if (V >= 4 && Cin >= 512 && Cin <= 2558) {
         *KC = Cin;
         *GS = (Cin > 1279 || (V == 4 && even_groups)) ? 4 : 2;
         return;
@@ -257,7 +308,7 @@ static int finish_pack(alcs_packed *p, int rc, alcs_packed_t **out) {
         default_tiles(p->Cin, p->k, p->V, even_groups, &KC, &GS);
         if (tuning().kc > 0) { KC = std::min(tuning().kc, p->Cin); GS = 1; }
         if (tuning().gs > 0 && p->k == 1 && p->V >= 4 && KC == p->Cin &&
-            (long long)(p->Cin + 1) * (kRowBytes1 / tuning().gs) <= 160 * 1024)
+            (long long)(p->Cin + 2) * (kRowBytes1 / tuning().gs) <= 160 * 1024)
             GS = tuning().gs;
         rc = build_layout(p, KC, GS);
     }
@@ -433,6 +484,7 @@ int alcs_packed_selfcheck(const alcs_packed_t *p) {
     }
     const uint32_t zero_bits = 0;
     std::vector<int64_t> next((size_t)p->G);  // next canonical block expected for every group
+    std::vector<char> seen_block(GS > 1 ? (size_t)p->nnzb : 0, 0);  // several groups per wavefront: blocks found so far
     for (int g = 0; g < p->G; ++g) next[g] = p->row_ptr[g];
     for (int b = 0; b < L.nbundles; ++b)
         for (int ch = 0; ch < L.nchunks; ++ch) {
@@ -454,22 +506,41 @@ int alcs_packed_selfcheck(const alcs_packed_t *p) {
                     const int64_t col = wk.start + j;
                     const size_t oi = off_index(L, col, s);
                     if (oi >= L.off[0].size()) return ALCS_E_INVALID_ARG;
-                    const bool is_pad = L.off[0][oi] == pad_off(c0, L.KC, k, 0, GS);
-                    if (in_pad && !is_pad) return ALCS_E_INVALID_ARG;  // real blocks come first
+                    // padding selects an all-zero row (one of two with several groups per wavefront)
+                    int which = -1;
+                    if (L.off[0][oi] == pad_off(c0, L.KC, k, 0, GS, 0)) which = 0;
+                    else if (GS > 1 && L.off[0][oi] == pad_off(c0, L.KC, k, 0, GS, 1)) which = 1;
+                    const bool is_pad = which >= 0;
+                    // one group per wavefront: real blocks come first, in canonical order; several:
+                    // any order (see arrange_slot), every canonical block exactly once
+                    if (GS == 1 && in_pad && !is_pad) return ALCS_E_INVALID_ARG;
                     in_pad = is_pad;
                     if (is_pad) {
                         for (int tb = 1; tb < L.noff; ++tb)
-                            if (L.off[tb][oi] != pad_off(c0, L.KC, k, tb, GS)) return ALCS_E_INVALID_ARG;
+                            if (L.off[tb][oi] != pad_off(c0, L.KC, k, tb, GS, which)) return ALCS_E_INVALID_ARG;
                         for (int q = 0; q < L.planes; ++q)
                             for (int i = 0; i < L.VV; ++i)
                                 if (std::memcmp(&L.w[(size_t)q * L.wplane + w_index(L, col, s, i)], &zero_bits, 4))
                                     return ALCS_E_INVALID_ARG;
                         continue;
                     }
-                    // a real block: the next canonical column of the slot's group, inside the
-                    // chunk's channel range (so that its LDS row exists) and the padded count
-                    if (g < 0 || j >= wk.cnt || next[g] >= p->row_ptr[g + 1]) return ALCS_E_INVALID_ARG;
-                    const int64_t t = next[g];
+                    if (g < 0 || j >= wk.cnt) return ALCS_E_INVALID_ARG;
+                    // a real block: a canonical column of the slot's group (the next one with one group
+                    // per wavefront), inside the chunk's channel range so that its LDS row exists
+                    int64_t t = -1;
+                    if (GS == 1) {
+                        if (next[g] >= p->row_ptr[g + 1]) return ALCS_E_INVALID_ARG;
+                        t = next[g];
+                    } else {
+                        // (1x1 only: the selector is the column times the row length)
+                        const int32_t want_col = L.off[0][oi] / (kRowBytes1 / GS);
+                        const int32_t *first = p->col_idx.data() + p->row_ptr[g], *last = p->col_idx.data() + p->row_ptr[g + 1];
+                        const int32_t *it = std::lower_bound(first, last, want_col);
+                        if (it == last || *it != want_col) return ALCS_E_INVALID_ARG;
+                        t = it - p->col_idx.data();
+                        if (seen_block[(size_t)t]) return ALCS_E_INVALID_ARG;
+                        seen_block[(size_t)t] = 1;
+                    }
                     const int cidx = p->col_idx[(size_t)t];
                     const int c = col_channel(cidx, k * k);
                     if (c < c0 || c >= c1) return ALCS_E_INVALID_ARG;

@@ -121,6 +121,16 @@ __device__ __forceinline__ void io_store1(io_t *p, float v) { __builtin_nontempo
 __device__ __forceinline__ void io_store2(io_t *p, f2 v) { __builtin_nontemporal_store(v, reinterpret_cast<f2 *>(p)); }
 __device__ __forceinline__ void io_store4(io_t *p, f4 v) { __builtin_nontemporal_store(v, reinterpret_cast<f4 *>(p)); }
 #endif
+// An ordinary (write-back) store of two elements: for runs that cover cache lines only in part and
+// whose neighbours are written soon after by the same workgroup, so that the L2 merges them into
+// whole lines before they leave for memory.
+__device__ __forceinline__ void io_store2_cached(io_t *p, f2 v) {
+#if ALCS_IO_BF16
+    *reinterpret_cast<unsigned int *>(p) = pack_bf2(v[0], v[1]);
+#else
+    *reinterpret_cast<f2 *>(p) = v;
+#endif
+}
 
 struct ConvArgs {
     const io_t *X;
@@ -392,6 +402,25 @@ __device__ __forceinline__ void mfma_batch(const float (&aw)[(V / 4) * GS], int 
 // MFMA form.  start/cnt are wave-uniform; base is the lane's byte offset inside an LDS
 // row (minus the chunk's first row); SH = log2(pixels per lane) for 1x1, 0 for 3x3.
 // `rs` holds the segment's first runs, loaded by the caller (see Runs).
+// Tells the compiler that the registers of `rs` are needed here: it places the wait for their
+// loads at this point.  Used where that wait is free (the loads were issued a whole multiply
+// earlier) and ahead of vector-memory operations a later wait would otherwise have to include:
+// the counter of outstanding vector-memory operations is a single in-order one that covers
+// loads and stores alike, and where paths of different length merge the compiler waits for it
+// to reach zero - which, behind a group's output stores or the next group's prefetches, means
+// waiting for those as well.
+template <int V, int GS>
+__device__ __forceinline__ void touch_runs(Runs<V, true, GS> &rs) {
+#pragma unroll
+    for (int i = 0; i < Runs<V, true, GS>::N; ++i) {
+#pragma unroll
+        for (int q = 0; q < (V / 4) * GS; ++q) asm volatile("" : "+v"(rs.r[i].a[q]));
+        asm volatile("" : "+v"(rs.r[i].o));
+    }
+}
+template <int V, int GS>
+__device__ __forceinline__ void touch_runs(Runs<V, false, GS> &) {}
+
 template <int V, int PV, int SH, int GS = 1, int PD = 1>
 __device__ __forceinline__ void mac_segment(const ConvArgs &a, int start, int cnt,
                                             const char *lds, int base, int lane,
@@ -399,7 +428,7 @@ __device__ __forceinline__ void mac_segment(const ConvArgs &a, int start, int cn
     constexpr int B = kCntAlign;  // columns whose LDS reads are in flight together
     constexpr int N = Runs<V, true, GS>::N;
     static_assert(B == 8, "a run of 16 columns is two batches");
-    for (int j0 = 0; j0 < cnt; j0 += 16 * N) {
+    auto pass = [&](int j0) {
         static_for<N>([&](auto ii) {
             constexpr int I = decltype(ii)::value;
             const int j = j0 + 16 * I;
@@ -411,6 +440,57 @@ __device__ __forceinline__ void mac_segment(const ConvArgs &a, int start, int cn
                 if (j + 16 * N < cnt) rs.r[I] = load_run<V, true, GS>(a, start + j + 16 * N, lane);
             }
         });
+    };
+    // The first pass runs on the registers the caller loaded (and has waited for): straight-line
+    // code in which nothing waits for vector memory.  Only longer segments enter the loop, whose
+    // head waits for the re-fills issued one pass earlier.
+    pass(0);
+    for (int j0 = 16 * N; j0 < cnt; j0 += 16 * N) pass(j0);
+}
+
+// The same segment for a caller that keeps `rs` (the segment's first runs) in registers across
+// many tiles: `rs` is only read; runs beyond it are fetched into two temporaries, each requested
+// one run ahead of its use.
+template <int V, int PV, int SH, int GS, bool TAIL>
+__device__ __forceinline__ void mac_segment_keep(const ConvArgs &a, int start, int cnt, const char *lds, int base,
+                                                 int lane, const Runs<V, true, GS> &rs, Acc<V, PV, true> &acc) {
+    constexpr int N = Runs<V, true, GS>::N;
+    // batches of four columns: the registers a batch of eight reads holds are needed for the
+    // resident weights (the wavefronts that share a SIMD cover the LDS latency between them)
+    auto eight = [&](auto b0, const float (&aw)[(V / 4) * GS], int ov) {
+        constexpr int B0 = decltype(b0)::value;
+        mfma_batch<B0, 4, V, PV, GS>(aw, ov, lds, base, acc);
+        mfma_batch<B0 + 4, 4, V, PV, GS>(aw, ov, lds, base, acc);
+    };
+    const bool tail = TAIL && cnt > 16 * N;  // without TAIL the caller guarantees at most 16 * N columns
+    Run<V, true, GS> t0, t1;
+    if (tail) t0 = load_run<V, true, GS>(a, start + 16 * N, lane);
+    static_for<N>([&](auto ii) {
+        constexpr int I = decltype(ii)::value;
+        const int j = 16 * I;
+        if (j < cnt) {
+            const int ov = rs.r[I].o << SH;
+            eight(std::integral_constant<int, 0>{}, rs.r[I].a, ov);
+            if (j + 8 < cnt) eight(std::integral_constant<int, 8>{}, rs.r[I].a, ov);
+        }
+    });
+    if (tail) {
+        for (int j = 16 * N; j < cnt; j += 32) {
+            const bool second = j + 16 < cnt;
+            if (second) t1 = load_run<V, true, GS>(a, start + j + 16, lane);
+            {
+                const int ov = t0.o << SH;
+                eight(std::integral_constant<int, 0>{}, t0.a, ov);
+                if (j + 8 < cnt) eight(std::integral_constant<int, 8>{}, t0.a, ov);
+            }
+            if (!second) break;
+            if (j + 32 < cnt) t0 = load_run<V, true, GS>(a, start + j + 32, lane);
+            {
+                const int ov = t1.o << SH;
+                eight(std::integral_constant<int, 0>{}, t1.a, ov);
+                if (j + 24 < cnt) eight(std::integral_constant<int, 8>{}, t1.a, ov);
+            }
+        }
     }
 }
 
@@ -730,7 +810,7 @@ __device__ __forceinline__ void load_slot_bias(const ConvArgs &a, int g, SlotBia
 // In vector form the two pixels of a lane are an 8-byte aligned pair inside one image and
 // go out as one store.  The output address is formed once per group and advanced by one
 // image plane per channel.
-template <int V, int PV, int GS, bool VEC>
+template <int V, int PV, int GS, bool VEC, bool PLAIN = false>
 __device__ __forceinline__ void store_slots(const ConvArgs &a, const Acc<V, PV, true> &acc, int g,
                                             const PixOut<PV> &px, const SlotBias<V> &sb) {
     static_assert(PV == 1 || PV == 2, "several groups per wavefront: one or two pixels per lane");
@@ -746,7 +826,8 @@ __device__ __forceinline__ void store_slots(const ConvArgs &a, const Acc<V, PV, 
                 f2 o = f2{acc.get(v, 0) + b, acc.get(v, 1) + b};
                 if (residual_of(a)) o += io_load2(residual_of(a) + plane + px.yoff[0]);
                 if (kFused && a.act) o = f2{activate(a, o[0]), activate(a, o[1])};
-                io_store2(a.Y + plane + px.yoff[0], o);
+                if constexpr (PLAIN) io_store2_cached(a.Y + plane + px.yoff[0], o);
+                else io_store2(a.Y + plane + px.yoff[0], o);
             }
         } else {
 #pragma unroll
@@ -805,9 +886,12 @@ __device__ __forceinline__ void pw_resident_body(const ConvArgs &a) {
 #else
     if (!(a.debug & 1)) stage_pw<TP, VEC, SPLIT>(a, lds, q0, 0, a.Cin, q_end);
 #endif
-    for (int t = tid; t < TP; t += blockDim.x) lds[a.KC * TP + t] = 0.f;  // the all-zero row
+    // the all-zero row(s) padded columns select: two, one of each channel parity, with several
+    // groups per wavefront (the packer picks the one that keeps the slots' reads on different banks)
+    for (int t = tid; t < (GS > 1 ? 2 : 1) * TP; t += blockDim.x) lds[a.KC * TP + t] = 0.f;
     __syncthreads();
     if (!any) return;
+    touch_runs<V, GS>(run0);  // fetched before the tile was staged: no wait left to inherit inside the walk
 
     const int plane = lane & (64 / GS - 1);  // the lane's place among the pixels (pairs, quads) of the tile
     PixOut<PV> px;
@@ -832,6 +916,9 @@ __device__ __forceinline__ void pw_resident_body(const ConvArgs &a) {
             load_slot_bias<V>(a, g_lane, sb);
         }
         if (!(a.debug & 2)) mac_segment<V, PV, SH, GS>(a, w0.start, w0.cnt, ldsb, base, lane, run0, acc);
+        // the next group's first runs have arrived long ago: take note of that before this
+        // group's stores join the queue (see touch_runs)
+        if (more) touch_runs<V, GS>(run1);
         if (!(a.debug & 4)) {
             if constexpr (GS == 1) store_group<V, PV, MF, VEC>(a, acc, w0.group[0], px, RES ? &rr : nullptr);
             else store_slots<V, PV, GS, VEC>(a, acc, g_lane, px, sb);
@@ -1152,6 +1239,152 @@ __global__ void __launch_bounds__(512) k_conv3(const ConvArgs a) {
             store_group<V, PV, MF, false>(a, acc[u], load_work(a.work, (size_t)slot[u] * a.nchunks).group[0], px);
 }
 
+
+// Mode 5 (pipelined): the many-tile regime of wide 1x1 layers (four groups per wavefront, all
+// input channels of a 32-pixel tile in LDS).  With one tile per workgroup the phases of a tile -
+// fetch, multiply, store - follow one another, and a launch of several rounds takes the sum of
+// them per round: a workgroup slot is busy for the whole chain while each of its resources
+// idles most of the time.  Here a workgroup is persistent, owns a run of consecutive tiles and
+// keeps two tile buffers: the rows of tile t+1 are requested (into registers) before tile t is
+// multiplied and written to the other buffer afterwards, so that memory and matrix pipes work at
+// the same time.  Every wavefront multiplies the same (at most KMAX) bundles for every tile, so
+// their first weight runs and their bias stay in registers for the whole kernel: in the steady
+// state the only vector-memory traffic is the input prefetch and the output stores, and nothing
+// in the multiply waits for it.  Per tile: prefetch -> multiply all bundles -> wait for the
+// prefetch (requested a whole multiply earlier) -> write it to LDS -> stores -> barrier; the
+// stores come last, because the wait that follows a store would include it (one in-order
+// counter covers loads and stores).  CACHED: ordinary instead of streaming stores, for images whose
+// channel planes do not start on line boundaries (the tile's runs then cover lines in part, and the
+// workgroup writes the neighbouring runs with its next tiles: the L2 merges them).
+template <int V, bool CACHED, int NT, int KMAX, int NR, bool TAIL>
+__global__ void __launch_bounds__(NT) k_pw_pipe(const ConvArgs a) {
+    constexpr int GS = 4, PV = 2, TP = 64 * PV / GS, SH = 1;
+    extern __shared__ float lds[];
+    const int logical = logical_wg(a);
+    if (logical >= a.total_wgs) return;
+    const int rg = logical / a.ngt, gt = logical - rg * a.ngt;
+    // tiles rg, rg + nranges, ...: workgroups that run side by side work on neighbouring tiles, whose
+    // rows are neighbours in memory
+    const int nranges = a.total_wgs / a.ngt;
+    const int t_begin = rg, t_end = a.npt;
+    if (t_begin >= t_end) return;
+    const int tid = threadIdx.x, lane = tid & 63, nt = blockDim.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), nw = nt >> 6;
+    const int g_begin = gt * a.gpt;
+    const int ng = min(a.G, g_begin + a.gpt) - g_begin;
+    auto nth = [&](int k) { return k * nw + ((k & 1) ? nw - 1 - wave : wave); };
+    const int bufstride = (a.KC + 2) * TP;  // floats per buffer: the rows and the two zero rows
+    for (int t = tid; t < 2 * 2 * TP; t += nt) lds[(t / (2 * TP)) * bufstride + a.KC * TP + (t % (2 * TP))] = 0.f;
+    // the bias behind the two buffers (read back per tile: LDS reads do not join the vector-memory queue)
+    float *lbias = lds + 2 * bufstride;
+    for (int c = tid; c < a.Cout; c += nt) lbias[c] = a.bias ? a.bias[c] : 0.f;
+
+    // the wavefront's bundles: work records and first weight runs - fetched once
+    Work wk[KMAX];
+    Runs<V, true, GS> rn[KMAX];
+    int g_lane[KMAX];
+#pragma unroll
+    for (int k = 0; k < KMAX; ++k) {
+        wk[k] = no_work();
+        g_lane[k] = -1;
+        if (nth(k) < ng) {
+            wk[k] = load_work(a.work, g_begin + nth(k));
+            rn[k] = load_runs<V, true, GS>(a, wk[k].start, wk[k].cnt, lane);
+            g_lane[k] = lane_group<GS>(wk[k], lane);
+        } else {
+#pragma unroll
+            for (int i = 0; i < Runs<V, true, GS>::N; ++i) {
+#pragma unroll
+                for (int q = 0; q < (V / 4) * GS; ++q) rn[k].r[i].a[q] = 0.f;
+                rn[k].r[i].o = 0;
+            }
+        }
+    }
+
+    // this thread's share of a tile: pixel quad `quad` of rows r0, r0 + rpp, ...
+    constexpr int NQ = TP / 4;
+    const int quad = tid % NQ, r0 = tid / NQ, rpp = nt / NQ;
+    const bool in_tile = quad * 4 < a.tile_px;
+    int fq = t_begin * a.tile_px + quad * 4;  // first pixel of the quad in the tile being fetched
+    int fn = fq / a.P, fp = fq - fn * a.P;
+    // The whole next tile is requested before the current one is multiplied: for its share of the
+    // memory bandwidth a compute unit has to keep about 40 KB in flight (latency x bandwidth / 256).
+    // Every load is issued, from a clamped address where the quad lies beyond the tile or the row
+    // beyond the channels (what such a load brings is never committed or never stored): a
+    // register that is loaded on some paths only would make the compiler wait for it where
+    // the paths meet, at the top of the loop, behind the previous tile's stores.
+    f4 v[NR];
+    auto fetch = [&]() {
+        const bool valid = in_tile && fq < a.NP;
+        const io_t *src = a.X + (valid ? ((size_t)fn * a.Cin) * a.P + fp : (size_t)0);
+#pragma unroll
+        for (int u = 0; u < NR; ++u) {
+            const int r = min(r0 + u * rpp, a.Cin - 1);
+            v[u] = io_load4(src + (size_t)r * a.P);
+        }
+        fq += nranges * a.tile_px;
+        fn = fq / a.P;
+        fp = fq - fn * a.P;
+    };
+    auto commit = [&](int b) {
+        float *dst = lds + b * bufstride + quad * 4;
+#pragma unroll
+        for (int u = 0; u < NR; ++u) {
+            const int r = r0 + u * rpp;
+            if (r < a.Cin) *reinterpret_cast<f4 *>(dst + r * TP) = v[u];
+        }
+    };
+    fetch();
+    commit(0);
+    if (t_begin + nranges < t_end) fetch();  // the second tile, on its way during the first multiply
+#pragma unroll
+    for (int k = 0; k < KMAX; ++k) touch_runs<V, GS>(rn[k]);
+    __syncthreads();
+
+    // where the lane's pixel pair of the current tile goes
+    const int plane = lane & (64 / GS - 1);
+    const int base = plane * PV * 4;
+    int oq = t_begin * a.tile_px + plane * PV;
+    int on = oq / a.P, op = oq - on * a.P;
+    const bool lane_in_tile = plane * PV < a.tile_px;
+    for (int t = t_begin, it = 0; t < t_end; t += nranges, ++it) {
+        const int cur = it & 1;
+        const bool more = t + nranges < t_end;
+        const char *ldsb = reinterpret_cast<const char *>(lds + cur * bufstride);
+        Acc<V, PV, true> acc[KMAX];
+#pragma unroll
+        for (int k = 0; k < KMAX; ++k) {
+            acc[k].zero();
+            mac_segment_keep<V, PV, SH, GS, TAIL>(a, wk[k].start, wk[k].cnt, ldsb, base, lane, rn[k], acc[k]);
+        }
+        // The registers hold the next tile, requested before the previous tile's stores: the
+        // wait for it (taken on every path, see fetch) also covers those stores, which are a whole
+        // multiply old.  It goes to the other buffer, and the tile after it is requested at once,
+        // ahead of this tile's stores, so that no wait ever follows a fresh store.
+#pragma unroll
+        for (int u = 0; u < NR; ++u) asm volatile("" : "+v"(v[u]));
+        if (more) {
+            commit(cur ^ 1);
+            if (t + 2 * nranges < t_end) fetch();
+        }
+        PixOut<PV> px;
+        px.valid[0] = px.valid[1] = lane_in_tile && oq < a.NP;
+        px.yoff[0] = (long long)on * a.Cout * a.P + op;
+        px.yoff[1] = px.yoff[0] + 1;
+#pragma unroll
+        for (int k = 0; k < KMAX; ++k) {
+            SlotBias<V> sb;
+#pragma unroll
+            for (int c = 0; c < V; ++c) sb.b[c] = (g_lane[k] >= 0 && g_lane[k] * V + c < a.Cout) ? lbias[g_lane[k] * V + c] : 0.f;
+            store_slots<V, PV, GS, true, CACHED>(a, acc[k], g_lane[k], px, sb);
+        }
+        oq += nranges * a.tile_px;
+        on = oq / a.P;
+        op = oq - on * a.P;
+        __syncthreads();
+    }
+}
+
 #endif  // !ALCS_RESIDENT_ONLY
 
 // ------------------------------------------------------------------ launcher
@@ -1358,6 +1591,7 @@ static int launch_sparse(const alcs_packed_t *Wp, const io_t *X_dev, const float
     if (V == 4 && T.path == 1) mfma = false;
     kern_t kern = nullptr;
     int lds = 0, nw = 0, pv = 1, mode = 0, ug = 4, ti = 0;
+    long long wg_count = 0;  // workgroups, where that is not pixel tiles x group tiles
 
     if (kernel == 1) {
         const bool vec = stride == 1 && (P % 4 == 0);
@@ -1400,11 +1634,48 @@ static int launch_sparse(const alcs_packed_t *Wp, const io_t *X_dev, const float
                 case 8: kern = pv == 4 ? k_pw_stream<8, 4, 8> : pv == 2 ? k_pw_stream<8, 2, 8> : k_pw_stream<8, 1, 8>; break;
                 case 16: kern = pv == 4 ? k_pw_stream<16, 4, 8> : pv == 2 ? k_pw_stream<16, 2, 8> : k_pw_stream<16, 1, 8>; break;
             }
-        } else
+        }
 #else
-        (void)s_pv; (void)s_lds; (void)s_nw; (void)s_nwg; (void)stream_ok;
+        (void)s_pv; (void)s_lds; (void)s_nw; (void)s_nwg;
 #endif
-        if (L.nchunks == 1) {
+        // pipelined kernel: four groups per wavefront, two tile buffers fit, and every compute unit
+        // gets several tiles (else there is nothing to overlap and the resident kernel's single
+        // tile per workgroup is the better shape)
+        bool pipe_ok = false;
+#if !ALCS_RESIDENT_ONLY
+        if (!stream_ok && L.nchunks == 1 && L.GS == 4 && V == 4 && vec && mfma && T.path != 6 && Cin <= 512 &&
+            2LL * (Cin + 2) * 32 * 4 + 4LL * Cout <= kMaxLds) {
+            // tiles of 28 pixels where they tile the image exactly and 32 do not (14x14, 28x28)
+            const int tp = (P % 32 != 0 && P % 28 == 0) ? 28 : 32;
+            const long long tiles = ((long long)a.NP + tp - 1) / tp;
+            // 16 wavefronts with at most two bundles each, whose weights (segments of at most 64
+            // columns, i.e. four runs) stay in registers for the whole kernel.  Longer segments would
+            // need temporaries for the runs beyond the fourth, which the 128 registers a lane has at
+            // 16 wavefronts per workgroup do not hold (a variant with 12 wavefronts of three bundles
+            // and one with a single temporary both spilled 15-28 registers): such layers keep the
+            // resident kernel.
+            const int pnw = 16, kmax = 2;
+            const bool fits = L.max_cnt <= 16 * Runs<4, true, 4>::N;
+            const int ngt_p = ceil_div(L.nbundles, kmax * pnw);
+            if (fits && (T.path == 5 || tiles * ngt_p >= 3LL * kCUs)) {
+                pipe_ok = true;
+                mode = 5;
+                pv = 2; nw = pnw;
+                lds = 2 * (Cin + 2) * 32 * 4 + 4 * Cout;
+                a.tile_px = tp;
+                a.npt = (int)tiles;
+                a.gpt = ceil_div(L.nbundles, ngt_p);
+                a.ngt = ceil_div(L.nbundles, a.gpt);
+                const int ranges = (int)std::max<long long>(1, std::min<long long>(tiles, kCUs / a.ngt));
+                wg_count = (long long)ranges * a.ngt;
+                const bool cached = ((long long)P * sizeof(io_t)) % 128 != 0;
+                // a pass of the workgroup stages 128 rows of 8 pixel quads: four rows per thread
+                kern = cached ? k_pw_pipe<4, true, 1024, 2, 4, false> : k_pw_pipe<4, false, 1024, 2, 4, false>;
+            }
+        }
+#endif
+        if (stream_ok || pipe_ok) {
+        } else if (L.nchunks == 1) {
             mode = 1;
             // Launch shape, from sweeps over the MobileNet/ResNet-shaped layers on MI355X:
             // pixels per lane - the widest tile whose Cin+1 rows stay below ~68 KB (two
@@ -1438,11 +1709,11 @@ static int launch_sparse(const alcs_packed_t *Wp, const io_t *X_dev, const float
             // half as many LDS rows per kept weight as two groups of 32 lanes with one pixel
             // (same 32-pixel tile; 512->512 @14x14: 17.4 -> 15.7 us).
             if (GS > 1) {
-                pv = (GS == 4 && (long long)(Cin + 1) * 32 * 4 <= kMaxLds) ? 2 : 1;
+                pv = (GS == 4 && (long long)(Cin + 2) * 32 * 4 <= kMaxLds) ? 2 : 1;
                 if (T.pv == 1 || T.pv == 2) pv = T.pv;
             }
             const int TP = 64 * pv / GS;
-            lds = (Cin + 1) * TP * 4;
+            lds = (Cin + (GS > 1 ? 2 : 1)) * TP * 4;  // the rows and the zero row(s)
             if (lds > kMaxLds) return ALCS_E_UNSUPPORTED;
             a.npt = ceil_div(a.NP, TP);
             a.tile_px = TP;
@@ -1567,7 +1838,7 @@ static int launch_sparse(const alcs_packed_t *Wp, const io_t *X_dev, const float
     // a launch that splits the groups is slower than the two layers run one after the other;
     // the caller that can do that (it has a workspace) is told to.
     if (kDw && decline_restaged && a.ngt > 1 && !(T.debug & 32)) return ALCS_E_UNSUPPORTED;
-    const long long total = (long long)a.npt * a.ngt;
+    const long long total = wg_count > 0 ? wg_count : (long long)a.npt * a.ngt;
     if (total > (1LL << 30)) return ALCS_E_UNSUPPORTED;
     a.total_wgs = (int)total;
     a.wg_per_xcd = ceil_div(total, kXcds);

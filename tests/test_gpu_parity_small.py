@@ -289,3 +289,22 @@ def test_sparse_at_sparsity_zero_equals_dense():
     a, _ = run_sparse(d)
     b = run_dense(d)
     assert rel_err(a, b) <= TOL
+
+
+@pytest.mark.parametrize("Cin,Cout,H,W,N", [
+    (64, 72, 14, 14, 9),     # 28-pixel tiles that tile the image; ordinary stores (planes off the line grid)
+    (40, 72, 8, 8, 21),      # 32-pixel tiles, planes on the line grid: streaming stores
+    (56, 40, 6, 10, 11),     # 60 pixels per image: tiles straddle images, ragged last tile
+    (64, 520, 14, 14, 5),    # 33 bundles: two group tiles
+    (48, 24, 2, 2, 50),      # 4 pixels per image, 8 images per tile
+    (512, 64, 14, 14, 40),   # 512 input channels (the widest the kernel takes), 280 tiles on 256 workgroups
+])
+def test_pointwise_pipelined_persistent(Cin, Cout, H, W, N):
+    """The persistent double-buffered kernel of the many-tile regime (four groups per wavefront,
+    weights resident in registers), forced onto small layers: one, two and more tiles per
+    workgroup, with and without bias."""
+    L = workloads.Layer("pipe_%d_%d" % (Cin, Cout), Cin, Cout, H, W, k=1, stride=1, N=N, V=4,
+                        sparsity=0.6 if Cin <= 64 else 0.93, w_std=0.2, x_dist="uniform")
+    for with_bias in (False, True):
+        info = check(L, 77 + Cin + Cout, with_bias=with_bias, group_slots=4, path=5)
+        assert info["mode"] == 5 and info["group_slots"] == 4, info
