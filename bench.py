@@ -74,10 +74,8 @@ def time_layer(alcs, torch, np, workloads, L, seed, dense=False, iters=10, tunin
     """Median kernel time of one layer (kernel time stamps), optionally with the dense conv
     (then the two results are compared with each other; parity with the CPU oracle is the
     business of the tests)."""
-    for k, v in (tuning or {}).items():
-        alcs.alcs_set_tuning(k, v)
     d = workloads.make_layer(L, seed)
-    p = alcs.alcs_pack_weights(d.W, d.mask, L.V)
+    p = alcs.alcs_pack_weights(d.W, d.mask, L.V, options=tuning or None)
     X = torch.from_numpy(d.X).cuda()
     Y = torch.empty((L.N, L.Cout, L.Ho, L.Wo), dtype=torch.float32, device="cuda")
     # rotate over enough copies that more than 600 MB is touched before a buffer comes round
@@ -133,8 +131,6 @@ def time_layer(alcs, torch, np, workloads, L, seed, dense=False, iters=10, tunin
     nn = p.nnzb
     by, fl = layer_bytes(L, nn), layer_flops(L, nn)
     p.free()
-    for k in (tuning or {}):
-        alcs.alcs_set_tuning(k, 0)
     roof = max(by / (HBM_PEAK_GBS * 1e9), fl / (MFMA_FP32_PEAK_TFLOPS * 1e12)) * 1e6
     bound = "hbm" if by / (HBM_PEAK_GBS * 1e9) >= fl / (MFMA_FP32_PEAK_TFLOPS * 1e12) else "mfma"
     return {"us": t, "dense_us": td, "lib_us": tl, "roof_us": roof, "bound": bound, "bytes": by, "flops": fl, "err": err,

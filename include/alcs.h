@@ -49,8 +49,10 @@ typedef enum alcs_status {
 } alcs_status;
 
 /* Opaque packed weight tensor; created by alcs_pack_weights, owned by the library
- * until alcs_packed_free.  Immutable after creation; may be used from several
- * streams at once. */
+ * until alcs_packed_free.  Immutable after creation (but for alcs_packed_set_options);
+ * may be used from several streams at once.  The library keeps no state outside
+ * handles except two per-thread diagnostics (alcs_last_hip_error, alcs_last_launch)
+ * and the device array of alcs_topn_mask_static. */
 typedef struct alcs_packed alcs_packed_t;
 
 /* Human-readable name of a status code (static string, never NULL). */
@@ -131,9 +133,10 @@ void alcs_packed_free(alcs_packed_t *p);
  *   Y_dev     [N, Cout, Ho, Wo] fp32, fully overwritten.
  *   Cin, Cout, kernel must equal the values the handle was packed with
  *   (ALCS_E_INVALID_ARG otherwise - checked on the host before anything is
- *   launched); stride is 1 or 2.  N*Cout*Ho*Wo and N*Cin*H*W must be < 2^31
- *   elements per image-channel plane product as checked by the library
- *   (ALCS_E_UNSUPPORTED).  N == 0 is a no-op that returns ALCS_OK.
+ *   launched); stride is 1 or 2.  Size limits (ALCS_E_UNSUPPORTED beyond): the
+ *   flattened output pixel axis N*Ho*Wo at most 2^31 - 1025, H*W and Ho*Wo below
+ *   2^31 each (tensors of more than 2^31 elements are fine: element offsets are
+ *   64-bit), at most 2^30 workgroups.  N == 0 is a no-op that returns ALCS_OK.
  *   The accumulation order inside a sum is unspecified (fp32 results agree with the
  *   definition to rounding, not bit for bit).
  */
@@ -236,37 +239,66 @@ int alcs_dense_conv(const float *W_dev, const float *X_dev, const float *bias_de
                     int N, int Cin, int Cout, int H, int W, int kernel, int stride, void *stream);
 
 /*
- * Tuning knobs for measurements and tests (process-wide, not thread-safe against
- * concurrent calls).  A value of 0 restores the automatic choice.
- *   read by alcs_sparse_conv:
- *     "pv"              pixels per lane of the 1x1 kernels: 1, 2 or 4 (1 or 2 with several
- *                       groups per wavefront); of the 3x3 kernel: 1 or 2 (2: tiles of twice the
- *                       height, stride 1 and V = 4 or 8 only)
- *     "waves"           wavefronts per workgroup
- *     "group_tiles"     number of workgroups that share one pixel tile
- *     "path"            1 = plain-FMA inner loop where it exists (V = 4), 2 = MFMA inner
- *                       loop, 4 = persistent double-buffered 1x1 kernel where applicable
- *     "tile_width"      output-tile width of the 3x3 kernel: 8, 16 or 32 (tile height 64/width)
- *     "debug"           measurement only, results become meaningless: bit 0 skips input
- *                       staging, bit 1 the multiply, bit 2 the output stores, bit 3
- *                       makes the kernel return at once; bit 4 (results unchanged) makes
- *                       the depthwise stage of alcs_dw_sparse_conv_fused load all nine
- *                       taps of a pixel itself instead of sharing them between lanes;
- *                       bit 5 (results unchanged) keeps alcs_dw_sparse_conv_fused in one
- *                       kernel even where it would use its workspace for speed; bit 6 (results
- *                       unchanged) keeps full pixel tiles where the 1x1 kernels would give
- *                       every workgroup fewer pixels to occupy all compute units
- *   read by alcs_pack_weights (they shape the device layout of handles packed later):
- *     "chunk_channels"  input channels per LDS chunk (forces the chunked kernels)
- *     "group_slots"     output-channel groups multiplied per wavefront: 1, 2 or 4 (automatic
- *                       choice: 1 below 512 input channels or for V < 4; from 512 channels on 4
- *                       for V = 4 when no group keeps more than twice the mean number of
- *                       columns, else 2; 4 from 1280 channels on)
- *     "groups_per_wave" reserved
- * Unknown names return ALCS_E_INVALID_ARG.  Results never depend on the knobs beyond
- * floating-point summation order (except "debug").
+ * Options of a packed tensor: the shape of its device layout and of the launches that use it.
+ * They belong to the handle (the library keeps no process-wide state); every field is an int,
+ * 0 = the automatic choice, negative values are ALCS_E_INVALID_ARG.  Results never depend on
+ * them beyond floating-point summation order.  For tests, benchmarks and callers who know
+ * their shapes; the defaults come from sweeps on MI355X.
+ *
+ *   read when the handle is packed (they shape the device layout; alcs_packed_set_options
+ *   leaves them as they were):
+ *     chunk_channels   input channels per on-chip chunk (forces the kernels that stream the
+ *                      input channels through LDS in chunks)
+ *     group_slots      output-channel groups multiplied per wavefront by the 1x1 kernels: 1, 2
+ *                      or 4 (automatic: 1 below 512 input channels or for V < 4; from 512
+ *                      channels on 4 for V = 4 when no group keeps more than twice the mean
+ *                      number of columns, else 2; 4 from 1280 channels on)
+ *   read at every launch:
+ *     pixels_per_lane  1x1 kernels: 1, 2 or 4 (1 or 2 with several groups per wavefront);
+ *                      3x3 kernel: 1 or 2 (2: tiles of twice the height, stride 1, V = 4 or 8)
+ *     waves            wavefronts per workgroup
+ *     group_tiles      number of workgroups that share one pixel tile
+ *     path             1 = plain-FMA inner loop where it exists (V = 4), 2 = MFMA inner loop,
+ *                      4 = persistent double-buffered 1x1 kernel with the weights in LDS where
+ *                      applicable, 5 = pipelined persistent 1x1 kernel (four groups per
+ *                      wavefront, at most 512 input channels and 64 kept columns per group)
+ *                      wherever it applies, 6 = never that kernel
+ *     tile_width       output-tile width of the 3x3 kernel: 8, 16 or 32 (tile height 64/width)
+ *     groups_per_wave  groups whose accumulators a wavefront of the chunked 1x1 kernel and of
+ *                      the 3x3 kernel holds: 2 or 4 (automatic: 4, or 2 when the layer has few
+ *                      groups, for V >= 8, or where halving lets two workgroups share a
+ *                      compute unit)
+ *     dw_own_taps      alcs_dw_sparse_conv_fused: every lane loads all nine taps of its pixel
+ *                      instead of sharing them with its neighbours
+ *     dw_one_kernel    alcs_dw_sparse_conv_fused: stay in one kernel even where the call would
+ *                      run the two layers through its workspace for speed
+ *     full_tiles       1x1 kernels: keep full pixel tiles where the launch would give every
+ *                      workgroup fewer pixels so as to occupy all compute units
+ *     measure_skip     must be 0.  (A measurement build of the library, compiled with
+ *                      -DALCS_MEASURE=1 and never shipped as libalcs.so, skips phases of the
+ *                      kernels by these bits - 1 input staging, 2 multiply, 4 output stores,
+ *                      8 everything - to time the others; results are then meaningless.)
+ *     reserved         must be 0
  */
-int alcs_set_tuning(const char *name, int value);
+typedef struct alcs_options {
+    int pixels_per_lane, waves, group_tiles, path, tile_width, groups_per_wave;
+    int chunk_channels, group_slots;
+    int dw_own_taps, dw_one_kernel, full_tiles;
+    int measure_skip;
+    int reserved[4];
+} alcs_options;
+
+/* alcs_pack_weights with options (NULL = all automatic, i.e. alcs_pack_weights itself); the
+ * offline re-organisation of Section 3.2.2, "Storage format".  ALCS_E_INVALID_ARG for a
+ * negative field, a non-zero reserved field or measure_skip. */
+int alcs_pack_weights_opt(const float *W_host, const uint8_t *mask_host, int Cout, int Cin, int kernel,
+                          int V, const alcs_options *options, alcs_packed_t **out);
+
+/* Replaces the launch options of a handle (the two layout fields keep their pack-time
+ * values) / reads the handle's options back.  Setting options is the one way a handle changes
+ * after it is packed: it must not run while another thread launches with that handle. */
+int alcs_packed_set_options(alcs_packed_t *p, const alcs_options *options);
+int alcs_packed_get_options(const alcs_packed_t *p, alcs_options *options);
 
 /* Latency model (Section 3.3 of the paper).  A layer is timed at n numbers of non-zero weights
  * k[0] < k[1] < ... < k[n-1] (the paper uses 0, 0.1 N, ..., N: eleven runs of
@@ -377,7 +409,8 @@ int alcs_pack_from_csr(const int32_t *row_ptr_host, const int32_t *col_idx_host,
 
 /* What the last alcs_sparse_conv call of this thread launched: fills up to `cap`
  * ints {mode (1 = all input channels resident in LDS, 2 = chunked, 3 = 3x3,
- * 4 = persistent double-buffered), pv, waves, workgroups, lds_bytes, group_tiles,
+ * 4 = persistent double-buffered with the weights in LDS, 5 = pipelined persistent),
+ * pv, waves, workgroups, lds_bytes, group_tiles,
  * chunk_channels, path, group_slots, tile_width (3x3 only, else 0)} and returns how many were
  * written.  For tests and benchmarks. */
 int alcs_last_launch(int *out, int cap);

@@ -7,6 +7,7 @@ built, loading fails with an ImportError.
 from ._binding import (  # noqa: F401
     AlcsError,
     HipEvents,
+    Options,
     Packed,
     alcs_block_scores,
     alcs_dense_conv,
@@ -20,7 +21,6 @@ from ._binding import (  # noqa: F401
     alcs_pack_on_device,
     alcs_pack_weights,
     alcs_project_latency,
-    alcs_set_tuning,
     alcs_sparse_conv,
     alcs_sparse_conv_bf16,
     alcs_sparse_conv_fused,

@@ -14,11 +14,38 @@ _lib = None
 EXPORTS = [
     "alcs_strerror", "alcs_last_hip_error", "alcs_version", "alcs_pack_weights", "alcs_packed_info",
     "alcs_packed_on_device", "alcs_packed_export", "alcs_packed_selfcheck", "alcs_packed_free",
-    "alcs_sparse_conv", "alcs_sparse_conv_timed", "alcs_sparse_conv_fused", "alcs_dense_conv", "alcs_set_tuning",
+    "alcs_sparse_conv", "alcs_sparse_conv_timed", "alcs_sparse_conv_fused", "alcs_dense_conv",
+    "alcs_pack_weights_opt", "alcs_packed_set_options", "alcs_packed_get_options",
     "alcs_depthwise_conv", "alcs_dw_sparse_conv_fused", "alcs_sparse_conv_bf16", "alcs_block_scores", "alcs_select_workspace_bytes",
     "alcs_topn_mask", "alcs_topn_mask_static", "alcs_project_latency", "alcs_pack_csr_device", "alcs_pack_from_csr",
     "alcs_last_launch", "alcs_latency_estimate", "alcs_network_latency",
 ]
+
+
+class Options(ctypes.Structure):
+    """alcs_options of include/alcs.h: plain ints, 0 = automatic."""
+    _fields_ = [(n, ctypes.c_int) for n in
+                ("pixels_per_lane", "waves", "group_tiles", "path", "tile_width", "groups_per_wave",
+                 "chunk_channels", "group_slots", "dw_own_taps", "dw_one_kernel", "full_tiles", "measure_skip")] + \
+               [("reserved", ctypes.c_int * 4)]
+
+    # short names used by tests and reports
+    ALIASES = {"pv": "pixels_per_lane"}
+
+    @classmethod
+    def make(cls, options):
+        """None, an Options, or a dict of field names (or aliases) to ints."""
+        if options is None:
+            return None
+        if isinstance(options, cls):
+            return options
+        o = cls()
+        for k, v in dict(options).items():
+            k = cls.ALIASES.get(k, k)
+            if k not in dict(cls._fields_) or k == "reserved":
+                raise ValueError("unknown option %r" % k)
+            setattr(o, k, int(v))
+        return o
 
 
 class AlcsError(RuntimeError):
@@ -58,7 +85,9 @@ def load_library():
     lib.alcs_sparse_conv_timed.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp, vp, vp]
     lib.alcs_sparse_conv_fused.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp]
     lib.alcs_dense_conv.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp]
-    lib.alcs_set_tuning.argtypes = [ctypes.c_char_p, ci]
+    lib.alcs_pack_weights_opt.argtypes = [vp, vp, ci, ci, ci, ci, vp, ctypes.POINTER(vp)]
+    lib.alcs_packed_set_options.argtypes = [vp, vp]
+    lib.alcs_packed_get_options.argtypes = [vp, vp]
     lib.alcs_last_launch.argtypes = [cip, ci]
     _lib = lib
     return lib
@@ -117,6 +146,20 @@ class Packed:
     def selfcheck(self) -> int:
         return int(load_library().alcs_packed_selfcheck(self.handle))
 
+    def set_options(self, options) -> None:
+        """Replace the handle's launch options (dict or Options; None = all automatic)."""
+        o = Options.make(options) or Options()
+        rc = load_library().alcs_packed_set_options(self.handle, ctypes.byref(o))
+        if rc != 0:
+            raise AlcsError(rc, "alcs_packed_set_options")
+
+    def get_options(self) -> dict:
+        o = Options()
+        rc = load_library().alcs_packed_get_options(self.handle, ctypes.byref(o))
+        if rc != 0:
+            raise AlcsError(rc, "alcs_packed_get_options")
+        return {n: getattr(o, n) for n, _ in Options._fields_ if n != "reserved"}
+
     def free(self):
         if self._h is not None:
             load_library().alcs_packed_free(self._h)
@@ -129,8 +172,9 @@ class Packed:
             pass
 
 
-def alcs_pack_weights(W: np.ndarray, mask: Optional[np.ndarray], V: int) -> Packed:
-    """W [Cout,Cin,k,k] fp32 host array, mask [G,Cin,k,k] uint8 host array or None."""
+def alcs_pack_weights(W: np.ndarray, mask: Optional[np.ndarray], V: int, options=None) -> Packed:
+    """W [Cout,Cin,k,k] fp32 host array, mask [G,Cin,k,k] uint8 host array or None; options: None, a
+    dict or an Options (then the call goes to alcs_pack_weights_opt)."""
     W = np.ascontiguousarray(W, dtype=np.float32)
     if W.ndim != 4 or W.shape[2] != W.shape[3]:
         raise ValueError("W must be [Cout, Cin, k, k]")
@@ -142,7 +186,12 @@ def alcs_pack_weights(W: np.ndarray, mask: Optional[np.ndarray], V: int) -> Pack
             raise ValueError("mask must be [ceil(Cout/V), Cin, k, k], got %r" % (mask.shape,))
         mptr = mask.ctypes.data
     out = ctypes.c_void_p()
-    rc = load_library().alcs_pack_weights(W.ctypes.data, mptr, Cout, Cin, k, int(V), ctypes.byref(out))
+    o = Options.make(options)
+    if o is None:
+        rc = load_library().alcs_pack_weights(W.ctypes.data, mptr, Cout, Cin, k, int(V), ctypes.byref(out))
+    else:
+        rc = load_library().alcs_pack_weights_opt(W.ctypes.data, mptr, Cout, Cin, k, int(V), ctypes.byref(o),
+                                                  ctypes.byref(out))
     if rc != 0:
         raise AlcsError(rc, "alcs_pack_weights")
     return Packed(out, Cout, Cin, k, int(V))
@@ -317,12 +366,6 @@ def alcs_dw_sparse_conv_fused(packed: Packed, D_dev, dw_bias, X, bias, residual,
         _stream_ptr(stream))
     if rc != 0:
         raise AlcsError(rc, "alcs_dw_sparse_conv_fused")
-
-
-def alcs_set_tuning(name: str, value: int) -> None:
-    rc = load_library().alcs_set_tuning(name.encode(), int(value))
-    if rc != 0:
-        raise AlcsError(rc, "alcs_set_tuning")
 
 
 def alcs_last_launch() -> dict:

@@ -30,7 +30,7 @@ struct DenseArgs {
     int N, Cin, Cout, H, W, Ho, Wo, stride, k;
     int P, Pin, K;
     int mt, nt;  // tiles along Cout and along pixels
-    int wg_per_xcd, total_wgs;
+    int wg_per_xcd, total_wgs, xcds;
 };
 
 constexpr int BK = 16;
@@ -45,7 +45,7 @@ __global__ void __launch_bounds__(256) k_dense(const DenseArgs a) {
     __shared__ float As[2][BK * LDA];
     __shared__ float Bs[2][BK * BN];
     const int id = blockIdx.x;
-    const int logical = (id % 8) * a.wg_per_xcd + id / 8;
+    const int logical = (id % a.xcds) * a.wg_per_xcd + id / a.xcds;
     if (logical >= a.total_wgs) return;
     // consecutive logical ids share the pixel tile (the large operand) and differ in the channel tile
     const int ntile = logical / a.mt, mtile = logical - ntile * a.mt;
@@ -224,17 +224,20 @@ extern "C" int alcs_dense_conv(const float *W_dev, const float *X_dev, const flo
     const bool vec = kernel == 1 && stride == 1 && (P % 4 == 0);
     const long long ntile = (a.NP + BN - 1) / BN;
     // 128 output channels per workgroup, or 64 when that leaves fewer workgroups than compute units
-    const int BM = (Cout > 64 && ntile * ((Cout + 127) / 128) >= 256) ? 128 : 64;
+    int cus = 0, xcds = 0;
+    if (current_device_shape(&cus, &xcds) != ALCS_OK) return ALCS_E_HIP;
+    const int BM = (Cout > 64 && ntile * ((Cout + 127) / 128) >= cus) ? 128 : 64;
     a.mt = (Cout + BM - 1) / BM;
     const long long total = ntile * a.mt;
     if (total > (1LL << 30)) return ALCS_E_UNSUPPORTED;
     a.nt = (int)ntile;
     a.total_wgs = (int)total;
-    a.wg_per_xcd = (int)((total + 7) / 8);
+    a.xcds = xcds;
+    a.wg_per_xcd = (int)((total + xcds - 1) / xcds);
     void (*kern)(const DenseArgs) = nullptr;
     if (BM == 128) kern = vec ? k_dense<128, true> : k_dense<128, false>;
     else kern = vec ? k_dense<64, true> : k_dense<64, false>;
-    hipLaunchKernelGGL(kern, dim3(a.wg_per_xcd * 8), dim3(256), 0, (hipStream_t)stream, a);
+    hipLaunchKernelGGL(kern, dim3(a.wg_per_xcd * xcds), dim3(256), 0, (hipStream_t)stream, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_hip_error((int)e); return ALCS_E_HIP; }
     return ALCS_OK;

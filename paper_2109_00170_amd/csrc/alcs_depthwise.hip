@@ -21,7 +21,7 @@ struct DwArgs {
     float *Z;           // [N, C, Ho, Wo]
     long long planes;   // N * C
     int nchunks;        // 64-pixel chunks per plane
-    unsigned wg_per_xcd, total_wgs;
+    unsigned wg_per_xcd, total_wgs, xcds;
     int C, H, W, Ho, Wo, P, Pin, stride, act;
 };
 
@@ -35,11 +35,11 @@ template <int MODE>
 __global__ void __launch_bounds__(256) k_depthwise(const DwArgs a) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Renumber them so that
+    // Workgroups are dealt round-robin to the XCDs, each with its own L2.  Renumber them so that
     // neighbouring 64-pixel chunks of the same planes - which share two of their three input rows -
     // run on one XCD and find those rows in its L2 (without this every row came from HBM about
     // three times: 42 us instead of 25 us for 32 channels at 112x112, batch 32).
-    const unsigned logical = (blockIdx.x % 8u) * a.wg_per_xcd + blockIdx.x / 8u;
+    const unsigned logical = (blockIdx.x % a.xcds) * a.wg_per_xcd + blockIdx.x / a.xcds;
     if (logical >= a.total_wgs) return;
     const unsigned chunk = logical % (unsigned)a.nchunks;
     const long long pg = (long long)(logical / (unsigned)a.nchunks) * 4 + wave;  // plane group
@@ -93,7 +93,7 @@ constexpr int kPlanesPerWaveQuad = 2;  // few planes per wavefront: four pixels 
 __global__ void __launch_bounds__(256) k_depthwise_quad(const DwArgs a) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const unsigned logical = (blockIdx.x % 8u) * a.wg_per_xcd + blockIdx.x / 8u;
+    const unsigned logical = (blockIdx.x % a.xcds) * a.wg_per_xcd + blockIdx.x / a.xcds;
     if (logical >= a.total_wgs) return;
     const unsigned chunk = logical % (unsigned)a.nchunks;
     const long long pg = (long long)(logical / (unsigned)a.nchunks) * 4 + wave;
@@ -180,12 +180,15 @@ extern "C" int alcs_depthwise_conv(const float *dw_weights_dev, const float *X_d
     const int ppw = quad ? kPlanesPerWaveQuad : kPlanesPerWave;
     const long long groups = (a.planes + 4 * ppw - 1) / (4 * ppw);
     const long long blocks = groups * a.nchunks;
-    if (blocks > INT32_MAX - 8) return ALCS_E_UNSUPPORTED;
+    if (blocks > INT32_MAX - 256) return ALCS_E_UNSUPPORTED;
+    int cus = 0, xcds = 0;
+    if (current_device_shape(&cus, &xcds) != ALCS_OK) return ALCS_E_HIP;
     a.total_wgs = (unsigned)blocks;
-    a.wg_per_xcd = (unsigned)((blocks + 7) / 8);
+    a.xcds = (unsigned)xcds;
+    a.wg_per_xcd = (unsigned)((blocks + xcds - 1) / xcds);
     const int mode = dw_mode_for(stride, W, X_dev);
     void (*kern)(const DwArgs) = quad ? k_depthwise_quad : mode == kDwPair ? k_depthwise<kDwPair> : k_depthwise<kDwNine>;
-    hipLaunchKernelGGL(kern, dim3(a.wg_per_xcd * 8), dim3(256), 0, (hipStream_t)stream, a);
+    hipLaunchKernelGGL(kern, dim3(a.wg_per_xcd * a.xcds), dim3(256), 0, (hipStream_t)stream, a);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_hip_error((int)e); return ALCS_E_HIP; }
     return ALCS_OK;

@@ -134,6 +134,7 @@ struct Layout {
 
 struct DeviceCopy {
     int device = -1;
+    int cus = 0, xcds = 0;  // compute units and XCDs (L2 domains) of that device, from its properties
     void *blob = nullptr;
     size_t bytes = 0;
     const Work *work = nullptr;
@@ -152,19 +153,33 @@ struct alcs_packed {
     std::vector<float> vals;
     alcs::Layout lay;
     alcs::DeviceCopy dev;
+    alcs_options opt = {};  // the options given at pack time / by alcs_packed_set_options; zero = automatic
 };
 
 namespace alcs {
 
 void set_hip_error(int e);
+// Compute units and XCDs (L2 domains; workgroups are dealt to them round-robin) of a device,
+// from its properties; looked up once per device and process (constants of the hardware).
+void device_shape(int device, int *cus, int *xcds);
+int current_device_shape(int *cus, int *xcds);  // of the current device; ALCS_OK or ALCS_E_HIP
 int build_layout(alcs_packed *p, int KC, int GS);
 int upload(alcs_packed *p);
 void release_device(alcs_packed *p);
 
+// The launch options of a handle in the launchers' short names.
 struct Tuning {
-    int pv = 0, waves = 0, group_tiles = 0, path = 0, kc = 0, ug = 0, debug = 0, gs = 0, tile_w = 0;
+    int pv = 0, waves = 0, group_tiles = 0, path = 0, ug = 0, tile_w = 0;
+    int dw_own_taps = 0, dw_one_kernel = 0, full_tiles = 0;
 };
-Tuning &tuning();
+inline Tuning tuning_of(const alcs_options &o) {
+    Tuning t;
+    t.pv = o.pixels_per_lane; t.waves = o.waves; t.group_tiles = o.group_tiles; t.path = o.path;
+    t.ug = o.groups_per_wave;
+    t.tile_w = (o.tile_width == 8 || o.tile_width == 16 || o.tile_width == 32) ? o.tile_width : 0;
+    t.dw_own_taps = o.dw_own_taps; t.dw_one_kernel = o.dw_one_kernel; t.full_tiles = o.full_tiles;
+    return t;
+}
 void record_launch(int mode, int pv, int waves, int wgs, int lds, int gtiles, int kc, int path, int gs,
                    int tile_w);
 

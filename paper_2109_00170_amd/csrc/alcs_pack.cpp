@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -17,15 +18,34 @@ static thread_local int g_last_hip = 0;
 static thread_local int g_last_launch[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 void set_hip_error(int e) { g_last_hip = e; }
 
-Tuning &tuning() {
-    static Tuning t;
-    return t;
-}
-
 void record_launch(int mode, int pv, int waves, int wgs, int lds, int gtiles, int kc, int path, int gs,
                    int tile_w) {
     int v[10] = {mode, pv, waves, wgs, lds, gtiles, kc, path, gs, tile_w};
     std::memcpy(g_last_launch, v, sizeof(v));
+}
+
+void device_shape(int device, int *cus, int *xcds) {
+    constexpr int kMax = 64;
+    static std::atomic<int> known[kMax];  // 0 = not looked up yet, else cus << 8 | xcds
+    int packed = (device >= 0 && device < kMax) ? known[device].load(std::memory_order_relaxed) : 0;
+    if (!packed) {
+        int c = 0, x = 0;
+        if (hipDeviceGetAttribute(&c, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || c <= 0) c = 256;
+        if (hipDeviceGetAttribute(&x, hipDeviceAttributeNumberOfXccs, device) != hipSuccess || x <= 0 || x > 255) x = 8;
+        (void)hipGetLastError();
+        packed = c << 8 | x;
+        if (device >= 0 && device < kMax) known[device].store(packed, std::memory_order_relaxed);
+    }
+    *cus = packed >> 8;
+    *xcds = packed & 255;
+}
+
+int current_device_shape(int *cus, int *xcds) {
+    int dev = 0;
+    const hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) { set_hip_error((int)e); return ALCS_E_HIP; }
+    device_shape(dev, cus, xcds);
+    return ALCS_OK;
 }
 
 static inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
@@ -253,7 +273,11 @@ int upload(alcs_packed *p) {
         (void)hipFree(blob);
         return ALCS_E_HIP;
     }
+    int cus = 0, xcds = 0;
+    device_shape(dev, &cus, &xcds);
     p->dev.device = dev;
+    p->dev.cus = cus;
+    p->dev.xcds = xcds;
     p->dev.blob = blob;
     p->dev.bytes = total;
     p->dev.work = (const Work *)(base + o_work);
@@ -300,16 +324,33 @@ using namespace alcs;
 
 extern "C" void alcs_packed_free(alcs_packed_t *p);
 
+// Options are plain non-negative ints; the phase-skipping field is honoured by the measurement
+// build only and refused by the product build.
+static int check_options(const alcs_options *o) {
+    const int *f = reinterpret_cast<const int *>(o);
+    for (size_t i = 0; i < sizeof(alcs_options) / sizeof(int); ++i)
+        if (f[i] < 0) return ALCS_E_INVALID_ARG;
+#if !defined(ALCS_MEASURE) || !ALCS_MEASURE
+    if (o->measure_skip != 0) return ALCS_E_INVALID_ARG;
+#endif
+    for (int r : o->reserved)
+        if (r != 0) return ALCS_E_INVALID_ARG;
+    return ALCS_OK;
+}
+
 // The tuned device layout and its upload, once the canonical arrays of the handle are in place.
-static int finish_pack(alcs_packed *p, int rc, alcs_packed_t **out) {
+static int finish_pack(alcs_packed *p, int rc, const alcs_options *opt, alcs_packed_t **out) {
+    if (rc == ALCS_OK && opt) rc = check_options(opt);
     if (rc == ALCS_OK) {
+        if (opt) p->opt = *opt;
         int KC = 0, GS = 1;
         const bool even_groups = (int64_t)p->max_count * p->G <= 2 * p->nnzb;
         default_tiles(p->Cin, p->k, p->V, even_groups, &KC, &GS);
-        if (tuning().kc > 0) { KC = std::min(tuning().kc, p->Cin); GS = 1; }
-        if (tuning().gs > 0 && p->k == 1 && p->V >= 4 && KC == p->Cin &&
-            (long long)(p->Cin + 2) * (kRowBytes1 / tuning().gs) <= 160 * 1024)
-            GS = tuning().gs;
+        const int kc = p->opt.chunk_channels, gs = p->opt.group_slots;
+        if (kc > 0) { KC = std::min(kc, p->Cin); GS = 1; }
+        if ((gs == 1 || gs == 2 || gs == 4) && p->k == 1 && p->V >= 4 && KC == p->Cin &&
+            (long long)(p->Cin + 2) * (kRowBytes1 / gs) <= 160 * 1024)
+            GS = gs;
         rc = build_layout(p, KC, GS);
     }
     if (rc == ALCS_OK) {
@@ -344,6 +385,11 @@ int alcs_version(void) { return 100; }
 
 int alcs_pack_weights(const float *W_host, const uint8_t *mask_host, int Cout, int Cin, int kernel,
                       int V, alcs_packed_t **out) {
+    return alcs_pack_weights_opt(W_host, mask_host, Cout, Cin, kernel, V, nullptr, out);
+}
+
+int alcs_pack_weights_opt(const float *W_host, const uint8_t *mask_host, int Cout, int Cin, int kernel,
+                          int V, const alcs_options *options, alcs_packed_t **out) {
     if (out) *out = nullptr;
     if (!W_host || !out || Cout <= 0 || Cin <= 0) return ALCS_E_INVALID_ARG;
     if (kernel != 1 && kernel != 3) return ALCS_E_UNSUPPORTED;
@@ -394,7 +440,7 @@ int alcs_pack_weights(const float *W_host, const uint8_t *mask_host, int Cout, i
     } catch (const std::bad_alloc &) {
         rc = ALCS_E_ALLOC;
     }
-    return finish_pack(p, rc, out);
+    return finish_pack(p, rc, options, out);
 }
 
 int alcs_pack_from_csr(const int32_t *row_ptr_host, const int32_t *col_idx_host, const float *vals_host,
@@ -434,7 +480,7 @@ int alcs_pack_from_csr(const int32_t *row_ptr_host, const int32_t *col_idx_host,
     } catch (const std::bad_alloc &) {
         rc = ALCS_E_ALLOC;
     }
-    return finish_pack(p, rc, out);
+    return finish_pack(p, rc, nullptr, out);
 }
 
 int alcs_packed_info(const alcs_packed_t *p, int *G, int *K, int64_t *nnzb) {
@@ -570,19 +616,21 @@ void alcs_packed_free(alcs_packed_t *p) {
     delete p;
 }
 
-int alcs_set_tuning(const char *name, int value) {
-    if (!name) return ALCS_E_INVALID_ARG;
-    Tuning &t = tuning();
-    if (!std::strcmp(name, "pv")) t.pv = value;
-    else if (!std::strcmp(name, "waves")) t.waves = value;
-    else if (!std::strcmp(name, "group_tiles")) t.group_tiles = value;
-    else if (!std::strcmp(name, "path")) t.path = value;
-    else if (!std::strcmp(name, "chunk_channels")) t.kc = value;
-    else if (!std::strcmp(name, "groups_per_wave")) t.ug = value;
-    else if (!std::strcmp(name, "debug")) t.debug = value;
-    else if (!std::strcmp(name, "tile_width")) t.tile_w = (value == 8 || value == 16 || value == 32) ? value : 0;
-    else if (!std::strcmp(name, "group_slots")) t.gs = (value == 1 || value == 2 || value == 4) ? value : 0;
-    else return ALCS_E_INVALID_ARG;
+int alcs_packed_set_options(alcs_packed_t *p, const alcs_options *options) {
+    if (!p || !options) return ALCS_E_INVALID_ARG;
+    const int rc = check_options(options);
+    if (rc != ALCS_OK) return rc;
+    // the layout is built: its fields keep the values it was built with
+    alcs_options o = *options;
+    o.chunk_channels = p->opt.chunk_channels;
+    o.group_slots = p->opt.group_slots;
+    p->opt = o;
+    return ALCS_OK;
+}
+
+int alcs_packed_get_options(const alcs_packed_t *p, alcs_options *options) {
+    if (!p || !options) return ALCS_E_INVALID_ARG;
+    *options = p->opt;
     return ALCS_OK;
 }
 

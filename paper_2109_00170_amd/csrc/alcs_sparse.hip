@@ -148,12 +148,12 @@ struct ConvArgs {
     int G, nchunks, KC;
     int npt, ngt, gpt;  // pixel tiles, group tiles, groups per group tile
     int tiles_x, tiles_y;  // 3x3: output tiles per image
-    int wg_per_xcd, total_wgs;
+    int wg_per_xcd, total_wgs, xcds;
     int ppw;            // streaming kernel: flattened pixels per workgroup (multiple of 4)
     int wfloats;        // streaming kernel: floats in the weight planes, planes * nblk * 4
     int nblk;           // padded blocks (= number of row selectors)
     int act;    // fused epilogue: 0 none, 1 max(., 0), 2 min(max(., 0), 6)
-    int debug;  // measurement only: bit 0 skips staging, bit 1 the multiply, bit 2 the stores
+    int debug;  // measurement build only (ALCS_MEASURE): bit 0 skips staging, bit 1 the multiply, bit 2 the stores
 #if ALCS_DW_STAGE
     // Depthwise stage: X is the depthwise layer's input [N, Cin, H, W]; its output
     // [N, Cin, Ho, Wo] is what the pointwise convolution (stride 1) multiplies.
@@ -163,6 +163,17 @@ struct ConvArgs {
     int dw_mode;           // DwMode: how lanes share taps
 #endif
 };
+
+// Phase skipping for measurements (alcs_options.measure_skip): compiled in only with
+// -DALCS_MEASURE=1, which the product build never sets - there the tests below fold to false
+// and the kernels hold no trace of them.
+#ifndef ALCS_MEASURE
+#define ALCS_MEASURE 0
+#endif
+__device__ __forceinline__ bool skip(const ConvArgs &a, int bit) {
+    if constexpr (ALCS_MEASURE != 0) return (a.debug & bit) != 0;
+    else return false;
+}
 
 // The element-wise tail of the fused epilogue (the plain convolution passes act = 0).
 __device__ __forceinline__ float activate(const ConvArgs &a, float v) {
@@ -178,7 +189,6 @@ __device__ __forceinline__ const io_t *residual_of(const ConvArgs &a) {
     else return nullptr;
 }
 
-constexpr int kXcds = 8;
 
 // Index arrays, segment table, bias and (for the FMA form) the weights are read
 // through the constant address space: the addresses are wave-uniform, and this lets
@@ -211,7 +221,7 @@ __device__ __forceinline__ Work no_work() { return Work{0, 0, {-1, -1, -1, -1}, 
 // group tile - land on the same XCD and find the tile's input rows in that L2.
 __device__ __forceinline__ int logical_wg(const ConvArgs &a) {
     const int id = blockIdx.x;
-    return (id % kXcds) * a.wg_per_xcd + id / kXcds;
+    return (id % a.xcds) * a.wg_per_xcd + id / a.xcds;
 }
 
 // ------------------------------------------------------------------ accumulators
@@ -849,7 +859,7 @@ __device__ __forceinline__ void store_slots(const ConvArgs &a, const Acc<V, PV, 
 // first run of group k+1 are fetched while group k is multiplied, and always before
 // group k's output stores are issued (memory operations retire in order, so a load
 // queued behind stores would wait for them).
-template <int V, int PV, bool MF, bool VEC, int GS, bool RES>
+template <int V, int PV, bool MF, bool VEC, int GS, bool RES, bool CACHED = false>
 __device__ __forceinline__ void pw_resident_body(const ConvArgs &a) {
     static_assert(!RES || GS == 1, "residual prefetch: one group per wavefront");
     static_assert(GS == 1 || (MF && PV <= 2), "several groups per wavefront: MFMA form, one or two pixels per lane");
@@ -858,7 +868,7 @@ __device__ __forceinline__ void pw_resident_body(const ConvArgs &a) {
     constexpr int SH = PV == 4 ? 2 : PV == 2 ? 1 : 0;
     constexpr bool SPLIT = GS > 1 && PV == 2 && !VEC;  // the lane's two pixels are TP/2 apart
     const int logical = logical_wg(a);
-    if (logical >= a.total_wgs || (a.debug & 8)) return;
+    if (logical >= a.total_wgs || skip(a, 8)) return;
     const int pt = logical / a.ngt, gt = logical - pt * a.ngt;
     // the workgroup's pixels [q0, q_end): all TP of the tile, or fewer when the launcher
     // spreads the pixels over more workgroups than full tiles would give (the rest of the
@@ -882,9 +892,9 @@ __device__ __forceinline__ void pw_resident_body(const ConvArgs &a) {
     }
 
 #if ALCS_DW_STAGE
-    if (!(a.debug & 1)) stage_dw<TP, SPLIT>(a, lds, q0, q_end);
+    if (!skip(a, 1)) stage_dw<TP, SPLIT>(a, lds, q0, q_end);
 #else
-    if (!(a.debug & 1)) stage_pw<TP, VEC, SPLIT>(a, lds, q0, 0, a.Cin, q_end);
+    if (!skip(a, 1)) stage_pw<TP, VEC, SPLIT>(a, lds, q0, 0, a.Cin, q_end);
 #endif
     // the all-zero row(s) padded columns select: two, one of each channel parity, with several
     // groups per wavefront (the packer picks the one that keeps the slots' reads on different banks)
@@ -915,13 +925,13 @@ __device__ __forceinline__ void pw_resident_body(const ConvArgs &a) {
             g_lane = lane_group<GS>(w0, lane);
             load_slot_bias<V>(a, g_lane, sb);
         }
-        if (!(a.debug & 2)) mac_segment<V, PV, SH, GS>(a, w0.start, w0.cnt, ldsb, base, lane, run0, acc);
+        if (!skip(a, 2)) mac_segment<V, PV, SH, GS>(a, w0.start, w0.cnt, ldsb, base, lane, run0, acc);
         // the next group's first runs have arrived long ago: take note of that before this
         // group's stores join the queue (see touch_runs)
         if (more) touch_runs<V, GS>(run1);
-        if (!(a.debug & 4)) {
+        if (!skip(a, 4)) {
             if constexpr (GS == 1) store_group<V, PV, MF, VEC>(a, acc, w0.group[0], px, RES ? &rr : nullptr);
-            else store_slots<V, PV, GS, VEC>(a, acc, g_lane, px, sb);
+            else store_slots<V, PV, GS, VEC, CACHED>(a, acc, g_lane, px, sb);
         }
         if (!more) break;
         w0 = w1;
@@ -933,6 +943,15 @@ __device__ __forceinline__ void pw_resident_body(const ConvArgs &a) {
 template <int V, int PV, bool MF, bool VEC, int GS>
 __global__ void __launch_bounds__(1024) k_pw_resident(const ConvArgs a) {
     pw_resident_body<V, PV, MF, VEC, GS, false>(a);
+}
+// Four groups per wavefront on pixel pairs, with ordinary instead of streaming stores: for launches
+// of several rounds over images whose channel planes do not start on cache lines (14x14, 28x28).
+// A tile's runs then cover lines in part, the neighbouring tiles - workgroups next in line, on the
+// same L2 - write the rest at about the same time, and the L2 merges them into whole lines
+// (512->512 @14x14, N=256, 90 % sparse: 89 -> 81 us; in a single round the streaming stores win).
+template <int V>
+__global__ void __launch_bounds__(1024) k_pw_resident_cached(const ConvArgs a) {
+    pw_resident_body<V, 2, true, true, 4, false, true>(a);
 }
 // The same walk with every group's residual fetched ahead of its multiply (fused epilogue,
 // MFMA and vector form, one group per wavefront).
@@ -950,7 +969,7 @@ __global__ void __launch_bounds__(512) k_pw_chunked(const ConvArgs a) {
     constexpr int TP = 64 * PV;
     constexpr int SH = PV == 4 ? 2 : PV == 2 ? 1 : 0;
     const int logical = logical_wg(a);
-    if (logical >= a.total_wgs || (a.debug & 8)) return;
+    if (logical >= a.total_wgs || skip(a, 8)) return;
     const int pt = logical / a.ngt, gt = logical - pt * a.ngt;
     const int q0 = pt * TP;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -982,19 +1001,19 @@ __global__ void __launch_bounds__(512) k_pw_chunked(const ConvArgs a) {
             }
         }
         if (ch) __syncthreads();
-        if (!(a.debug & 1)) stage_pw<TP, VEC>(a, lds, q0, c0, c1, a.NP);
+        if (!skip(a, 1)) stage_pw<TP, VEC>(a, lds, q0, c0, c1, a.NP);
         __syncthreads();
         const int base = lane * PV * 4 - c0 * (kRowBytes1 << SH);
 #pragma unroll
         for (int u = 0; u < UG; ++u)
-            if (slot[u] >= 0 && !(a.debug & 2))
+            if (slot[u] >= 0 && !skip(a, 2))
                 mac_segment<V, PV, SH>(a, wk[u].start, wk[u].cnt, ldsb, base, lane, rn[u], acc[u]);
     }
     PixOut<PV> px;
     pix_out<PV, VEC>(a, q0, lane, px, a.NP);
 #pragma unroll
     for (int u = 0; u < UG; ++u)
-        if (slot[u] >= 0 && !(a.debug & 4))
+        if (slot[u] >= 0 && !skip(a, 4))
             store_group<V, PV, MF, VEC>(a, acc[u], load_work(a.work, (size_t)slot[u] * a.nchunks).group[0], px);
 }
 
@@ -1019,7 +1038,7 @@ __global__ void __launch_bounds__(512) k_pw_stream(const ConvArgs a) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), nw = nt >> 6;
     const int q_begin = blockIdx.x * a.ppw;
     const int q_end = min(a.NP, q_begin + a.ppw);
-    if (q_begin >= q_end || (a.debug & 8)) return;
+    if (q_begin >= q_end || skip(a, 8)) return;
     const int ntiles = (q_end - q_begin + TP - 1) / TP;
     const int bufstride = (a.Cin + 1) * TP;  // floats per buffer: Cin rows + the all-zero row
     float *wl = lds + 2 * bufstride;
@@ -1058,7 +1077,7 @@ __global__ void __launch_bounds__(512) k_pw_stream(const ConvArgs a) {
             if (r < a.Cin) *reinterpret_cast<f4 *>(dst + r * TP) = v[u];
         }
     };
-    if (!(a.debug & 1)) { fetch(); commit(0); }
+    if (!skip(a, 1)) { fetch(); commit(0); }
     __syncthreads();
 
     ConvArgs al = a;   // same arguments, weights and selectors read from LDS
@@ -1070,7 +1089,7 @@ __global__ void __launch_bounds__(512) k_pw_stream(const ConvArgs a) {
     int oq = q_begin + lane * PV;
     int on = oq / a.P, op = oq - on * a.P;
     for (int t = 0; t < ntiles; ++t) {
-        if (t + 1 < ntiles && !(a.debug & 1)) fetch();
+        if (t + 1 < ntiles && !skip(a, 1)) fetch();
         if (any) {
             PixOut<PV> px;
 #pragma unroll
@@ -1092,8 +1111,8 @@ __global__ void __launch_bounds__(512) k_pw_stream(const ConvArgs a) {
                 }
                 Acc<V, PV, true> acc;
                 acc.zero();
-                if (!(a.debug & 2)) mac_segment<V, PV, SH>(al, w0.start, w0.cnt, ldsb, base, lane, run0, acc);
-                if (!(a.debug & 4)) store_group<V, PV, true, true>(a, acc, w0.group[0], px);
+                if (!skip(a, 2)) mac_segment<V, PV, SH>(al, w0.start, w0.cnt, ldsb, base, lane, run0, acc);
+                if (!skip(a, 4)) store_group<V, PV, true, true>(a, acc, w0.group[0], px);
                 if (!more) break;
                 w0 = w1;
                 w1 = w2;
@@ -1103,7 +1122,7 @@ __global__ void __launch_bounds__(512) k_pw_stream(const ConvArgs a) {
         oq += TP;
         op += TP;
         while (op >= a.P) { op -= a.P; ++on; }
-        if (t + 1 < ntiles && !(a.debug & 1)) commit((t + 1) & 1);
+        if (t + 1 < ntiles && !skip(a, 1)) commit((t + 1) & 1);
         __syncthreads();
     }
 }
@@ -1130,7 +1149,7 @@ __global__ void __launch_bounds__(512) k_conv3(const ConvArgs a) {
     constexpr int HA = halo_area3(STRIDE, TI, TALL);
     constexpr int HPOS = ROWS * COLS;          // halo positions that are actually loaded
     const int logical = logical_wg(a);
-    if (logical >= a.total_wgs || (a.debug & 8)) return;
+    if (logical >= a.total_wgs || skip(a, 8)) return;
     const int pt = logical / a.ngt, gt = logical - pt * a.ngt;
     const int tiles_per_img = a.tiles_x * a.tiles_y;
     const int n = pt / tiles_per_img, trem = pt - n * tiles_per_img;
@@ -1179,7 +1198,7 @@ __global__ void __launch_bounds__(512) k_conv3(const ConvArgs a) {
             }
         }
         if (ch) __syncthreads();
-        if (a.debug & 1) {
+        if (skip(a, 1)) {
         } else if (rpp >= 1) {
             if (r0 < rpp) {
                 constexpr int U = 8;
@@ -1224,7 +1243,7 @@ __global__ void __launch_bounds__(512) k_conv3(const ConvArgs a) {
         const int base = (lane_base - c0 * HA) * 4;
 #pragma unroll
         for (int u = 0; u < UG; ++u)
-            if (slot[u] >= 0 && !(a.debug & 2)) mac_segment<V, PV, 0, 1, PD>(a, wk[u].start, wk[u].cnt, ldsb, base, lane, rn[u], acc[u]);
+            if (slot[u] >= 0 && !skip(a, 2)) mac_segment<V, PV, 0, 1, PD>(a, wk[u].start, wk[u].cnt, ldsb, base, lane, rn[u], acc[u]);
     }
     const int oy = oy0 + ly, ox = ox0 + lx;
     PixOut<PV> px;
@@ -1235,7 +1254,7 @@ __global__ void __launch_bounds__(512) k_conv3(const ConvArgs a) {
     }
 #pragma unroll
     for (int u = 0; u < UG; ++u)
-        if (slot[u] >= 0 && !(a.debug & 4))
+        if (slot[u] >= 0 && !skip(a, 4))
             store_group<V, PV, MF, false>(a, acc[u], load_work(a.work, (size_t)slot[u] * a.nchunks).group[0], px);
 }
 
@@ -1390,7 +1409,6 @@ __global__ void __launch_bounds__(NT) k_pw_pipe(const ConvArgs a) {
 // ------------------------------------------------------------------ launcher
 
 constexpr int kMaxLds = 160 * 1024;
-constexpr int kCUs = 256;
 
 static inline int ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
 
@@ -1567,8 +1585,10 @@ static int launch_sparse(const alcs_packed_t *Wp, const io_t *X_dev, const float
     if (cur != Wp->dev.device) return ALCS_E_INVALID_ARG;
 
     const Layout &L = Wp->lay;
-    const Tuning &T = tuning();
+    const Tuning T = tuning_of(Wp->opt);
     const int V = Wp->V, G = Wp->G;
+    // compute units and L2 domains (XCDs) of the device the handle lives on
+    const int kCUs = Wp->dev.cus, kXcds = Wp->dev.xcds;
     ConvArgs a{};
     a.X = X_dev; a.bias = bias_dev; a.Y = Y_dev;
     a.residual = residual_dev; a.act = activation;
@@ -1580,10 +1600,10 @@ static int launch_sparse(const alcs_packed_t *Wp, const io_t *X_dev, const float
     if ((long long)N * P > INT32_MAX - 1024) return ALCS_E_UNSUPPORTED;
     a.NP = (int)((long long)N * P);
     a.G = L.nbundles; a.nchunks = L.nchunks; a.KC = L.KC;  // kernels count bundles of GS groups
-    a.debug = T.debug;
+    a.debug = ALCS_MEASURE ? Wp->opt.measure_skip : 0;
 #if ALCS_DW_STAGE
     a.dw_w = dw->w; a.dw_bias = dw->bias; a.dw_stride = dw->stride; a.dw_act = dw->act;
-    a.dw_mode = dw_mode_for(dw->stride, W, X_dev, (T.debug & 16) != 0);
+    a.dw_mode = dw_mode_for(dw->stride, W, X_dev, T.dw_own_taps != 0);
     if (!dw_offsets_fit(Cin, Pin, P)) return ALCS_E_UNSUPPORTED;  // tap offsets are 32-bit
 #endif
 
@@ -1682,7 +1702,7 @@ static int launch_sparse(const alcs_packed_t *Wp, const io_t *X_dev, const float
             // workgroups per compute unit) and that still leaves >= 1.5 workgroups per
             // compute unit: wider tiles mean longer contiguous runs for loads and stores.
             constexpr int kTwoPerCu = 68 * 1024;
-            constexpr int kMinWgs = 3 * kCUs / 2;
+            const int kMinWgs = 3 * kCUs / 2;
             const int GS = L.GS, NB = L.nbundles;
             if (GS > 1 && !mfma) return ALCS_E_UNSUPPORTED;  // the packer pairs groups only for V >= 4
             pv = 1;
@@ -1735,7 +1755,7 @@ static int launch_sparse(const alcs_packed_t *Wp, const io_t *X_dev, const float
             // from 512 input channels on, where the multiply weighs most: on the layers with
             // fewer channels the shorter, less aligned load and store runs cost as much as the
             // idle compute units (256->256 @28x28: 17.0 -> 17.5 us).
-            if (GS > 1 && (long long)a.npt * a.ngt < kCUs && !(T.debug & 64)) {
+            if (GS > 1 && (long long)a.npt * a.ngt < kCUs && !T.full_tiles) {
                 const int tiles_wanted = kCUs / a.ngt;
                 const int tp = (ceil_div(a.NP, tiles_wanted) + 3) & ~3;
                 if (tp < TP && 2 * tp >= TP) {
@@ -1754,6 +1774,14 @@ static int launch_sparse(const alcs_packed_t *Wp, const io_t *X_dev, const float
                 case 4: kern = mfma ? pick_resident<4, true>(pv, vec, GS, a.residual != nullptr) : pick_resident<4, false>(pv, vec, GS); break;
                 case 8: kern = pick_resident<8, true>(pv, vec, GS, a.residual != nullptr); break;
                 case 16: kern = pick_resident<16, true>(pv, vec, GS, a.residual != nullptr); break;
+            }
+            if (GS == 4 && pv == 2 && vec && mfma && (long long)a.npt * a.ngt > 2LL * kCUs &&
+                ((long long)P * sizeof(io_t)) % 128 != 0) {
+                switch (V) {
+                    case 4: kern = k_pw_resident_cached<4>; break;
+                    case 8: kern = k_pw_resident_cached<8>; break;
+                    case 16: kern = k_pw_resident_cached<16>; break;
+                }
             }
             // A kernel that holds more than 64 registers per lane fits fewer than 32 wavefronts
             // on a compute unit, so two of its 16-wavefront workgroups cannot share one.  With
@@ -1837,10 +1865,11 @@ static int launch_sparse(const alcs_packed_t *Wp, const io_t *X_dev, const float
     // Depthwise stage: every group tile of a pixel tile evaluates the depthwise layer again, so
     // a launch that splits the groups is slower than the two layers run one after the other;
     // the caller that can do that (it has a workspace) is told to.
-    if (kDw && decline_restaged && a.ngt > 1 && !(T.debug & 32)) return ALCS_E_UNSUPPORTED;
+    if (kDw && decline_restaged && a.ngt > 1 && !T.dw_one_kernel) return ALCS_E_UNSUPPORTED;
     const long long total = wg_count > 0 ? wg_count : (long long)a.npt * a.ngt;
     if (total > (1LL << 30)) return ALCS_E_UNSUPPORTED;
     a.total_wgs = (int)total;
+    a.xcds = kXcds;
     a.wg_per_xcd = ceil_div(total, kXcds);
     int rc = set_lds_limit(kern, lds);
     if (rc != ALCS_OK) return rc;

@@ -39,11 +39,12 @@ def assert_close_after_activation(got, ref, pre, what):
     return err / max(s_ref, 1e-300), err / max(s_pre, 1e-300)
 
 
-def run_sparse(d: workloads.LayerData, check_pack=True):
-    """Pack on the library side, run alcs_sparse_conv on cuda:0, return (Y numpy, launch info)."""
+def run_sparse(d: workloads.LayerData, check_pack=True, options=None):
+    """Pack on the library side (with the handle's options, a dict, if any), run alcs_sparse_conv on
+    cuda:0, return (Y numpy, launch info)."""
     import torch
     L = d.layer
-    packed = alcs.alcs_pack_weights(d.W, d.mask, L.V)
+    packed = alcs.alcs_pack_weights(d.W, d.mask, L.V, options=options or None)
     assert packed.on_device
     if check_pack:
         for got, want in zip(packed.export(), oracle.pack(d.W, d.mask, L.V)):

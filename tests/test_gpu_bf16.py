@@ -13,27 +13,10 @@ from gpu_util import TOL
 
 pytestmark = pytest.mark.gpu
 
-KNOBS = ("pv", "waves", "group_tiles", "path", "chunk_channels", "groups_per_wave", "group_slots", "debug",
-         "tile_width")
-
-
-@pytest.fixture(autouse=True)
-def _reset_tuning():
-    yield
-    for k in KNOBS:
-        alcs.alcs_set_tuning(k, 0)
-
-
 def run_bf16(L, seed, act=None, with_res=False, with_bias=True, in_place=False, pack_tuning=None, **tuning):
     import torch
-    for k, v in (pack_tuning or {}).items():
-        alcs.alcs_set_tuning(k, v)
     d = workloads.make_layer(L, seed, with_bias=with_bias)
-    packed = alcs.alcs_pack_weights(d.W, d.mask, L.V)
-    for k in (pack_tuning or {}):
-        alcs.alcs_set_tuning(k, 0)
-    for k, v in tuning.items():
-        alcs.alcs_set_tuning(k, v)
+    packed = alcs.alcs_pack_weights(d.W, d.mask, L.V, options=dict(pack_tuning or {}, **tuning))
     Xb = oracle.round_bf16(d.X)                                  # the tensor as stored: bfloat16 values
     rng = np.random.default_rng(seed + 1)
     Rb = oracle.round_bf16((rng.standard_normal((L.N, L.Cout, L.Ho, L.Wo)) * 2).astype(np.float32)) if with_res else None
@@ -98,8 +81,8 @@ def test_several_groups_per_wavefront_pixel_pairs_bf16(slots, pv):
 
 def test_single_round_spreads_pixels_over_all_compute_units_bf16():
     L = workloads.Layer("bf_narrow", 512, 64, 14, 14, N=32, V=4, sparsity=0.9, w_std=0.1)
-    full = run_bf16(L, 3570, act="relu", with_res=True, debug=64)
-    spread = run_bf16(L, 3570, act="relu", with_res=True, debug=0)
+    full = run_bf16(L, 3570, act="relu", with_res=True, full_tiles=1)
+    spread = run_bf16(L, 3570, act="relu", with_res=True)
     assert spread["workgroups"] > full["workgroups"], (full, spread)
 
 

@@ -12,17 +12,6 @@ from gpu_util import TOL, assert_close_after_activation
 
 pytestmark = pytest.mark.gpu
 
-KNOBS = ("pv", "waves", "group_tiles", "path", "chunk_channels", "groups_per_wave", "group_slots", "debug",
-         "tile_width")
-
-
-@pytest.fixture(autouse=True)
-def _reset_tuning():
-    yield
-    for k in KNOBS:
-        alcs.alcs_set_tuning(k, 0)
-
-
 def dw_inputs(C, N, H, W, seed, x_scale=1.5):
     rng = np.random.default_rng(seed)
     D = (rng.standard_normal((C, 3, 3)) * 0.4).astype(np.float32)
@@ -57,14 +46,8 @@ def run_block(L, Hin, Win, dw_stride, seed, dw_act="relu", act=None, with_res=Fa
     """L describes the pointwise layer (its H x W is the depthwise layer's output)."""
     import torch
     assert (oracle.out_size(Hin, 3, dw_stride), oracle.out_size(Win, 3, dw_stride)) == (L.H, L.W)
-    for k, v in (pack_tuning or {}).items():
-        alcs.alcs_set_tuning(k, v)
     d = workloads.make_layer(L, seed, with_bias=with_bias)
-    packed = alcs.alcs_pack_weights(d.W, d.mask, L.V)
-    for k in (pack_tuning or {}):
-        alcs.alcs_set_tuning(k, 0)
-    for k, v in tuning.items():
-        alcs.alcs_set_tuning(k, v)
+    packed = alcs.alcs_pack_weights(d.W, d.mask, L.V, options=dict(pack_tuning or {}, **tuning))
     D, X, b1 = dw_inputs(L.Cin, L.N, Hin, Win, seed + 7)
     if not dw_bias:
         b1 = None
@@ -117,10 +100,10 @@ def test_block_workgroups_smaller_than_the_tile(pv, waves):
 @pytest.mark.parametrize("dw_stride", [1, 2])
 @pytest.mark.parametrize("slots", [1, 2])
 def test_block_taps_loaded_one_by_one(dw_stride, slots):
-    # debug bit 4: the stage that shares no taps between lanes must give the same block
+    # dw_own_taps: the stage that shares no taps between lanes must give the same block
     Cin = 64 if slots == 1 else 700
     L = workloads.Layer("blk_generic", Cin, 24, 14, 14, N=3, V=4, sparsity=0.8, w_std=0.2)
-    run_block(L, 14 * dw_stride, 14 * dw_stride, dw_stride, 2080 + slots, debug=16,
+    run_block(L, 14 * dw_stride, 14 * dw_stride, dw_stride, 2080 + slots, dw_own_taps=1,
               pack_tuning={"group_slots": slots} if slots > 1 else None)
 
 
@@ -152,8 +135,8 @@ def test_block_several_groups_per_wavefront(Cin, slots):
 def test_block_single_round_spreads_pixels_over_all_compute_units(Cin, hw, dw_stride, N):
     # workgroups that take fewer pixels than their tile holds (see the pointwise test of the same name)
     L = workloads.Layer("blk_narrow", Cin, 64, hw, hw, N=N, V=4, sparsity=0.9, w_std=0.1)
-    full = run_block(L, hw * dw_stride, hw * dw_stride, dw_stride, 2400 + hw, debug=64)
-    spread = run_block(L, hw * dw_stride, hw * dw_stride, dw_stride, 2400 + hw, debug=0)
+    full = run_block(L, hw * dw_stride, hw * dw_stride, dw_stride, 2400 + hw, full_tiles=1)
+    spread = run_block(L, hw * dw_stride, hw * dw_stride, dw_stride, 2400 + hw)
     assert spread["workgroups"] > full["workgroups"], (full, spread)
 
 
@@ -191,7 +174,7 @@ def test_block_through_the_workspace_when_channels_are_chunked():
     L1 = workloads.Layer("blk_split", 64, 256, 7, 7, N=4, V=4, sparsity=0.8, w_std=0.2)
     info = run_block(L1, 7, 7, 1, 2502, workspace=True, expect_mode=None)
     assert info["group_tiles"] > 1
-    info = run_block(L1, 7, 7, 1, 2502, workspace=True, expect_mode=1, debug=32)
+    info = run_block(L1, 7, 7, 1, 2502, workspace=True, expect_mode=1, dw_one_kernel=1)
     assert info["group_tiles"] > 1
     run_block(L1, 7, 7, 1, 2502, workspace=False, expect_mode=1)
     # a resident layout with one group tile leaves the workspace alone

@@ -12,27 +12,12 @@ from gpu_util import TOL, assert_close_after_activation, rel_err
 
 pytestmark = pytest.mark.gpu
 
-KNOBS = ("pv", "waves", "group_tiles", "path", "chunk_channels", "groups_per_wave", "group_slots", "debug",
-         "tile_width")
-
-
-@pytest.fixture(autouse=True)
-def _reset_tuning():
-    yield
-    for k in KNOBS:
-        alcs.alcs_set_tuning(k, 0)
-
-
 def run_fused(L, seed, act, with_res=True, in_place=False, with_bias=True, pack_tuning=None, **tuning):
     import torch
-    for k, v in (pack_tuning or {}).items():
-        alcs.alcs_set_tuning(k, v)
-    for k, v in tuning.items():
-        alcs.alcs_set_tuning(k, v)
     d = workloads.make_layer(L, seed, with_bias=with_bias)
     rng = np.random.default_rng(seed + 1)
     R = (rng.standard_normal((L.N, L.Cout, L.Ho, L.Wo)) * 2).astype(np.float32) if with_res else None
-    packed = alcs.alcs_pack_weights(d.W, d.mask, L.V)
+    packed = alcs.alcs_pack_weights(d.W, d.mask, L.V, options=dict(pack_tuning or {}, **tuning))
     X = torch.from_numpy(d.X).cuda()
     b = None if d.bias is None else torch.from_numpy(d.bias).cuda()
     if in_place:

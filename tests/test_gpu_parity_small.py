@@ -11,19 +11,9 @@ from gpu_util import TOL, oracle_ref, rel_err, run_dense, run_sparse
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(autouse=True)
-def _reset_tuning():
-    yield
-    for k in ("pv", "waves", "group_tiles", "path", "chunk_channels", "groups_per_wave", "group_slots", "debug",
-              "tile_width"):
-        alcs.alcs_set_tuning(k, 0)
-
-
 def check(L, seed, with_bias=True, **tuning):
-    for k, v in tuning.items():
-        alcs.alcs_set_tuning(k, v)
     d = workloads.make_layer(L, seed, with_bias=with_bias)
-    got, info = run_sparse(d)
+    got, info = run_sparse(d, options=tuning)
     ref = oracle_ref(d)
     assert got.shape == ref.shape
     assert not np.isnan(got).any(), "some outputs were never written"
@@ -111,10 +101,9 @@ def test_pointwise_several_groups_per_wavefront_two_pixels_per_lane(V, gs, hw):
                                            (1300, 64, 14, 15)])  # one pixel per lane: 16-pixel tiles, 12 of 16
 def test_pointwise_single_round_spreads_pixels_over_all_compute_units(Cin, Cout, hw, N):
     """A launch of one round with fewer workgroups than compute units gives every workgroup
-    fewer pixels than its tile holds; debug bit 6 keeps full tiles.  Both must match the oracle."""
+    fewer pixels than its tile holds; the option full_tiles keeps full tiles.  Both must match the oracle."""
     L = workloads.Layer("pw_narrow", Cin, Cout, hw, hw, N=N, V=4, sparsity=0.9)
-    full = check(L, 480 + Cin + hw, debug=64)
-    alcs.alcs_set_tuning("debug", 0)
+    full = check(L, 480 + Cin + hw, full_tiles=1)
     spread = check(L, 480 + Cin + hw)
     assert full["mode"] == 1 and spread["mode"] == 1
     assert spread["workgroups"] > full["workgroups"], (full, spread)

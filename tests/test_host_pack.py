@@ -100,22 +100,28 @@ def test_argument_validation_on_the_host():
     assert lib.alcs_dense_conv(None, x, None, x, 1, 4, 8, 4, 4, 1, 1, None) == E_INVALID
     assert lib.alcs_dense_conv(x, x, None, x, 1, 4, 8, 4, 4, 2, 1, None) == E_UNSUPPORTED
     assert lib.alcs_dense_conv(x, x, None, x, 0, 4, 8, 4, 4, 1, 1, None) == 0
-    assert lib.alcs_set_tuning(b"no_such_knob", 1) == E_INVALID
+    # options: negative fields, reserved fields and the measurement-only field are refused
+    for bad in ({"waves": -1}, {"measure_skip": 1}):
+        with pytest.raises(alcs.AlcsError) as e:
+            alcs.alcs_pack_weights(np.zeros((8, 4, 1, 1), np.float32), None, 4, options=bad)
+        assert e.value.status == E_INVALID
+    o = alcs.Options()
+    o.reserved[2] = 1
+    with pytest.raises(alcs.AlcsError):
+        alcs.alcs_pack_weights(np.zeros((8, 4, 1, 1), np.float32), None, 4, options=o)
+    with pytest.raises(ValueError):
+        alcs.alcs_pack_weights(np.zeros((8, 4, 1, 1), np.float32), None, 4, options={"no_such_option": 1})
 
 
 def test_chunked_layouts_selfcheck_for_every_chunk_size():
     rng = np.random.default_rng(3)
     W = rng.standard_normal((20, 37, 1, 1)).astype(np.float32)
     mask = (rng.random((5, 37, 1, 1)) < 0.3).astype(np.uint8)
-    try:
-        for kc in (1, 5, 8, 36, 37, 64):
-            alcs.alcs_set_tuning("chunk_channels", kc)
-            p = alcs.alcs_pack_weights(W, mask, 4)
-            assert p.selfcheck() == 0
-            for got, want in zip(p.export(), oracle.pack(W, mask, 4)):
-                assert got.tobytes() == want.tobytes()
-    finally:
-        alcs.alcs_set_tuning("chunk_channels", 0)
+    for kc in (1, 5, 8, 36, 37, 64):
+        p = alcs.alcs_pack_weights(W, mask, 4, options={"chunk_channels": kc})
+        assert p.selfcheck() == 0
+        for got, want in zip(p.export(), oracle.pack(W, mask, 4)):
+            assert got.tobytes() == want.tobytes()
 
 
 @pytest.mark.parametrize("gs", [1, 2, 4])
@@ -127,11 +133,7 @@ def test_group_slot_layouts_selfcheck(gs, V, Cout):
     W = rng.standard_normal((Cout, 70, 1, 1)).astype(np.float32)
     mask = (rng.random((G, 70, 1, 1)) < 0.35).astype(np.uint8)
     mask[1] = 0          # an empty group ends up in the last bundle
-    try:
-        alcs.alcs_set_tuning("group_slots", gs)
-        p = alcs.alcs_pack_weights(W, mask, V)
-    finally:
-        alcs.alcs_set_tuning("group_slots", 0)
+    p = alcs.alcs_pack_weights(W, mask, V, options={"group_slots": gs})
     assert p.selfcheck() == 0
     for got, want in zip(p.export(), oracle.pack(W, mask, V)):
         assert got.tobytes() == want.tobytes()
