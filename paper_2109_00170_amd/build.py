@@ -46,5 +46,30 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+MEASURE_LIB = os.path.join(HERE, "libalcs_measure.so")
+
+
+def build_measure(verbose: bool = False) -> str:
+    """The measurement build: the same library with -DALCS_MEASURE=1, in which the option
+    ``measure_skip`` makes the kernels of alcs_sparse_conv skip phases (staging, multiply, stores)
+    so that the others can be timed.  Never loaded by the package (point ALCS_LIBRARY at it for a
+    measurement run); needs the objects of build() to exist."""
+    objs = []
+    for src in SOURCES:
+        obj = os.path.join(CSRC, os.path.splitext(src)[0] + ".o")
+        if src in ("alcs_pack.cpp", "alcs_sparse.hip"):
+            obj = os.path.join(CSRC, os.path.splitext(src)[0] + "_measure.o")
+            cmd = ["hipcc", "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj, "-DALCS_MEASURE=1"] + FLAGS
+            if verbose:
+                print(" ".join(cmd), flush=True)
+            subprocess.run(cmd, check=True, stdout=subprocess.DEVNULL if not verbose else None,
+                           stderr=subprocess.DEVNULL if not verbose else None)
+        objs.append(obj)
+    subprocess.check_call(["hipcc", "-shared", "-fPIC", "--offload-arch=gfx950", "-o", MEASURE_LIB] + objs)
+    return MEASURE_LIB
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
+    if "--measure" in sys.argv:
+        print(build_measure(verbose=True))

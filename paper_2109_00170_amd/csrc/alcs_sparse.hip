@@ -1662,7 +1662,8 @@ static int launch_sparse(const alcs_packed_t *Wp, const io_t *X_dev, const float
         // gets several tiles (else there is nothing to overlap and the resident kernel's single
         // tile per workgroup is the better shape)
         bool pipe_ok = false;
-#if !ALCS_RESIDENT_ONLY
+#if !ALCS_RESIDENT_ONLY && !ALCS_FUSED_EPILOGUE
+        // (not in the builds with the fused epilogue: its extra registers make this kernel spill)
         if (!stream_ok && L.nchunks == 1 && L.GS == 4 && V == 4 && vec && mfma && T.path != 6 && Cin <= 512 &&
             2LL * (Cin + 2) * 32 * 4 + 4LL * Cout <= kMaxLds) {
             // tiles of 28 pixels where they tile the image exactly and 32 do not (14x14, 28x28)
