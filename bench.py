@@ -54,10 +54,30 @@ def kernel_symbol(L, info):
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_mobilenetv1_pointwise_b32.txt")
 
 
+KERNEL_SOURCES = ("alcs_sparse.hip", "alcs_pack.cpp", "alcs_internal.h")
+
+
+def kernel_sources_digest():
+    """SHA-256 over the sources that decide the 1x1 kernels and their weight layout: the stamp the
+    traffic profile carries, so that a profile taken before a kernel change is not quoted after it."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2109_00170_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
 def read_traffic(symbol):
     """HBM bytes per launch of `symbol` from the committed rocprofv3 --pmc summary
-    (FETCH_SIZE + WRITE_SIZE, each scaled by a plain copy of known size), or None."""
+    (FETCH_SIZE + WRITE_SIZE, each scaled by a plain copy of known size), or None - also when the
+    summary was taken with other kernel sources than the ones in the tree (its `# sources:` stamp)."""
     try:
+        with open(TRAFFIC_FILE) as f:
+            lines = f.read().splitlines()
+        stamp = [l.split(":", 1)[1].strip() for l in lines if l.startswith("# sources:")]
+        if not stamp or stamp[0] != kernel_sources_digest():
+            return None
         with open(TRAFFIC_FILE) as f:
             for line in f:
                 if line.startswith("#") or "|" not in line:
@@ -70,7 +90,38 @@ def read_traffic(symbol):
     return None
 
 
-def time_layer(alcs, torch, np, workloads, L, seed, dense=False, iters=10, tuning=None):
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown CPU"
+
+
+def cpu_oracle_us(np, d, L, images=None):
+    """cpu_baseline leg: the oracle (oracle_conv on the masked weights, all host threads) on the
+    layer's inputs.  images: run the first `images` of the batch only and scale linearly (images
+    are independent); returns (microseconds for the whole batch, "measured" | "extrapolated")."""
+    import oracle
+    nb = L.N if images is None else max(1, min(images, L.N))
+    Wd = oracle.densify(d.W, d.mask, L.V)
+    xs = np.ascontiguousarray(d.X[:nb])
+    t0 = time.perf_counter()
+    oracle.conv(Wd, xs, stride=L.stride, nthreads=oracle.max_threads())
+    t = time.perf_counter() - t0
+    return t * 1e6 * L.N / nb, ("measured" if nb == L.N else "extrapolated from %d images" % nb)
+
+
+def cpu_header(pr):
+    import oracle
+    pr("CPU oracle column: oracle_conv (plain C, double accumulation, zero weights skipped) on %d threads of: %s\n"
+       % (oracle.max_threads(), cpu_model()))
+
+
+def time_layer(alcs, torch, np, workloads, L, seed, dense=False, iters=10, tuning=None, cpu_images=0):
     """Median kernel time of one layer (kernel time stamps), optionally with the dense conv
     (then the two results are compared with each other; parity with the CPU oracle is the
     business of the tests)."""
@@ -131,75 +182,138 @@ def time_layer(alcs, torch, np, workloads, L, seed, dense=False, iters=10, tunin
     nn = p.nnzb
     by, fl = layer_bytes(L, nn), layer_flops(L, nn)
     p.free()
+    cpu_us = cpu_how = None
+    if cpu_images != 0:
+        cpu_us, cpu_how = cpu_oracle_us(np, d, L, None if cpu_images < 0 else cpu_images)
     roof = max(by / (HBM_PEAK_GBS * 1e9), fl / (MFMA_FP32_PEAK_TFLOPS * 1e12)) * 1e6
     bound = "hbm" if by / (HBM_PEAK_GBS * 1e9) >= fl / (MFMA_FP32_PEAK_TFLOPS * 1e12) else "mfma"
     return {"us": t, "dense_us": td, "lib_us": tl, "roof_us": roof, "bound": bound, "bytes": by, "flops": fl, "err": err,
-            "info": info}
+            "info": info, "cpu_us": cpu_us, "cpu_how": cpu_how}
 
 
 def report(kind, alcs, workloads, torch, np):
     """Per-layer tables for configurations 3, 4, 5 and the MFMA / FMA comparison (markdown on stdout)."""
     pr = lambda *a: print(*a, flush=True)
     if kind == "sweep":
-        pr("| sparsity | sparse us | dense us | speed-up | PyTorch dense us | vs PyTorch | dense-equiv TFLOP/s | actual TFLOP/s | bound | roofline frac | max diff vs dense |")
-        pr("|---|---|---|---|---|---|---|---|---|---|---|")
+        cpu_header(pr)
+        pr("| sparsity | sparse us | kernel | dense us | speed-up | PyTorch dense us | vs PyTorch | dense-equiv TFLOP/s | actual TFLOP/s | bound | roofline frac | max diff vs dense | CPU oracle ms (whole batch) |")
+        pr("|---|---|---|---|---|---|---|---|---|---|---|---|---|")
         for s in workloads.SWEEP_SPARSITIES:
             L = workloads.sweep_layer(s)
-            r = time_layer(alcs, torch, np, workloads, L, workloads.seed_for(4, int(round(s * 100))), dense=True)
-            pr("| %.2f | %.1f | %.1f | %.2f | %.1f | %.2f | %.1f | %.1f | %s | %.3f | %.1e |" %
-               (s, r["us"], r["dense_us"], r["dense_us"] / r["us"], r["lib_us"], r["lib_us"] / r["us"], L.dense_flops() / r["us"] / 1e6,
-                r["flops"] / r["us"] / 1e6, r["bound"], r["roof_us"] / r["us"], r["err"]))
+            r = time_layer(alcs, torch, np, workloads, L, workloads.seed_for(4, int(round(s * 100))), dense=True, cpu_images=-1)
+            pr("| %.2f | %.1f | mode %d | %.1f | %.2f | %.1f | %.2f | %.1f | %.1f | %s | %.3f | %.1e | %.0f (%s) |" %
+               (s, r["us"], r["info"]["mode"], r["dense_us"], r["dense_us"] / r["us"], r["lib_us"], r["lib_us"] / r["us"], L.dense_flops() / r["us"] / 1e6,
+                r["flops"] / r["us"] / 1e6, r["bound"], r["roof_us"] / r["us"], r["err"], r["cpu_us"] / 1e3, r["cpu_how"]))
+    elif kind == "config1":
+        cpu_header(pr)
+        L = workloads.config1()
+        r = time_layer(alcs, torch, np, workloads, L, workloads.seed_for(1, 0), dense=True, cpu_images=-1, iters=50)
+        pr("| layer | sparse us | dense us | PyTorch dense us | roofline us | roofline frac | max diff vs dense | CPU oracle ms |")
+        pr("|---|---|---|---|---|---|---|---|")
+        pr("| %s %d->%d @%d, batch %d, %d %% of the blocks kept | %.2f | %.2f | %.2f | %.2f | %.3f | %.1e | %.2f |" %
+           (L.name, L.Cin, L.Cout, L.H, L.N, round(100 * (1 - L.sparsity)), r["us"], r["dense_us"], r["lib_us"], r["roof_us"],
+            r["roof_us"] / r["us"], r["err"], r["cpu_us"] / 1e3))
+        pr("\n(a launch-bound layer: its roofline is 0.2 us, an empty kernel takes 3.9 us by its own time stamps)")
+    elif kind == "floor":
+        # What bounds a layer apart from its roofline: (a) a vendor copy kernel that moves the layer's
+        # algorithmic bytes (X read once, Y written once) on the same rotating, cache-cold buffers;
+        # (b) the multiply alone at the rate the LDS-fed 4x4x1 inner loop reaches on this chip
+        # (72.5 TFLOP/s of kept weights with two pixels per lane, measured with a register-and-LDS-only
+        # loop of the same instructions), spread over all SIMDs; (c) the time stamps of an empty kernel.
+        MUL_TFLOPS = 72.5
+        EMPTY_US = 3.9
+        pr("| layer | Cin->Cout | HxW | roofline us (8 TB/s) | copy of the same bytes us | multiply alone us | empty kernel us | "
+           "measured us | measured / roofline | copy / measured |")
+        pr("|---|---|---|---|---|---|---|---|---|---|")
+        tot = tcopy = troof = 0.0
+        for i, L in enumerate(workloads.mobilenet_v1_pointwise(32, 0.9)):
+            r = time_layer(alcs, torch, np, workloads, L, workloads.seed_for(2, i))
+            R = max(2, min(8, int(600e6 // (L.x_bytes() + L.y_bytes())) + 1))
+            Xr = [torch.randn((L.N, L.Cin, L.H, L.W), device="cuda") for _ in range(R)]
+            Yr = [torch.empty((L.N, L.Cout, L.Ho, L.Wo), device="cuda") for _ in range(R)]
+            rep = L.Cout // L.Cin
+
+            def copy(j):
+                if rep == 1:
+                    Yr[j % R].copy_(Xr[j % R])
+                else:
+                    torch.cat([Xr[j % R]] * rep, dim=1, out=Yr[j % R])
+            for j in range(R):
+                copy(j)
+            torch.cuda.synchronize()
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(3 * R)]
+            for j, (a, b) in enumerate(evs):
+                a.record()
+                copy(j)
+                b.record()
+            torch.cuda.synchronize()
+            c_us = float(np.median([a.elapsed_time(b) * 1e3 for a, b in evs]))
+            m_us = r["flops"] / (MUL_TFLOPS * 1e12) * 1e6
+            tot += r["us"]
+            tcopy += c_us
+            troof += r["roof_us"]
+            pr("| %s | %d->%d | %d | %.2f | %.2f | %.2f | %.1f | %.2f | %.2f | %.2f |" %
+               (L.name, L.Cin, L.Cout, L.H, r["roof_us"], c_us, m_us, EMPTY_US, r["us"], r["us"] / r["roof_us"], c_us / r["us"]))
+            del Xr, Yr
+            torch.cuda.empty_cache()
+        pr("\n13 layers: measured %.0f us, copies of the same bytes %.0f us, rooflines %.0f us" % (tot, tcopy, troof))
     elif kind == "resnet":
-        pr("| layer | Cin->Cout | k/s | HxW | x | sparse us | dense us | speed-up | PyTorch dense us | vs PyTorch | actual TFLOP/s | eff GB/s | bound | roofline frac | max diff vs dense |")
-        pr("|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|")
-        tot = troof = tdense = tlib = 0.0
+        cpu_header(pr)
+        pr("| layer | Cin->Cout | k/s | HxW | x | sparse us | dense us | speed-up | PyTorch dense us | vs PyTorch | actual TFLOP/s | eff GB/s | bound | roofline frac | max diff vs dense | CPU oracle ms (batch 64, extrapolated from 2 images) |")
+        pr("|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|")
+        tot = troof = tdense = tlib = tcpu = 0.0
         for i, L in enumerate(workloads.resnet50_bottlenecks(64)):
-            r = time_layer(alcs, torch, np, workloads, L, workloads.seed_for(3, i), dense=True)
+            r = time_layer(alcs, torch, np, workloads, L, workloads.seed_for(3, i), dense=True, cpu_images=2)
+            tcpu += r["cpu_us"] * L.repeats
             tot += r["us"] * L.repeats
             troof += r["roof_us"] * L.repeats
             tdense += r["dense_us"] * L.repeats
             tlib += r["lib_us"] * L.repeats
-            pr("| %s | %d->%d | %d/%d | %d | %d | %.1f | %.1f | %.2f | %.1f | %.2f | %.1f | %.0f | %s | %.3f | %.1e |" %
+            pr("| %s | %d->%d | %d/%d | %d | %d | %.1f | %.1f | %.2f | %.1f | %.2f | %.1f | %.0f | %s | %.3f | %.1e | %.0f |" %
                (L.name, L.Cin, L.Cout, L.k, L.stride, L.H, L.repeats, r["us"], r["dense_us"],
                 r["dense_us"] / r["us"], r["lib_us"], r["lib_us"] / r["us"], r["flops"] / r["us"] / 1e6,
-                r["bytes"] / r["us"] / 1e3, r["bound"], r["roof_us"] / r["us"], r["err"]))
-        pr("\nall 48 convs, batch 64: sparse %.0f us, dense %.0f us (%.2fx), PyTorch dense %.0f us (%.2fx), sum of rooflines %.0f us (%.3f)" %
-           (tot, tdense, tdense / tot, tlib, tlib / tot, troof, troof / tot))
+                r["bytes"] / r["us"] / 1e3, r["bound"], r["roof_us"] / r["us"], r["err"], r["cpu_us"] / 1e3))
+        pr("\nall 48 convs, batch 64: sparse %.0f us, dense %.0f us (%.2fx), PyTorch dense %.0f us (%.2fx), sum of rooflines %.0f us (%.3f), CPU oracle %.0f ms (extrapolated)" %
+           (tot, tdense, tdense / tot, tlib, tlib / tot, troof, troof / tot, tcpu / 1e3))
     elif kind == "mbv2":
+        cpu_header(pr)
         for V in (1, 4, 8, 16):
             pr("\nV = %d" % V)
-            pr("| layer | sparse us | eff GB/s | bound | roofline frac | longest/mean group |")
-            pr("|---|---|---|---|---|---|")
-            tot = troof = 0.0
+            pr("| layer | sparse us | eff GB/s | bound | roofline frac | longest/mean group | CPU oracle ms (batch 128, extrapolated from 2 images) |")
+            pr("|---|---|---|---|---|---|---|")
+            tot = troof = tcpu = 0.0
             for i, L in enumerate(workloads.mobilenet_v2_pointwise(128, V)):
-                r = time_layer(alcs, torch, np, workloads, L, workloads.seed_for(5, 100 * V + i))
+                r = time_layer(alcs, torch, np, workloads, L, workloads.seed_for(5, 100 * V + i), cpu_images=2)
                 tot += r["us"] * L.repeats
                 troof += r["roof_us"] * L.repeats
+                tcpu += r["cpu_us"] * L.repeats
                 cnt = workloads.zipf_counts(L.G, L.K, 1.0 - L.sparsity)
-                pr("| %s | %.1f | %.0f | %s | %.3f | %.1f |" %
+                pr("| %s | %.1f | %.0f | %s | %.3f | %.1f | %.1f |" %
                    (L.name, r["us"], r["bytes"] / r["us"] / 1e3, r["bound"], r["roof_us"] / r["us"],
-                    cnt.max() / max(cnt.mean(), 1e-9)))
-            pr("total (with repeats) %.0f us, sum of rooflines %.0f us (%.3f)" % (tot, troof, troof / tot))
+                    cnt.max() / max(cnt.mean(), 1e-9), r["cpu_us"] / 1e3))
+            pr("total (with repeats) %.0f us, sum of rooflines %.0f us (%.3f), CPU oracle %.0f ms (extrapolated)" % (tot, troof, troof / tot, tcpu / 1e3))
     elif kind == "mbv1":
+        cpu_header(pr)
         for N, sp, label in ((32, 0.9, "batch 32, block sparsity 0.9 in every layer"),
                              (32, None, "batch 32, per-layer block sparsity drawn from U(0.7, 0.9)"),
                              (1, None, "batch 1, per-layer block sparsity drawn from U(0.7, 0.9)")):
             pr("\n%s" % label)
-            pr("| layer | Cin->Cout | HxW | sparsity | sparse us | dense us | speed-up | PyTorch dense us | vs PyTorch | eff GB/s | bound | roofline us | roofline frac | max diff vs dense |")
-            pr("|---|---|---|---|---|---|---|---|---|---|---|---|---|---|")
-            tot = troof = tdense = tlib = 0.0
+            pr("| layer | Cin->Cout | HxW | sparsity | sparse us | dense us | speed-up | PyTorch dense us | vs PyTorch | eff GB/s | bound | roofline us | roofline frac | max diff vs dense | CPU oracle ms (whole batch) |")
+            pr("|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|")
+            tot = troof = tdense = tlib = tcpu = 0.0
             for i, L in enumerate(workloads.mobilenet_v1_pointwise(N, sp)):
-                r = time_layer(alcs, torch, np, workloads, L, workloads.seed_for(2, i), dense=True)
+                r = time_layer(alcs, torch, np, workloads, L, workloads.seed_for(2, i), dense=True, cpu_images=-1)
+                tcpu += r["cpu_us"]
                 tot += r["us"]
                 troof += r["roof_us"]
                 tdense += r["dense_us"]
                 tlib += r["lib_us"]
-                pr("| %s | %d->%d | %d | %.3f | %.1f | %.1f | %.2f | %.1f | %.2f | %.0f | %s | %.2f | %.3f | %.1e |" %
+                pr("| %s | %d->%d | %d | %.3f | %.1f | %.1f | %.2f | %.1f | %.2f | %.0f | %s | %.2f | %.3f | %.1e | %.1f |" %
                    (L.name, L.Cin, L.Cout, L.H, L.sparsity, r["us"], r["dense_us"], r["dense_us"] / r["us"],
                     r["lib_us"], r["lib_us"] / r["us"], r["bytes"] / r["us"] / 1e3, r["bound"], r["roof_us"],
-                    r["roof_us"] / r["us"], r["err"]))
-            pr("13 layers: sparse %.0f us, dense %.0f us (%.2fx), PyTorch dense %.0f us (%.2fx), sum of rooflines %.0f us (%.3f)" %
-               (tot, tdense, tdense / tot, tlib, tlib / tot, troof, troof / tot))
+                    r["roof_us"] / r["us"], r["err"], r["cpu_us"] / 1e3))
+            pr("13 layers: sparse %.0f us, dense %.0f us (%.2fx), PyTorch dense %.0f us (%.2fx), sum of rooflines %.0f us (%.3f), CPU oracle %.0f ms" %
+               (tot, tdense, tdense / tot, tlib, tlib / tot, troof, troof / tot, tcpu / 1e3))
     elif kind == "fused":
         # the element-wise layers behind a convolution folded into its epilogue, against the plain
         # convolution followed by PyTorch's in-place element-wise kernels on the same buffers
@@ -580,7 +694,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-batch", type=int, default=32)
     ap.add_argument("--layers-json", default=None, help="also write the per-layer table to this file")
-    ap.add_argument("--report", choices=["sweep", "resnet", "mbv2", "paths", "mbv1", "fused", "latency", "block", "project", "bf16"], default=None,
+    ap.add_argument("--report", choices=["sweep", "resnet", "mbv2", "paths", "mbv1", "fused", "latency", "block", "project", "bf16", "config1", "floor"], default=None,
                     help="instead of the benchmark line, print a per-layer table for another configuration: "
                          "the sparsity sweep with the same-GPU dense conv (config 4), the ResNet-50-shaped "
                          "bottleneck convs (config 3), the MobileNetV2-shaped pointwise convs for V in "
@@ -799,7 +913,7 @@ def main():
             got = Ys[i][:nb].cpu().numpy()
             max_err = max(max_err, float(np.max(np.abs(got - ref)) / max(float(np.max(np.abs(ref))), 1e-30)))
         out["cpu_baseline"] = {"value": round(fl / t_cpu / 1e9, 2), "unit": "GFLOP/s (dense-equivalent)",
-                               "cores": threads, "kind": "oracle",
+                               "cores": threads, "kind": "oracle", "cpu": cpu_model(),
                                "sample": "same 13 layers and weights, first %d of %d images, %.1f s of CPU time"
                                          % (nb, args.batch, t_cpu)}
         out["max_rel_err_vs_oracle"] = float("%.3g" % max_err)

@@ -117,6 +117,14 @@ int alcs_packed_export(const alcs_packed_t *p, int32_t *row_ptr_host, int32_t *c
  * Returns ALCS_OK or ALCS_E_INVALID_ARG on the first inconsistency. */
 int alcs_packed_selfcheck(const alcs_packed_t *p);
 
+/* A 64-bit hash (FNV-1a) of the layout the kernels read - its tile parameters, group order, work
+ * records, weight planes and selector tables - into *hash_out (host).  Two handles whose layouts
+ * are the same bytes have the same hash: the check that a handle built on the device
+ * (alcs_pack_from_csr_device) equals the one alcs_pack_weights builds on the host.  For a
+ * handle built on the device this, like alcs_packed_export and alcs_packed_selfcheck, fetches the
+ * arrays to the host first (blocking copies; ALCS_E_HIP if they fail). */
+int alcs_packed_layout_hash(const alcs_packed_t *p, unsigned long long *hash_out);
+
 /* Releases host and device memory of a handle (NULL is ignored).  The caller must
  * make sure no launch that reads it is still in flight. */
 void alcs_packed_free(alcs_packed_t *p);
@@ -400,12 +408,31 @@ int alcs_topn_mask_static(const float *scores_dev, long long n_blocks, long long
  *   (copied; columns must ascend inside every group and lie below K, counts must add up:
  *   ALCS_E_INVALID_ARG otherwise).  Together: device flags -> device arrays -> one copy of the
  *   kept values to the host -> handle, without the dense weights leaving the device.
+ *
+ * alcs_pack_from_csr_device: the same handle from canonical arrays in device memory (caller's;
+ *   copied into the handle's own allocation), with the layout the kernels read built by kernels
+ *   on `stream`: the host reads back a few scalars (block count, longest group, padded length)
+ *   and neither the arrays nor the layout cross the bus.  The arrays are checked on the device
+ *   like alcs_pack_from_csr checks them on the host (ALCS_E_INVALID_ARG).  `options` as for
+ *   alcs_pack_weights_opt (NULL = automatic).  The call returns with the handle complete (it
+ *   synchronises `stream`); alcs_packed_export and alcs_packed_selfcheck fetch the arrays to the
+ *   host on first use.  More than 16384 groups: ALCS_E_UNSUPPORTED (go through the host).
+ *
+ * alcs_pack_weights_device: W_dev and mask_dev as for alcs_pack_csr_device -> handle, i.e. the
+ *   two calls above in one with the intermediate arrays in a temporary of the library (sized for
+ *   every block kept, freed before the call returns).  This is the re-packing step of a pruning
+ *   loop (Section 3.4, Algorithm 1) whose weights and flags live on the device.
  */
 int alcs_pack_csr_device(const float *W_dev, const uint8_t *mask_dev, int Cout, int Cin, int kernel,
                          int V, int32_t *row_ptr_dev, int32_t *col_idx_dev, float *vals_dev,
                          long long capacity_blocks, long long *nnzb_out, void *stream);
 int alcs_pack_from_csr(const int32_t *row_ptr_host, const int32_t *col_idx_host, const float *vals_host,
                        int Cout, int Cin, int kernel, int V, alcs_packed_t **out);
+int alcs_pack_from_csr_device(const int32_t *row_ptr_dev, const int32_t *col_idx_dev, const float *vals_dev,
+                              int Cout, int Cin, int kernel, int V, const alcs_options *options, void *stream,
+                              alcs_packed_t **out);
+int alcs_pack_weights_device(const float *W_dev, const uint8_t *mask_dev, int Cout, int Cin, int kernel, int V,
+                             const alcs_options *options, void *stream, alcs_packed_t **out);
 
 /* What the last alcs_sparse_conv call of this thread launched: fills up to `cap`
  * ints {mode (1 = all input channels resident in LDS, 2 = chunked, 3 = 3x3,

@@ -18,6 +18,8 @@ from ._binding import (  # noqa: F401
     alcs_network_latency,
     alcs_pack_csr_device,
     alcs_pack_from_csr,
+    alcs_pack_from_csr_device,
+    alcs_pack_weights_device,
     alcs_pack_on_device,
     alcs_pack_weights,
     alcs_project_latency,

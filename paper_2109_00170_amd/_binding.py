@@ -18,6 +18,7 @@ EXPORTS = [
     "alcs_pack_weights_opt", "alcs_packed_set_options", "alcs_packed_get_options",
     "alcs_depthwise_conv", "alcs_dw_sparse_conv_fused", "alcs_sparse_conv_bf16", "alcs_block_scores", "alcs_select_workspace_bytes",
     "alcs_topn_mask", "alcs_topn_mask_static", "alcs_project_latency", "alcs_pack_csr_device", "alcs_pack_from_csr",
+    "alcs_pack_from_csr_device", "alcs_pack_weights_device", "alcs_packed_layout_hash",
     "alcs_last_launch", "alcs_latency_estimate", "alcs_network_latency",
 ]
 
@@ -79,6 +80,7 @@ def load_library():
     lib.alcs_packed_on_device.argtypes = [vp]
     lib.alcs_packed_export.argtypes = [vp, vp, vp, vp]
     lib.alcs_packed_selfcheck.argtypes = [vp]
+    lib.alcs_packed_layout_hash.argtypes = [vp, vp]
     lib.alcs_packed_free.argtypes = [vp]
     lib.alcs_packed_free.restype = None
     lib.alcs_sparse_conv.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp]
@@ -145,6 +147,13 @@ class Packed:
 
     def selfcheck(self) -> int:
         return int(load_library().alcs_packed_selfcheck(self.handle))
+
+    def layout_hash(self) -> int:
+        h = ctypes.c_ulonglong()
+        rc = load_library().alcs_packed_layout_hash(self._h, ctypes.byref(h))
+        if rc != 0:
+            raise AlcsError(rc, "alcs_packed_layout_hash")
+        return int(h.value)
 
     def set_options(self, options) -> None:
         """Replace the handle's launch options (dict or Options; None = all automatic)."""
@@ -558,8 +567,41 @@ def alcs_pack_from_csr(row_ptr, col_idx, vals, Cout: int, Cin: int, kernel: int,
     return Packed(out, Cout, Cin, kernel, int(V))
 
 
-def alcs_pack_on_device(W_dev, mask_dev, V: int) -> Packed:
-    """Device weights and flags -> device CSR -> one copy of the kept values to the host -> handle."""
+def alcs_pack_from_csr_device(row_ptr, col_idx, vals, Cout: int, Cin: int, kernel: int, V: int, options=None,
+                              stream=None) -> Packed:
+    """A handle from canonical arrays that are device tensors (int32, int32, float32); the layout
+    the kernels read is built on the device."""
+    G = (Cout + V - 1) // V
+    if row_ptr.numel() != G + 1 or vals.numel() != col_idx.numel() * V:
+        raise ValueError("array sizes do not fit the layer")
+    out = ctypes.c_void_p()
+    opt = Options.make(options)
+    rc = load_library().alcs_pack_from_csr_device(
+        _dev_ptr(row_ptr, "row_ptr", "torch.int32"), _dev_ptr(col_idx, "col_idx", "torch.int32") if col_idx.numel() else None,
+        _dev_ptr(vals, "vals") if vals.numel() else None, int(Cout), int(Cin), int(kernel), int(V),
+        None if opt is None else ctypes.byref(opt), _stream_ptr(stream), ctypes.byref(out))
+    if rc != 0:
+        raise AlcsError(rc, "alcs_pack_from_csr_device")
+    return Packed(out, Cout, Cin, kernel, int(V))
+
+
+def alcs_pack_weights_device(W_dev, mask_dev, V: int, options=None, stream=None) -> Packed:
+    """Device weights [Cout,Cin,k,k] and device flags (uint8 [G,Cin,k,k] or None) -> handle; arrays
+    and layout are built by kernels, the host reads back a few scalars."""
     Cout, Cin, k, _ = W_dev.shape
-    row_ptr, col_idx, vals = alcs_pack_csr_device(W_dev, mask_dev, V)
-    return alcs_pack_from_csr(row_ptr.cpu().numpy(), col_idx.cpu().numpy(), vals.cpu().numpy(), Cout, Cin, k, V)
+    G = (Cout + V - 1) // V
+    if mask_dev is not None and mask_dev.numel() != G * Cin * k * k:
+        raise ValueError("mask must have %d entries" % (G * Cin * k * k))
+    out = ctypes.c_void_p()
+    opt = Options.make(options)
+    rc = load_library().alcs_pack_weights_device(
+        _dev_ptr(W_dev, "W"), _dev_ptr(mask_dev, "mask", "torch.uint8"), int(Cout), int(Cin), int(k), int(V),
+        None if opt is None else ctypes.byref(opt), _stream_ptr(stream), ctypes.byref(out))
+    if rc != 0:
+        raise AlcsError(rc, "alcs_pack_weights_device")
+    return Packed(out, Cout, Cin, k, int(V))
+
+
+def alcs_pack_on_device(W_dev, mask_dev, V: int, options=None) -> Packed:
+    """Device weights and flags -> handle without the host seeing weights, flags or layout."""
+    return alcs_pack_weights_device(W_dev, mask_dev, V, options=options)

@@ -3,6 +3,7 @@
 #pragma once
 
 #include <cstdint>
+#include <mutex>
 #include <vector>
 
 #include "alcs.h"
@@ -89,6 +90,42 @@ constexpr int kRowBytes1 = 256;
 
 constexpr int kMaxSlots = 4;
 
+// Host and device code alike (the layout is built by alcs_pack.cpp on the host and by
+// alcs_layoutdev.hip on the device, to the same bytes).
+#if defined(__HIPCC__) || defined(__HIP__)
+#define ALCS_HD __host__ __device__
+#else
+#define ALCS_HD
+#endif
+
+// LDS row selector (a byte offset) of the block at canonical column `col`, see Layout::off.
+ALCS_HD inline int32_t layout_off_of(int col, int k, int table, int GS) {
+    if (k == 1) return col * (kRowBytes1 / GS);
+    const int c = col / 9, tap = col % 9, r = tap / 3, s = tap % 3;
+    const int stride = table_stride3(table), ti = table_ti3(table);
+    return (c * halo_area3(stride, ti, table_tall3(table)) + r * pitch3(stride, ti) + halo_col3(stride, ti, s)) * 4;
+}
+// Selector of a padded column: an all-zero row behind the chunk's rows.  Layouts with several
+// groups per wavefront have two of them (rows KC and KC + 1, one of each channel parity);
+// `which` picks one.
+ALCS_HD inline int32_t layout_pad_off(int c0, int KC, int k, int table, int GS, int which) {
+    if (k == 1) return (c0 + KC + which) * (kRowBytes1 / GS);
+    return (c0 + KC) * halo_area3(table_stride3(table), table_ti3(table), table_tall3(table)) * 4;
+}
+// Index of (padded column `col` counted from the start of the arrays, slot s) in a weight plane
+// (row i) and in a selector table; VV = min(V, 4).
+ALCS_HD inline size_t layout_w_index(int GS, int VV, int64_t col, int s, int i) {
+    const int cpa = 16 / GS;
+    const int64_t R = col / 16 * 16;
+    const int c = (int)(col % 16);
+    if (VV < 4) return (size_t)(col * VV + i);  // V < 4: GS == 1, VV floats per column
+    return (size_t)(R * 4 * GS + (c / cpa) * 64 + s * (64 / GS) + (c % cpa) * 4 + i);
+}
+ALCS_HD inline size_t layout_off_index(int GS, int64_t col, int s) {
+    const int64_t R = col / 16 * 16;
+    return (size_t)(R * GS + s * 16 + col % 16);
+}
+
 // What a wavefront needs to process one bundle of GS groups inside one channel chunk.
 // Bundles are formed from the groups sorted by descending kept-column count (slot s of
 // bundle b is the (b*GS+s)-th longest group) and handed out in that order.
@@ -140,6 +177,10 @@ struct DeviceCopy {
     const Work *work = nullptr;
     const float *w = nullptr;
     const int32_t *off[kMaxOff] = {};
+    // handles built on the device (alcs_pack_from_csr_device) also keep, in the same blob, the
+    // group order and the canonical arrays, which the host fetches only when it is asked for them
+    const int32_t *order = nullptr, *row_ptr = nullptr, *col_idx = nullptr;
+    const float *vals = nullptr;
 };
 
 }  // namespace alcs
@@ -154,6 +195,10 @@ struct alcs_packed {
     alcs::Layout lay;
     alcs::DeviceCopy dev;
     alcs_options opt = {};  // the options given at pack time / by alcs_packed_set_options; zero = automatic
+    // Built on the device: the vectors above (canonical arrays, layout arrays) are empty until
+    // alcs_packed_export / alcs_packed_selfcheck ask for them (host_arrays, under host_mu).
+    bool host_arrays = true;
+    std::mutex host_mu;
 };
 
 namespace alcs {
@@ -163,7 +208,12 @@ void set_hip_error(int e);
 // from its properties; looked up once per device and process (constants of the hardware).
 void device_shape(int device, int *cus, int *xcds);
 int current_device_shape(int *cus, int *xcds);  // of the current device; ALCS_OK or ALCS_E_HIP
+int check_options(const alcs_options *o);  // ALCS_OK or ALCS_E_INVALID_ARG
 int build_layout(alcs_packed *p, int KC, int GS);
+// tile policy: channels per chunk and groups per wavefront of a handle, from its shape and options
+void choose_tiles(const alcs_packed *p, int *KC, int *GS);
+// canonical arrays and layout arrays of a handle built on the device, fetched to the host (once)
+int fetch_host_arrays(alcs_packed *p);
 int upload(alcs_packed *p);
 void release_device(alcs_packed *p);
 

@@ -53,21 +53,12 @@ static inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * 
 // Channel of a canonical column index.
 static inline int col_channel(int col, int kk) { return col / kk; }
 
-// LDS row selector of a real block (see Layout::off): a byte offset.
-static inline int32_t off_of(int col, int k, int table, int GS) {
-    if (k == 1) return col * (kRowBytes1 / GS);
-    const int c = col / 9, tap = col % 9, r = tap / 3, s = tap % 3;
-    const int stride = table_stride3(table), ti = table_ti3(table);
-    return (c * halo_area3(stride, ti, table_tall3(table)) + r * pitch3(stride, ti) + halo_col3(stride, ti, s)) * 4;
-}
-
-// Selector of a padded column: an all-zero row behind the chunk's rows.  Layouts with several
-// groups per wavefront have two of them (rows KC and KC + 1, one of each channel parity, see
-// arrange_slot); `which` picks one.
+static inline int32_t off_of(int col, int k, int table, int GS) { return layout_off_of(col, k, table, GS); }
 static inline int32_t pad_off(int c0, int KC, int k, int table, int GS, int which = 0) {
-    if (k == 1) return (c0 + KC + which) * (kRowBytes1 / GS);
-    return (c0 + KC) * halo_area3(table_stride3(table), table_ti3(table), table_tall3(table)) * 4;
+    return layout_pad_off(c0, KC, k, table, GS, which);
 }
+static inline size_t w_index(const Layout &L, int64_t col, int s, int i) { return layout_w_index(L.GS, L.VV, col, s, i); }
+static inline size_t off_index(const Layout &L, int64_t col, int s) { return layout_off_index(L.GS, col, s); }
 
 // Order of one slot's columns inside a bundle segment of L columns (several groups per wavefront).
 // The 16- or 32-lane slots of a wavefront read different LDS rows in the same instruction; with
@@ -87,20 +78,6 @@ static void arrange_slot(const int32_t *cols, int n, int kk, int L, bool evens_f
         const bool to_back = (col_channel(cols[i], kk) & 1) == (evens_first ? 1 : 0);
         place[(size_t)(to_back ? back++ : front++)] = i;
     }
-}
-
-// Index of (bundle column `col` counted from the start of the arrays, slot s) in a
-// weight plane (row i) and in a selector table.
-static inline size_t w_index(const Layout &L, int64_t col, int s, int i) {
-    const int GS = L.GS, cpa = 16 / GS;
-    const int64_t R = col / 16 * 16;
-    const int c = (int)(col % 16);
-    if (L.VV < 4) return (size_t)(col * L.VV + i);  // V < 4: GS == 1, VV floats per column
-    return (size_t)(R * 4 * GS + (c / cpa) * 64 + s * (64 / GS) + (c % cpa) * 4 + i);
-}
-static inline size_t off_index(const Layout &L, int64_t col, int s) {
-    const int64_t R = col / 16 * 16;
-    return (size_t)(R * L.GS + s * 16 + col % 16);
 }
 
 int build_layout(alcs_packed *p, int KC, int GS) {
@@ -318,15 +295,56 @@ static void default_tiles(int Cin, int k, int V, bool even_groups, int *KC, int 
     *KC = 256;
 }
 
-}  // namespace alcs
+void choose_tiles(const alcs_packed *p, int *KC, int *GS) {
+    const bool even_groups = (int64_t)p->max_count * p->G <= 2 * p->nnzb;
+    default_tiles(p->Cin, p->k, p->V, even_groups, KC, GS);
+    const int kc = p->opt.chunk_channels, gs = p->opt.group_slots;
+    if (kc > 0) { *KC = std::min(kc, p->Cin); *GS = 1; }
+    if ((gs == 1 || gs == 2 || gs == 4) && p->k == 1 && p->V >= 4 && *KC == p->Cin &&
+        (long long)(p->Cin + 2) * (kRowBytes1 / gs) <= 160 * 1024)
+        *GS = gs;
+}
 
-using namespace alcs;
-
-extern "C" void alcs_packed_free(alcs_packed_t *p);
+// A handle built on the device keeps its arrays there; export and self-check work on host
+// copies, fetched on first use (blocking copies on the null stream).
+int fetch_host_arrays(alcs_packed *p) {
+    std::lock_guard<std::mutex> lock(p->host_mu);
+    if (p->host_arrays) return ALCS_OK;
+    if (!p->dev.blob || !p->dev.row_ptr) return ALCS_E_NO_DEVICE;
+    int cur = -1;
+    hipError_t e = hipGetDevice(&cur);
+    if (e != hipSuccess) { set_hip_error((int)e); return ALCS_E_HIP; }
+    if (cur != p->dev.device && (e = hipSetDevice(p->dev.device)) != hipSuccess) { set_hip_error((int)e); return ALCS_E_HIP; }
+    Layout &L = p->lay;
+    try {
+        p->row_ptr.resize((size_t)p->G + 1);
+        p->col_idx.resize((size_t)p->nnzb);
+        p->vals.resize((size_t)p->nnzb * p->V);
+        L.order.resize((size_t)p->G);
+        L.work.resize((size_t)L.nbundles * L.nchunks);
+        L.w.resize((size_t)L.planes * L.wplane);
+        for (int t = 0; t < L.noff; ++t) L.off[t].resize((size_t)L.ncol * L.GS);
+    } catch (const std::bad_alloc &) {
+        if (cur != p->dev.device) (void)hipSetDevice(cur);
+        return ALCS_E_ALLOC;
+    }
+    auto get = [&](void *dst, const void *src, size_t n) { return n ? hipMemcpy(dst, src, n, hipMemcpyDeviceToHost) : hipSuccess; };
+    e = get(p->row_ptr.data(), p->dev.row_ptr, p->row_ptr.size() * 4);
+    if (e == hipSuccess) e = get(p->col_idx.data(), p->dev.col_idx, p->col_idx.size() * 4);
+    if (e == hipSuccess) e = get(p->vals.data(), p->dev.vals, p->vals.size() * 4);
+    if (e == hipSuccess) e = get(L.order.data(), p->dev.order, L.order.size() * 4);
+    if (e == hipSuccess) e = get(L.work.data(), p->dev.work, L.work.size() * sizeof(Work));
+    if (e == hipSuccess) e = get(L.w.data(), p->dev.w, L.w.size() * 4);
+    for (int t = 0; t < L.noff && e == hipSuccess; ++t) e = get(L.off[t].data(), p->dev.off[t], L.off[t].size() * 4);
+    if (cur != p->dev.device) (void)hipSetDevice(cur);
+    if (e != hipSuccess) { set_hip_error((int)e); return ALCS_E_HIP; }
+    p->host_arrays = true;
+    return ALCS_OK;
+}
 
 // Options are plain non-negative ints; the phase-skipping field is honoured by the measurement
 // build only and refused by the product build.
-static int check_options(const alcs_options *o) {
+int check_options(const alcs_options *o) {
     const int *f = reinterpret_cast<const int *>(o);
     for (size_t i = 0; i < sizeof(alcs_options) / sizeof(int); ++i)
         if (f[i] < 0) return ALCS_E_INVALID_ARG;
@@ -338,19 +356,19 @@ static int check_options(const alcs_options *o) {
     return ALCS_OK;
 }
 
+}  // namespace alcs
+
+using namespace alcs;
+
+extern "C" void alcs_packed_free(alcs_packed_t *p);
+
 // The tuned device layout and its upload, once the canonical arrays of the handle are in place.
 static int finish_pack(alcs_packed *p, int rc, const alcs_options *opt, alcs_packed_t **out) {
     if (rc == ALCS_OK && opt) rc = check_options(opt);
     if (rc == ALCS_OK) {
         if (opt) p->opt = *opt;
         int KC = 0, GS = 1;
-        const bool even_groups = (int64_t)p->max_count * p->G <= 2 * p->nnzb;
-        default_tiles(p->Cin, p->k, p->V, even_groups, &KC, &GS);
-        const int kc = p->opt.chunk_channels, gs = p->opt.group_slots;
-        if (kc > 0) { KC = std::min(kc, p->Cin); GS = 1; }
-        if ((gs == 1 || gs == 2 || gs == 4) && p->k == 1 && p->V >= 4 && KC == p->Cin &&
-            (long long)(p->Cin + 2) * (kRowBytes1 / gs) <= 160 * 1024)
-            GS = gs;
+        choose_tiles(p, &KC, &GS);
         rc = build_layout(p, KC, GS);
     }
     if (rc == ALCS_OK) {
@@ -500,6 +518,10 @@ int alcs_packed_export(const alcs_packed_t *p, int32_t *row_ptr_host, int32_t *c
                        float *vals_host) {
     if (!p || !row_ptr_host) return ALCS_E_INVALID_ARG;
     if (p->nnzb > 0 && (!col_idx_host || !vals_host)) return ALCS_E_INVALID_ARG;
+    if (!p->host_arrays) {
+        const int rc = fetch_host_arrays(const_cast<alcs_packed_t *>(p));
+        if (rc != ALCS_OK) return rc;
+    }
     std::memcpy(row_ptr_host, p->row_ptr.data(), p->row_ptr.size() * sizeof(int32_t));
     if (p->nnzb > 0) {
         std::memcpy(col_idx_host, p->col_idx.data(), p->col_idx.size() * sizeof(int32_t));
@@ -510,6 +532,11 @@ int alcs_packed_export(const alcs_packed_t *p, int32_t *row_ptr_host, int32_t *c
 
 int alcs_packed_selfcheck(const alcs_packed_t *p) {
     if (!p) return ALCS_E_INVALID_ARG;
+    if (!p->host_arrays) {
+        // built on the device: what is checked is the layout the device built, fetched as it is
+        const int rc = fetch_host_arrays(const_cast<alcs_packed_t *>(p));
+        if (rc != ALCS_OK) return rc;
+    }
     const Layout &L = p->lay;
     const int k = p->k, V = p->V, GS = L.GS;
     if (L.KC <= 0 || L.nchunks != (p->Cin + L.KC - 1) / L.KC) return ALCS_E_INVALID_ARG;
@@ -607,6 +634,29 @@ int alcs_packed_selfcheck(const alcs_packed_t *p) {
         }
     for (int g = 0; g < p->G; ++g)
         if (next[g] != p->row_ptr[g + 1]) return ALCS_E_INVALID_ARG;  // every canonical block was found
+    return ALCS_OK;
+}
+
+int alcs_packed_layout_hash(const alcs_packed_t *p, unsigned long long *hash_out) {
+    if (!p || !hash_out) return ALCS_E_INVALID_ARG;
+    if (!p->host_arrays) {
+        const int rc = fetch_host_arrays(const_cast<alcs_packed_t *>(p));
+        if (rc != ALCS_OK) return rc;
+    }
+    // FNV-1a over the layout's scalars and arrays, in a fixed order
+    unsigned long long h = 1469598103934665603ull;
+    auto eat = [&](const void *data, size_t n) {
+        const unsigned char *b = static_cast<const unsigned char *>(data);
+        for (size_t i = 0; i < n; ++i) { h ^= b[i]; h *= 1099511628211ull; }
+    };
+    const Layout &L = p->lay;
+    const int64_t scalars[] = {L.KC, L.nchunks, L.GS, L.nbundles, L.planes, L.VV, L.max_cnt, L.ncol, L.wplane, L.noff};
+    eat(scalars, sizeof(scalars));
+    eat(L.order.data(), L.order.size() * sizeof(int32_t));
+    eat(L.work.data(), L.work.size() * sizeof(Work));
+    eat(L.w.data(), L.w.size() * sizeof(float));
+    for (int t = 0; t < L.noff; ++t) eat(L.off[t].data(), L.off[t].size() * sizeof(int32_t));
+    *hash_out = h;
     return ALCS_OK;
 }
 
