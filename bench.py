@@ -596,9 +596,38 @@ def report(kind, alcs, workloads, torch, np):
             t_host = (time.perf_counter() - t0) * 1e3
             for h in hs:
                 h.free()
-            notes.append("%s: storage format on the device %.2f ms (%d layers, 2 calls each), arrays to the host + "
-                         "layout + upload %.2f ms; host path: weights and flags to the host %.2f ms, alcs_pack_weights "
-                         "%.2f ms." % (title, t_csr, len(shapes), t_from, t_down, t_host))
+            # everything on the device: weights + flags -> arrays -> layout -> handle (alcs_pack_weights_device)
+            m8 = [m.contiguous() for m in masks]
+            hs = [alcs.alcs_pack_weights_device(W, m, V) for W, m in zip(Ws, m8)]      # warm-up
+            for h in hs:
+                h.free()
+            torch.cuda.synchronize()
+            t_dev = []
+            for _ in range(5):
+                t0 = time.perf_counter()
+                hs = [alcs.alcs_pack_weights_device(W, m, V) for W, m in zip(Ws, m8)]
+                torch.cuda.synchronize()
+                t_dev.append((time.perf_counter() - t0) * 1e3)
+                for h in hs:
+                    h.free()
+            ws = torch.empty((alcs.alcs_pack_workspace_bytes(Ws, m8, V),), dtype=torch.uint8, device="cuda")
+            t_net = []
+            for _ in range(6):
+                t0 = time.perf_counter()
+                hs = alcs.alcs_pack_network_device(Ws, m8, V, workspace=ws)
+                torch.cuda.synchronize()
+                t_net.append((time.perf_counter() - t0) * 1e3)
+                for h in hs:
+                    h.free()
+            t_net = t_net[1:]
+            notes.append("%s: weights + flags on the device -> handles, all layers in one call "
+                         "(alcs_pack_network_device, caller's workspace of %.1f MB) **%.2f ms** (median of 5, min %.2f); "
+                         "layer by layer with alcs_pack_weights_device %.2f ms "
+                         "(median of 5, min %.2f; %d layers); in steps through the host: storage format on the device "
+                         "%.2f ms (2 calls a layer), arrays to the host + layout + upload %.2f ms; all on the host: "
+                         "weights and flags to the host %.2f ms, alcs_pack_weights %.2f ms." %
+                         (title, ws.numel() / 1e6, float(np.median(t_net)), min(t_net), float(np.median(t_dev)), min(t_dev),
+                          len(shapes), t_csr, t_from, t_down, t_host))
         pr("")
         for line in notes:
             pr(line)

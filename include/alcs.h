@@ -422,7 +422,26 @@ int alcs_topn_mask_static(const float *scores_dev, long long n_blocks, long long
  *   two calls above in one with the intermediate arrays in a temporary of the library (sized for
  *   every block kept, freed before the call returns).  This is the re-packing step of a pruning
  *   loop (Section 3.4, Algorithm 1) whose weights and flags live on the device.
+ *
+ * alcs_pack_network_device: the same for n_layers layers in one call - every step is enqueued for
+ *   all layers before the host waits for its scalars, so a network costs three waits on `stream`
+ *   instead of three a layer.  layers[i] names layer i (device pointers as for
+ *   alcs_pack_csr_device; options may be NULL); out [n_layers] receives the handles - all of them,
+ *   or none (every entry NULL) when the call fails.  workspace_dev: device memory of at least
+ *   alcs_pack_workspace_bytes(layers, n_layers) bytes, 256-byte aligned, the caller's, free for
+ *   other use when the call returns; NULL (workspace_bytes ignored) lets the call allocate and
+ *   free it itself.  alcs_pack_workspace_bytes depends on the layers' shapes and options only
+ *   (it sizes for every block kept) and returns a negative status for shapes the packer refuses.
  */
+typedef struct alcs_layer_desc {
+    const float *W_dev;       /* [Cout, Cin, kernel, kernel] */
+    const uint8_t *mask_dev;  /* [G, Cin, kernel, kernel] keep flags, NULL keeps every block */
+    int Cout, Cin, kernel, V;
+    const alcs_options *options; /* host pointer, NULL = automatic */
+} alcs_layer_desc;
+long long alcs_pack_workspace_bytes(const alcs_layer_desc *layers, int n_layers);
+int alcs_pack_network_device(const alcs_layer_desc *layers, int n_layers, void *workspace_dev,
+                             long long workspace_bytes, void *stream, alcs_packed_t **out);
 int alcs_pack_csr_device(const float *W_dev, const uint8_t *mask_dev, int Cout, int Cin, int kernel,
                          int V, int32_t *row_ptr_dev, int32_t *col_idx_dev, float *vals_dev,
                          long long capacity_blocks, long long *nnzb_out, void *stream);

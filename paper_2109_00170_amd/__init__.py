@@ -19,6 +19,8 @@ from ._binding import (  # noqa: F401
     alcs_pack_csr_device,
     alcs_pack_from_csr,
     alcs_pack_from_csr_device,
+    alcs_pack_network_device,
+    alcs_pack_workspace_bytes,
     alcs_pack_weights_device,
     alcs_pack_on_device,
     alcs_pack_weights,

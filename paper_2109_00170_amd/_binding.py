@@ -19,6 +19,7 @@ EXPORTS = [
     "alcs_depthwise_conv", "alcs_dw_sparse_conv_fused", "alcs_sparse_conv_bf16", "alcs_block_scores", "alcs_select_workspace_bytes",
     "alcs_topn_mask", "alcs_topn_mask_static", "alcs_project_latency", "alcs_pack_csr_device", "alcs_pack_from_csr",
     "alcs_pack_from_csr_device", "alcs_pack_weights_device", "alcs_packed_layout_hash",
+    "alcs_pack_workspace_bytes", "alcs_pack_network_device",
     "alcs_last_launch", "alcs_latency_estimate", "alcs_network_latency",
 ]
 
@@ -600,6 +601,53 @@ def alcs_pack_weights_device(W_dev, mask_dev, V: int, options=None, stream=None)
     if rc != 0:
         raise AlcsError(rc, "alcs_pack_weights_device")
     return Packed(out, Cout, Cin, k, int(V))
+
+
+class LayerDesc(ctypes.Structure):
+    """alcs_layer_desc of include/alcs.h."""
+    _fields_ = [("W_dev", ctypes.c_void_p), ("mask_dev", ctypes.c_void_p), ("Cout", ctypes.c_int), ("Cin", ctypes.c_int),
+                ("kernel", ctypes.c_int), ("V", ctypes.c_int), ("options", ctypes.c_void_p)]
+
+
+def _layer_descs(Ws, masks, Vs, options):
+    n = len(Ws)
+    Vs = [int(Vs)] * n if np.isscalar(Vs) else [int(v) for v in Vs]
+    opts = [Options.make(o) for o in (options if isinstance(options, (list, tuple)) else [options] * n)]
+    descs = (LayerDesc * n)()
+    for i, (W, m) in enumerate(zip(Ws, masks)):
+        Cout, Cin, k, _ = W.shape
+        G = (Cout + Vs[i] - 1) // Vs[i]
+        if m is not None and m.numel() != G * Cin * k * k:
+            raise ValueError("mask %d must have %d entries" % (i, G * Cin * k * k))
+        wp, mp = _dev_ptr(W, "W"), _dev_ptr(m, "mask", "torch.uint8")
+        descs[i] = LayerDesc(wp.value, None if mp is None else mp.value, Cout, Cin, k, Vs[i],
+                             None if opts[i] is None else ctypes.addressof(opts[i]))
+    return descs, opts, Vs
+
+
+def alcs_pack_workspace_bytes(Ws, masks, Vs, options=None) -> int:
+    descs, _keep, _ = _layer_descs(Ws, masks, Vs, options)
+    lib = load_library()
+    lib.alcs_pack_workspace_bytes.restype = ctypes.c_longlong
+    n = int(lib.alcs_pack_workspace_bytes(descs, len(Ws)))
+    if n < 0:
+        raise AlcsError(n, "alcs_pack_workspace_bytes")
+    return n
+
+
+def alcs_pack_network_device(Ws, masks, Vs, options=None, workspace=None, stream=None):
+    """Handles for a list of layers (device weights [Cout,Cin,k,k], device flags or None each) in one
+    call; workspace: a uint8 device tensor of alcs_pack_workspace_bytes bytes, or None."""
+    descs, _keep, Vs = _layer_descs(Ws, masks, Vs, options)
+    n = len(Ws)
+    out = (ctypes.c_void_p * n)()
+    ws_ptr, ws_bytes = None, 0
+    if workspace is not None:
+        ws_ptr, ws_bytes = _dev_ptr(workspace, "workspace", "torch.uint8"), workspace.numel()
+    rc = load_library().alcs_pack_network_device(descs, n, ws_ptr, ctypes.c_longlong(ws_bytes), _stream_ptr(stream), out)
+    if rc != 0:
+        raise AlcsError(rc, "alcs_pack_network_device")
+    return [Packed(ctypes.c_void_p(out[i]), W.shape[0], W.shape[1], W.shape[2], Vs[i]) for i, W in enumerate(Ws)]
 
 
 def alcs_pack_on_device(W_dev, mask_dev, V: int, options=None) -> Packed:

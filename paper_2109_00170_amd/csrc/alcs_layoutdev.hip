@@ -17,7 +17,9 @@
 //   6. every kept block to its place: weights, selectors, parity note          k_ld_scatter
 //   7. padded places: selector of the zero row that avoids the partner's banks k_ld_pads
 // The host reads back two sets of scalars (longest group / block count, then padded columns /
-// longest segment) to size the allocation; values are moved, never computed.
+// longest segment) to choose the tiles and to size the allocation; values are moved, never
+// computed.  Several layers are built in one call (alcs_pack_network_device): every step is
+// enqueued for all of them before the host waits, so a network costs three waits, not three a layer.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -29,6 +31,12 @@
 #include "alcs_internal.h"
 
 namespace alcs {
+
+// alcs_packdev.hip: the canonical arrays from weights and flags (counts + scan; compaction)
+int enqueue_csr_count(const uint8_t *mask_dev, int G, int K, int32_t *row_ptr_dev, hipStream_t st);
+int enqueue_csr_fill(const float *W_dev, const uint8_t *mask_dev, int Cout, int K, int V, int G,
+                     const int32_t *row_ptr_dev, int32_t *col_idx_dev, float *vals_dev, hipStream_t st);
+
 namespace {
 
 constexpr int kRankLimit = 16384;  // groups the quadratic rank kernel takes; beyond, the host builds the layout
@@ -39,18 +47,23 @@ struct LdShape {
 };
 
 // scal[0] = longest group, scal[1] = 1 if the arrays are not canonical, scal[2] = padded columns in
-// use, scal[3] = longest segment
+// use, scal[3] = longest segment, scal[4] = 1 if the padded columns overflow
+// scal[5] = blocks in all (row_ptr[G]).  `walk` = 0 skips the columns (arrays the library's own
+// kernels have written).
 __global__ void __launch_bounds__(256) k_ld_stats(const int32_t *row_ptr, const int32_t *col_idx, int G, int K,
-                                                  long long nnzb, int *scal) {
+                                                  long long room, int walk, int *scal) {
     const int g = blockIdx.x * 256 + threadIdx.x;
     if (g >= G) return;
+    const long long nnzb = row_ptr[G];
     const long long lo = row_ptr[g], hi = row_ptr[g + 1];
-    bool bad = lo < 0 || hi < lo || hi > nnzb || hi - lo > K || (g == 0 && lo != 0);
+    if (g == G - 1) scal[5] = (int)nnzb;
+    bool bad = lo < 0 || hi < lo || hi > nnzb || nnzb > room || hi - lo > K || (g == 0 && lo != 0);
     if (!bad) {
-        for (long long t = lo; t < hi; ++t) {
-            const int col = col_idx[t];
-            if (col < 0 || col >= K || (t > lo && col <= col_idx[t - 1])) { bad = true; break; }
-        }
+        if (walk)
+            for (long long t = lo; t < hi; ++t) {
+                const int col = col_idx[t];
+                if (col < 0 || col >= K || (t > lo && col <= col_idx[t - 1])) { bad = true; break; }
+            }
         atomicMax(&scal[0], (int)(hi - lo));
     }
     if (bad) atomicMax(&scal[1], 1);
@@ -244,6 +257,274 @@ int check(hipError_t e) {
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+int check_shape(int Cout, int Cin, int kernel, int V) {
+    if (Cout <= 0 || Cin <= 0) return ALCS_E_INVALID_ARG;
+    if (kernel != 1 && kernel != 3) return ALCS_E_UNSUPPORTED;
+    if (V != 1 && V != 2 && V != 4 && V != 8 && V != 16) return ALCS_E_UNSUPPORTED;
+    const int64_t K64 = (int64_t)Cin * kernel * kernel;
+    if (K64 > (1 << 24) || Cout > (1 << 24)) return ALCS_E_UNSUPPORTED;
+    const int G = (Cout + V - 1) / V;
+    if ((int64_t)G * K64 > (int64_t)INT32_MAX - 1024) return ALCS_E_UNSUPPORTED;
+    if (G > kRankLimit) return ALCS_E_UNSUPPORTED;
+    return ALCS_OK;
+}
+
+// One layer on its way to a handle.
+struct Job {
+    // what the caller gave: weights + flags, or the canonical arrays
+    const float *W = nullptr;
+    const uint8_t *mask = nullptr;
+    const int32_t *rp = nullptr, *ci = nullptr;
+    const float *va = nullptr;
+    bool own_arrays = false;  // rp / ci / va lie in the temporary and are filled here
+    alcs_packed *p = nullptr;
+    long long cap = 0;        // blocks the temporaries have room for
+    long long max_seg = 0;    // (bundle, chunk) pairs they have room for
+    // temporaries
+    int *scal = nullptr;
+    int32_t *t_rp = nullptr, *t_ci = nullptr, *pos = nullptr, *ev = nullptr, *lo = nullptr, *n = nullptr, *span = nullptr,
+            *order = nullptr;
+    float *t_va = nullptr;
+    Work *work = nullptr;
+    LdShape sh{};
+    long long used = 0;
+    void *blob = nullptr;
+};
+
+// Upper bound of the (bundle, chunk) pairs of a layer: one group per bundle, the chunk size of the
+// tile policy (which does not depend on the flags).
+long long seg_bound(int Cout, int Cin, int kernel, int V, const alcs_options *opt) {
+    alcs_packed probe;
+    probe.Cout = Cout; probe.Cin = Cin; probe.k = kernel; probe.V = V;
+    probe.G = (Cout + V - 1) / V;
+    probe.K = Cin * kernel * kernel;
+    if (opt) probe.opt = *opt;
+    int KC = 0, GS = 1;
+    choose_tiles(&probe, &KC, &GS);
+    return (long long)probe.G * ((Cin + KC - 1) / KC);
+}
+
+// Bytes of temporary a layer needs, and (carve != null) the pointers into one.
+size_t carve(Job *j, char *base, int Cout, int Cin, int kernel, int V, const alcs_options *opt, bool own_arrays) {
+    const int G = (Cout + V - 1) / V;
+    const long long cap = (long long)G * Cin * kernel * kernel;
+    const long long nseg = seg_bound(Cout, Cin, kernel, V, opt);
+    size_t o = 0;
+    auto take = [&](size_t bytes) { const size_t at = o; o = align256(o + bytes); return at; };
+    const size_t o_rp = take(own_arrays ? 4 * (size_t)(G + 1) : 0);
+    const size_t o_ci = take(own_arrays ? 4 * (size_t)cap : 0);
+    const size_t o_va = take(own_arrays ? 4 * (size_t)cap * V : 0);
+    const size_t o_pos = take(4 * (size_t)G);
+    const size_t o_ev = take(4 * (size_t)(cap + G + 1));
+    const size_t o_lo = take(4 * (size_t)nseg * kMaxSlots);
+    const size_t o_n = take(4 * (size_t)nseg * kMaxSlots);
+    const size_t o_span = take(4 * (size_t)nseg);
+    const size_t o_work = take(sizeof(Work) * (size_t)nseg);
+    const size_t o_order = take(4 * (size_t)G);
+    if (j) {
+        j->cap = cap;
+        j->max_seg = nseg;
+        j->t_rp = (int32_t *)(base + o_rp);
+        j->t_ci = (int32_t *)(base + o_ci);
+        j->t_va = (float *)(base + o_va);
+        j->pos = (int32_t *)(base + o_pos);
+        j->ev = (int32_t *)(base + o_ev);
+        j->lo = (int32_t *)(base + o_lo);
+        j->n = (int32_t *)(base + o_n);
+        j->span = (int32_t *)(base + o_span);
+        j->work = (Work *)(base + o_work);
+        j->order = (int32_t *)(base + o_order);
+    }
+    return o;
+}
+
+struct LayerIn {
+    const float *W;
+    const uint8_t *mask;
+    const int32_t *rp, *ci;
+    const float *va;
+    int Cout, Cin, kernel, V;
+    const alcs_options *opt;
+};
+
+// All layers through the three steps; out[i] receive the handles (all or none).
+int build_all(const LayerIn *in, int n, void *workspace, size_t workspace_bytes, hipStream_t st, alcs_packed_t **out) {
+    for (int i = 0; i < n; ++i) out[i] = nullptr;
+    for (int i = 0; i < n; ++i) {
+        int rc = check_shape(in[i].Cout, in[i].Cin, in[i].kernel, in[i].V);
+        if (rc == ALCS_OK && in[i].opt) rc = check_options(in[i].opt);
+        if (rc != ALCS_OK) return rc;
+        if (!in[i].W && !in[i].rp) return ALCS_E_INVALID_ARG;
+    }
+    int dev = 0;
+    int rc = check(hipGetDevice(&dev));
+    if (rc != ALCS_OK) return rc;
+    int cus = 0, xcds = 0;
+    device_shape(dev, &cus, &xcds);
+    std::vector<Job> jobs;
+    std::vector<int> h_scal;
+    try {
+        jobs.resize((size_t)n);
+        h_scal.resize((size_t)n * 8);
+    } catch (const std::bad_alloc &) {
+        return ALCS_E_ALLOC;
+    }
+    // the jobs' scalars (8 ints each) lie together at the start, so that one copy reads them all
+    const size_t scal_bytes = align256(8 * sizeof(int) * (size_t)n);
+    size_t need = scal_bytes;
+    for (int i = 0; i < n; ++i) need += carve(nullptr, nullptr, in[i].Cout, in[i].Cin, in[i].kernel, in[i].V, in[i].opt, in[i].W != nullptr);
+    void *own_ws = nullptr;
+    if (!workspace) {
+        if ((rc = check(hipMalloc(&own_ws, need))) != ALCS_OK) return rc;
+        workspace = own_ws;
+    } else if (workspace_bytes < need || ((uintptr_t)workspace & 255) != 0) {
+        return ALCS_E_INVALID_ARG;
+    }
+    auto fail = [&](int code) {
+        (void)hipStreamSynchronize(st);  // nothing may still write what is freed here
+        for (Job &j : jobs) {
+            if (j.blob) (void)hipFree(j.blob);
+            delete j.p;
+        }
+        if (own_ws) (void)hipFree(own_ws);
+        return code;
+    };
+    {
+        char *base = (char *)workspace + scal_bytes;
+        for (int i = 0; i < n; ++i) {
+            Job &j = jobs[(size_t)i];
+            j.scal = (int *)workspace + 8 * i;
+            j.own_arrays = in[i].W != nullptr;
+            base += carve(&j, base, in[i].Cout, in[i].Cin, in[i].kernel, in[i].V, in[i].opt, j.own_arrays);
+            j.W = in[i].W; j.mask = in[i].mask;
+            j.rp = j.own_arrays ? j.t_rp : in[i].rp;
+            j.ci = j.own_arrays ? j.t_ci : in[i].ci;
+            j.va = j.own_arrays ? j.t_va : in[i].va;
+            j.p = new (std::nothrow) alcs_packed();
+            if (!j.p) return fail(ALCS_E_ALLOC);
+            alcs_packed *p = j.p;
+            p->Cout = in[i].Cout; p->Cin = in[i].Cin; p->k = in[i].kernel; p->V = in[i].V;
+            p->G = (p->Cout + p->V - 1) / p->V;
+            p->K = p->Cin * p->k * p->k;
+            if (in[i].opt) p->opt = *in[i].opt;
+        }
+    }
+    auto read_scalars = [&]() {
+        const int r = check(hipMemcpyAsync(h_scal.data(), workspace, 8 * sizeof(int) * (size_t)n, hipMemcpyDeviceToHost, st));
+        return r != ALCS_OK ? r : check(hipStreamSynchronize(st));
+    };
+
+    // step 1: arrays' row pointers (own arrays), lengths, validity
+    if ((rc = check(hipMemsetAsync(workspace, 0, 8 * sizeof(int) * (size_t)n, st))) != ALCS_OK) return fail(rc);
+    for (Job &j : jobs) {
+        const alcs_packed *p = j.p;
+        if (j.own_arrays && (rc = enqueue_csr_count(j.mask, p->G, p->K, j.t_rp, st)) != ALCS_OK) return fail(rc);
+        hipLaunchKernelGGL(k_ld_stats, dim3((p->G + 255) / 256), dim3(256), 0, st, j.rp, j.ci, p->G, p->K, j.cap,
+                           j.own_arrays ? 0 : 1, j.scal);
+    }
+    if ((rc = check(hipGetLastError())) != ALCS_OK) return fail(rc);
+    if ((rc = read_scalars()) != ALCS_OK) return fail(rc);
+
+    // step 2: tiles, then order, segments and their starts
+    for (int i = 0; i < n; ++i) {
+        Job &j = jobs[(size_t)i];
+        alcs_packed *p = j.p;
+        const int *hs = &h_scal[(size_t)i * 8];
+        if (hs[1]) return fail(ALCS_E_INVALID_ARG);
+        p->max_count = hs[0];
+        p->nnzb = hs[5];
+        if (p->nnzb > 0 && !j.own_arrays && (!j.ci || !j.va)) return fail(ALCS_E_INVALID_ARG);
+        int KC = 0, GS = 1;
+        choose_tiles(p, &KC, &GS);
+        Layout &L = p->lay;
+        L.KC = KC;
+        L.nchunks = (p->Cin + KC - 1) / KC;
+        L.GS = GS;
+        L.nbundles = (p->G + GS - 1) / GS;
+        L.planes = p->V >= 4 ? p->V / 4 : 1;
+        L.VV = p->V >= 4 ? 4 : p->V;
+        L.noff = p->k == 1 ? 1 : kMaxOff;
+        if (GS > 1 && (p->V < 4 || p->k != 1 || L.nchunks != 1)) return fail(ALCS_E_INVALID_ARG);
+        const long long nseg = (long long)L.nbundles * L.nchunks;
+        if (nseg > j.max_seg) return fail(ALCS_E_INVALID_ARG);  // cannot happen: the bound takes one group per bundle
+        j.sh = LdShape{p->G, p->K, p->k * p->k, p->V, L.VV, L.planes, p->Cin, p->k, KC, L.nchunks, GS, L.nbundles, L.noff, p->nnzb};
+        if (j.own_arrays && p->nnzb &&
+            (rc = enqueue_csr_fill(j.W, j.mask, p->Cout, p->K, p->V, p->G, j.t_rp, j.t_ci, j.t_va, st)) != ALCS_OK)
+            return fail(rc);
+        hipLaunchKernelGGL(k_ld_rank, dim3((p->G + 255) / 256), dim3(256), 0, st, j.rp, p->G, j.order, j.pos);
+        if (GS > 1) hipLaunchKernelGGL(k_ld_parity, dim3(p->G), dim3(64), 0, st, j.rp, j.ci, p->k * p->k, j.ev);
+        hipLaunchKernelGGL(k_ld_segments, dim3((unsigned)((nseg + 255) / 256)), dim3(256), 0, st, j.sh, j.rp, j.ci, j.order,
+                           j.work, j.lo, j.n, j.span, j.scal);
+        hipLaunchKernelGGL(k_ld_scan, dim3(1), dim3(1024), 0, st, j.span, j.work, (int)nseg, j.scal);
+    }
+    if ((rc = check(hipGetLastError())) != ALCS_OK) return fail(rc);
+    if ((rc = read_scalars()) != ALCS_OK) return fail(rc);
+
+    // step 3: the handles' allocations, every block to its place
+    for (int i = 0; i < n; ++i) {
+        Job &j = jobs[(size_t)i];
+        alcs_packed *p = j.p;
+        Layout &L = p->lay;
+        const int *hs = &h_scal[(size_t)i * 8];
+        const int GS = L.GS, G = p->G, V = p->V;
+        const long long nnzb = p->nnzb, nseg = (long long)L.nbundles * L.nchunks;
+        j.used = hs[2];
+        if (hs[4] || j.used > INT32_MAX / (4 * GS) - 64) return fail(ALCS_E_UNSUPPORTED);
+        L.max_cnt = hs[3];
+        L.ncol = j.used + kSegAlign;
+        L.wplane = L.ncol * L.VV * GS;
+        // work | weight planes | selector tables | order | canonical arrays | (parity notes, build only)
+        const size_t b_work = sizeof(Work) * (size_t)nseg, b_w = 4 * (size_t)L.planes * (size_t)L.wplane;
+        const size_t b_off = 4 * (size_t)L.ncol * GS;
+        size_t q = 0;
+        auto take = [&](size_t bytes) { const size_t at = q; q = align256(q + bytes); return at; };
+        const size_t q_work = take(b_work), q_w = take(b_w), q_off = take(b_off * L.noff), q_order = take(4 * (size_t)G);
+        const size_t q_rp = take(4 * (size_t)(G + 1)), q_ci = take(4 * (size_t)nnzb), q_va = take(4 * (size_t)nnzb * V);
+        const size_t total = q + 256;
+        const size_t b_par = (size_t)L.ncol * GS;
+        if ((rc = check(hipMalloc(&j.blob, total + align256(b_par)))) != ALCS_OK) return fail(rc);
+        char *bb = (char *)j.blob;
+        uint8_t *d_par = (uint8_t *)(bb + total);
+        float *d_w = (float *)(bb + q_w);
+        int32_t *d_off = (int32_t *)(bb + q_off);
+        hipError_t e = hipMemsetAsync(d_w, 0, b_w, st);
+        if (e == hipSuccess) e = hipMemsetAsync(d_par, 0xFF, b_par, st);
+        if (e == hipSuccess) e = hipMemcpyAsync(bb + q_work, j.work, b_work, hipMemcpyDeviceToDevice, st);
+        if (e == hipSuccess) e = hipMemcpyAsync(bb + q_order, j.order, 4 * (size_t)G, hipMemcpyDeviceToDevice, st);
+        if (e == hipSuccess) e = hipMemcpyAsync(bb + q_rp, j.rp, 4 * (size_t)(G + 1), hipMemcpyDeviceToDevice, st);
+        if (e == hipSuccess && nnzb) e = hipMemcpyAsync(bb + q_ci, j.ci, 4 * (size_t)nnzb, hipMemcpyDeviceToDevice, st);
+        if (e == hipSuccess && nnzb) e = hipMemcpyAsync(bb + q_va, j.va, 4 * (size_t)nnzb * V, hipMemcpyDeviceToDevice, st);
+        if ((rc = check(e)) != ALCS_OK) return fail(rc);
+        if (nnzb)
+            hipLaunchKernelGGL(k_ld_scatter, dim3((unsigned)((nnzb + 255) / 256)), dim3(256), 0, st, j.sh, j.rp, j.ci, j.va, j.pos,
+                               j.ev, (const Work *)(bb + q_work), j.lo, j.n, d_w, (long long)L.wplane, d_off,
+                               (long long)(b_off / 4), d_par);
+        hipLaunchKernelGGL(k_ld_pads, dim3((unsigned)nseg + 1), dim3(256), 0, st, j.sh, (const Work *)(bb + q_work), d_off,
+                           (long long)(b_off / 4), d_par, j.used, (long long)L.ncol);
+        p->host_arrays = false;
+        p->dev.device = dev;
+        p->dev.cus = cus;
+        p->dev.xcds = xcds;
+        p->dev.bytes = total;
+        p->dev.work = (const Work *)(bb + q_work);
+        p->dev.w = d_w;
+        for (int t = 0; t < kMaxOff; ++t) p->dev.off[t] = t < L.noff ? d_off + (size_t)t * (b_off / 4) : nullptr;
+        p->dev.order = (const int32_t *)(bb + q_order);
+        p->dev.row_ptr = (const int32_t *)(bb + q_rp);
+        p->dev.col_idx = (const int32_t *)(bb + q_ci);
+        p->dev.vals = (const float *)(bb + q_va);
+    }
+    if ((rc = check(hipGetLastError())) != ALCS_OK) return fail(rc);
+    if ((rc = check(hipStreamSynchronize(st))) != ALCS_OK) return fail(rc);  // the temporaries are free again
+    for (int i = 0; i < n; ++i) {
+        Job &j = jobs[(size_t)i];
+        j.p->dev.blob = j.blob;
+        out[i] = j.p;
+    }
+    if (own_ws) (void)hipFree(own_ws);
+    return ALCS_OK;
+}
+
 }  // namespace
 }  // namespace alcs
 
@@ -253,173 +534,46 @@ extern "C" int alcs_pack_from_csr_device(const int32_t *row_ptr_dev, const int32
                                          int Cout, int Cin, int kernel, int V, const alcs_options *options,
                                          void *stream, alcs_packed_t **out) {
     if (out) *out = nullptr;
-    if (!row_ptr_dev || !out || Cout <= 0 || Cin <= 0) return ALCS_E_INVALID_ARG;
-    if (kernel != 1 && kernel != 3) return ALCS_E_UNSUPPORTED;
-    if (V != 1 && V != 2 && V != 4 && V != 8 && V != 16) return ALCS_E_UNSUPPORTED;
-    const int64_t K64 = (int64_t)Cin * kernel * kernel;
-    if (K64 > (1 << 24) || Cout > (1 << 24)) return ALCS_E_UNSUPPORTED;
-    const int K = (int)K64, G = (Cout + V - 1) / V;
-    if ((int64_t)G * K > (int64_t)INT32_MAX - 1024) return ALCS_E_UNSUPPORTED;
-    hipStream_t st = (hipStream_t)stream;
-    int dev = 0;
-    int rc = check(hipGetDevice(&dev));
-    if (rc != ALCS_OK) return rc;
-
-    // block count and, if the arrays are not the canonical form, nothing else
-    int32_t nnzb32 = 0;
-    rc = check(hipMemcpyAsync(&nnzb32, row_ptr_dev + G, sizeof(int32_t), hipMemcpyDeviceToHost, st));
-    if (rc != ALCS_OK) return rc;
-    int *scal = nullptr;
-    rc = check(hipMalloc((void **)&scal, 8 * sizeof(int)));
-    if (rc != ALCS_OK) return rc;
-    void *tmp = nullptr, *blob = nullptr;
-    alcs_packed *p = nullptr;
-    auto fail = [&](int code) {
-        if (scal) (void)hipFree(scal);
-        if (tmp) (void)hipFree(tmp);
-        if (blob) (void)hipFree(blob);
-        delete p;
-        return code;
-    };
-    if ((rc = check(hipMemsetAsync(scal, 0, 8 * sizeof(int), st))) != ALCS_OK) return fail(rc);
-    if ((rc = check(hipStreamSynchronize(st))) != ALCS_OK) return fail(rc);
-    const long long nnzb = nnzb32;
-    if (nnzb < 0 || nnzb > (long long)G * K) return fail(ALCS_E_INVALID_ARG);
-    if (nnzb > 0 && (!col_idx_dev || !vals_dev)) return fail(ALCS_E_INVALID_ARG);
-    hipLaunchKernelGGL(k_ld_stats, dim3((G + 255) / 256), dim3(256), 0, st, row_ptr_dev, col_idx_dev, G, K, nnzb, scal);
-    int h_scal[8] = {0};
-    if ((rc = check(hipMemcpyAsync(h_scal, scal, sizeof(h_scal), hipMemcpyDeviceToHost, st))) != ALCS_OK) return fail(rc);
-    if ((rc = check(hipStreamSynchronize(st))) != ALCS_OK) return fail(rc);
-    if (h_scal[1]) return fail(ALCS_E_INVALID_ARG);
-
-    p = new (std::nothrow) alcs_packed();
-    if (!p) return fail(ALCS_E_ALLOC);
-    p->Cout = Cout; p->Cin = Cin; p->k = kernel; p->V = V; p->G = G; p->K = K;
-    p->nnzb = nnzb;
-    p->max_count = h_scal[0];
-    if (options) {
-        if ((rc = check_options(options)) != ALCS_OK) return fail(rc);
-        p->opt = *options;
-    }
-    int KC = 0, GS = 1;
-    choose_tiles(p, &KC, &GS);
-    Layout &L = p->lay;
-    L.KC = KC;
-    L.nchunks = (Cin + KC - 1) / KC;
-    L.GS = GS;
-    L.nbundles = (G + GS - 1) / GS;
-    L.planes = V >= 4 ? V / 4 : 1;
-    L.VV = V >= 4 ? 4 : V;
-    L.noff = kernel == 1 ? 1 : kMaxOff;
-    if (GS > 1 && (V < 4 || kernel != 1 || L.nchunks != 1)) return fail(ALCS_E_INVALID_ARG);
-    if (G > kRankLimit) return fail(ALCS_E_UNSUPPORTED);  // the caller goes through the host (alcs_pack_from_csr)
-
-    const LdShape sh{G, K, kernel * kernel, V, L.VV, L.planes, Cin, kernel, KC, L.nchunks, GS, L.nbundles, L.noff, nnzb};
-    const long long nseg = (long long)L.nbundles * L.nchunks;
-    if (nseg > (1LL << 26)) return fail(ALCS_E_UNSUPPORTED);
-    // temporaries: pos[G] | evens[nnzb + G + 1] | seg_lo[nseg * 4] | seg_n[nseg * 4] | span[nseg] | work[nseg] | order[G]
-    size_t o = 0;
-    const size_t o_pos = o; o = align256(o + 4 * (size_t)G);
-    const size_t o_ev = o; o = align256(o + 4 * (size_t)(nnzb + G + 1));
-    const size_t o_lo = o; o = align256(o + 4 * (size_t)nseg * kMaxSlots);
-    const size_t o_n = o; o = align256(o + 4 * (size_t)nseg * kMaxSlots);
-    const size_t o_span = o; o = align256(o + 4 * (size_t)nseg);
-    const size_t o_work = o; o = align256(o + sizeof(Work) * (size_t)nseg);
-    const size_t o_order = o; o = align256(o + 4 * (size_t)G);
-    if ((rc = check(hipMalloc(&tmp, o))) != ALCS_OK) return fail(rc);
-    char *tb = (char *)tmp;
-    int32_t *d_pos = (int32_t *)(tb + o_pos), *d_ev = (int32_t *)(tb + o_ev), *d_lo = (int32_t *)(tb + o_lo);
-    int32_t *d_n = (int32_t *)(tb + o_n), *d_span = (int32_t *)(tb + o_span), *d_order = (int32_t *)(tb + o_order);
-    Work *d_work = (Work *)(tb + o_work);
-    hipLaunchKernelGGL(k_ld_rank, dim3((G + 255) / 256), dim3(256), 0, st, row_ptr_dev, G, d_order, d_pos);
-    if (GS > 1) hipLaunchKernelGGL(k_ld_parity, dim3(G), dim3(64), 0, st, row_ptr_dev, col_idx_dev, kernel * kernel, d_ev);
-    hipLaunchKernelGGL(k_ld_segments, dim3((unsigned)((nseg + 255) / 256)), dim3(256), 0, st, sh, row_ptr_dev, col_idx_dev,
-                       d_order, d_work, d_lo, d_n, d_span, scal);
-    hipLaunchKernelGGL(k_ld_scan, dim3(1), dim3(1024), 0, st, d_span, d_work, (int)nseg, scal);
-    if ((rc = check(hipGetLastError())) != ALCS_OK) return fail(rc);
-    if ((rc = check(hipMemcpyAsync(h_scal, scal, sizeof(h_scal), hipMemcpyDeviceToHost, st))) != ALCS_OK) return fail(rc);
-    if ((rc = check(hipStreamSynchronize(st))) != ALCS_OK) return fail(rc);
-    const long long used = h_scal[2];
-    if (h_scal[4] || used > INT32_MAX / (4 * GS) - 64) return fail(ALCS_E_UNSUPPORTED);
-    L.max_cnt = h_scal[3];
-    L.ncol = used + kSegAlign;
-    L.wplane = L.ncol * L.VV * GS;
-
-    // the handle's allocation: work | weight planes | selector tables | order | canonical arrays | (parity notes)
-    const size_t b_work = sizeof(Work) * (size_t)nseg, b_w = 4 * (size_t)L.planes * (size_t)L.wplane;
-    const size_t b_off = 4 * (size_t)L.ncol * GS;
-    size_t q = 0;
-    const size_t q_work = q; q = align256(q + b_work);
-    const size_t q_w = q; q = align256(q + b_w);
-    const size_t q_off = q; q = align256(q + b_off * L.noff);
-    const size_t q_order = q; q = align256(q + 4 * (size_t)G);
-    const size_t q_rp = q; q = align256(q + 4 * (size_t)(G + 1));
-    const size_t q_ci = q; q = align256(q + 4 * (size_t)nnzb);
-    const size_t q_va = q; q = align256(q + 4 * (size_t)nnzb * V);
-    const size_t total = q + 256;
-    const size_t b_par = (size_t)L.ncol * GS;
-    if ((rc = check(hipMalloc(&blob, total + align256(b_par)))) != ALCS_OK) return fail(rc);
-    char *bb = (char *)blob;
-    uint8_t *d_par = (uint8_t *)(bb + total);
-    float *d_w = (float *)(bb + q_w);
-    int32_t *d_off = (int32_t *)(bb + q_off);
-    hipError_t e = hipMemsetAsync(d_w, 0, b_w, st);
-    if (e == hipSuccess) e = hipMemsetAsync(d_par, 0xFF, b_par, st);
-    if (e == hipSuccess) e = hipMemcpyAsync(bb + q_work, d_work, b_work, hipMemcpyDeviceToDevice, st);
-    if (e == hipSuccess) e = hipMemcpyAsync(bb + q_order, d_order, 4 * (size_t)G, hipMemcpyDeviceToDevice, st);
-    if (e == hipSuccess) e = hipMemcpyAsync(bb + q_rp, row_ptr_dev, 4 * (size_t)(G + 1), hipMemcpyDeviceToDevice, st);
-    if (e == hipSuccess && nnzb) e = hipMemcpyAsync(bb + q_ci, col_idx_dev, 4 * (size_t)nnzb, hipMemcpyDeviceToDevice, st);
-    if (e == hipSuccess && nnzb) e = hipMemcpyAsync(bb + q_va, vals_dev, 4 * (size_t)nnzb * V, hipMemcpyDeviceToDevice, st);
-    if ((rc = check(e)) != ALCS_OK) return fail(rc);
-    if (nnzb)
-        hipLaunchKernelGGL(k_ld_scatter, dim3((unsigned)((nnzb + 255) / 256)), dim3(256), 0, st, sh, row_ptr_dev, col_idx_dev,
-                           vals_dev, d_pos, d_ev, (const Work *)(bb + q_work), d_lo, d_n, d_w, (long long)L.wplane, d_off,
-                           (long long)(b_off / 4), d_par);
-    hipLaunchKernelGGL(k_ld_pads, dim3((unsigned)nseg + 1), dim3(256), 0, st, sh, (const Work *)(bb + q_work), d_off,
-                       (long long)(b_off / 4), d_par, used, (long long)L.ncol);
-    if ((rc = check(hipGetLastError())) != ALCS_OK) return fail(rc);
-    if ((rc = check(hipStreamSynchronize(st))) != ALCS_OK) return fail(rc);  // the temporaries go away below
-
-    p->host_arrays = false;
-    p->dev.device = dev;
-    device_shape(dev, &p->dev.cus, &p->dev.xcds);
-    p->dev.blob = blob;
-    p->dev.bytes = total;
-    p->dev.work = (const Work *)(bb + q_work);
-    p->dev.w = d_w;
-    for (int t = 0; t < kMaxOff; ++t) p->dev.off[t] = t < L.noff ? d_off + (size_t)t * (b_off / 4) : nullptr;
-    p->dev.order = (const int32_t *)(bb + q_order);
-    p->dev.row_ptr = (const int32_t *)(bb + q_rp);
-    p->dev.col_idx = (const int32_t *)(bb + q_ci);
-    p->dev.vals = (const float *)(bb + q_va);
-    (void)hipFree(tmp);
-    (void)hipFree(scal);
-    *out = p;
-    return ALCS_OK;
+    if (!row_ptr_dev || !out) return ALCS_E_INVALID_ARG;
+    const LayerIn in{nullptr, nullptr, row_ptr_dev, col_idx_dev, vals_dev, Cout, Cin, kernel, V, options};
+    return build_all(&in, 1, nullptr, 0, (hipStream_t)stream, out);
 }
 
 extern "C" int alcs_pack_weights_device(const float *W_dev, const uint8_t *mask_dev, int Cout, int Cin, int kernel, int V,
                                         const alcs_options *options, void *stream, alcs_packed_t **out) {
     if (out) *out = nullptr;
-    if (!W_dev || !out || Cout <= 0 || Cin <= 0) return ALCS_E_INVALID_ARG;
-    if (kernel != 1 && kernel != 3) return ALCS_E_UNSUPPORTED;
-    if (V != 1 && V != 2 && V != 4 && V != 8 && V != 16) return ALCS_E_UNSUPPORTED;
-    const int64_t K64 = (int64_t)Cin * kernel * kernel;
-    if (K64 > (1 << 24) || Cout > (1 << 24)) return ALCS_E_UNSUPPORTED;
-    const int G = (Cout + V - 1) / V;
-    const long long cap = (long long)G * K64;
-    if (cap > (long long)INT32_MAX - 1024) return ALCS_E_UNSUPPORTED;
-    // canonical arrays sized for every block kept: one allocation, no counting pass of its own
-    const size_t o_rp = 0, o_ci = align256(4 * (size_t)(G + 1)), o_va = align256(o_ci + 4 * (size_t)cap);
-    void *tmp = nullptr;
-    int rc = check(hipMalloc(&tmp, o_va + 4 * (size_t)cap * V));
-    if (rc != ALCS_OK) return rc;
-    char *tb = (char *)tmp;
-    rc = alcs_pack_csr_device(W_dev, mask_dev, Cout, Cin, kernel, V, (int32_t *)(tb + o_rp), (int32_t *)(tb + o_ci),
-                              (float *)(tb + o_va), cap, nullptr, stream);
-    if (rc == ALCS_OK)
-        rc = alcs_pack_from_csr_device((const int32_t *)(tb + o_rp), (const int32_t *)(tb + o_ci), (const float *)(tb + o_va),
-                                       Cout, Cin, kernel, V, options, stream, out);
-    (void)hipFree(tmp);
-    return rc;
+    if (!W_dev || !out) return ALCS_E_INVALID_ARG;
+    const LayerIn in{W_dev, mask_dev, nullptr, nullptr, nullptr, Cout, Cin, kernel, V, options};
+    return build_all(&in, 1, nullptr, 0, (hipStream_t)stream, out);
+}
+
+extern "C" long long alcs_pack_workspace_bytes(const alcs_layer_desc *layers, int n_layers) {
+    if (!layers || n_layers <= 0) return ALCS_E_INVALID_ARG;
+    size_t need = align256(8 * sizeof(int) * (size_t)n_layers);
+    for (int i = 0; i < n_layers; ++i) {
+        const alcs_layer_desc &d = layers[i];
+        int rc = check_shape(d.Cout, d.Cin, d.kernel, d.V);
+        if (rc == ALCS_OK && d.options) rc = check_options(d.options);
+        if (rc != ALCS_OK) return rc;
+        need += carve(nullptr, nullptr, d.Cout, d.Cin, d.kernel, d.V, d.options, true);
+    }
+    return (long long)need;
+}
+
+extern "C" int alcs_pack_network_device(const alcs_layer_desc *layers, int n_layers, void *workspace_dev,
+                                        long long workspace_bytes, void *stream, alcs_packed_t **out) {
+    if (!layers || n_layers <= 0 || !out || workspace_bytes < 0) return ALCS_E_INVALID_ARG;
+    std::vector<LayerIn> in;
+    try {
+        in.reserve((size_t)n_layers);
+    } catch (const std::bad_alloc &) {
+        return ALCS_E_ALLOC;
+    }
+    for (int i = 0; i < n_layers; ++i) {
+        out[i] = nullptr;
+        const alcs_layer_desc &d = layers[i];
+        if (!d.W_dev) return ALCS_E_INVALID_ARG;
+        in.push_back(LayerIn{d.W_dev, d.mask_dev, nullptr, nullptr, nullptr, d.Cout, d.Cin, d.kernel, d.V, d.options});
+    }
+    return build_all(in.data(), n_layers, workspace_dev, (size_t)workspace_bytes, (hipStream_t)stream, out);
 }

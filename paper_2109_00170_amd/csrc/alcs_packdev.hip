@@ -90,15 +90,35 @@ __global__ void __launch_bounds__(256) k_pack_fill(const float *W, const uint8_t
     }
 }
 
-}  // namespace alcs
-
-using namespace alcs;
-
 static int check(hipError_t e) {
     if (e == hipSuccess) return ALCS_OK;
     set_hip_error((int)e);
     return ALCS_E_HIP;
 }
+
+int enqueue_csr_count(const uint8_t *mask_dev, int G, int K, int32_t *row_ptr_dev, hipStream_t st) {
+    hipLaunchKernelGGL(k_pack_count, dim3(G), dim3(256), 0, st, mask_dev, K, row_ptr_dev);
+    hipLaunchKernelGGL(k_pack_scan, dim3(1), dim3(1024), 0, st, row_ptr_dev, G);
+    return check(hipGetLastError());
+}
+
+int enqueue_csr_fill(const float *W_dev, const uint8_t *mask_dev, int Cout, int K, int V, int G,
+                     const int32_t *row_ptr_dev, int32_t *col_idx_dev, float *vals_dev, hipStream_t st) {
+    void (*kern)(const float *, const uint8_t *, int, int, const int32_t *, int32_t *, float *) = nullptr;
+    switch (V) {
+        case 1: kern = k_pack_fill<1>; break;
+        case 2: kern = k_pack_fill<2>; break;
+        case 4: kern = k_pack_fill<4>; break;
+        case 8: kern = k_pack_fill<8>; break;
+        default: kern = k_pack_fill<16>; break;
+    }
+    hipLaunchKernelGGL(kern, dim3(G), dim3(256), 0, st, W_dev, mask_dev, Cout, K, row_ptr_dev, col_idx_dev, vals_dev);
+    return check(hipGetLastError());
+}
+
+}  // namespace alcs
+
+using namespace alcs;
 
 extern "C" int alcs_pack_csr_device(const float *W_dev, const uint8_t *mask_dev, int Cout, int Cin, int kernel,
                                     int V, int32_t *row_ptr_dev, int32_t *col_idx_dev, float *vals_dev,
@@ -111,9 +131,7 @@ extern "C" int alcs_pack_csr_device(const float *W_dev, const uint8_t *mask_dev,
     const int K = (int)K64, G = (Cout + V - 1) / V;
     if ((long long)G * K > (long long)INT32_MAX - 1024) return ALCS_E_UNSUPPORTED;
     hipStream_t st = (hipStream_t)stream;
-    hipLaunchKernelGGL(k_pack_count, dim3(G), dim3(256), 0, st, mask_dev, K, row_ptr_dev);
-    hipLaunchKernelGGL(k_pack_scan, dim3(1), dim3(1024), 0, st, row_ptr_dev, G);
-    int rc = check(hipGetLastError());
+    int rc = enqueue_csr_count(mask_dev, G, K, row_ptr_dev, st);
     if (rc != ALCS_OK) return rc;
     int32_t nnzb = 0;
     rc = check(hipMemcpyAsync(&nnzb, row_ptr_dev + G, sizeof(int32_t), hipMemcpyDeviceToHost, st));
@@ -124,14 +142,5 @@ extern "C" int alcs_pack_csr_device(const float *W_dev, const uint8_t *mask_dev,
     if (!col_idx_dev && !vals_dev) return ALCS_OK;  // counting pass only
     if (!col_idx_dev || !vals_dev || nnzb > capacity_blocks) return ALCS_E_INVALID_ARG;
     if (nnzb == 0) return ALCS_OK;
-    void (*kern)(const float *, const uint8_t *, int, int, const int32_t *, int32_t *, float *) = nullptr;
-    switch (V) {
-        case 1: kern = k_pack_fill<1>; break;
-        case 2: kern = k_pack_fill<2>; break;
-        case 4: kern = k_pack_fill<4>; break;
-        case 8: kern = k_pack_fill<8>; break;
-        default: kern = k_pack_fill<16>; break;
-    }
-    hipLaunchKernelGGL(kern, dim3(G), dim3(256), 0, st, W_dev, mask_dev, Cout, K, row_ptr_dev, col_idx_dev, vals_dev);
-    return check(hipGetLastError());
+    return enqueue_csr_fill(W_dev, mask_dev, Cout, K, V, G, row_ptr_dev, col_idx_dev, vals_dev, st);
 }

@@ -129,3 +129,37 @@ def test_set_options_and_reuse_of_a_device_built_handle():
         torch.cuda.synchronize()
         assert float(np.max(np.abs(Y.cpu().numpy() - ref))) <= TOL * scale, opts
     dev.free()
+
+
+def test_network_in_one_call_equals_layer_by_layer():
+    import torch
+    rng = np.random.default_rng(4198)
+    shapes = [(64, 32, 1, 4), (128, 64, 1, 4), (72, 520, 1, 4), (24, 16, 3, 4), (40, 700, 1, 2), (64, 512, 1, 8), (16, 16, 1, 4)]
+    Ws, masks, Vs = [], [], []
+    for i, (co, ci, k, V) in enumerate(shapes):
+        W = (rng.standard_normal((co, ci, k, k)) * 0.2).astype(np.float32)
+        m = workloads.mask_exact((co + V - 1) // V, ci, k, 1.0 if i == 6 else 0.85, rng)
+        Ws.append(W); masks.append(m); Vs.append(V)
+    Wd = [torch.from_numpy(W).cuda() for W in Ws]
+    md = [torch.from_numpy(m).cuda() for m in masks]
+    md[1] = None                                            # everything kept
+    masks[1] = np.ones_like(masks[1])
+    need = alcs.alcs_pack_workspace_bytes(Wd, md, Vs)
+    ws = torch.empty((need,), dtype=torch.uint8, device="cuda")
+    for workspace in (ws, None):
+        hs = alcs.alcs_pack_network_device(Wd, md, Vs, workspace=workspace)
+        for h, W, m, V in zip(hs, Ws, masks, Vs):
+            host = alcs.alcs_pack_weights(W, m, V)
+            assert h.selfcheck() == 0 and h.layout_hash() == host.layout_hash()
+            for got, want in zip(h.export(), oracle.pack(W, m, V)):
+                assert got.tobytes() == want.tobytes()
+            host.free()
+            h.free()
+    # too small a workspace, a layer the packer refuses: no handles, an error
+    with pytest.raises(alcs.AlcsError) as ei:
+        alcs.alcs_pack_network_device(Wd, md, Vs, workspace=ws[: need - 256])
+    assert ei.value.status == -1
+    with pytest.raises(alcs.AlcsError) as ei:
+        alcs.alcs_pack_network_device(Wd, [None] * 7, [4, 4, 4, 4, 3, 8, 4])          # V = 3
+    assert ei.value.status == -2
+    torch.cuda.synchronize()
