@@ -509,6 +509,85 @@ def report(kind, alcs, workloads, torch, np):
                (L.name, L.Cin, L.Cout, L.H, a, b_, a / b_, by16 / 1e6, by16 / b_ / 1e3, by16 / (HBM_PEAK_GBS * 1e3) / b_, diff))
         pr("| 13 MobileNetV1-shaped layers, batch 32, 90 %% block sparsity | %.0f | %.0f | %.2f | | | %.3f | |" %
            (t32, t16, t32 / t16, roof / t16))
+    elif kind == "math16":
+        # 16-bit arithmetic (alcs_sparse_conv_bf16_mfma: bfloat16 tensors and weights on the 16-bit matrix
+        # instruction) against the float32 path and against bfloat16 storage with float32 arithmetic;
+        # bias + ReLU in all three; stream events over rotated buffers of the same number of bytes
+        import dataclasses
+
+        def one(L, seed):
+            d = workloads.make_layer(L, seed, with_bias=True)
+            p = alcs.alcs_pack_weights(d.W, d.mask, L.V)
+            small = L.Cin <= 639
+            p16 = alcs.alcs_pack_weights(d.W, d.mask, L.V, options={"group_slots": 1}) if small else None
+            if p16 is not None:
+                p16.add_bf16_weights()
+            b = torch.from_numpy(d.bias).cuda()
+            X = torch.from_numpy(d.X).cuda()
+            R = max(2, min(8, int(600e6 // (L.x_bytes() + L.y_bytes())) + 1))
+            X32 = [X] + [X.clone() for _ in range(R - 1)]
+            Y32 = [torch.empty((L.N, L.Cout, L.Ho, L.Wo), dtype=torch.float32, device="cuda") for _ in range(R)]
+            X16 = [x.to(torch.bfloat16) for x in X32] + [X.to(torch.bfloat16) for _ in range(R)]
+            Y16 = [torch.empty((L.N, L.Cout, L.Ho, L.Wo), dtype=torch.bfloat16, device="cuda") for _ in range(2 * R)]
+
+            def f32(i):
+                alcs.alcs_sparse_conv_fused(p, X32[i % R], b, None, Y32[i % R], stride=L.stride, activation="relu")
+
+            def f16(i):
+                alcs.alcs_sparse_conv_bf16(p, X16[i % (2 * R)], b, None, Y16[i % (2 * R)], stride=L.stride, activation="relu")
+
+            def m16(i):
+                alcs.alcs_sparse_conv_bf16_mfma(p16, X16[i % (2 * R)], b, None, Y16[i % (2 * R)], stride=L.stride, activation="relu")
+
+            res = []
+            for fn in (f32, f16, m16):
+                if fn is m16 and p16 is None:
+                    res.append(float("nan"))
+                    continue
+                for i in range(3):
+                    fn(i)
+                torch.cuda.synchronize()
+                n = 6 * R
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for i in range(n):
+                    fn(i)
+                e1.record()
+                torch.cuda.synchronize()
+                res.append(e0.elapsed_time(e1) * 1e3 / n)
+            diff = float("nan")
+            if p16 is not None:
+                f32(0)
+                m16(0)
+                torch.cuda.synchronize()
+                diff = float((Y32[0] - Y16[0].float()).abs().max() / Y32[0].abs().max().clamp_min(1e-30))
+                p16.free()
+            wb = layer_bytes(L, p.nnzb) - L.x_bytes() - L.y_bytes()
+            by16 = (L.x_bytes() + L.y_bytes()) // 2 + wb // 2 + 4 * L.Cout
+            p.free()
+            return res, by16, diff
+
+        for V in (8, 16, 4):
+            pr("")
+            pr("V = %d" % V)
+            pr("")
+            pr("| layer | float32 us | bfloat16 storage us | 16-bit arithmetic us | float32 / 16-bit | storage / 16-bit | "
+               "16-bit bytes MB | eff GB/s | HBM roofline frac | max diff to float32 (of max) |")
+            pr("|---|---|---|---|---|---|---|---|---|---|")
+            tot = [0.0, 0.0, 0.0]
+            for i, L0 in enumerate(workloads.mobilenet_v1_pointwise(32, 0.9)):
+                L = dataclasses.replace(L0, V=V)
+                (a, b_, c), by16, diff = one(L, workloads.seed_for(2, i))
+                if c == c:
+                    tot = [tot[0] + a, tot[1] + b_, tot[2] + c]
+                    pr("| %s %d->%d @%d | %.1f | %.1f | %.1f | %.2f | %.2f | %.1f | %.0f | %.3f | %.1e |" %
+                       (L.name, L.Cin, L.Cout, L.H, a, b_, c, a / c, b_ / c, by16 / 1e6, by16 / c / 1e3,
+                        by16 / (HBM_PEAK_GBS * 1e3) / c, diff))
+                else:
+                    pr("| %s %d->%d @%d | %.1f | %.1f | n/a (input channels beyond one 16-bit tile) | | | | | | |" %
+                       (L.name, L.Cin, L.Cout, L.H, a, b_))
+            pr("| layers with a 16-bit time | %.0f | %.0f | %.0f | %.2f | %.2f | | | | |" %
+               (tot[0], tot[1], tot[2], tot[0] / tot[2], tot[1] / tot[2]))
     elif kind == "project":
         # Algorithm 1 on the GPU: block scores, top-N selection, the bisection; times are wall-clock
         # around synchronised calls (the bisection synchronises once per step by design)
@@ -723,7 +802,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-batch", type=int, default=32)
     ap.add_argument("--layers-json", default=None, help="also write the per-layer table to this file")
-    ap.add_argument("--report", choices=["sweep", "resnet", "mbv2", "paths", "mbv1", "fused", "latency", "block", "project", "bf16", "config1", "floor"], default=None,
+    ap.add_argument("--report", choices=["sweep", "resnet", "mbv2", "paths", "mbv1", "fused", "latency", "block", "project", "bf16", "math16", "config1", "floor"], default=None,
                     help="instead of the benchmark line, print a per-layer table for another configuration: "
                          "the sparsity sweep with the same-GPU dense conv (config 4), the ResNet-50-shaped "
                          "bottleneck convs (config 3), the MobileNetV2-shaped pointwise convs for V in "

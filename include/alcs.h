@@ -201,6 +201,30 @@ int alcs_sparse_conv_bf16(const alcs_packed_t *Wp, const uint16_t *X_dev, const 
                           int H, int W, int kernel, int stride, int activation, void *stream);
 
 /*
+ * The same layer in 16-bit arithmetic (Section 3.2.1: the group size follows the width of the
+ * machine's vector unit over the element width - here the 16-bit matrix instruction, which takes
+ * four kept columns of four output channels at a time; groups of V = 8 and 16 are two and four
+ * such instructions on one input operand): X_dev, residual_dev and Y_dev bfloat16 as for
+ * alcs_sparse_conv_bf16, and the packed WEIGHTS rounded to bfloat16 (nearest even) as well;
+ * products are exact, sums float32, the bias float32, Y rounded once at the end.  The result is
+ * the definition evaluated on the rounded weights and inputs, up to float32 summation error.
+ *
+ * alcs_packed_add_bf16_weights: gives a handle the rounded copy of its weights in the
+ *   instruction's layout (device memory of the handle, freed with it; a kernel on `stream`, no
+ *   wait: use the handle on that stream, or synchronise first).  Once per handle; a second call
+ *   does nothing.  Handles it takes: kernel 1, V in {4, 8, 16}, one group per wavefront and all
+ *   input channels in one on-chip tile (what alcs_pack_weights builds for Cin <= 511, and for
+ *   Cin <= 639 with the option group_slots = 1); others ALCS_E_UNSUPPORTED.  ALCS_E_NO_DEVICE
+ *   for a handle without a device copy; the handle's device must be current.
+ * alcs_sparse_conv_bf16_mfma: arguments and errors as alcs_sparse_conv_bf16, the three tensors
+ *   16-byte aligned; ALCS_E_INVALID_ARG for a handle without the rounded weights.
+ */
+int alcs_packed_add_bf16_weights(alcs_packed_t *p, void *stream);
+int alcs_sparse_conv_bf16_mfma(const alcs_packed_t *Wp, const uint16_t *X_dev, const float *bias_dev,
+                               const uint16_t *residual_dev, uint16_t *Y_dev, int N, int Cin, int Cout,
+                               int H, int W, int kernel, int stride, int activation, void *stream);
+
+/*
  * Depthwise 3x3 layer and the MobileNet block (the network pruned in Section 4 of the paper:
  * every pointwise convolution is preceded by a depthwise 3x3 layer with its own bias and
  * activation; they are among the layers behind the constant tau of Section 3.3, Eq. (2)).
@@ -455,7 +479,8 @@ int alcs_pack_weights_device(const float *W_dev, const uint8_t *mask_dev, int Co
 
 /* What the last alcs_sparse_conv call of this thread launched: fills up to `cap`
  * ints {mode (1 = all input channels resident in LDS, 2 = chunked, 3 = 3x3,
- * 4 = persistent double-buffered with the weights in LDS, 5 = pipelined persistent),
+ * 4 = persistent double-buffered with the weights in LDS, 5 = pipelined persistent,
+ * 6 = the 16-bit kernel of alcs_sparse_conv_bf16_mfma, whose path reads 3),
  * pv, waves, workgroups, lds_bytes, group_tiles,
  * chunk_channels, path, group_slots, tile_width (3x3 only, else 0)} and returns how many were
  * written.  For tests and benchmarks. */

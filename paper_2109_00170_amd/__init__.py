@@ -27,6 +27,7 @@ from ._binding import (  # noqa: F401
     alcs_project_latency,
     alcs_sparse_conv,
     alcs_sparse_conv_bf16,
+    alcs_sparse_conv_bf16_mfma,
     alcs_sparse_conv_fused,
     alcs_strerror,
     alcs_topn_mask,

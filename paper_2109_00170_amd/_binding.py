@@ -19,7 +19,8 @@ EXPORTS = [
     "alcs_depthwise_conv", "alcs_dw_sparse_conv_fused", "alcs_sparse_conv_bf16", "alcs_block_scores", "alcs_select_workspace_bytes",
     "alcs_topn_mask", "alcs_topn_mask_static", "alcs_project_latency", "alcs_pack_csr_device", "alcs_pack_from_csr",
     "alcs_pack_from_csr_device", "alcs_pack_weights_device", "alcs_packed_layout_hash",
-    "alcs_pack_workspace_bytes", "alcs_pack_network_device",
+    "alcs_pack_workspace_bytes", "alcs_pack_network_device", "alcs_packed_add_bf16_weights",
+    "alcs_sparse_conv_bf16_mfma",
     "alcs_last_launch", "alcs_latency_estimate", "alcs_network_latency",
 ]
 
@@ -149,6 +150,11 @@ class Packed:
     def selfcheck(self) -> int:
         return int(load_library().alcs_packed_selfcheck(self.handle))
 
+    def add_bf16_weights(self, stream=None) -> None:
+        rc = load_library().alcs_packed_add_bf16_weights(self._h, _stream_ptr(stream))
+        if rc != 0:
+            raise AlcsError(rc, "alcs_packed_add_bf16_weights")
+
     def layout_hash(self) -> int:
         h = ctypes.c_ulonglong()
         rc = load_library().alcs_packed_layout_hash(self._h, ctypes.byref(h))
@@ -267,8 +273,11 @@ def alcs_sparse_conv_fused(packed: Packed, X, bias, residual, Y, stride: int = 1
         raise AlcsError(rc, "alcs_sparse_conv_fused")
 
 
-def alcs_sparse_conv_bf16(packed: Packed, X, bias, residual, Y, stride: int = 1, activation=None, stream=None) -> None:
-    """alcs_sparse_conv_fused on torch.bfloat16 tensors X, residual (or None) and Y; bias stays float32."""
+def alcs_sparse_conv_bf16(packed: Packed, X, bias, residual, Y, stride: int = 1, activation=None, stream=None,
+                          mfma16: bool = False) -> None:
+    """alcs_sparse_conv_fused on torch.bfloat16 tensors X, residual (or None) and Y; bias stays float32.
+    mfma16 routes the call to alcs_sparse_conv_bf16_mfma (weights rounded to bfloat16 as well; the
+    handle needs Packed.add_bf16_weights() first)."""
     N, Cin, H, W = X.shape
     k = packed.kernel
     exp = (N, packed.Cout, out_size(H, k, stride), out_size(W, k, stride))
@@ -278,11 +287,17 @@ def alcs_sparse_conv_bf16(packed: Packed, X, bias, residual, Y, stride: int = 1,
         raise ValueError("residual must have shape %r, got %r" % (exp, tuple(residual.shape)))
     act = activation if isinstance(activation, int) else ACTIVATIONS[activation]
     bf = "torch.bfloat16"
-    rc = load_library().alcs_sparse_conv_bf16(packed.handle, _dev_ptr(X, "X", bf), _dev_ptr(bias, "bias"),
-                                              _dev_ptr(residual, "residual", bf), _dev_ptr(Y, "Y", bf), N, Cin,
-                                              packed.Cout, H, W, k, int(stride), int(act), _stream_ptr(stream))
+    lib = load_library()
+    fn, name = (lib.alcs_sparse_conv_bf16_mfma, "alcs_sparse_conv_bf16_mfma") if mfma16 else \
+        (lib.alcs_sparse_conv_bf16, "alcs_sparse_conv_bf16")
+    rc = fn(packed.handle, _dev_ptr(X, "X", bf), _dev_ptr(bias, "bias"), _dev_ptr(residual, "residual", bf),
+            _dev_ptr(Y, "Y", bf), N, Cin, packed.Cout, H, W, k, int(stride), int(act), _stream_ptr(stream))
     if rc != 0:
-        raise AlcsError(rc, "alcs_sparse_conv_bf16")
+        raise AlcsError(rc, name)
+
+
+def alcs_sparse_conv_bf16_mfma(packed: Packed, X, bias, residual, Y, stride: int = 1, activation=None, stream=None) -> None:
+    alcs_sparse_conv_bf16(packed, X, bias, residual, Y, stride=stride, activation=activation, stream=stream, mfma16=True)
 
 
 class HipEvents:

@@ -181,6 +181,9 @@ struct DeviceCopy {
     // group order and the canonical arrays, which the host fetches only when it is asked for them
     const int32_t *order = nullptr, *row_ptr = nullptr, *col_idx = nullptr;
     const float *vals = nullptr;
+    // the weight planes rounded to bfloat16 in the layout of the 16-bit matrix instruction, an
+    // allocation of its own made by alcs_packed_add_bf16_weights (null before)
+    const uint16_t *w16 = nullptr;
 };
 
 }  // namespace alcs

@@ -201,13 +201,11 @@ static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 void release_device(alcs_packed *p) {
     if (p->dev.blob) {
         int cur = -1;
-        if (hipGetDevice(&cur) == hipSuccess && cur != p->dev.device) {
-            (void)hipSetDevice(p->dev.device);
-            (void)hipFree(p->dev.blob);
-            (void)hipSetDevice(cur);
-        } else {
-            (void)hipFree(p->dev.blob);
-        }
+        const bool elsewhere = hipGetDevice(&cur) == hipSuccess && cur != p->dev.device;
+        if (elsewhere) (void)hipSetDevice(p->dev.device);
+        (void)hipFree(p->dev.blob);
+        if (p->dev.w16) (void)hipFree(const_cast<uint16_t *>(p->dev.w16));
+        if (elsewhere) (void)hipSetDevice(cur);
     }
     p->dev = DeviceCopy();
 }
@@ -301,7 +299,7 @@ void choose_tiles(const alcs_packed *p, int *KC, int *GS) {
     const int kc = p->opt.chunk_channels, gs = p->opt.group_slots;
     if (kc > 0) { *KC = std::min(kc, p->Cin); *GS = 1; }
     if ((gs == 1 || gs == 2 || gs == 4) && p->k == 1 && p->V >= 4 && *KC == p->Cin &&
-        (long long)(p->Cin + 2) * (kRowBytes1 / gs) <= 160 * 1024)
+        (long long)(p->Cin + (gs > 1 ? 2 : 1)) * (kRowBytes1 / gs) <= 160 * 1024)
         *GS = gs;
 }
 
