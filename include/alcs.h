@@ -294,7 +294,10 @@ int alcs_dense_conv(const float *W_dev, const float *X_dev, const float *bias_de
  *                      4 = persistent double-buffered 1x1 kernel with the weights in LDS where
  *                      applicable, 5 = pipelined persistent 1x1 kernel (four groups per
  *                      wavefront, at most 512 input channels and 64 kept columns per group)
- *                      wherever it applies, 6 = never that kernel
+ *                      wherever it applies, 6 = never that kernel and, for 3x3 handles whose
+ *                      pattern is shared by the nine taps, the column-by-column walk instead
+ *                      of the walk over channel records; 7 = that record walk wherever it
+ *                      exists (V = 4 or 8; the default takes it with pixels_per_lane 2 only)
  *     tile_width       output-tile width of the 3x3 kernel: 8, 16 or 32 (tile height 64/width)
  *     groups_per_wave  groups whose accumulators a wavefront of the chunked 1x1 kernel and of
  *                      the 3x3 kernel holds: 2 or 4 (automatic: 4, or 2 when the layer has few
@@ -480,7 +483,8 @@ int alcs_pack_weights_device(const float *W_dev, const uint8_t *mask_dev, int Co
 /* What the last alcs_sparse_conv call of this thread launched: fills up to `cap`
  * ints {mode (1 = all input channels resident in LDS, 2 = chunked, 3 = 3x3,
  * 4 = persistent double-buffered with the weights in LDS, 5 = pipelined persistent,
- * 6 = the 16-bit kernel of alcs_sparse_conv_bf16_mfma, whose path reads 3),
+ * 6 = the 16-bit kernel of alcs_sparse_conv_bf16_mfma, whose path reads 3,
+ * 7 = 3x3 walking channel records (handles whose pattern is shared by the nine taps)),
  * pv, waves, workgroups, lds_bytes, group_tiles,
  * chunk_channels, path, group_slots, tile_width (3x3 only, else 0)} and returns how many were
  * written.  For tests and benchmarks. */

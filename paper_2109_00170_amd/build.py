@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libalcs.so")
-SOURCES = ["alcs_pack.cpp", "alcs_latency.cpp", "alcs_sparse.hip", "alcs_sparse_fused.hip", "alcs_sparse_dw.hip", "alcs_sparse_bf16.hip", "alcs_sparse_math16.hip", "alcs_depthwise.hip", "alcs_project.hip", "alcs_packdev.hip", "alcs_layoutdev.hip", "alcs_dense.hip"]
+SOURCES = ["alcs_pack.cpp", "alcs_latency.cpp", "alcs_sparse.hip", "alcs_sparse_fused.hip", "alcs_sparse_dw.hip", "alcs_sparse_bf16.hip", "alcs_sparse_math16.hip", "alcs_depthwise.hip", "alcs_project.hip", "alcs_packdev.hip", "alcs_layoutdev.hip", "alcs_chanrec.hip", "alcs_dense.hip"]
 
 # -packed-fp32-ops is switched off on purpose: packed fp32 VALU forms are not used.
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Wall", "-Wno-unused-function",

@@ -160,6 +160,9 @@ struct Layout {
     int64_t ncol = 0; // padded columns in total (multiple of kSegAlign)
     int64_t wplane = 0;  // floats per weight plane: ncol * VV * GS
     int noff = 0;     // 1 for kernel 1; kMaxOff for kernel 3 (one table per stride and tile shape)
+    // kernel 3: every kept input channel of every group keeps all nine taps (the per-channel
+    // pattern copied to the taps); such handles also get channel records on the device
+    bool tap_shared = false;
     std::vector<float> w;          // [planes][wplane]
     std::vector<int32_t> off[kMaxOff];   // [ncol * GS] each; LDS row selector of every block, in bytes:
                                    //   kernel 1: c * kRowBytes1 / GS        (pad: (c0 + KC) * kRowBytes1 / GS)
@@ -184,6 +187,14 @@ struct DeviceCopy {
     // the weight planes rounded to bfloat16 in the layout of the 16-bit matrix instruction, an
     // allocation of its own made by alcs_packed_add_bf16_weights (null before)
     const uint16_t *w16 = nullptr;
+    // Channel records of a tap-shared 3x3 handle (an allocation of its own, null otherwise): per
+    // (bundle, chunk) the first record and the number of records (cwork, two ints), per record the
+    // chunk-relative input channel (csel) and, in each plane of cwplane floats, 64 weights
+    // [tap 0..15][row 0..3] of which taps 9..15 are zero (cw).
+    void *chan_blob = nullptr;
+    const float *cw = nullptr;
+    const int32_t *csel = nullptr, *cwork = nullptr;
+    long long cwplane = 0;
 };
 
 }  // namespace alcs
@@ -218,6 +229,9 @@ void choose_tiles(const alcs_packed *p, int *KC, int *GS);
 // canonical arrays and layout arrays of a handle built on the device, fetched to the host (once)
 int fetch_host_arrays(alcs_packed *p);
 int upload(alcs_packed *p);
+// alcs_chanrec.hip: builds the channel records of a tap-shared 3x3 handle from its device arrays
+// (kernels on `stream`, a hipStream_t; no wait); does nothing for other handles
+int add_channel_records(alcs_packed *p, void *stream);
 void release_device(alcs_packed *p);
 
 // The launch options of a handle in the launchers' short names.

@@ -69,6 +69,23 @@ __global__ void __launch_bounds__(256) k_ld_stats(const int32_t *row_ptr, const 
     if (bad) atomicMax(&scal[1], 1);
 }
 
+// scal[6] = 1 unless every group's kept columns are whole channels of nine taps (3x3 handles)
+__global__ void __launch_bounds__(256) k_ld_tapshared(const int32_t *row_ptr, const int32_t *col_idx, int G, long long nnzb,
+                                                      int *scal) {
+    const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (t >= nnzb) return;
+    int lo = 0, hi = G;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (row_ptr[mid] <= t) lo = mid;
+        else hi = mid;
+    }
+    const int rel = (int)(t - row_ptr[lo]);
+    bool ok = rel % 9 == 0 ? col_idx[t] % 9 == 0 : col_idx[t] == col_idx[t - 1] + 1;
+    if (rel == 0) ok = ok && (row_ptr[lo + 1] - row_ptr[lo]) % 9 == 0;
+    if (!ok) atomicMax(&scal[6], 1);
+}
+
 // order[rank] = g with rank = groups that are longer, or as long with a lower index (the stable
 // descending sort of the host)
 __global__ void __launch_bounds__(256) k_ld_rank(const int32_t *row_ptr, int G, int32_t *order, int32_t *pos) {
@@ -384,6 +401,7 @@ int build_all(const LayerIn *in, int n, void *workspace, size_t workspace_bytes,
         (void)hipStreamSynchronize(st);  // nothing may still write what is freed here
         for (Job &j : jobs) {
             if (j.blob) (void)hipFree(j.blob);
+            if (j.p && j.p->dev.chan_blob) (void)hipFree(j.p->dev.chan_blob);
             delete j.p;
         }
         if (own_ws) (void)hipFree(own_ws);
@@ -451,6 +469,9 @@ int build_all(const LayerIn *in, int n, void *workspace, size_t workspace_bytes,
         if (j.own_arrays && p->nnzb &&
             (rc = enqueue_csr_fill(j.W, j.mask, p->Cout, p->K, p->V, p->G, j.t_rp, j.t_ci, j.t_va, st)) != ALCS_OK)
             return fail(rc);
+        if (p->k == 3 && p->nnzb > 0 && p->nnzb % 9 == 0)
+            hipLaunchKernelGGL(k_ld_tapshared, dim3((unsigned)((p->nnzb + 255) / 256)), dim3(256), 0, st, j.rp, j.ci, p->G,
+                               (long long)p->nnzb, j.scal);
         hipLaunchKernelGGL(k_ld_rank, dim3((p->G + 255) / 256), dim3(256), 0, st, j.rp, p->G, j.order, j.pos);
         if (GS > 1) hipLaunchKernelGGL(k_ld_parity, dim3(p->G), dim3(64), 0, st, j.rp, j.ci, p->k * p->k, j.ev);
         hipLaunchKernelGGL(k_ld_segments, dim3((unsigned)((nseg + 255) / 256)), dim3(256), 0, st, j.sh, j.rp, j.ci, j.order,
@@ -471,6 +492,7 @@ int build_all(const LayerIn *in, int n, void *workspace, size_t workspace_bytes,
         j.used = hs[2];
         if (hs[4] || j.used > INT32_MAX / (4 * GS) - 64) return fail(ALCS_E_UNSUPPORTED);
         L.max_cnt = hs[3];
+        L.tap_shared = p->k == 3 && nnzb > 0 && nnzb % 9 == 0 && hs[6] == 0;
         L.ncol = j.used + kSegAlign;
         L.wplane = L.ncol * L.VV * GS;
         // work | weight planes | selector tables | order | canonical arrays | (parity notes, build only)
@@ -513,6 +535,10 @@ int build_all(const LayerIn *in, int n, void *workspace, size_t workspace_bytes,
         p->dev.row_ptr = (const int32_t *)(bb + q_rp);
         p->dev.col_idx = (const int32_t *)(bb + q_ci);
         p->dev.vals = (const float *)(bb + q_va);
+        p->dev.blob = j.blob;  // for the channel records; taken back below if the call fails
+        rc = add_channel_records(p, st);
+        p->dev.blob = nullptr;
+        if (rc != ALCS_OK) return fail(rc);
     }
     if ((rc = check(hipGetLastError())) != ALCS_OK) return fail(rc);
     if ((rc = check(hipStreamSynchronize(st))) != ALCS_OK) return fail(rc);  // the temporaries are free again

@@ -99,6 +99,17 @@ int build_layout(alcs_packed *p, int KC, int GS) {
         std::stable_sort(L.order.begin(), L.order.end(), [&](int a, int b) {
             return p->row_ptr[a + 1] - p->row_ptr[a] > p->row_ptr[b + 1] - p->row_ptr[b];
         });
+        // tap-shared pattern: the kept columns of every group come as whole channels, nine taps each
+        if (k == 3 && p->nnzb > 0) {
+            bool shared = p->nnzb % 9 == 0;
+            for (int g = 0; g < G && shared; ++g) {
+                const int32_t b = p->row_ptr[g], e = p->row_ptr[g + 1];
+                shared = (e - b) % 9 == 0;
+                for (int32_t t = b; t < e && shared; ++t)
+                    shared = (t - b) % 9 == 0 ? p->col_idx[t] % 9 == 0 : p->col_idx[t] == p->col_idx[t - 1] + 1;
+            }
+            L.tap_shared = shared;
+        }
         // canonical range [lo, hi) of every (group, chunk)
         std::vector<int32_t> lo((size_t)G * L.nchunks), hi((size_t)G * L.nchunks);
         for (int g = 0; g < G; ++g) {
@@ -205,6 +216,7 @@ void release_device(alcs_packed *p) {
         if (elsewhere) (void)hipSetDevice(p->dev.device);
         (void)hipFree(p->dev.blob);
         if (p->dev.w16) (void)hipFree(const_cast<uint16_t *>(p->dev.w16));
+        if (p->dev.chan_blob) (void)hipFree(p->dev.chan_blob);
         if (elsewhere) (void)hipSetDevice(cur);
     }
     p->dev = DeviceCopy();
@@ -258,6 +270,11 @@ int upload(alcs_packed *p) {
     p->dev.work = (const Work *)(base + o_work);
     p->dev.w = (const float *)(base + o_w);
     for (int t = 0; t < kMaxOff; ++t) p->dev.off[t] = t < L.noff ? (const int32_t *)(base + o_off[t]) : nullptr;
+    if (L.tap_shared) {
+        const int rc = add_channel_records(p, nullptr);
+        if (rc == ALCS_OK && (e = hipStreamSynchronize(nullptr)) != hipSuccess) { set_hip_error((int)e); return ALCS_E_HIP; }
+        return rc;  // on failure the caller frees the handle and with it the device memory
+    }
     return ALCS_OK;
 }
 

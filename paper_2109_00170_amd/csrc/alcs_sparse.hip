@@ -152,6 +152,10 @@ struct ConvArgs {
     int ppw;            // streaming kernel: flattened pixels per workgroup (multiple of 4)
     int wfloats;        // streaming kernel: floats in the weight planes, planes * nblk * 4
     int nblk;           // padded blocks (= number of row selectors)
+    // 3x3 with a tap-shared pattern: channel records (see alcs_chanrec.hip), null otherwise
+    const float *cw;
+    const int32_t *csel, *cwork;
+    long long cwplane;
     int act;    // fused epilogue: 0 none, 1 max(., 0), 2 min(max(., 0), 6)
     int debug;  // measurement build only (ALCS_MEASURE): bit 0 skips staging, bit 1 the multiply, bit 2 the stores
 #if ALCS_DW_STAGE
@@ -1127,6 +1131,67 @@ __global__ void __launch_bounds__(512) k_pw_stream(const ConvArgs a) {
     }
 }
 
+// ------------------------------------------------------------------ 3x3, tap-shared pattern
+
+// One (group, chunk) of a handle whose kept channels keep all nine taps: one record per kept
+// CHANNEL (its chunk-relative index and its 9 x V weights, see alcs_chanrec.hip) instead of one
+// column per tap.  The nine LDS reads of a channel differ by compile-time offsets from one
+// address, so the per-column selector broadcast and address add of the column-by-column walk
+// (one vector instruction for every two matrix instructions) shrink to one v_readlane and one
+// add per channel, and a channel's weights are one 256-byte line per plane in block-broadcast
+// order (lane 4t + i = tap t, row i: abid = t) instead of nine sixteenths of two runs.
+// Measured on this GPU the multiply is bound by the sum of vector and matrix instructions
+// issued per SIMD, not by LDS bandwidth: a variant that read each input row once and took the
+// left and right taps from the neighbouring lanes (two DPP shifts per row and pixel, halo words
+// only in the row's end lanes: 3 + 3 narrow reads instead of 9) was 10-30 % SLOWER than the
+// column walk (64->64 @56x56: 91 against 83 us, 256->256 @14x14: 103 against 79), because its
+// 24 extra vector instructions per channel cost more than the 6 reads they saved.
+template <int V, int STRIDE, int TI, bool TALL>
+__device__ __forceinline__ void mac_channels(const ConvArgs &a, int first, int n, const char *ldsb, int lane_byte,
+                                             int lane, Acc<V, TALL ? 2 : 1, true> &acc) {
+    constexpr int PV = TALL ? 2 : 1;
+    constexpr int PD = TALL ? tall_step3(TI) : 1;
+    constexpr int PITCH = pitch3(STRIDE, TI);
+    constexpr int PLANE = halo_area3(STRIDE, TI, TALL) * 4;
+    constexpr int NACC = Acc<V, PV, true>::NACC;
+    if (n <= 0) return;
+    const float *wp = a.cw + (size_t)first * 64 + lane;
+    float wa[V / 4], wb[V / 4];
+#pragma unroll
+    for (int q = 0; q < V / 4; ++q) wa[q] = wp[(size_t)q * a.cwplane];
+    int selv = a.csel[first + min(lane, n - 1)];
+    auto channel = [&](int j, const float (&w)[V / 4]) {
+        const int crel = __builtin_amdgcn_readlane(selv, j & 63);
+        const char *pl = ldsb + lane_byte + crel * PLANE;
+        float x[9][PV];
+        static_for<9>([&](auto tt) {
+            constexpr int T = decltype(tt)::value;
+            lds_read<PV, PD>(reinterpret_cast<const float *>(pl + ((T / 3) * PITCH + halo_col3(STRIDE, TI, T % 3)) * 4), x[T]);
+        });
+        static_for<9>([&](auto tt) {
+            constexpr int T = decltype(tt)::value;
+#pragma unroll
+            for (int q = 0; q < V / 4; ++q)
+#pragma unroll
+                for (int pv = 0; pv < PV; ++pv)
+                    acc.a[T % NACC][q][pv] = __builtin_amdgcn_mfma_f32_4x4x1f32(w[q], x[T][pv], acc.a[T % NACC][q][pv], 4, T, 0);
+        });
+    };
+    for (int j = 0; j < n; j += 2) {
+        // the next record's weights are requested before this one is multiplied; beyond the last
+        // record the last one is read again
+        if ((j & 63) == 0 && j) selv = a.csel[first + j + min(lane, n - j - 1)];
+        const float *w1 = wp + (size_t)min(j + 1, n - 1) * 64;
+#pragma unroll
+        for (int q = 0; q < V / 4; ++q) wb[q] = w1[(size_t)q * a.cwplane];
+        channel(j, wa);
+        const float *w2 = wp + (size_t)min(j + 2, n - 1) * 64;
+#pragma unroll
+        for (int q = 0; q < V / 4; ++q) wa[q] = w2[(size_t)q * a.cwplane];
+        if (j + 1 < n) channel(j + 1, wb);
+    }
+}
+
 // ------------------------------------------------------------------ 3x3 kernel
 
 // One workgroup = one TH x TW tile of output pixels of one image (lane = pixel, see the
@@ -1137,9 +1202,10 @@ __global__ void __launch_bounds__(512) k_pw_stream(const ConvArgs a) {
 // TALL (stride 1, MFMA form): the tile has 2*TH rows and a lane owns the pixels (ly, lx) and
 // (ly + TH, lx), whose LDS words one ds_read2_b32 fetches together: two MFMAs per LDS
 // instruction instead of one, in a kernel whose multiply is bound by its LDS reads.
-template <int V, int STRIDE, int TI, int UG, bool MF, bool TALL = false>
+template <int V, int STRIDE, int TI, int UG, bool MF, bool TALL = false, bool TS = false>
 __global__ void __launch_bounds__(512) k_conv3(const ConvArgs a) {
     static_assert(!TALL || (STRIDE == 1 && MF), "tall tiles: stride 1, MFMA form");
+    static_assert(!TS || MF, "channel records: MFMA form");
     extern __shared__ float lds[];
     constexpr int PV = TALL ? 2 : 1;
     constexpr int PD = TALL ? tall_step3(TI) : 1;
@@ -1189,12 +1255,20 @@ __global__ void __launch_bounds__(512) k_conv3(const ConvArgs a) {
         // that their latency is covered by the staging (vector memory returns in order)
         Work wk[UG];
         Runs<V, MF> rn[UG];
+        int cfirst[UG], cn[UG];
 #pragma unroll
         for (int u = 0; u < UG; ++u) {
             wk[u] = no_work();
+            cfirst[u] = cn[u] = 0;
             if (slot[u] >= 0) {
-                wk[u] = load_work(a.work, (size_t)slot[u] * a.nchunks + ch);
-                rn[u] = load_runs<V, MF>(a, wk[u].start, wk[u].cnt, lane);
+                if constexpr (TS) {
+                    const cptr<int32_t> cwk = as_const(a.cwork) + 2 * ((size_t)slot[u] * a.nchunks + ch);
+                    cfirst[u] = __builtin_amdgcn_readfirstlane(cwk[0]);
+                    cn[u] = __builtin_amdgcn_readfirstlane(cwk[1]);
+                } else {
+                    wk[u] = load_work(a.work, (size_t)slot[u] * a.nchunks + ch);
+                    rn[u] = load_runs<V, MF>(a, wk[u].start, wk[u].cnt, lane);
+                }
             }
         }
         if (ch) __syncthreads();
@@ -1240,10 +1314,17 @@ __global__ void __launch_bounds__(512) k_conv3(const ConvArgs a) {
             }
         }
         __syncthreads();
-        const int base = (lane_base - c0 * HA) * 4;
+        if constexpr (TS) {
 #pragma unroll
-        for (int u = 0; u < UG; ++u)
-            if (slot[u] >= 0 && !skip(a, 2)) mac_segment<V, PV, 0, 1, PD>(a, wk[u].start, wk[u].cnt, ldsb, base, lane, rn[u], acc[u]);
+            for (int u = 0; u < UG; ++u)
+                if (slot[u] >= 0 && !skip(a, 2))
+                    mac_channels<V, STRIDE, TI, TALL>(a, cfirst[u], cn[u], ldsb, lane_base * 4, lane, acc[u]);
+        } else {
+            const int base = (lane_base - c0 * HA) * 4;
+#pragma unroll
+            for (int u = 0; u < UG; ++u)
+                if (slot[u] >= 0 && !skip(a, 2)) mac_segment<V, PV, 0, 1, PD>(a, wk[u].start, wk[u].cnt, ldsb, base, lane, rn[u], acc[u]);
+        }
     }
     const int oy = oy0 + ly, ox = ox0 + lx;
     PixOut<PV> px;
@@ -1464,6 +1545,20 @@ static kern_t pick_conv3_shape(int stride, int ug, bool tall) {
     if (tall) return nullptr;
     if (ug == 2) return stride == 1 ? k_conv3<V, 1, TI, 2, MF> : k_conv3<V, 2, TI, 2, MF>;
     return stride == 1 ? k_conv3<V, 1, TI, 4, MF> : k_conv3<V, 2, TI, 4, MF>;
+}
+// channel-record kernels (tap-shared pattern): MFMA form, V = 4 or 8
+template <int V, int TI>
+static kern_t pick_conv3_shared_shape(int stride, int ug, bool tall) {
+    if (tall && stride == 1) return ug == 2 ? k_conv3<V, 1, TI, 2, true, true, true> : k_conv3<V, 1, TI, 4, true, true, true>;
+    if (tall) return nullptr;
+    if (ug == 2) return stride == 1 ? k_conv3<V, 1, TI, 2, true, false, true> : k_conv3<V, 2, TI, 2, true, false, true>;
+    return stride == 1 ? k_conv3<V, 1, TI, 4, true, false, true> : k_conv3<V, 2, TI, 4, true, false, true>;
+}
+template <int V>
+static kern_t pick_conv3_shared(int stride, int ti, int ug, bool tall) {
+    if (ti == 2) return pick_conv3_shared_shape<V, 2>(stride, ug, tall);
+    if (ti == 1) return pick_conv3_shared_shape<V, 1>(stride, ug, tall);
+    return pick_conv3_shared_shape<V, 0>(stride, ug, tall);
 }
 template <int V, bool MF>
 static kern_t pick_conv3(int stride, int ti, int ug, bool tall) {
@@ -1830,10 +1925,16 @@ static int launch_sparse(const alcs_packed_t *Wp, const io_t *X_dev, const float
         bool tall = stride == 1 && mfma && V <= 8 &&
                     (T.pv == 2 || (T.pv == 0 && Ho >= 12 && Wo >= 12));
         ti = pick_tile3(Ho, Wo, T.tile_w, tall);
+        // Handles with channel records (the pattern is shared by the nine taps) and groups of 4 or 8
+        // channels walk records instead of columns; "path" = 6 keeps the column-by-column kernel.
+        // By default only with tall tiles, where it measures 0-7 % faster (128->128 @28x28, N=64: 71.4
+        // -> 66.5 us; 256->256 @14x14: 80.6 -> 78.3; 64->64 @56x56 equal); with one pixel per lane it
+        // is slower (512->512 stride 2: 129 -> 157 us), "path" = 7 asks for it anyway.
         if (tall && (L.KC + 1) * halo_area3(stride, ti, true) * 4 > kMaxLds) {
             tall = false;
             ti = pick_tile3(Ho, Wo, T.tile_w, false);
         }
+        const bool shared = Wp->dev.cw && mfma && V <= 8 && T.path != 6 && (tall || T.path == 7);
         pv = tall ? 2 : 1;
         a.off = Wp->dev.off[off_table3(stride, ti, tall)];
         lds = (L.KC + 1) * halo_area3(stride, ti, tall) * 4;
@@ -1859,6 +1960,11 @@ static int launch_sparse(const alcs_packed_t *Wp, const io_t *X_dev, const float
             case 8: kern = pick_conv3<8, true>(stride, ti, ug, tall); break;
             case 16: kern = pick_conv3<16, true>(stride, ti, ug, tall); break;
         }
+        if (shared) {
+            a.cw = Wp->dev.cw; a.csel = Wp->dev.csel; a.cwork = Wp->dev.cwork; a.cwplane = Wp->dev.cwplane;
+            kern = V == 4 ? pick_conv3_shared<4>(stride, ti, ug, tall) : pick_conv3_shared<8>(stride, ti, ug, tall);
+            mode = 7;
+        }
 #endif
     }
     (void)ug; (void)ti; (void)G;
@@ -1874,7 +1980,7 @@ static int launch_sparse(const alcs_packed_t *Wp, const io_t *X_dev, const float
     a.wg_per_xcd = ceil_div(total, kXcds);
     int rc = set_lds_limit(kern, lds);
     if (rc != ALCS_OK) return rc;
-    record_launch(mode, pv, nw, a.total_wgs, lds, a.ngt, L.KC, mfma ? 2 : 1, L.GS, mode == 3 ? tile_w3(ti) : 0);
+    record_launch(mode, pv, nw, a.total_wgs, lds, a.ngt, L.KC, mfma ? 2 : 1, L.GS, (mode == 3 || mode == 7) ? tile_w3(ti) : 0);
     const int grid = mode == 4 ? a.npt : a.wg_per_xcd * kXcds;
     if (ev_start || ev_stop) {
         // the events take the kernel's own begin and end time stamps (no gap for event

@@ -29,7 +29,9 @@ def test_packer_latency_model_and_oracle_under_asan_and_ubsan(tmp_path):
                     '    int N, int Cin, int Cout, int H, int W, int kernel, int stride, void *) {\n'
                     '  if (!Wp || N < 0 || H <= 0 || W <= 0 || !X || !Y) return ALCS_E_INVALID_ARG;\n'
                     '  if (Cin != Wp->Cin || Cout != Wp->Cout || kernel != Wp->k) return ALCS_E_INVALID_ARG;\n'
-                    '  (void)stride; return Wp->dev.blob ? ALCS_E_UNSUPPORTED : ALCS_E_NO_DEVICE; }\n')
+                    '  (void)stride; return Wp->dev.blob ? ALCS_E_UNSUPPORTED : ALCS_E_NO_DEVICE; }\n'
+                    '// device-side part of the upload (never reached without a GPU)\n'
+                    'namespace alcs { int add_channel_records(alcs_packed *, void *) { return ALCS_OK; } }\n')
     oracle_o = str(tmp_path / "oracle.o")
     subprocess.check_call([clang.replace("clang++", "clang"), "-std=c99", "-c", os.path.join(ROOT, "oracle", "alcs_oracle.c"),
                            "-o", oracle_o] + san)
