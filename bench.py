@@ -46,8 +46,10 @@ def kernel_symbol(L, info):
         return "alcs::k_pw_resident<%d, %d, %s, %s, %d>" % (L.V, info["pv"], b(mf), b(vec), info["group_slots"])
     if info["mode"] == 2:
         return "alcs::k_pw_chunked<%d, %d, 4, %s, %s>" % (L.V, info["pv"], b(mf), b(vec))
-    if info["mode"] == 3:
-        return "alcs::k_conv3<%d, %d, 4, %s>" % (L.V, L.stride, b(mf))
+    if info["mode"] in (3, 7):
+        return "alcs::k_conv3<%d, %d" % (L.V, L.stride)          # prefix: tile shape and flags follow
+    if info["mode"] == 5:
+        return "alcs::k_pw_pipe<%d" % L.V
     return "alcs::k_pw_stream<%d, %d, 8>" % (L.V, info["pv"])
 
 

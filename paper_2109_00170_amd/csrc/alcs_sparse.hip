@@ -1765,15 +1765,19 @@ static int launch_sparse(const alcs_packed_t *Wp, const io_t *X_dev, const float
             const int tp = (P % 32 != 0 && P % 28 == 0) ? 28 : 32;
             const long long tiles = ((long long)a.NP + tp - 1) / tp;
             // 16 wavefronts with at most two bundles each, whose weights (segments of at most 64
-            // columns, i.e. four runs) stay in registers for the whole kernel.  Longer segments would
-            // need temporaries for the runs beyond the fourth, which the 128 registers a lane has at
-            // 16 wavefronts per workgroup do not hold (a variant with 12 wavefronts of three bundles
-            // and one with a single temporary both spilled 15-28 registers): such layers keep the
-            // resident kernel.
-            const int pnw = 16, kmax = 2;
-            const bool fits = L.max_cnt <= 16 * Runs<4, true, 4>::N;
+            // columns, i.e. four runs) stay in registers for the whole kernel; 128 registers a lane
+            // at 16 wavefronts per workgroup hold no more (a variant with 12 wavefronts of three
+            // bundles and one with a single temporary both spilled 15-28 registers).
+            // Segments of 65 to 96 columns: one bundle per wavefront (twice the group tiles), which
+            // leaves registers for the two temporaries of the runs beyond the fourth - on request
+            // only ("path" = 5): with every tile staged by two workgroups and loads inside the
+            // multiply it is slower than the resident kernel (512->512 @14x14, N=256, 90 % sparse:
+            // 91 against 80 us).
+            const bool lng = L.max_cnt > 16 * Runs<4, true, 4>::N;
+            const int pnw = 16, kmax = lng ? 1 : 2;
+            const bool fits = L.max_cnt <= 16 * (Runs<4, true, 4>::N + 2);
             const int ngt_p = ceil_div(L.nbundles, kmax * pnw);
-            if (fits && (T.path == 5 || tiles * ngt_p >= 3LL * kCUs)) {
+            if (fits && (T.path == 5 || (!lng && tiles * ngt_p >= 3LL * kCUs))) {
                 pipe_ok = true;
                 mode = 5;
                 pv = 2; nw = pnw;
@@ -1786,7 +1790,8 @@ static int launch_sparse(const alcs_packed_t *Wp, const io_t *X_dev, const float
                 wg_count = (long long)ranges * a.ngt;
                 const bool cached = ((long long)P * sizeof(io_t)) % 128 != 0;
                 // a pass of the workgroup stages 128 rows of 8 pixel quads: four rows per thread
-                kern = cached ? k_pw_pipe<4, true, 1024, 2, 4, false> : k_pw_pipe<4, false, 1024, 2, 4, false>;
+                if (lng) kern = cached ? k_pw_pipe<4, true, 1024, 1, 4, true> : k_pw_pipe<4, false, 1024, 1, 4, true>;
+                else kern = cached ? k_pw_pipe<4, true, 1024, 2, 4, false> : k_pw_pipe<4, false, 1024, 2, 4, false>;
             }
         }
 #endif

@@ -297,3 +297,16 @@ def test_pointwise_pipelined_persistent(Cin, Cout, H, W, N):
     for with_bias in (False, True):
         info = check(L, 77 + Cin + Cout, with_bias=with_bias, group_slots=4, path=5)
         assert info["mode"] == 5 and info["group_slots"] == 4, info
+
+
+@pytest.mark.parametrize("Cin,Cout,sparsity,N", [(512, 136, 0.87, 40), (200, 72, 0.62, 12), (160, 40, 0.55, 30)])
+def test_pointwise_pipelined_persistent_long_segments(Cin, Cout, sparsity, N):
+    """Segments of 65 to 96 columns: one bundle per wavefront, the runs beyond the fourth through
+    two temporaries inside the multiply."""
+    L = workloads.Layer("pipe_long_%d" % Cin, Cin, Cout, 14, 14, k=1, stride=1, N=N, V=4, sparsity=sparsity, w_std=0.2,
+                        x_dist="uniform")
+    d = workloads.make_layer(L, 91 + Cin)
+    longest = int(d.mask.reshape(L.G, -1).sum(axis=1).max())
+    assert 64 < longest <= 96, longest
+    info = check(L, 91 + Cin, with_bias=True, group_slots=4, path=5)
+    assert info["mode"] == 5 and info["group_slots"] == 4, info
