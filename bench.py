@@ -225,8 +225,8 @@ def report(kind, alcs, workloads, torch, np):
         MUL_TFLOPS = 72.5
         EMPTY_US = 3.9
         pr("| layer | Cin->Cout | HxW | roofline us (8 TB/s) | copy of the same bytes us | multiply alone us | empty kernel us | "
-           "measured us | measured / roofline | copy / measured |")
-        pr("|---|---|---|---|---|---|---|---|---|---|")
+           "measured us | measured / roofline | copy / measured | at least 50 % of the roofline |")
+        pr("|---|---|---|---|---|---|---|---|---|---|---|")
         tot = tcopy = troof = 0.0
         for i, L in enumerate(workloads.mobilenet_v1_pointwise(32, 0.9)):
             r = time_layer(alcs, torch, np, workloads, L, workloads.seed_for(2, i))
@@ -254,8 +254,9 @@ def report(kind, alcs, workloads, torch, np):
             tot += r["us"]
             tcopy += c_us
             troof += r["roof_us"]
-            pr("| %s | %d->%d | %d | %.2f | %.2f | %.2f | %.1f | %.2f | %.2f | %.2f |" %
-               (L.name, L.Cin, L.Cout, L.H, r["roof_us"], c_us, m_us, EMPTY_US, r["us"], r["us"] / r["roof_us"], c_us / r["us"]))
+            pr("| %s | %d->%d | %d | %.2f | %.2f | %.2f | %.1f | %.2f | %.2f | %.2f | %s |" %
+               (L.name, L.Cin, L.Cout, L.H, r["roof_us"], c_us, m_us, EMPTY_US, r["us"], r["us"] / r["roof_us"], c_us / r["us"],
+                "yes" if 2 * r["roof_us"] >= r["us"] else "no"))
             del Xr, Yr
             torch.cuda.empty_cache()
         pr("\n13 layers: measured %.0f us, copies of the same bytes %.0f us, rooflines %.0f us" % (tot, tcopy, troof))
