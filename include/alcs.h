@@ -443,7 +443,8 @@ int alcs_topn_mask_static(const float *scores_dev, long long n_blocks, long long
  *   like alcs_pack_from_csr checks them on the host (ALCS_E_INVALID_ARG).  `options` as for
  *   alcs_pack_weights_opt (NULL = automatic).  The call returns with the handle complete (it
  *   synchronises `stream`); alcs_packed_export and alcs_packed_selfcheck fetch the arrays to the
- *   host on first use.  More than 16384 groups: ALCS_E_UNSUPPORTED (go through the host).
+ *   host on first use.  With more than 16384 groups (an FC layer of more than 16384 * V outputs) the
+ *   arrays are copied to the host once and the layout is built there, as alcs_pack_from_csr does.
  *
  * alcs_pack_weights_device: W_dev and mask_dev as for alcs_pack_csr_device -> handle, i.e. the
  *   two calls above in one with the intermediate arrays in a temporary of the library (sized for
@@ -458,7 +459,8 @@ int alcs_topn_mask_static(const float *scores_dev, long long n_blocks, long long
  *   alcs_pack_workspace_bytes(layers, n_layers) bytes, 256-byte aligned, the caller's, free for
  *   other use when the call returns; NULL (workspace_bytes ignored) lets the call allocate and
  *   free it itself.  alcs_pack_workspace_bytes depends on the layers' shapes and options only
- *   (it sizes for every block kept) and returns a negative status for shapes the packer refuses.
+ *   (it sizes for every block kept) and returns a negative status for shapes the packer refuses;
+ *   layers of more than 16384 groups are not taken here (ALCS_E_UNSUPPORTED: pack them one by one).
  */
 typedef struct alcs_layer_desc {
     const float *W_dev;       /* [Cout, Cin, kernel, kernel] */

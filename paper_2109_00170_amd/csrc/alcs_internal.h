@@ -223,6 +223,9 @@ void set_hip_error(int e);
 void device_shape(int device, int *cus, int *xcds);
 int current_device_shape(int *cus, int *xcds);  // of the current device; ALCS_OK or ALCS_E_HIP
 int check_options(const alcs_options *o);  // ALCS_OK or ALCS_E_INVALID_ARG
+// alcs_pack_from_csr with the handle's options (null = automatic)
+int pack_from_csr_host(const int32_t *row_ptr_host, const int32_t *col_idx_host, const float *vals_host, int Cout,
+                       int Cin, int kernel, int V, const alcs_options *options, alcs_packed_t **out);
 int build_layout(alcs_packed *p, int KC, int GS);
 // tile policy: channels per chunk and groups per wavefront of a handle, from its shape and options
 void choose_tiles(const alcs_packed *p, int *KC, int *GS);

@@ -274,7 +274,7 @@ int check(hipError_t e) {
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-int check_shape(int Cout, int Cin, int kernel, int V) {
+int check_shape(int Cout, int Cin, int kernel, int V) {  // the limits of alcs_pack_weights
     if (Cout <= 0 || Cin <= 0) return ALCS_E_INVALID_ARG;
     if (kernel != 1 && kernel != 3) return ALCS_E_UNSUPPORTED;
     if (V != 1 && V != 2 && V != 4 && V != 8 && V != 16) return ALCS_E_UNSUPPORTED;
@@ -282,8 +282,38 @@ int check_shape(int Cout, int Cin, int kernel, int V) {
     if (K64 > (1 << 24) || Cout > (1 << 24)) return ALCS_E_UNSUPPORTED;
     const int G = (Cout + V - 1) / V;
     if ((int64_t)G * K64 > (int64_t)INT32_MAX - 1024) return ALCS_E_UNSUPPORTED;
-    if (G > kRankLimit) return ALCS_E_UNSUPPORTED;
     return ALCS_OK;
+}
+
+// More groups than the quadratic rank kernel takes (an FC layer with more than 16384 * V outputs):
+// the canonical arrays go to the host once and alcs_pack.cpp builds the layout there.
+bool too_many_groups(int Cout, int V) { return (Cout + V - 1) / V > kRankLimit; }
+
+int through_the_host(const int32_t *rp_dev, const int32_t *ci_dev, const float *va_dev, int Cout, int Cin, int kernel, int V,
+                     const alcs_options *options, hipStream_t st, alcs_packed_t **out) {
+    const int G = (Cout + V - 1) / V;
+    std::vector<int32_t> rp, ci;
+    std::vector<float> va;
+    try {
+        rp.resize((size_t)G + 1);
+        int rc = check(hipMemcpyAsync(rp.data(), rp_dev, 4 * ((size_t)G + 1), hipMemcpyDeviceToHost, st));
+        if (rc == ALCS_OK) rc = check(hipStreamSynchronize(st));
+        if (rc != ALCS_OK) return rc;
+        const long long nnzb = rp[(size_t)G];
+        if (nnzb < 0 || nnzb > (long long)G * Cin * kernel * kernel) return ALCS_E_INVALID_ARG;
+        if (nnzb > 0 && (!ci_dev || !va_dev)) return ALCS_E_INVALID_ARG;
+        ci.resize((size_t)nnzb);
+        va.resize((size_t)nnzb * V);
+        if (nnzb) {
+            rc = check(hipMemcpyAsync(ci.data(), ci_dev, 4 * (size_t)nnzb, hipMemcpyDeviceToHost, st));
+            if (rc == ALCS_OK) rc = check(hipMemcpyAsync(va.data(), va_dev, 4 * (size_t)nnzb * V, hipMemcpyDeviceToHost, st));
+            if (rc == ALCS_OK) rc = check(hipStreamSynchronize(st));
+            if (rc != ALCS_OK) return rc;
+        }
+    } catch (const std::bad_alloc &) {
+        return ALCS_E_ALLOC;
+    }
+    return pack_from_csr_host(rp.data(), ci.data(), va.data(), Cout, Cin, kernel, V, options, out);
 }
 
 // One layer on its way to a handle.
@@ -369,6 +399,7 @@ int build_all(const LayerIn *in, int n, void *workspace, size_t workspace_bytes,
     for (int i = 0; i < n; ++i) out[i] = nullptr;
     for (int i = 0; i < n; ++i) {
         int rc = check_shape(in[i].Cout, in[i].Cin, in[i].kernel, in[i].V);
+        if (rc == ALCS_OK && too_many_groups(in[i].Cout, in[i].V)) rc = ALCS_E_UNSUPPORTED;
         if (rc == ALCS_OK && in[i].opt) rc = check_options(in[i].opt);
         if (rc != ALCS_OK) return rc;
         if (!in[i].W && !in[i].rp) return ALCS_E_INVALID_ARG;
@@ -561,6 +592,8 @@ extern "C" int alcs_pack_from_csr_device(const int32_t *row_ptr_dev, const int32
                                          void *stream, alcs_packed_t **out) {
     if (out) *out = nullptr;
     if (!row_ptr_dev || !out) return ALCS_E_INVALID_ARG;
+    if (check_shape(Cout, Cin, kernel, V) == ALCS_OK && too_many_groups(Cout, V))
+        return through_the_host(row_ptr_dev, col_idx_dev, vals_dev, Cout, Cin, kernel, V, options, (hipStream_t)stream, out);
     const LayerIn in{nullptr, nullptr, row_ptr_dev, col_idx_dev, vals_dev, Cout, Cin, kernel, V, options};
     return build_all(&in, 1, nullptr, 0, (hipStream_t)stream, out);
 }
@@ -569,6 +602,23 @@ extern "C" int alcs_pack_weights_device(const float *W_dev, const uint8_t *mask_
                                         const alcs_options *options, void *stream, alcs_packed_t **out) {
     if (out) *out = nullptr;
     if (!W_dev || !out) return ALCS_E_INVALID_ARG;
+    if (check_shape(Cout, Cin, kernel, V) == ALCS_OK && too_many_groups(Cout, V)) {
+        // the storage format on the device, then through the host
+        const int G = (Cout + V - 1) / V;
+        const long long cap = (long long)G * Cin * kernel * kernel;
+        const size_t o_ci = align256(4 * (size_t)(G + 1)), o_va = align256(o_ci + 4 * (size_t)cap);
+        void *tmp = nullptr;
+        int rc = check(hipMalloc(&tmp, o_va + 4 * (size_t)cap * V));
+        if (rc != ALCS_OK) return rc;
+        char *tb = (char *)tmp;
+        rc = alcs_pack_csr_device(W_dev, mask_dev, Cout, Cin, kernel, V, (int32_t *)tb, (int32_t *)(tb + o_ci),
+                                  (float *)(tb + o_va), cap, nullptr, stream);
+        if (rc == ALCS_OK)
+            rc = through_the_host((const int32_t *)tb, (const int32_t *)(tb + o_ci), (const float *)(tb + o_va), Cout, Cin,
+                                  kernel, V, options, (hipStream_t)stream, out);
+        (void)hipFree(tmp);
+        return rc;
+    }
     const LayerIn in{W_dev, mask_dev, nullptr, nullptr, nullptr, Cout, Cin, kernel, V, options};
     return build_all(&in, 1, nullptr, 0, (hipStream_t)stream, out);
 }
@@ -579,6 +629,7 @@ extern "C" long long alcs_pack_workspace_bytes(const alcs_layer_desc *layers, in
     for (int i = 0; i < n_layers; ++i) {
         const alcs_layer_desc &d = layers[i];
         int rc = check_shape(d.Cout, d.Cin, d.kernel, d.V);
+        if (rc == ALCS_OK && too_many_groups(d.Cout, d.V)) rc = ALCS_E_UNSUPPORTED;
         if (rc == ALCS_OK && d.options) rc = check_options(d.options);
         if (rc != ALCS_OK) return rc;
         need += carve(nullptr, nullptr, d.Cout, d.Cin, d.kernel, d.V, d.options, true);

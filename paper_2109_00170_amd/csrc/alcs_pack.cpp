@@ -478,6 +478,13 @@ int alcs_pack_weights_opt(const float *W_host, const uint8_t *mask_host, int Cou
 
 int alcs_pack_from_csr(const int32_t *row_ptr_host, const int32_t *col_idx_host, const float *vals_host,
                        int Cout, int Cin, int kernel, int V, alcs_packed_t **out) {
+    return alcs::pack_from_csr_host(row_ptr_host, col_idx_host, vals_host, Cout, Cin, kernel, V, nullptr, out);
+}
+
+}  // extern "C"
+
+int alcs::pack_from_csr_host(const int32_t *row_ptr_host, const int32_t *col_idx_host, const float *vals_host,
+                             int Cout, int Cin, int kernel, int V, const alcs_options *options, alcs_packed_t **out) {
     if (out) *out = nullptr;
     if (!row_ptr_host || !out || Cout <= 0 || Cin <= 0) return ALCS_E_INVALID_ARG;
     if (kernel != 1 && kernel != 3) return ALCS_E_UNSUPPORTED;
@@ -513,8 +520,10 @@ int alcs_pack_from_csr(const int32_t *row_ptr_host, const int32_t *col_idx_host,
     } catch (const std::bad_alloc &) {
         rc = ALCS_E_ALLOC;
     }
-    return finish_pack(p, rc, nullptr, out);
+    return finish_pack(p, rc, options, out);
 }
+
+extern "C" {
 
 int alcs_packed_info(const alcs_packed_t *p, int *G, int *K, int64_t *nnzb) {
     if (!p) return ALCS_E_INVALID_ARG;

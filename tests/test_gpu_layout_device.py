@@ -163,3 +163,30 @@ def test_network_in_one_call_equals_layer_by_layer():
         alcs.alcs_pack_network_device(Wd, [None] * 7, [4, 4, 4, 4, 3, 8, 4])          # V = 3
     assert ei.value.status == -2
     torch.cuda.synchronize()
+
+
+def test_more_groups_than_the_rank_kernel_takes_go_through_the_host():
+    """20000 groups (V = 1): the device entry points fetch the arrays once and build the layout on the host."""
+    import torch
+    rng = np.random.default_rng(4199)
+    Cout, Cin, V = 20000, 24, 1
+    W = (rng.standard_normal((Cout, Cin, 1, 1)) * 0.2).astype(np.float32)
+    mask = workloads.mask_exact(Cout, Cin, 1, 0.7, rng)
+    host = alcs.alcs_pack_weights(W, mask, V)
+    dev = alcs.alcs_pack_weights_device(torch.from_numpy(W).cuda(), torch.from_numpy(mask).cuda(), V)
+    assert dev.layout_hash() == host.layout_hash() and dev.selfcheck() == 0
+    rp, ci, va = oracle.pack(W, mask, V)
+    dev2 = alcs.alcs_pack_from_csr_device(torch.from_numpy(rp).cuda(), torch.from_numpy(ci).cuda(), torch.from_numpy(va).cuda(),
+                                          Cout, Cin, 1, V)
+    assert dev2.layout_hash() == host.layout_hash()
+    with pytest.raises(alcs.AlcsError) as ei:
+        alcs.alcs_pack_network_device([torch.from_numpy(W).cuda()], [None], V)
+    assert ei.value.status == -2
+    X = rng.standard_normal((2, Cin, 3, 3)).astype(np.float32)
+    Y = torch.empty((2, Cout, 3, 3), device="cuda")
+    alcs.alcs_sparse_conv(dev, torch.from_numpy(X).cuda(), None, Y)
+    torch.cuda.synchronize()
+    ref = oracle.sparse_conv(W, mask, X, V)
+    assert float(np.max(np.abs(Y.cpu().numpy() - ref))) <= TOL * float(np.max(np.abs(ref)))
+    for h in (host, dev, dev2):
+        h.free()
