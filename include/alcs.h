@@ -283,7 +283,7 @@ int alcs_dense_conv(const float *W_dev, const float *X_dev, const float *bias_de
  *                      input channels through LDS in chunks)
  *     group_slots      output-channel groups multiplied per wavefront by the 1x1 kernels: 1, 2
  *                      or 4 (automatic: 1 below 512 input channels or for V < 4; from 512
- *                      channels on 4 for V = 4 when no group keeps more than twice the mean
+ *                      channels on 4 for V = 4 or 8 when no group keeps more than twice the mean
  *                      number of columns, else 2; 4 from 1280 channels on)
  *   read at every launch:
  *     pixels_per_lane  1x1 kernels: 1, 2 or 4 (1 or 2 with several groups per wavefront);

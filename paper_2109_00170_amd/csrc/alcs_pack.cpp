@@ -283,15 +283,16 @@ int upload(alcs_packed *p) {
 // input channels on (V >= 4 only) the tile shrinks to 32 or 16 pixels and a wavefront
 // multiplies 2 or 4 groups: two workgroups then share a compute unit and one fills its
 // tile while the other multiplies (512 channels: 512->1024 @7x7 16.9 -> 11.0 us).
-// Up to 1279 channels, V = 4 and groups of similar length (the longest at most twice the
+// Up to 1279 channels, V = 4 or 8 and groups of similar length (the longest at most twice the
 // mean) take 4 groups per wavefront, each on 16 lanes that hold two pixels of the 32-pixel
 // tile, which halves the LDS row reads per kept weight (512->512 @14x14: 17.2 us with one
 // group per wavefront, 17.1 with two, 15.6 with four; 512->128 @28x28, N=64: 58 -> 43 us).
 // With groups of very different lengths a workgroup's time is the walk through its longest
 // bundle, which two pixels per lane make 1.5x longer (576->96 @14x14, longest group 6x the
-// mean: 39 us with two groups per wavefront, 45 with four); V = 8 and 16 gain nothing from
-// four (their accumulators already alternate).  With 256 input channels one group per
-// wavefront stays ahead.
+// mean: 39 us with two groups per wavefront, 45 with four).  V = 8 takes four as well (512->1024
+// @7x7, N=32: 12.9 -> 10.0 us, 1024->1024 @7x7: 19.4 -> 15.4, 512->512 @14x14 unchanged); V = 16
+// does not (512->512 @14x14: 15 us with two, 22 with four - 32 accumulator registers per pixel
+// pair).  With 256 input channels one group per wavefront stays ahead.
 // Beyond 2558 channels, or beyond 639 for V < 4, chunks of 256 channels.
 // Kernel 3: 32 channels per chunk (the haloed tile plane is 240 to 476 floats per channel);
 // 64 from 512 input channels on - such layers sit on 14x14 and 7x7 images, where a workgroup's
@@ -303,7 +304,7 @@ static void default_tiles(int Cin, int k, int V, bool even_groups, int *KC, int 
     if (k == 3) { *KC = Cin >= 512 ? 64 : std::min(Cin, 32); return; }
     if (V >= 4 && Cin >= 512 && Cin <= 2558) {
         *KC = Cin;
-        *GS = (Cin > 1279 || (V == 4 && even_groups)) ? 4 : 2;
+        *GS = (Cin > 1279 || (V <= 8 && even_groups)) ? 4 : 2;
         return;
     }
     if (Cin <= 639) { *KC = Cin; return; }

@@ -1777,7 +1777,11 @@ static int launch_sparse(const alcs_packed_t *Wp, const io_t *X_dev, const float
             const int pnw = 16, kmax = lng ? 1 : 2;
             const bool fits = L.max_cnt <= 16 * (Runs<4, true, 4>::N + 2);
             const int ngt_p = ceil_div(L.nbundles, kmax * pnw);
-            if (fits && (T.path == 5 || (!lng && tiles * ngt_p >= 3LL * kCUs))) {
+            // (by itself only from 257 input channels on: with fewer, a handle packed with four groups per
+            // wavefront on request is faster through the resident kernel - 256->256 @28x28, N=32: 16.6 us
+            // against 22.7, 32->64 @112x112: 25 against 54 - the 32-pixel tiles' 128-byte runs cost more
+            // than the overlap gains when the multiply is short)
+            if (fits && (T.path == 5 || (!lng && Cin > 256 && tiles * ngt_p >= 3LL * kCUs))) {
                 pipe_ok = true;
                 mode = 5;
                 pv = 2; nw = pnw;
