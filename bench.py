@@ -521,10 +521,12 @@ def report(kind, alcs, workloads, torch, np):
         def one(L, seed):
             d = workloads.make_layer(L, seed, with_bias=True)
             p = alcs.alcs_pack_weights(d.W, d.mask, L.V)
-            small = L.Cin <= 639
-            p16 = alcs.alcs_pack_weights(d.W, d.mask, L.V, options={"group_slots": 1}) if small else None
-            if p16 is not None:
-                p16.add_bf16_weights()
+            p16 = None
+            try:
+                p.add_bf16_weights()                       # the same handle serves all three entry points
+                p16 = p
+            except alcs.AlcsError:
+                pass                                       # more input channels than one 16-bit tile holds
             b = torch.from_numpy(d.bias).cuda()
             X = torch.from_numpy(d.X).cuda()
             R = max(2, min(8, int(600e6 // (L.x_bytes() + L.y_bytes())) + 1))
@@ -564,7 +566,6 @@ def report(kind, alcs, workloads, torch, np):
                 m16(0)
                 torch.cuda.synchronize()
                 diff = float((Y32[0] - Y16[0].float()).abs().max() / Y32[0].abs().max().clamp_min(1e-30))
-                p16.free()
             wb = layer_bytes(L, p.nnzb) - L.x_bytes() - L.y_bytes()
             by16 = (L.x_bytes() + L.y_bytes()) // 2 + wb // 2 + 4 * L.Cout
             p.free()

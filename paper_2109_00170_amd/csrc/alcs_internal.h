@@ -184,9 +184,12 @@ struct DeviceCopy {
     // group order and the canonical arrays, which the host fetches only when it is asked for them
     const int32_t *order = nullptr, *row_ptr = nullptr, *col_idx = nullptr;
     const float *vals = nullptr;
-    // the weight planes rounded to bfloat16 in the layout of the 16-bit matrix instruction, an
-    // allocation of its own made by alcs_packed_add_bf16_weights (null before)
+    // the 16-bit layout made by alcs_packed_add_bf16_weights (null before; one allocation of its own
+    // that starts at w16): weight planes rounded to bfloat16 in the order of the 16-bit matrix
+    // instruction, row selectors for 256-byte rows, one work record per group
     const uint16_t *w16 = nullptr;
+    const int32_t *off16 = nullptr;
+    const Work *work16 = nullptr;
     // Channel records of a tap-shared 3x3 handle (an allocation of its own, null otherwise): per
     // (bundle, chunk) the first record and the number of records (cwork, two ints), per record the
     // chunk-relative input channel (csel) and, in each plane of cwplane floats, 64 weights

@@ -52,6 +52,7 @@ struct Args {
     int N, Cin, Cout, H, W, Ho, Wo, stride;
     int P, Pin, NP;
     int G, ngt, gpt;
+    int zero_rows;  // all-zero rows behind the Cin rows of the tile: 1, or 2 for handles with several groups per wavefront
     int tile_px;  // pixels of the flattened axis per workgroup (<= kTilePx, a multiple of 4)
     int wg_per_xcd, total_wgs, xcds;
     int act;
@@ -377,7 +378,7 @@ __global__ void __launch_bounds__(1024) k_pw16(const Args a) {
         if (nth(1) < ng) w1 = load_work(a.work, g_begin + nth(1));
     }
     stage<VEC>(a, lds, q0, q_end);
-    if (tid < kRowBytes / 4) reinterpret_cast<unsigned int *>(lds + (size_t)a.Cin * kRowBytes)[tid] = 0u;  // the zero row
+    if (tid < a.zero_rows * (kRowBytes / 4)) reinterpret_cast<unsigned int *>(lds + (size_t)a.Cin * kRowBytes)[tid] = 0u;  // the zero row(s)
     __syncthreads();
     if (!any) return;
     touch_runs<V>(run0);
@@ -402,19 +403,32 @@ __global__ void __launch_bounds__(1024) k_pw16(const Args a) {
     }
 }
 
-// The handle's float32 weight planes (one group per wavefront: 4 floats a column) rounded to
-// bfloat16 and laid out for the instruction: word (col / 16) * 64 + ((col % 16) / 4) * 16 + i * 4
-// + col % 4 of plane q = channel 4q + i of padded column col.
-__global__ void __launch_bounds__(256) k_w16(const float *w, long long wplane, uint16_t *w16, long long wplane16,
-                                             int planes) {
-    const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (e >= wplane16 * planes) return;
-    const int q = (int)(e / wplane16);
-    const long long d = e - (long long)q * wplane16;
-    const long long R = d / 64;
-    const int within = (int)(d % 64), l = within / 4, k = within % 4, b = l / 4, i = l % 4;
-    const long long col = 16 * R + 4 * b + k;
-    w16[e] = (uint16_t)(pack_bf2(w[(size_t)q * wplane + col * 4 + i], 0.f) & 0xffffu);
+// The 16-bit layout of a handle, derived from the arrays every 1x1 handle has (one workgroup per
+// bundle): every group gets a segment of its own again, also where the float32 layout interleaves
+// the groups of a bundle - slot s of the bundle that starts at padded column `start` with `span`
+// columns (its length rounded up to 16) goes to columns GS * start + s * span ... of the 16-bit
+// arrays.  Per column: the weights rounded to bfloat16 (nearest even), word (col / 16) * 64 + ((col
+// % 16) / 4) * 16 + 4 i + col % 4 of plane q = channel 4q + i; the row selector scaled to 256-byte
+// rows; and per group a work record {first column, padded length, group}.
+__global__ void __launch_bounds__(256) k_layout16(const Work *work, const float *w, long long wplane, const int32_t *off,
+                                                  int GS, int planes, int Cin, Work *work16, uint16_t *w16,
+                                                  long long wplane16, int32_t *off16) {
+    const int b = blockIdx.x;
+    const Work wk = work[b];
+    const int span = (wk.cnt + 15) & ~15;
+    for (int s = 0; s < GS; ++s) {
+        const long long first = (long long)GS * wk.start + (long long)s * span;
+        if (threadIdx.x == 0) work16[(size_t)b * GS + s] = Work{(int32_t)first, wk.cnt, {wk.group[s], -1, -1, -1}, {0, 0}};
+        for (int e = threadIdx.x; e < span * 4 * planes; e += 256) {
+            const int q = e / (span * 4), r = e - q * span * 4, j = r >> 2, i = r & 3;
+            const long long col = first + j;
+            const float v = j < wk.cnt ? w[(size_t)q * wplane + layout_w_index(GS, 4, (long long)wk.start + j, s, i)] : 0.f;
+            w16[(size_t)q * wplane16 + (col / 16) * 64 + ((col % 16) / 4) * 16 + i * 4 + col % 4] =
+                (uint16_t)(pack_bf2(v, 0.f) & 0xffffu);
+        }
+        for (int j = threadIdx.x; j < span; j += 256)
+            off16[first + j] = j < wk.cnt ? off[layout_off_index(GS, (long long)wk.start + j, s)] * GS : Cin * kRowBytes;
+    }
 }
 
 typedef void (*kern_t)(const Args);
@@ -434,9 +448,11 @@ static int check(hipError_t e) {
 
 using namespace alcs;
 
+static int zero_rows16(const alcs_packed_t *p) { return p->lay.GS > 1 ? 2 : 1; }
+
 static bool math16_layout(const alcs_packed_t *p) {
-    return p->k == 1 && p->V >= 4 && p->lay.GS == 1 && p->lay.nchunks == 1 &&
-           (long long)(p->Cin + 1) * m16::kRowBytes <= 160 * 1024;
+    return p->k == 1 && p->V >= 4 && p->lay.nchunks == 1 &&
+           (long long)(p->Cin + zero_rows16(p)) * m16::kRowBytes <= 160 * 1024;
 }
 
 extern "C" int alcs_packed_add_bf16_weights(alcs_packed_t *p, void *stream) {
@@ -450,17 +466,32 @@ extern "C" int alcs_packed_add_bf16_weights(alcs_packed_t *p, void *stream) {
     if (rc != ALCS_OK) return rc;
     if (cur != p->dev.device) return ALCS_E_INVALID_ARG;
     const Layout &L = p->lay;
-    const long long wplane16 = L.ncol * 4;
+    const long long ncol16 = L.ncol * L.GS, wplane16 = ncol16 * 4;
+    auto align256 = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    const size_t o_w = 0;
+    const size_t o_off = align256((size_t)wplane16 * L.planes * sizeof(uint16_t));
+    const size_t o_work = align256(o_off + 4 * (size_t)ncol16);
+    const size_t total = align256(o_work + sizeof(Work) * (size_t)L.nbundles * L.GS) + 256;
     void *buf = nullptr;
-    if ((rc = m16::check(hipMalloc(&buf, (size_t)wplane16 * L.planes * sizeof(uint16_t) + 256))) != ALCS_OK) return rc;
-    const long long total = wplane16 * L.planes;
-    hipLaunchKernelGGL(m16::k_w16, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream, p->dev.w,
-                       (long long)L.wplane, (uint16_t *)buf, wplane16, L.planes);
-    if ((rc = m16::check(hipGetLastError())) != ALCS_OK) {
+    if ((rc = m16::check(hipMalloc(&buf, total))) != ALCS_OK) return rc;
+    char *bb = (char *)buf;
+    hipStream_t st = (hipStream_t)stream;
+    // what no bundle covers (the spare run at the end): zero weights, selector of the zero row
+    hipError_t e = hipMemsetAsync(bb + o_w, 0, o_off, st);
+    if (e == hipSuccess) e = hipMemsetAsync(bb + o_off, 0, 4 * (size_t)ncol16, st);
+    if (e == hipSuccess) {
+        hipLaunchKernelGGL(m16::k_layout16, dim3((unsigned)L.nbundles), dim3(256), 0, st, p->dev.work, p->dev.w,
+                           (long long)L.wplane, p->dev.off[0], L.GS, L.planes, p->Cin, (Work *)(bb + o_work),
+                           (uint16_t *)(bb + o_w), wplane16, (int32_t *)(bb + o_off));
+        e = hipGetLastError();
+    }
+    if ((rc = m16::check(e)) != ALCS_OK) {
         (void)hipFree(buf);
         return rc;
     }
-    p->dev.w16 = (const uint16_t *)buf;
+    p->dev.w16 = (const uint16_t *)(bb + o_w);
+    p->dev.off16 = (const int32_t *)(bb + o_off);
+    p->dev.work16 = (const Work *)(bb + o_work);
     return ALCS_OK;
 }
 
@@ -492,13 +523,14 @@ extern "C" int alcs_sparse_conv_bf16_mfma(const alcs_packed_t *Wp, const uint16_
     const int kCUs = Wp->dev.cus, kXcds = Wp->dev.xcds;
     m16::Args a{};
     a.X = X_dev; a.residual = residual_dev; a.Y = Y_dev; a.bias = bias_dev;
-    a.work = Wp->dev.work; a.w16 = Wp->dev.w16; a.off = Wp->dev.off[0];
-    a.wplane16 = L.ncol * 4;
+    a.work = Wp->dev.work16; a.w16 = Wp->dev.w16; a.off = Wp->dev.off16;
+    a.wplane16 = L.ncol * L.GS * 4;
+    a.zero_rows = zero_rows16(Wp);
     a.N = N; a.Cin = Cin; a.Cout = Cout; a.H = H; a.W = W; a.Ho = Ho; a.Wo = Wo; a.stride = stride;
     a.P = (int)P; a.Pin = (int)Pin; a.NP = (int)NP;
     a.G = Wp->G;
     const bool vec = stride == 1 && P % 4 == 0;
-    const int lds = (Cin + 1) * m16::kRowBytes;
+    const int lds = (Cin + a.zero_rows) * m16::kRowBytes;
     const int npt_full = (int)((NP + m16::kTilePx - 1) / m16::kTilePx);
     // group tiles only when the pixel tiles alone leave compute units idle (every group tile
     // stages the pixel tile's rows again)

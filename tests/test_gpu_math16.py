@@ -88,6 +88,17 @@ def test_group_tiles_and_wavefront_counts_16bit(tiles, waves):
         assert info["group_tiles"] == min(tiles, 32)
 
 
+@pytest.mark.parametrize("V", [4, 8, 16])
+@pytest.mark.parametrize("slots", [0, 2, 4])
+def test_handles_with_several_groups_per_wavefront_16bit(V, slots):
+    """Handles whose float32 layout interleaves the groups of a bundle (the default from 512 input
+    channels on): the 16-bit layout gives every group a segment of its own again."""
+    L = workloads.Layer("m16_gs%d_v%d" % (slots, V), 520, 5 * V + 2, 12, 12, N=3, V=V, sparsity=0.9, w_std=0.1)
+    run_m16(L, 5570 + V + slots, act="relu", with_res=True, options={"group_slots": slots} if slots else None)
+    Lu = workloads.Layer("m16_gsu%d_v%d" % (slots, V), 638, 3 * V, 7, 7, N=5, V=V, sparsity=0.8, w_std=0.1, mask_kind="zipf")
+    run_m16(Lu, 5575 + V + slots, options={"group_slots": slots} if slots else None)
+
+
 def test_in_place_residual_no_bias_and_device_built_handle_16bit():
     L = workloads.Layer("m16_inplace", 64, 64, 14, 14, N=4, V=8, sparsity=0.8, w_std=0.3)
     run_m16(L, 5590, act="relu", with_res=True, in_place=True, with_bias=False, on_device=True)
@@ -102,9 +113,9 @@ def test_mobilenet_shapes_16bit():
 
 def test_unsupported_layouts_and_rejected_arguments_16bit():
     import torch
-    # 3x3 handles, several groups per wavefront, chunked layouts and V < 4 are refused
+    # 3x3 handles, more input channels than one 16-bit tile holds, chunked layouts and V < 4 are refused
     for L in (workloads.Layer("m16_3x3", 16, 8, 8, 8, k=3, N=1, V=4, sparsity=0.5),
-              workloads.Layer("m16_gs", 520, 16, 4, 4, N=1, V=4, sparsity=0.9),
+              workloads.Layer("m16_wide", 700, 16, 4, 4, N=1, V=4, sparsity=0.9),
               workloads.Layer("m16_chunk", 700, 8, 4, 4, N=1, V=2, sparsity=0.9),
               workloads.Layer("m16_v2", 16, 8, 4, 4, N=1, V=2, sparsity=0.5)):
         d = workloads.make_layer(L, 5700)
