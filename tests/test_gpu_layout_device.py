@@ -39,6 +39,9 @@ CASES = [
     (16, 16, 1, 4, 1.0, None, True),            # nothing kept
     (16, 24, 1, 4, 0.0, None, True),            # everything kept
     (1024, 512, 1, 4, 0.9, None, True),         # a MobileNet-sized layer
+    (4400, 24, 1, 4, 0.5, None, False),         # 1100 segments: the scan of their starts takes two rounds
+    (2000, 700, 1, 2, 0.9, None, True),         # 1000 groups x 3 chunks
+    (300, 100, 3, 4, 0.8, None, False),         # 3x3, four chunks
 ]
 
 

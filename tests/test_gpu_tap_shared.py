@@ -111,3 +111,10 @@ def test_resnet_shaped_layers_at_two_images():
     for (c, hw) in ((64, 56), (128, 28), (256, 14)):
         L = workloads.Layer("ts_rn_%d" % c, c, c, hw, hw, k=3, N=2, V=4, sparsity=0.8, w_std=0.1, tap_shared=True)
         run(L, 6200 + c)
+
+
+def test_more_than_1024_segments():
+    """520 groups x 3 chunks: the scan that numbers the channel records takes two rounds."""
+    L = workloads.Layer("ts_many", 96, 2080, 12, 12, k=3, N=1, V=4, sparsity=0.9, w_std=0.2, tap_shared=True)
+    run(L, 6210)
+    run(L, 6210, on_device=True)
