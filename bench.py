@@ -588,7 +588,7 @@ def report(kind, alcs, workloads, torch, np):
                        (L.name, L.Cin, L.Cout, L.H, a, b_, c, a / c, b_ / c, by16 / 1e6, by16 / c / 1e3,
                         by16 / (HBM_PEAK_GBS * 1e3) / c, diff))
                 else:
-                    pr("| %s %d->%d @%d | %.1f | %.1f | n/a (input channels beyond one 16-bit tile) | | | | | | |" %
+                    pr("| %s %d->%d @%d | %.1f | %.1f | n/a (more than 1278 input channels) | | | | | | |" %
                        (L.name, L.Cin, L.Cout, L.H, a, b_))
             pr("| layers with a 16-bit time | %.0f | %.0f | %.0f | %.2f | %.2f | | | | |" %
                (tot[0], tot[1], tot[2], tot[0] / tot[2], tot[1] / tot[2]))

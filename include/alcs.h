@@ -213,10 +213,11 @@ int alcs_sparse_conv_bf16(const alcs_packed_t *Wp, const uint16_t *X_dev, const 
  *   instruction's layout (device memory of the handle, freed with it; a kernel on `stream`, no
  *   wait: use the handle on that stream, or synchronise first).  Once per handle; a second call
  *   does nothing.  Handles it takes: kernel 1, V in {4, 8, 16}, all input channels in one
- *   on-chip tile of 256-byte rows: at most 638 input channels (639 for handles with one group per
- *   wavefront); handles that alcs_pack_weights built with several groups per wavefront are taken
- *   as they are (every group gets a segment of its own in the 16-bit arrays).  Others
- *   ALCS_E_UNSUPPORTED.  ALCS_E_NO_DEVICE
+ *   on-chip tile: at most 1278 input channels (1279 for handles with one group per wavefront;
+ *   up to 638 the tile has 128 pixels and a lane two of them, beyond that 64 and one); handles
+ *   that alcs_pack_weights built with several groups per wavefront are taken as they are (every
+ *   group gets a segment of its own in the 16-bit arrays).  Others ALCS_E_UNSUPPORTED.
+ *   ALCS_E_NO_DEVICE
  *   for a handle without a device copy; the handle's device must be current.
  * alcs_sparse_conv_bf16_mfma: arguments and errors as alcs_sparse_conv_bf16, the three tensors
  *   16-byte aligned; ALCS_E_INVALID_ARG for a handle without the rounded weights.

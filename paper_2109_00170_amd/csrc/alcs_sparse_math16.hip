@@ -38,8 +38,7 @@ typedef float f2 __attribute__((ext_vector_type(2)));
 typedef unsigned int u2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
 
-constexpr int kTilePx = 128;   // pixels per tile: 64 lanes x 2
-constexpr int kRowBytes = 256; // bytes per LDS row = kRowBytes1, the selectors' unit
+constexpr int kRowBytes = 256; // bytes per LDS row with two pixels per lane = kRowBytes1, the selectors' unit
 
 struct Args {
     const uint16_t *X, *residual;
@@ -135,16 +134,18 @@ __device__ __forceinline__ void touch_runs(Runs<V> &rs) {
 }
 
 // Partial sums: acc[k][q][pv][i] = channel 4q+i of the group, pixel pv of the lane; two partial
-// sets (k) for V = 4, whose two chains per column quad would otherwise wait for each other.
-template <int V>
+// sets (k) where a lane has a single chain per column quad (V = 4 with one pixel per lane).
+template <int V, int PV>
 struct Acc {
-    static constexpr int NACC = V == 4 ? 2 : 1;
-    f4 a[NACC][V / 4][2];
+    static constexpr int NACC = (V / 4) * PV == 1 ? 2 : 1;
+    f4 a[NACC][V / 4][PV];
     __device__ __forceinline__ void zero() {
 #pragma unroll
         for (int k = 0; k < NACC; ++k)
 #pragma unroll
-            for (int q = 0; q < V / 4; ++q) a[k][q][0] = a[k][q][1] = f4{0.f, 0.f, 0.f, 0.f};
+            for (int q = 0; q < V / 4; ++q)
+#pragma unroll
+                for (int pv = 0; pv < PV; ++pv) a[k][q][pv] = f4{0.f, 0.f, 0.f, 0.f};
     }
     __device__ __forceinline__ float get(int q, int pv, int i) const {
         float s = a[0][q][pv][i];
@@ -153,47 +154,59 @@ struct Acc {
     }
 };
 
-// Columns B0 .. B0+7 of the current run: eight LDS reads (both pixels of the lane each), then per
-// column quad the two input operands and V/4 * 2 matrix instructions.
-template <int B0, int V>
-__device__ __forceinline__ void mfma_batch(const s4 (&aw)[V / 4], int ov, const char *lds, int base, Acc<V> &acc) {
+// Columns B0 .. B0+7 of the current run: eight LDS reads, then per column quad the input operand(s)
+// and V/4 * PV matrix instructions.  PV = 2: a 4-byte read fetches both pixels of the lane and two
+// byte permutes per column pair sort the halves; PV = 1: 2-byte reads, one shift-or per column pair.
+template <int B0, int V, int PV>
+__device__ __forceinline__ void mfma_batch(const s4 (&aw)[V / 4], int ov, const char *lds, int base, Acc<V, PV> &acc) {
     unsigned int x[8];
     static_for<8>([&](auto c) {
         constexpr int C = decltype(c)::value;
-        x[C] = *reinterpret_cast<const unsigned int *>(lds + base + bcast_sel<B0 + C>(ov));
+        if constexpr (PV == 2) x[C] = *reinterpret_cast<const unsigned int *>(lds + base + bcast_sel<B0 + C>(ov));
+        else x[C] = *reinterpret_cast<const uint16_t *>(lds + base + bcast_sel<B0 + C>(ov));
     });
     __builtin_amdgcn_sched_barrier(0);
     static_for<2>([&](auto kq) {
         constexpr int K4 = decltype(kq)::value;
         constexpr int ABID = B0 / 4 + K4;
-        // element k of an operand = column 4*ABID + k; low halves are the lane's first pixel
-        const unsigned int lo01 = __builtin_amdgcn_perm(x[4 * K4 + 1], x[4 * K4 + 0], 0x05040100u);
-        const unsigned int lo23 = __builtin_amdgcn_perm(x[4 * K4 + 3], x[4 * K4 + 2], 0x05040100u);
-        const unsigned int hi01 = __builtin_amdgcn_perm(x[4 * K4 + 1], x[4 * K4 + 0], 0x07060302u);
-        const unsigned int hi23 = __builtin_amdgcn_perm(x[4 * K4 + 3], x[4 * K4 + 2], 0x07060302u);
-        const s4 b0 = __builtin_bit_cast(s4, u2{lo01, lo23});
-        const s4 b1 = __builtin_bit_cast(s4, u2{hi01, hi23});
-        constexpr int K = ABID % Acc<V>::NACC;
+        constexpr int K = ABID % Acc<V, PV>::NACC;
+        // element k of an operand = column 4*ABID + k
+        if constexpr (PV == 2) {
+            // low halves are the lane's first pixel
+            const unsigned int lo01 = __builtin_amdgcn_perm(x[4 * K4 + 1], x[4 * K4 + 0], 0x05040100u);
+            const unsigned int lo23 = __builtin_amdgcn_perm(x[4 * K4 + 3], x[4 * K4 + 2], 0x05040100u);
+            const unsigned int hi01 = __builtin_amdgcn_perm(x[4 * K4 + 1], x[4 * K4 + 0], 0x07060302u);
+            const unsigned int hi23 = __builtin_amdgcn_perm(x[4 * K4 + 3], x[4 * K4 + 2], 0x07060302u);
+            const s4 b0 = __builtin_bit_cast(s4, u2{lo01, lo23});
+            const s4 b1 = __builtin_bit_cast(s4, u2{hi01, hi23});
 #pragma unroll
-        for (int q = 0; q < V / 4; ++q) {
-            acc.a[K][q][0] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(aw[q], b0, acc.a[K][q][0], 4, ABID, 0);
-            acc.a[K][q][1] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(aw[q], b1, acc.a[K][q][1], 4, ABID, 0);
+            for (int q = 0; q < V / 4; ++q) {
+                acc.a[K][q][0] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(aw[q], b0, acc.a[K][q][0], 4, ABID, 0);
+                acc.a[K][q][1] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(aw[q], b1, acc.a[K][q][1], 4, ABID, 0);
+            }
+        } else {
+            const s4 b0 = __builtin_bit_cast(s4, u2{x[4 * K4 + 0] | (x[4 * K4 + 1] << 16), x[4 * K4 + 2] | (x[4 * K4 + 3] << 16)});
+#pragma unroll
+            for (int q = 0; q < V / 4; ++q)
+                acc.a[K][q][0] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(aw[q], b0, acc.a[K][q][0], 4, ABID, 0);
         }
     });
 }
 
 // One segment: the kept columns of one group (padded to a multiple of 8).  `rs` holds its first
 // runs; longer segments re-fill register set i right after its use with the run two places on.
-template <int V>
+// The selectors are byte offsets for 256-byte rows; one pixel per lane has 128-byte rows.
+template <int V, int PV>
 __device__ __forceinline__ void mac_segment(const Args &a, int start, int cnt, const char *lds, int base, int lane,
-                                            Runs<V> rs, Acc<V> &acc) {
+                                            Runs<V> rs, Acc<V, PV> &acc) {
     auto pass = [&](int j0) {
         static_for<kRunsAhead>([&](auto ii) {
             constexpr int I = decltype(ii)::value;
             const int j = j0 + 16 * I;
             if (j < cnt) {
-                mfma_batch<0, V>(rs.r[I].a, rs.r[I].o, lds, base, acc);
-                if (j + 8 < cnt) mfma_batch<8, V>(rs.r[I].a, rs.r[I].o, lds, base, acc);
+                const int ov = PV == 2 ? rs.r[I].o : rs.r[I].o >> 1;
+                mfma_batch<0, V, PV>(rs.r[I].a, ov, lds, base, acc);
+                if (j + 8 < cnt) mfma_batch<8, V, PV>(rs.r[I].a, ov, lds, base, acc);
                 if (j + 16 * kRunsAhead < cnt) rs.r[I] = load_run<V>(a, start + j + 16 * kRunsAhead, lane);
             }
         });
@@ -202,16 +215,17 @@ __device__ __forceinline__ void mac_segment(const Args &a, int start, int cnt, c
     for (int j0 = 16 * kRunsAhead; j0 < cnt; j0 += 16 * kRunsAhead) pass(j0);
 }
 
-// The tile's rows from HBM to LDS.  VEC: stride 1 and P a multiple of 4, so that four consecutive
-// pixels of the flattened axis lie in one image and their 8 bytes are aligned.
-template <bool VEC>
+// The tile's rows (64 * PV pixels, 128 * PV bytes each) from HBM to LDS.  VEC: stride 1 and P a
+// multiple of 4, so that four consecutive pixels of the flattened axis lie in one image and their 8
+// bytes are aligned; with P a multiple of 8, eight pixels (16 bytes) per lane.
+template <int PV, bool VEC>
 __device__ __forceinline__ void stage(const Args &a, char *lds, int q0, int q_end) {
+    constexpr int TP = 64 * PV, RB = 128 * PV;
     const int tid = threadIdx.x, nt = blockDim.x;
     if constexpr (VEC) {
         if ((a.P & 7) == 0) {
-            // eight pixels (16 bytes) per lane
             typedef unsigned int u4 __attribute__((ext_vector_type(4)));
-            constexpr int NO = kTilePx / 8;
+            constexpr int NO = TP / 8;
             const int oct = tid % NO, r0 = tid / NO, rpp = nt / NO;
             const int q = q0 + oct * 8;
             const bool valid = q < q_end;
@@ -229,16 +243,16 @@ __device__ __forceinline__ void stage(const Args &a, char *lds, int q0, int q_en
                     if (valid) v[u] = *reinterpret_cast<const u4 *>(src + (size_t)(r + u * rpp) * a.P);
                 }
 #pragma unroll
-                for (int u = 0; u < U; ++u) *reinterpret_cast<u4 *>(dst + (r + u * rpp) * kRowBytes) = v[u];
+                for (int u = 0; u < U; ++u) *reinterpret_cast<u4 *>(dst + (r + u * rpp) * RB) = v[u];
             }
             for (; r < a.Cin; r += rpp) {
                 u4 v0 = u4{0u, 0u, 0u, 0u};
                 if (valid) v0 = *reinterpret_cast<const u4 *>(src + (size_t)r * a.P);
-                *reinterpret_cast<u4 *>(dst + r * kRowBytes) = v0;
+                *reinterpret_cast<u4 *>(dst + r * RB) = v0;
             }
             return;
         }
-        constexpr int NQ = kTilePx / 4;
+        constexpr int NQ = TP / 4;
         const int quad = tid % NQ, r0 = tid / NQ, rpp = nt / NQ;
         const int q = q0 + quad * 4;
         const bool valid = q < q_end;
@@ -256,15 +270,15 @@ __device__ __forceinline__ void stage(const Args &a, char *lds, int q0, int q_en
                 if (valid) v[u] = *reinterpret_cast<const u2 *>(src + (size_t)(r + u * rpp) * a.P);
             }
 #pragma unroll
-            for (int u = 0; u < U; ++u) *reinterpret_cast<u2 *>(dst + (r + u * rpp) * kRowBytes) = v[u];
+            for (int u = 0; u < U; ++u) *reinterpret_cast<u2 *>(dst + (r + u * rpp) * RB) = v[u];
         }
         for (; r < a.Cin; r += rpp) {
             u2 v0 = u2{0u, 0u};
             if (valid) v0 = *reinterpret_cast<const u2 *>(src + (size_t)r * a.P);
-            *reinterpret_cast<u2 *>(dst + r * kRowBytes) = v0;
+            *reinterpret_cast<u2 *>(dst + r * RB) = v0;
         }
     } else {
-        const int e = tid % kTilePx, r0 = tid / kTilePx, rpp = nt / kTilePx;  // the launcher gives >= 128 threads
+        const int e = tid % TP, r0 = tid / TP, rpp = nt / TP;  // the launcher gives at least 128 threads
         const int q = q0 + e;
         const bool valid = q < q_end;
         const int n = valid ? q / a.P : 0;
@@ -279,22 +293,23 @@ __device__ __forceinline__ void stage(const Args &a, char *lds, int q0, int q_en
 #pragma unroll
             for (int u = 0; u < U; ++u) v[u] = valid ? src[(size_t)(r + u * rpp) * a.Pin] : (uint16_t)0;
 #pragma unroll
-            for (int u = 0; u < U; ++u) dst[(r + u * rpp) * kTilePx] = v[u];
+            for (int u = 0; u < U; ++u) dst[(r + u * rpp) * TP] = v[u];
         }
-        for (; r < a.Cin; r += rpp) dst[r * kTilePx] = valid ? src[(size_t)r * a.Pin] : (uint16_t)0;
+        for (; r < a.Cin; r += rpp) dst[r * TP] = valid ? src[(size_t)r * a.Pin] : (uint16_t)0;
     }
 }
 
-// Where the lane's two pixels go in Y (element offsets of channel 0), and whether they exist.
+// Where the lane's pixel(s) go in Y (element offsets of channel 0), and whether they exist.
+template <int PV>
 struct PixOut {
-    size_t o[2];
-    bool ok[2];
+    size_t o[PV];
+    bool ok[PV];
 };
 
-template <bool VEC>
-__device__ __forceinline__ PixOut pix_out(const Args &a, int q0, int lane, int q_end) {
-    PixOut px;
-    if constexpr (VEC) {
+template <int PV, bool VEC>
+__device__ __forceinline__ PixOut<PV> pix_out(const Args &a, int q0, int lane, int q_end) {
+    PixOut<PV> px;
+    if constexpr (VEC && PV == 2) {
         const int q = q0 + 2 * lane;  // P is even: both pixels lie in one image
         px.ok[0] = px.ok[1] = q < q_end;
         const int n = px.ok[0] ? q / a.P : 0;
@@ -302,8 +317,8 @@ __device__ __forceinline__ PixOut pix_out(const Args &a, int q0, int lane, int q
         px.o[1] = px.o[0] + 1;
     } else {
 #pragma unroll
-        for (int pv = 0; pv < 2; ++pv) {
-            const int q = q0 + 2 * lane + pv;
+        for (int pv = 0; pv < PV; ++pv) {
+            const int q = q0 + PV * lane + pv;
             px.ok[pv] = q < q_end;
             const int n = px.ok[pv] ? q / a.P : 0;
             px.o[pv] = (size_t)n * a.Cout * a.P + (px.ok[pv] ? q - n * a.P : 0);
@@ -318,8 +333,8 @@ __device__ __forceinline__ float activate(const Args &a, float v) {
     return v;
 }
 
-template <int V, bool VEC>
-__device__ __forceinline__ void store_group(const Args &a, const Acc<V> &acc, int g, const PixOut &px) {
+template <int V, int PV, bool VEC>
+__device__ __forceinline__ void store_group(const Args &a, const Acc<V, PV> &acc, int g, const PixOut<PV> &px) {
     const cptr<float> bias = (cptr<float>)(uintptr_t)a.bias;
 #pragma unroll
     for (int q = 0; q < V / 4; ++q)
@@ -328,10 +343,10 @@ __device__ __forceinline__ void store_group(const Args &a, const Acc<V> &acc, in
             const int ch = g * V + 4 * q + i;  // wave-uniform
             if (ch >= a.Cout) continue;
             const float b = a.bias ? bias[ch] : 0.f;
-            float v0 = acc.get(q, 0, i) + b, v1 = acc.get(q, 1, i) + b;
             const size_t co = (size_t)ch * a.P;
-            if constexpr (VEC) {
+            if constexpr (VEC && PV == 2) {
                 if (!px.ok[0]) continue;
+                float v0 = acc.get(q, 0, i) + b, v1 = acc.get(q, 1, i) + b;
                 if (a.residual) {
                     const unsigned int r = *reinterpret_cast<const unsigned int *>(a.residual + px.o[0] + co);
                     v0 += widen(r & 0xffffu);
@@ -340,27 +355,26 @@ __device__ __forceinline__ void store_group(const Args &a, const Acc<V> &acc, in
                 __builtin_nontemporal_store(pack_bf2(activate(a, v0), activate(a, v1)),
                                             reinterpret_cast<unsigned int *>(a.Y + px.o[0] + co));
             } else {
-                if (px.ok[0]) {
-                    if (a.residual) v0 += widen(a.residual[px.o[0] + co]);
-                    __builtin_nontemporal_store((uint16_t)(pack_bf2(activate(a, v0), 0.f) & 0xffffu), a.Y + px.o[0] + co);
-                }
-                if (px.ok[1]) {
-                    if (a.residual) v1 += widen(a.residual[px.o[1] + co]);
-                    __builtin_nontemporal_store((uint16_t)(pack_bf2(activate(a, v1), 0.f) & 0xffffu), a.Y + px.o[1] + co);
+#pragma unroll
+                for (int pv = 0; pv < PV; ++pv) {
+                    if (!px.ok[pv]) continue;
+                    float v = acc.get(q, pv, i) + b;
+                    if (a.residual) v += widen(a.residual[px.o[pv] + co]);
+                    __builtin_nontemporal_store((uint16_t)(pack_bf2(activate(a, v), 0.f) & 0xffffu), a.Y + px.o[pv] + co);
                 }
             }
         }
 }
 
-template <int V, bool VEC>
+template <int V, int PV, bool VEC>
 __global__ void __launch_bounds__(1024) k_pw16(const Args a) {
     extern __shared__ char lds[];
+    constexpr int RB = 128 * PV;
     // consecutive logical ids share a pixel tile and land on the same XCD (L2)
     const int logical = ((int)blockIdx.x % a.xcds) * a.wg_per_xcd + (int)blockIdx.x / a.xcds;
     if (logical >= a.total_wgs) return;
     const int pt = logical / a.ngt, gt = logical - pt * a.ngt;
-    // the workgroup's pixels [q0, q_end): the whole tile, or fewer when the launcher evens out the
-    // workgroups per compute unit (the rest of the tile is staged as zeros and not stored)
+    // the workgroup's pixels [q0, q_end)
     const int q0 = pt * a.tile_px;
     const int q_end = min(a.NP, q0 + a.tile_px);
     const int tid = threadIdx.x, lane = tid & 63;
@@ -377,13 +391,13 @@ __global__ void __launch_bounds__(1024) k_pw16(const Args a) {
         run0 = load_runs<V>(a, w0.start, w0.cnt, lane);
         if (nth(1) < ng) w1 = load_work(a.work, g_begin + nth(1));
     }
-    stage<VEC>(a, lds, q0, q_end);
-    if (tid < a.zero_rows * (kRowBytes / 4)) reinterpret_cast<unsigned int *>(lds + (size_t)a.Cin * kRowBytes)[tid] = 0u;  // the zero row(s)
+    stage<PV, VEC>(a, lds, q0, q_end);
+    if (tid < a.zero_rows * (RB / 4)) reinterpret_cast<unsigned int *>(lds + (size_t)a.Cin * RB)[tid] = 0u;  // the zero row(s)
     __syncthreads();
     if (!any) return;
     touch_runs<V>(run0);
-    const PixOut px = pix_out<VEC>(a, q0, lane, q_end);
-    const int base = lane * 4;
+    const PixOut<PV> px = pix_out<PV, VEC>(a, q0, lane, q_end);
+    const int base = lane * 2 * PV;
     for (int k = 0;; ++k) {
         const bool more = nth(k + 1) < ng;
         Work w2 = Work{0, 0, {-1, -1, -1, -1}, {0, 0}};
@@ -391,11 +405,11 @@ __global__ void __launch_bounds__(1024) k_pw16(const Args a) {
             run1 = load_runs<V>(a, w1.start, w1.cnt, lane);
             if (nth(k + 2) < ng) w2 = load_work(a.work, g_begin + nth(k + 2));
         }
-        Acc<V> acc;
+        Acc<V, PV> acc;
         acc.zero();
-        mac_segment<V>(a, w0.start, w0.cnt, lds, base, lane, run0, acc);
+        mac_segment<V, PV>(a, w0.start, w0.cnt, lds, base, lane, run0, acc);
         if (more) touch_runs<V>(run1);
-        store_group<V, VEC>(a, acc, w0.group[0], px);
+        store_group<V, PV, VEC>(a, acc, w0.group[0], px);
         if (!more) break;
         w0 = w1;
         w1 = w2;
@@ -433,8 +447,9 @@ __global__ void __launch_bounds__(256) k_layout16(const Work *work, const float 
 
 typedef void (*kern_t)(const Args);
 template <int V>
-static kern_t pick(bool vec) {
-    return vec ? k_pw16<V, true> : k_pw16<V, false>;
+static kern_t pick(int pv, bool vec) {
+    if (pv == 2) return vec ? k_pw16<V, 2, true> : k_pw16<V, 2, false>;
+    return vec ? k_pw16<V, 1, true> : k_pw16<V, 1, false>;
 }
 
 static int check(hipError_t e) {
@@ -452,7 +467,7 @@ static int zero_rows16(const alcs_packed_t *p) { return p->lay.GS > 1 ? 2 : 1; }
 
 static bool math16_layout(const alcs_packed_t *p) {
     return p->k == 1 && p->V >= 4 && p->lay.nchunks == 1 &&
-           (long long)(p->Cin + zero_rows16(p)) * m16::kRowBytes <= 160 * 1024;
+           (long long)(p->Cin + zero_rows16(p)) * (m16::kRowBytes / 2) <= 160 * 1024;  // one pixel per lane: 128-byte rows
 }
 
 extern "C" int alcs_packed_add_bf16_weights(alcs_packed_t *p, void *stream) {
@@ -530,8 +545,17 @@ extern "C" int alcs_sparse_conv_bf16_mfma(const alcs_packed_t *Wp, const uint16_
     a.P = (int)P; a.Pin = (int)Pin; a.NP = (int)NP;
     a.G = Wp->G;
     const bool vec = stride == 1 && P % 4 == 0;
-    const int lds = (Cin + a.zero_rows) * m16::kRowBytes;
-    const int npt_full = (int)((NP + m16::kTilePx - 1) / m16::kTilePx);
+    // Two pixels per lane (128-pixel tiles, 256-byte rows) where the rows fit; one pixel per lane
+    // (64-pixel tiles) beyond 638 input channels and for fewer than 4096 pixels in all, where the
+    // many group tiles of a 128-pixel tile each stage twice the rows (512->1024 @7x7, N=32: 13.5 ->
+    // 11.3 us; from 14x14 images on two pixels per lane win by 5-20 %); "pixels_per_lane" decides.
+    const bool fits2 = (long long)(Cin + a.zero_rows) * m16::kRowBytes <= 160 * 1024;
+    int pv = fits2 && NP >= 4096 ? 2 : 1;
+    if (T.pv == 1) pv = 1;
+    if (T.pv == 2 && fits2) pv = 2;
+    const int tile = 64 * pv;
+    const int lds = (Cin + a.zero_rows) * (m16::kRowBytes / 2) * pv;
+    const int npt_full = (int)((NP + tile - 1) / tile);
     // group tiles only when the pixel tiles alone leave compute units idle (every group tile
     // stages the pixel tile's rows again)
     // With tiles of which at most two fit a compute unit aim at one round (<= one workgroup per
@@ -555,7 +579,7 @@ extern "C" int alcs_sparse_conv_bf16_mfma(const alcs_packed_t *Wp, const uint16_
     // Full tiles only: narrower ones even out the workgroups per compute unit but end rows off the
     // 128-byte lines, which costs more than the idle units (64->128 @56x56: 11.4 us with 784 full
     // tiles, 13.7 us with 1004 tiles of 100 pixels).
-    a.tile_px = m16::kTilePx;
+    a.tile_px = tile;
     const int npt = (int)((NP + a.tile_px - 1) / a.tile_px);
     // wavefronts per workgroup, from sweeps over the MobileNet-shaped layers: 4 for tiles up to
     // 24 KB (32->64 @112x112: 17.0 us against 18.9 with 8), 16 beyond 40 KB, else 8; never more
@@ -570,15 +594,15 @@ extern "C" int alcs_sparse_conv_bf16_mfma(const alcs_packed_t *Wp, const uint16_
     a.act = activation;
     m16::kern_t kern = nullptr;
     switch (Wp->V) {
-        case 4: kern = m16::pick<4>(vec); break;
-        case 8: kern = m16::pick<8>(vec); break;
-        default: kern = m16::pick<16>(vec); break;
+        case 4: kern = m16::pick<4>(pv, vec); break;
+        case 8: kern = m16::pick<8>(pv, vec); break;
+        default: kern = m16::pick<16>(pv, vec); break;
     }
     if (lds > 64 * 1024) {
         rc = m16::check(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds));
         if (rc != ALCS_OK) return rc;
     }
-    record_launch(6, 2, nw, a.total_wgs, lds, a.ngt, L.KC, 3, 1, 0);
+    record_launch(6, pv, nw, a.total_wgs, lds, a.ngt, L.KC, 3, 1, 0);
     hipLaunchKernelGGL(kern, dim3((unsigned)(a.wg_per_xcd * kXcds)), dim3(nw * 64), lds, (hipStream_t)stream, a);
     return m16::check(hipGetLastError());
 }

@@ -99,6 +99,27 @@ def test_handles_with_several_groups_per_wavefront_16bit(V, slots):
     run_m16(Lu, 5575 + V + slots, options={"group_slots": slots} if slots else None)
 
 
+@pytest.mark.parametrize("V", [4, 8, 16])
+@pytest.mark.parametrize("Cin,H,W", [(700, 14, 14), (1278, 7, 7), (1024, 5, 9)])
+def test_wide_layers_one_pixel_per_lane_16bit(V, Cin, H, W):
+    """More than 638 input channels: 64-pixel tiles of 128-byte rows, one pixel per lane (up to 1278)."""
+    L = workloads.Layer("m16_wide%d_v%d" % (Cin, V), Cin, 3 * V + 1, H, W, N=5, V=V, sparsity=0.9, w_std=0.1)
+    info = run_m16(L, 5610 + Cin + V, act="relu", with_res=True)
+    assert info["pv"] == 1
+
+
+@pytest.mark.parametrize("V", [4, 8, 16])
+@pytest.mark.parametrize("H,W,stride", [(16, 16, 1), (14, 14, 1), (7, 7, 1), (9, 5, 1), (14, 14, 2)])
+def test_one_pixel_per_lane_on_request_16bit(V, H, W, stride):
+    L = workloads.Layer("m16_pv1_v%d" % V, 48, 2 * V + 3, H, W, stride=stride, N=7, V=V, sparsity=0.6, w_std=0.2)
+    info = run_m16(L, 5630 + V + H + W, act="relu6", with_res=True, options={"pixels_per_lane": 1})
+    assert info["pv"] == 1
+    info = run_m16(L, 5630 + V + H + W, act="relu6", with_res=True, options={"pixels_per_lane": 2})
+    assert info["pv"] == 2
+    L5 = workloads.Layer("m16_pv1_gs_v%d" % V, 520, 2 * V, H, W, stride=stride, N=3, V=V, sparsity=0.9, w_std=0.1)
+    run_m16(L5, 5650 + V + H + W, options={"pixels_per_lane": 1})
+
+
 def test_in_place_residual_no_bias_and_device_built_handle_16bit():
     L = workloads.Layer("m16_inplace", 64, 64, 14, 14, N=4, V=8, sparsity=0.8, w_std=0.3)
     run_m16(L, 5590, act="relu", with_res=True, in_place=True, with_bias=False, on_device=True)
@@ -115,7 +136,7 @@ def test_unsupported_layouts_and_rejected_arguments_16bit():
     import torch
     # 3x3 handles, more input channels than one 16-bit tile holds, chunked layouts and V < 4 are refused
     for L in (workloads.Layer("m16_3x3", 16, 8, 8, 8, k=3, N=1, V=4, sparsity=0.5),
-              workloads.Layer("m16_wide", 700, 16, 4, 4, N=1, V=4, sparsity=0.9),
+              workloads.Layer("m16_wide", 1300, 16, 4, 4, N=1, V=4, sparsity=0.9),
               workloads.Layer("m16_chunk", 700, 8, 4, 4, N=1, V=2, sparsity=0.9),
               workloads.Layer("m16_v2", 16, 8, 4, 4, N=1, V=2, sparsity=0.5)):
         d = workloads.make_layer(L, 5700)
