@@ -49,10 +49,12 @@ typedef enum alcs_status {
 } alcs_status;
 
 /* Opaque packed weight tensor; created by alcs_pack_weights, owned by the library
- * until alcs_packed_free.  Immutable after creation (but for alcs_packed_set_options);
+ * until alcs_packed_free.  Immutable after creation (but for alcs_packed_set_options and
+ * alcs_packed_add_bf16_weights, neither of which may run while another thread uses the handle);
  * may be used from several streams at once.  The library keeps no state outside
- * handles except two per-thread diagnostics (alcs_last_hip_error, alcs_last_launch)
- * and the device array of alcs_topn_mask_static. */
+ * handles except two per-thread diagnostics (alcs_last_hip_error, alcs_last_launch),
+ * the device array of alcs_topn_mask_static and the compute-unit / XCD counts of each
+ * device, read from its properties once. */
 typedef struct alcs_packed alcs_packed_t;
 
 /* Human-readable name of a status code (static string, never NULL). */
@@ -334,7 +336,8 @@ int alcs_pack_weights_opt(const float *W_host, const uint8_t *mask_host, int Cou
 
 /* Replaces the launch options of a handle (the two layout fields keep their pack-time
  * values) / reads the handle's options back.  Setting options is the one way a handle changes
- * after it is packed: it must not run while another thread launches with that handle. */
+ * after it is packed (besides alcs_packed_add_bf16_weights, which only adds): it must not run
+ * while another thread launches with that handle. */
 int alcs_packed_set_options(alcs_packed_t *p, const alcs_options *options);
 int alcs_packed_get_options(const alcs_packed_t *p, alcs_options *options);
 
