@@ -132,6 +132,15 @@ def test_mobilenet_shapes_16bit():
             run_m16(L, 5600 + cin + V, act="relu")
 
 
+@pytest.mark.parametrize("V", [8, 16])
+def test_benchmark_layers_at_full_batch_16bit(V):
+    """The 13 MobileNetV1-shaped pointwise layers at batch 32 and 90 % block sparsity, full tensors, in
+    the launch configuration the 16-bit report times (default handles)."""
+    import dataclasses
+    for i, L0 in enumerate(workloads.mobilenet_v1_pointwise(32, 0.9)):
+        run_m16(dataclasses.replace(L0, V=V), workloads.seed_for(2, i), act="relu")
+
+
 def test_unsupported_layouts_and_rejected_arguments_16bit():
     import torch
     # 3x3 handles, more input channels than one 16-bit tile holds, chunked layouts and V < 4 are refused
